@@ -1,0 +1,393 @@
+/*
+ * ep_oracle.c -- plain sequential CPU oracle for one rank's share of MoE
+ * dispatch and combine.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the yardstick the HIP path is checked
+ * against; nothing in the product path may call it.  It shares no code, header,
+ * table or helper with the HIP kernels.  Every function is a direct, slow,
+ * single-threaded transcription of a definition, with no blocking, fusion or
+ * reordering.
+ *
+ * What is computed (paper notation: N ranks, B tokens, E experts, L experts per
+ * rank, K top-k, R(r,t) the routing vector; here R ranks, T tokens, route[t][k]):
+ *
+ *   - dispatch sends every token to the ranks hosting its K selected experts
+ *     (Sec. II-B "Dispatch"); combine brings the expert outputs back to the
+ *     token's position and forms the gate-weighted sum over the K outputs
+ *     (Sec. II-B "Combine", Sec. III-B).  Both equal a plain permutation and a
+ *     plain weighted sum -- the "AllToAll dispatcher" of Sec. I (permute,
+ *     exchange, unpermute) -- so the oracle is that plain definition.
+ *   - experts are placed block-wise, expert e lives on rank floor(e / L)
+ *     (Sec. IV-A).
+ *   - the slot a token takes inside an expert's receive area is "the next
+ *     unused index" for that (expert, source rank) pair (Sec. IV-B, send phase);
+ *     scanning the routing table in flattened (t, k) order makes that index
+ *     deterministic and stable: (source rank, token index) order.
+ *   - output layouts: 3-D expert-major with a fixed number of slots per
+ *     (expert, source) sub-region, or 2-D concatenated with per-expert counts
+ *     (Sec. III-E "Tensor Layouts").
+ *   - the footprint-optimised dispatch sends a token once per destination rank
+ *     with the routing vector in the message header; the receiver fans it out
+ *     to its local experts (Sec. IV-D "Communication buffer layout
+ *     optimization").
+ *
+ * Conventions the paper leaves open (the same choices are made, independently,
+ * by the HIP path; parity for them is unpinned by the paper):
+ *   - topk_idx is int32; -1 marks "not routed"; any other id outside [0, E) is
+ *     counted as invalid and treated as not routed.
+ *   - padded layout: an entry whose slot is >= C is dropped (dst_row = -1); it
+ *     contributes zero to combine and weights are not renormalised.
+ *   - footprint-optimised message: { int32 src_token; int32 route[K];
+ *     float w[K]; zero padding to a multiple of 16 bytes; 2H payload bytes }.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_LAYOUT_CONCAT 0
+#define ORACLE_LAYOUT_PADDED 1
+
+/* ---- bf16 <-> real ------------------------------------------------------ */
+
+static float bf16_to_float(uint16_t b) {
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* Round a double to the nearest bfloat16 (8 significant bits, float32 exponent
+ * range), ties to even, by rounding to the nearest multiple of the bf16 quantum
+ * of its binade.  All scalings are by powers of two, hence exact. */
+static uint16_t double_to_bf16(double v) {
+    float f;
+    uint32_t u;
+    if (isnan(v)) return 0x7FC0;
+    if (isinf(v)) return v > 0 ? 0x7F80 : 0xFF80;
+    if (v == 0.0) return signbit(v) ? 0x8000 : 0x0000;
+    int ex;
+    (void)frexp(v, &ex);         /* |v| = m * 2^ex, m in [0.5, 1)  =>  2^(ex-1) <= |v| */
+    int e = ex - 1;              /* binade exponent */
+    if (e < -126) e = -126;      /* subnormal range shares the quantum of the lowest binade */
+    double q = ldexp(1.0, e - 7);
+    double r = nearbyint(v / q) * q; /* default rounding mode: to nearest, ties to even */
+    f = (float)r;                /* exact, or overflows to infinity exactly when bf16 would */
+    memcpy(&u, &f, 4);
+    return (uint16_t)(u >> 16);
+}
+
+uint16_t ep_oracle_double_to_bf16(double v) { return double_to_bf16(v); }
+float ep_oracle_bf16_to_float(uint16_t b) { return bf16_to_float(b); }
+
+/* ---- routing layout ------------------------------------------------------ */
+
+/*
+ * Routing layout of one source rank (Sec. IV-A index algebra, Sec. IV-B slot
+ * rule, Sec. III-E layouts, Sec. IV-D once-per-rank sends).
+ *
+ * in : topk_idx[T*K]; expert_base[E] or NULL (row where this source's rows of
+ *      expert e start in the receiver's concatenated tensor; NULL = exclusive
+ *      prefix of this source's own counts)
+ * out: expert_count[E]   demand per expert (before any capacity cut)
+ *      expert_kept[E]    rows actually placed per expert
+ *      expert_offset[E+1] first row of expert e; entry E = one past the last row
+ *      slot[T*K]         index of (t,k) among entries naming the same expert
+ *      dst_row[T*K]      expert_offset[e] + slot, or -1
+ *      sorted_token/k/row[T*K]  entries in (expert, slot) order; first n_sorted used
+ *      rank_pair_count[R]  entries per destination rank
+ *      rank_token_count[R] tokens per destination rank (each token once)
+ *      rank_offset[R+1]  first message slot of rank d in the staging windows
+ *      rank_row[T*K]     for the first k of token t that names rank d:
+ *                        rank_offset[d] + (tokens before t that name d); else -1
+ *      totals[6]         kept rows, dropped, masked(-1), invalid ids, sorted
+ *                        entries, rank messages
+ */
+void ep_oracle_layout(const int32_t *topk_idx, int T, int K, int E, int R, int layout, int C,
+                      int C_rank, const int32_t *expert_base, int32_t *expert_count,
+                      int32_t *expert_kept, int32_t *expert_offset, int32_t *slot,
+                      int32_t *dst_row, int32_t *sorted_token, int32_t *sorted_k,
+                      int32_t *sorted_row, int32_t *rank_pair_count, int32_t *rank_token_count,
+                      int32_t *rank_offset, int32_t *rank_row, int64_t *totals) {
+    const int L = E / R;
+    int64_t kept = 0, dropped = 0, masked = 0, invalid = 0;
+
+    for (int e = 0; e < E; ++e) expert_count[e] = 0;
+    /* slot = next unused index of the expert, scanning (t,k) in flattened order */
+    for (int i = 0; i < T * K; ++i) {
+        int e = topk_idx[i];
+        if (e == -1) { slot[i] = -1; ++masked; continue; }
+        if (e < 0 || e >= E) { slot[i] = -1; ++invalid; continue; }
+        slot[i] = expert_count[e];
+        expert_count[e] += 1;
+    }
+
+    /* where each expert's rows start */
+    if (layout == ORACLE_LAYOUT_PADDED) {
+        for (int e = 0; e < E; ++e) {
+            expert_offset[e] = e * C;
+            expert_kept[e] = expert_count[e] < C ? expert_count[e] : C;
+        }
+        expert_offset[E] = E * C;
+    } else if (expert_base) {
+        int32_t end = 0;
+        for (int e = 0; e < E; ++e) {
+            expert_offset[e] = expert_base[e];
+            expert_kept[e] = expert_count[e];
+            if (expert_count[e] > 0 && expert_base[e] + expert_count[e] > end)
+                end = expert_base[e] + expert_count[e];
+        }
+        expert_offset[E] = end;
+    } else {
+        int32_t run = 0;
+        for (int e = 0; e < E; ++e) {
+            expert_offset[e] = run;
+            expert_kept[e] = expert_count[e];
+            run += expert_count[e];
+        }
+        expert_offset[E] = run;
+    }
+
+    /* destination rows, and the entries listed in (expert, slot) order */
+    int32_t *own_prefix = (int32_t *)malloc(sizeof(int32_t) * (size_t)(E + 1));
+    own_prefix[0] = 0;
+    for (int e = 0; e < E; ++e) own_prefix[e + 1] = own_prefix[e] + expert_count[e];
+    for (int i = 0; i < T * K; ++i) {
+        int e = topk_idx[i];
+        if (slot[i] < 0) { dst_row[i] = -1; continue; }
+        if (layout == ORACLE_LAYOUT_PADDED && slot[i] >= C) {
+            dst_row[i] = -1;
+            ++dropped;
+        } else {
+            dst_row[i] = expert_offset[e] + slot[i];
+            ++kept;
+        }
+        int pos = own_prefix[e] + slot[i];
+        sorted_token[pos] = i / K;
+        sorted_k[pos] = i % K;
+        sorted_row[pos] = dst_row[i];
+    }
+    int64_t n_sorted = own_prefix[E];
+    free(own_prefix);
+
+    /* per destination rank: entries, and tokens counted once */
+    for (int d = 0; d < R; ++d) { rank_pair_count[d] = 0; rank_token_count[d] = 0; }
+    for (int e = 0; e < E; ++e) rank_pair_count[e / L] += expert_count[e];
+    int32_t *rank_slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T * K + 1));
+    for (int t = 0; t < T; ++t) {
+        for (int k = 0; k < K; ++k) {
+            int i = t * K + k;
+            int e = topk_idx[i];
+            rank_slot[i] = -1;
+            if (e < 0 || e >= E) continue;
+            int d = e / L;
+            int first = 1;
+            for (int k2 = 0; k2 < k; ++k2) {
+                int e2 = topk_idx[t * K + k2];
+                if (e2 >= 0 && e2 < E && e2 / L == d) first = 0;
+            }
+            if (first) { rank_slot[i] = rank_token_count[d]; rank_token_count[d] += 1; }
+        }
+    }
+    if (layout == ORACLE_LAYOUT_PADDED) {
+        for (int d = 0; d <= R; ++d) rank_offset[d] = d * C_rank;
+    } else {
+        rank_offset[0] = 0;
+        for (int d = 0; d < R; ++d) rank_offset[d + 1] = rank_offset[d] + rank_token_count[d];
+    }
+    int64_t msgs = 0;
+    for (int i = 0; i < T * K; ++i) {
+        if (rank_slot[i] < 0) { rank_row[i] = -1; continue; }
+        rank_row[i] = rank_offset[topk_idx[i] / L] + rank_slot[i];
+        ++msgs;
+    }
+    free(rank_slot);
+
+    totals[0] = kept; totals[1] = dropped; totals[2] = masked; totals[3] = invalid;
+    totals[4] = n_sorted; totals[5] = msgs;
+}
+
+/* ---- window addressing ---------------------------------------------------- */
+
+/* Element offset of logical row `row` in the receive windows.
+ * concat: 2-D [rows, H], offset = row * stride0.
+ * padded: 3-D [E, C, H], row = e*C + s, offset = e * stride0 + s * stride1. */
+static int64_t row_offset(int64_t row, int layout, int C, int64_t stride0, int64_t stride1) {
+    if (layout == ORACLE_LAYOUT_PADDED) return (row / C) * stride0 + (row % C) * stride1;
+    return row * stride0;
+}
+
+/* ---- dispatch (direct) ------------------------------------------------------ */
+
+/* For every routed entry copy the token's row to its destination row
+ * (Sec. IV-C "Send Tokens"; the row is pure token data, the source index and
+ * the gate weight travel in side arrays).  Rows not named by dst_row are left
+ * untouched.  recv_w / recv_src / w may be NULL. */
+void ep_oracle_dispatch(const uint16_t *x, int64_t x_stride, const float *w, const int32_t *dst_row,
+                        int T, int K, int H, int layout, int C, int64_t stride0, int64_t stride1,
+                        uint16_t *recv_x, float *recv_w, int32_t *recv_src) {
+    for (int t = 0; t < T; ++t) {
+        for (int k = 0; k < K; ++k) {
+            int32_t row = dst_row[t * K + k];
+            if (row < 0) continue;
+            uint16_t *dst = recv_x + row_offset(row, layout, C, stride0, stride1);
+            for (int h = 0; h < H; ++h) dst[h] = x[(int64_t)t * x_stride + h];
+            if (recv_w && w) recv_w[row] = w[t * K + k];
+            if (recv_src) recv_src[row] = t;
+        }
+    }
+}
+
+/* ---- combine ---------------------------------------------------------------- */
+
+/* out[t][h] = bf16( sum_{k ascending} w[t][k] * y[dst_row[t][k]][h] ), entries
+ * with dst_row < 0 contribute nothing, w == NULL means all weights are 1
+ * (Sec. II-B "Combine", Sec. III-B, Sec. IV-B receive phase).
+ * acc_mode 0: products and sum in float64 (exact products), one rounding to bf16.
+ * acc_mode 1: float32 multiply then float32 add, each rounded to nearest even,
+ *             k ascending, then one rounding to bf16 (the precision the
+ *             build's target statement fixes for the accelerator path). */
+void ep_oracle_combine(const uint16_t *y, int layout, int C, int64_t stride0, int64_t stride1,
+                       const float *w, const int32_t *dst_row, int T, int K, int H,
+                       uint16_t *out, int64_t out_stride, int acc_mode) {
+    for (int t = 0; t < T; ++t) {
+        for (int h = 0; h < H; ++h) {
+            if (acc_mode == 0) {
+                double acc = 0.0;
+                for (int k = 0; k < K; ++k) {
+                    int32_t row = dst_row[t * K + k];
+                    if (row < 0) continue;
+                    double wk = w ? (double)w[t * K + k] : 1.0;
+                    double v = (double)bf16_to_float(y[row_offset(row, layout, C, stride0, stride1) + h]);
+                    acc = acc + wk * v;
+                }
+                out[(int64_t)t * out_stride + h] = double_to_bf16(acc);
+            } else {
+                volatile float acc = 0.0f;
+                for (int k = 0; k < K; ++k) {
+                    int32_t row = dst_row[t * K + k];
+                    if (row < 0) continue;
+                    float wk = w ? w[t * K + k] : 1.0f;
+                    float v = bf16_to_float(y[row_offset(row, layout, C, stride0, stride1) + h]);
+                    volatile float prod = wk * v;
+                    acc = acc + prod;
+                }
+                out[(int64_t)t * out_stride + h] = double_to_bf16((double)acc);
+            }
+        }
+    }
+}
+
+/* ---- footprint-optimised dispatch: once per destination rank ------------------ */
+
+int64_t ep_oracle_msg_header_bytes(int K) {
+    int64_t raw = 4 + 4 * (int64_t)K + 4 * (int64_t)K;
+    return (raw + 15) / 16 * 16;
+}
+
+/* Sender: each token goes once to every rank that hosts one of its experts;
+ * the header carries the source token index, the routing vector and the gate
+ * weights (Sec. IV-D).  rank_win is a byte array of message slots of
+ * msg_bytes = header + 2H bytes; slot index = rank_row. */
+void ep_oracle_dedup_send(const uint16_t *x, int64_t x_stride, const int32_t *topk_idx,
+                          const float *w, const int32_t *rank_row, int T, int K, int H,
+                          uint8_t *rank_win) {
+    const int64_t hdr = ep_oracle_msg_header_bytes(K);
+    const int64_t msg = hdr + 2 * (int64_t)H;
+    for (int t = 0; t < T; ++t) {
+        for (int k = 0; k < K; ++k) {
+            int32_t m = rank_row[t * K + k];
+            if (m < 0) continue;
+            uint8_t *p = rank_win + (int64_t)m * msg;
+            memset(p, 0, (size_t)hdr);
+            int32_t tok = t;
+            memcpy(p, &tok, 4);
+            memcpy(p + 4, topk_idx + (int64_t)t * K, 4 * (size_t)K);
+            if (w) memcpy(p + 4 + 4 * (int64_t)K, w + (int64_t)t * K, 4 * (size_t)K);
+            else {
+                float one = 1.0f;
+                for (int j = 0; j < K; ++j) memcpy(p + 4 + 4 * (int64_t)K + 4 * j, &one, 4);
+            }
+            memcpy(p + hdr, x + (int64_t)t * x_stride, 2 * (size_t)H);
+        }
+    }
+}
+
+/* Receiver side of every simulated destination rank d: walk the messages of
+ * window d in slot order; each message is expanded to every local expert its
+ * header names, the row index inside the expert being the running count of
+ * earlier arrivals for that expert (Sec. IV-C "Dispatch/recv": contiguous slots
+ * per (expert, source), messages in order).  Uses only the windows, the
+ * per-rank message counts and offsets, and (concat layout) where each expert's
+ * rows start, which it derives from the headers themselves unless expert_base
+ * is given.  recv_count[E] receives the rows placed per expert. */
+void ep_oracle_dedup_recv(const uint8_t *rank_win, const int32_t *rank_offset,
+                          const int32_t *rank_token_count, int K, int H, int E, int R,
+                          int layout, int C, const int32_t *expert_base, int64_t stride0,
+                          int64_t stride1, uint16_t *recv_x, float *recv_w, int32_t *recv_src,
+                          int32_t *recv_count, int64_t *dropped_out) {
+    const int L = E / R;
+    const int64_t hdr = ep_oracle_msg_header_bytes(K);
+    const int64_t msg = hdr + 2 * (int64_t)H;
+    int32_t *demand = (int32_t *)calloc((size_t)E, sizeof(int32_t));
+    int32_t *start = (int32_t *)calloc((size_t)E + 1, sizeof(int32_t));
+    int32_t *next = (int32_t *)calloc((size_t)E, sizeof(int32_t));
+    int64_t dropped = 0;
+    /* pass 1: how many rows each expert will receive */
+    for (int d = 0; d < R; ++d) {
+        for (int j = 0; j < rank_token_count[d]; ++j) {
+            const uint8_t *p = rank_win + (int64_t)(rank_offset[d] + j) * msg;
+            for (int k = 0; k < K; ++k) {
+                int32_t e;
+                memcpy(&e, p + 4 + 4 * (int64_t)k, 4);
+                if (e >= 0 && e < E && e / L == d) demand[e] += 1;
+            }
+        }
+    }
+    for (int e = 0; e < E; ++e) {
+        if (layout == ORACLE_LAYOUT_PADDED) start[e] = e * C;
+        else if (expert_base) start[e] = expert_base[e];
+        else start[e + 1] = start[e] + demand[e];
+    }
+    /* pass 2: place rows */
+    for (int d = 0; d < R; ++d) {
+        for (int j = 0; j < rank_token_count[d]; ++j) {
+            const uint8_t *p = rank_win + (int64_t)(rank_offset[d] + j) * msg;
+            int32_t tok;
+            memcpy(&tok, p, 4);
+            for (int k = 0; k < K; ++k) {
+                int32_t e;
+                float wk;
+                memcpy(&e, p + 4 + 4 * (int64_t)k, 4);
+                memcpy(&wk, p + 4 + 4 * (int64_t)K + 4 * (int64_t)k, 4);
+                if (e < 0 || e >= E || e / L != d) continue;
+                int32_t s = next[e];
+                next[e] += 1;
+                if (layout == ORACLE_LAYOUT_PADDED && s >= C) { ++dropped; continue; }
+                int64_t row = (int64_t)start[e] + s;
+                memcpy(recv_x + row_offset(row, layout, C, stride0, stride1), p + hdr, 2 * (size_t)H);
+                if (recv_w) recv_w[row] = wk;
+                if (recv_src) recv_src[row] = tok;
+            }
+        }
+    }
+    for (int e = 0; e < E; ++e) {
+        int32_t placed = next[e];
+        if (layout == ORACLE_LAYOUT_PADDED && placed > C) placed = C;
+        recv_count[e] = placed;
+    }
+    if (dropped_out) *dropped_out = dropped;
+    free(demand); free(start); free(next);
+}
+
+/* ---- buffer footprints (Sec. IV-D, footprint equation) ------------------------ */
+
+/* Per-expert sub-region scheme: E sub-regions of B slots of P bytes for dispatch
+ * and the same for combine. */
+int64_t ep_oracle_footprint_per_expert(int64_t E, int64_t B, int64_t P) { return 2 * E * B * P; }
+
+/* Footprint-optimised scheme: N sub-regions of B slots for dispatch, B*K slots
+ * for combine. */
+int64_t ep_oracle_footprint_optimised(int64_t N, int64_t B, int64_t K, int64_t P) {
+    return N * B * P + B * K * P;
+}

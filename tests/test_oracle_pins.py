@@ -1,0 +1,504 @@
+"""Pins for the CPU oracle: each test ties an oracle function to something that is
+not the oracle -- the hand-worked example, values the paper prints, closed forms,
+library routines (stable sort, bincount, cumsum, index_select), exact rational
+arithmetic, brute force on tiny inputs.  A dropped term, a wrong sign or index, or
+a transposed operand in the oracle fails at least one of them."""
+import itertools
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_13606_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _golden(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return json.load(f)
+
+
+# --------------------------------------------------------------------------- layout
+
+
+def test_worked_example_concat(oracle_mod):
+    g = _golden("worked_example_layout.json")
+    c = g["concat"]
+    lay = oracle_mod.layout(np.array(g["topk_idx"], np.int32), E=g["E"], R=g["R"])
+    assert lay.expert_count.tolist() == c["expert_count"]
+    assert lay.expert_kept.tolist() == c["expert_count"]
+    assert lay.expert_offset.tolist() == c["expert_offset"]
+    assert lay.slot.tolist() == c["slot"]
+    assert lay.dst_row.tolist() == c["dst_row"]
+    assert lay.sorted_token[: lay.n_sorted].tolist() == c["sorted_token"]
+    assert lay.sorted_k[: lay.n_sorted].tolist() == c["sorted_k"]
+    assert lay.sorted_row[: lay.n_sorted].tolist() == list(range(8))
+    assert lay.rank_pair_count.tolist() == c["rank_pair_count"]
+    assert lay.rank_token_count.tolist() == c["rank_token_count"]
+    assert lay.rank_offset.tolist() == c["rank_offset"]
+    L = g["E"] // g["R"]
+    topk = np.array(g["topk_idx"])
+    for d_str, per_tok in c["rank_slot_by_rank"].items():
+        d = int(d_str)
+        for t_str, s in per_tok.items():
+            t = int(t_str)
+            ks = [k for k in range(g["K"]) if topk[t, k] // L == d]
+            assert lay.rank_row[t, ks[0]] == c["rank_offset"][d] + s
+            for k in ks[1:]:
+                assert lay.rank_row[t, k] == -1
+    assert (lay.kept, lay.dropped, lay.masked, lay.invalid, lay.n_msgs) == (8, 0, 0, 0, 7)
+
+
+def test_worked_example_padded_overflow(oracle_mod):
+    g = _golden("worked_example_layout.json")
+    p = g["padded_C2"]
+    lay = oracle_mod.layout(np.array(g["topk_idx"], np.int32), E=g["E"], R=g["R"],
+                            layout=oracle_mod.LAYOUT_PADDED, C=p["C"])
+    assert lay.expert_count.tolist() == g["concat"]["expert_count"]  # demand is not capped
+    assert lay.expert_kept.tolist() == p["expert_kept"]
+    assert lay.expert_offset.tolist() == p["expert_offset"]
+    assert lay.dst_row.tolist() == p["dst_row"]
+    assert lay.dropped == p["dropped"] and lay.kept == 7
+    assert lay.slot.tolist() == g["concat"]["slot"]
+    # staging windows in the 3-D mode have T slots per destination rank
+    assert lay.rank_offset.tolist() == [0, 4, 8]
+
+
+def _brute_slot(topk, E):
+    """O(n^2) definition: slot = number of earlier flattened entries naming the same expert."""
+    flat = topk.reshape(-1)
+    out = np.full(flat.shape, -1, np.int64)
+    for i, e in enumerate(flat):
+        if 0 <= e < E:
+            out[i] = sum(1 for j in range(i) if flat[j] == e)
+    return out.reshape(topk.shape)
+
+
+def test_exhaustive_tiny_against_predecessor_count(oracle_mod):
+    E, R, K = 4, 2, 2
+    L = E // R
+    vals = [-1, 0, 1, 2, 3, 9]  # -1 masked, 9 invalid
+    for T in (1, 2, 3):
+        pool = vals if T < 3 else vals[:5]
+        for flat in itertools.product(pool, repeat=T * K):
+            topk = np.array(flat, np.int32).reshape(T, K)
+            lay = oracle_mod.layout(topk, E=E, R=R)
+            slot = _brute_slot(topk, E)
+            assert np.array_equal(lay.slot, slot)
+            cnt = np.array([(topk == e).sum() for e in range(E)])
+            assert np.array_equal(lay.expert_count, cnt)
+            off = np.concatenate([[0], np.cumsum(cnt)])
+            assert np.array_equal(lay.expert_offset, off)
+            valid = (topk >= 0) & (topk < E)
+            want = np.where(valid, off[np.clip(topk, 0, E - 1)] + slot, -1)
+            assert np.array_equal(lay.dst_row, want)
+            # each token counted once per destination rank, in token order
+            rtc = np.zeros(R, np.int64)
+            for t in range(T):
+                seen = []
+                for k in range(K):
+                    if not valid[t, k]:
+                        assert lay.rank_row[t, k] == -1
+                        continue
+                    d = topk[t, k] // L
+                    if d in seen:
+                        assert lay.rank_row[t, k] == -1
+                    else:
+                        seen.append(d)
+                        # filled in after counts are known (needs rank_offset)
+                for d in set(seen):
+                    rtc[d] += 1
+            assert np.array_equal(lay.rank_token_count, rtc)
+            assert lay.masked == int((topk == -1).sum())
+            assert lay.invalid == int(((topk != -1) & ~valid).sum())
+
+
+def _torch_layout(topk, E):
+    """Counting sort by library routines: stable sort of the flattened expert ids."""
+    flat = torch.from_numpy(topk.reshape(-1).astype(np.int64))
+    valid = (flat >= 0) & (flat < E)
+    key = torch.where(valid, flat, torch.full_like(flat, E))
+    _, perm = torch.sort(key, stable=True)
+    n_valid = int(valid.sum())
+    perm = perm[:n_valid]
+    dst = torch.full_like(flat, -1)
+    dst[perm] = torch.arange(n_valid)
+    counts = torch.bincount(flat[valid], minlength=E)
+    offs = torch.cat([torch.zeros(1, dtype=torch.int64), torch.cumsum(counts, 0)])
+    return dst.numpy().reshape(topk.shape), counts.numpy(), offs.numpy(), perm.numpy()
+
+
+@pytest.mark.parametrize("name,T", [("tiny", None), ("ll_decode", None), ("skew", 777),
+                                    ("ht_prefill", 1500), ("stress_hot", 2048)])
+def test_layout_equals_stable_sort(oracle_mod, name, T):
+    spec = wl.SPECS[name]
+    topk, _, _ = wl.make_routing(spec, T=T)
+    rng = np.random.default_rng(5)
+    topk = topk.copy()
+    topk[rng.random(topk.shape) < 0.03] = -1  # a few masked entries
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R)
+    dst, counts, offs, perm = _torch_layout(topk, spec.E)
+    K = spec.K
+    assert np.array_equal(lay.dst_row, dst)
+    assert np.array_equal(lay.expert_count, counts)
+    assert np.array_equal(lay.expert_offset, offs)
+    assert np.array_equal(lay.sorted_token[: lay.n_sorted], perm // K)
+    assert np.array_equal(lay.sorted_k[: lay.n_sorted], perm % K)
+    assert np.array_equal(lay.sorted_row[: lay.n_sorted], np.arange(lay.n_sorted))
+    # invariants
+    assert lay.expert_count.sum() == topk.size - lay.masked
+    L = spec.L
+    assert np.array_equal(lay.rank_pair_count, counts.reshape(spec.R, L).sum(1))
+    owners = np.where(topk >= 0, topk // L, -1)
+    distinct = [set(r[r >= 0].tolist()) for r in owners]
+    assert lay.rank_token_count.sum() == sum(len(s) for s in distinct) == lay.n_msgs
+    for d in range(spec.R):
+        toks = [t for t, s in enumerate(distinct) if d in s]
+        assert lay.rank_token_count[d] == len(toks)
+        assert lay.rank_token_count[d] <= min(len(topk), lay.rank_pair_count[d])
+        got = sorted((int(lay.rank_row[t][np.argmax(owners[t] == d)]), t) for t in toks)
+        # slots are consecutive from rank_offset[d] and increase with the token index
+        assert [g[0] for g in got] == list(range(lay.rank_offset[d], lay.rank_offset[d] + len(toks)))
+        assert [g[1] for g in got] == toks
+    assert (lay.rank_row >= 0).sum() == lay.n_msgs
+    # within each expert the source tokens are non-decreasing
+    for e in range(spec.E):
+        seg = lay.sorted_token[lay.expert_offset[e]: lay.expert_offset[e + 1]]
+        assert np.all(np.diff(seg) >= 0)
+
+
+def test_padded_overflow_drops_highest_tokens(oracle_mod):
+    spec = wl.SPECS["skew_rank0"]
+    topk, _, _ = wl.make_routing(spec, T=1024)
+    C = 2 * 1024 * spec.K // spec.E
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, layout=oracle_mod.LAYOUT_PADDED, C=C)
+    ref = oracle_mod.layout(topk, E=spec.E, R=spec.R)
+    assert lay.dropped > 0
+    assert np.array_equal(lay.slot, ref.slot) and np.array_equal(lay.expert_count, ref.expert_count)
+    assert np.array_equal(lay.expert_kept, np.minimum(ref.expert_count, C))
+    want = np.where(ref.slot < C, topk * C + ref.slot, -1)
+    assert np.array_equal(lay.dst_row, want)
+    assert lay.dropped == int((ref.slot >= C).sum()) and lay.kept + lay.dropped == topk.size
+    assert np.array_equal(lay.rank_offset, np.arange(spec.R + 1) * 1024)
+
+
+def test_expert_base_shifts_rows(oracle_mod):
+    spec = wl.SPECS["tiny"]
+    topk, _, _ = wl.make_routing(spec)
+    base = (np.arange(spec.E, dtype=np.int32) * 100 + 7).astype(np.int32)
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, expert_base=base)
+    ref = oracle_mod.layout(topk, E=spec.E, R=spec.R)
+    assert np.array_equal(lay.dst_row, base[topk] + ref.slot)
+    assert lay.expert_offset[-1] == max(base[e] + ref.expert_count[e] for e in range(spec.E)
+                                        if ref.expert_count[e] > 0)
+    assert np.array_equal(lay.sorted_token[: lay.n_sorted], ref.sorted_token[: ref.n_sorted])
+
+
+def test_empty_and_single(oracle_mod):
+    lay = oracle_mod.layout(np.zeros((0, 8), np.int32), E=16, R=4)
+    assert lay.expert_count.sum() == 0 and lay.expert_offset.tolist() == [0] * 17 and lay.kept == 0
+    lay = oracle_mod.layout(np.array([[5]], np.int32), E=16, R=4)
+    assert lay.dst_row.tolist() == [[0]] and lay.rank_token_count.tolist() == [0, 1, 0, 0]
+
+
+# --------------------------------------------------------------------------- bf16 rounding
+
+
+def test_bf16_roundtrip_all_values(oracle_mod):
+    lib = oracle_mod.lib()
+    for b in range(0, 65536):
+        f = np.array([b], np.uint16).astype(np.uint32) << 16
+        v = float(f.view(np.float32)[0])
+        if v != v:
+            assert oracle_mod.double_to_bf16(v) & 0x7F80 == 0x7F80 and oracle_mod.double_to_bf16(v) & 0x7F
+            continue
+        assert oracle_mod.double_to_bf16(v) == b
+        assert lib.ep_oracle_bf16_to_float(b) == v
+
+
+def test_bf16_ties_and_neighbours(oracle_mod):
+    # 1 + 2^-8 is exactly between bf16 1.0 (mantissa 0, even) and 1.0078125 (odd)
+    assert oracle_mod.double_to_bf16(1.0 + 2.0 ** -8) == 0x3F80
+    assert oracle_mod.double_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -40) == 0x3F81
+    assert oracle_mod.double_to_bf16(1.0078125 + 2.0 ** -8) == 0x3F82  # tie goes up to even
+    assert oracle_mod.double_to_bf16(1.0078125 + 2.0 ** -8 - 2.0 ** -40) == 0x3F81
+    assert oracle_mod.double_to_bf16(-(1.0 + 2.0 ** -8)) == 0xBF80
+    assert oracle_mod.double_to_bf16(1.99609375 + 2.0 ** -8) == 0x4000  # carries into next binade
+    assert oracle_mod.double_to_bf16(3.4e38) == 0x7F80  # rounds to infinity
+    assert oracle_mod.double_to_bf16(2.0 ** -133) == 0x0001  # smallest subnormal
+    assert oracle_mod.double_to_bf16(2.0 ** -134) == 0x0000  # tie to even (zero)
+    assert oracle_mod.double_to_bf16(2.0 ** -134 * 1.0001) == 0x0001
+    assert oracle_mod.double_to_bf16(-0.0) == 0x8000
+
+
+def test_bf16_matches_torch_rne(oracle_mod):
+    rng = np.random.default_rng(3)
+    a = np.concatenate([rng.standard_normal(20000).astype(np.float32) * 3,
+                        (rng.standard_normal(2000) * 1e-3).astype(np.float32),
+                        np.float32(2.0) ** rng.integers(-140, 127, 2000).astype(np.float32)])
+    want = torch.from_numpy(a).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = np.array([oracle_mod.double_to_bf16(float(v)) for v in a], np.uint16)
+    assert np.array_equal(got, want)
+    assert np.array_equal(wl.f32_to_bf16_bits(a), want)  # the input generator's own conversion
+
+
+# --------------------------------------------------------------------------- dispatch
+
+
+@pytest.mark.parametrize("name,T", [("tiny", None), ("ll_decode", 40), ("skew", 300)])
+def test_dispatch_is_index_select(oracle_mod, name, T):
+    w = wl.make_workload(name, T=T)
+    spec = w.spec
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R)
+    rows = lay.expert_offset[-1]
+    guard = 3
+    recv = np.full((rows + guard, spec.H), 0xDEAD, np.uint16)
+    recv_w = np.full(rows + guard, np.float32(-77.0), np.float32)
+    recv_src = np.full(rows + guard, -5, np.int32)
+    oracle_mod.dispatch(w.x_bits, w.topk_w, lay, recv, recv_w, recv_src)
+    dst, counts, offs, perm = _torch_layout(w.topk_idx, spec.E)
+    xt = torch.from_numpy(w.x_bits.view(np.int16))
+    want = xt.index_select(0, torch.from_numpy(perm // spec.K)).numpy().view(np.uint16)
+    assert np.array_equal(recv[:rows], want)
+    assert np.all(recv[rows:] == 0xDEAD) and np.all(recv_w[rows:] == -77.0) and np.all(recv_src[rows:] == -5)
+    assert np.array_equal(recv_src[:rows], perm // spec.K)
+    assert np.array_equal(recv_w[:rows], w.topk_w.reshape(-1)[perm])
+    # every token lands exactly once per selected expert
+    for e in range(spec.E):
+        seg = recv_src[offs[e]: offs[e + 1]]
+        want_tok = np.nonzero((w.topk_idx == e).any(1))[0]
+        assert np.array_equal(seg, want_tok)
+
+
+def test_dispatch_padded_strided_and_poison(oracle_mod):
+    """3-D [E, C, H] windows embedded in a receiver tensor [E, R*C, H]: only this
+    source's sub-region of each expert may change (Sec. III-E LL layout)."""
+    w = wl.make_workload("tiny")
+    spec = w.spec
+    C, my_rank = 6, 1
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, layout=oracle_mod.LAYOUT_PADDED, C=C)
+    assert lay.dropped > 0
+    full = np.full((spec.E, spec.R * C, spec.H), 0xBEEF, np.uint16)
+    view = full[:, my_rank * C:(my_rank + 1) * C, :]
+    oracle_mod.dispatch(w.x_bits, None, lay, view, stride0=spec.R * C * spec.H, stride1=spec.H)
+    for e in range(spec.E):
+        toks = [t for t in range(spec.T) for k in range(spec.K) if w.topk_idx[t, k] == e]
+        kept = toks[:C]
+        assert lay.expert_kept[e] == len(kept)
+        for s, t in enumerate(kept):
+            assert np.array_equal(full[e, my_rank * C + s], w.x_bits[t])
+        assert np.all(full[e, my_rank * C + len(kept):(my_rank + 1) * C] == 0xBEEF)
+        assert np.all(full[e, :my_rank * C] == 0xBEEF)
+
+
+# --------------------------------------------------------------------------- combine
+
+
+def _exact_bf16_neighbours(fr: Fraction):
+    """The two bf16 values bracketing an exact rational, and the nearest (None on a tie)."""
+    if fr == 0:
+        return 0.0, 0.0, 0.0
+    a = abs(fr)
+    e = 0
+    while Fraction(2) ** (e + 1) <= a:
+        e += 1
+    while Fraction(2) ** e > a:
+        e -= 1
+    q = Fraction(2) ** (max(e, -126) - 7)
+    lo = (a // q) * q
+    hi = lo + q
+    sgn = -1 if fr < 0 else 1
+    if a - lo < hi - a:
+        near = lo
+    elif a - lo > hi - a:
+        near = hi
+    else:
+        near = None
+    return sgn * float(lo), sgn * float(hi), (None if near is None else sgn * float(near))
+
+
+def test_combine_against_exact_rational(oracle_mod):
+    w = wl.make_workload("tiny", expert_scale=True)
+    spec = w.spec
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R)
+    rows = lay.expert_offset[-1]
+    rng = np.random.default_rng(11)
+    y = wl.f32_to_bf16_bits(rng.standard_normal((rows, spec.H)).astype(np.float32))
+    out64 = oracle_mod.combine(y, w.topk_w, lay, spec.H, acc="f64")
+    out32 = oracle_mod.combine(y, w.topk_w, lay, spec.H, acc="f32")
+    yf = wl.bf16_bits_to_f32(y)
+    o64 = wl.bf16_bits_to_f32(out64)
+    o32 = wl.bf16_bits_to_f32(out32)
+    checked = 0
+    for t in range(0, spec.T, 5):
+        for h in range(0, spec.H, 37):
+            exact = sum(Fraction(float(w.topk_w[t, k])) * Fraction(float(yf[lay.dst_row[t, k], h]))
+                        for k in range(spec.K))
+            lo, hi, near = _exact_bf16_neighbours(exact)
+            assert o64[t, h] in (lo, hi)
+            if near is not None and abs(exact - Fraction(near)) * 2 ** 30 < abs(Fraction(hi) - Fraction(lo)) * (2 ** 29 - 1):
+                assert o64[t, h] == near  # not within 2^-30 of a tie: must be the nearest
+            assert o32[t, h] in (lo, hi)
+            checked += 1
+    assert checked > 50
+
+
+def test_combine_one_hot_weights_select_the_kth_row(oracle_mod):
+    w = wl.make_workload("ll_decode", T=24, H=64)
+    spec = w.spec
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R)
+    rows = lay.expert_offset[-1]
+    y = wl.f32_to_bf16_bits(np.random.default_rng(2).standard_normal((rows, spec.H)).astype(np.float32))
+    for j in range(spec.K):
+        onehot = np.zeros((spec.T, spec.K), np.float32)
+        onehot[:, j] = 1.0
+        for acc in ("f64", "f32"):
+            out = oracle_mod.combine(y, onehot, lay, spec.H, acc=acc)
+            want = y[lay.dst_row[:, j]]
+            # adding +0 keeps every value; -0 becomes +0
+            want = np.where(want == 0x8000, 0, want)
+            assert np.array_equal(out, want)
+
+
+def test_combine_matches_torch_within_one_ulp(oracle_mod):
+    w = wl.make_workload("skew", T=200, H=512)
+    spec = w.spec
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R)
+    rows = lay.expert_offset[-1]
+    recv = np.zeros((rows, spec.H), np.uint16)
+    oracle_mod.dispatch(w.x_bits, None, lay, recv)
+    scale = wl.expert_scale_table(spec)
+    row_e = np.repeat(np.arange(spec.E), lay.expert_count)
+    y = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(recv) * scale[row_e][:, None])
+    out = wl.bf16_bits_to_f32(oracle_mod.combine(y, w.topk_w, lay, spec.H))
+    yt = torch.from_numpy(wl.bf16_bits_to_f32(y)).double()
+    ref = (yt[torch.from_numpy(lay.dst_row.astype(np.int64))] *
+           torch.from_numpy(w.topk_w).double()[..., None]).sum(1)
+    ref_bf = ref.float().to(torch.bfloat16).float().numpy()
+    ulp = np.maximum(np.abs(ref_bf), 2.0 ** -126) * 2.0 ** -7
+    assert np.all(np.abs(out - ref_bf) <= ulp)
+    assert (out == ref_bf).mean() > 0.999
+    # closed form of the stand-in experts: x * sum_k w_k (1 + e_k/256), y rounded once
+    x = wl.bf16_bits_to_f32(w.x_bits).astype(np.float64)
+    g = (w.topk_w.astype(np.float64) * scale[w.topk_idx].astype(np.float64)).sum(1)
+    closed = x * g[:, None]
+    assert np.all(np.abs(out - closed) <= 2.5 * np.maximum(np.abs(closed), 1e-30) * 2.0 ** -8)
+
+
+def test_round_trip_identity_experts(oracle_mod):
+    """combine(dispatch(x)) = bf16(x * sum_k w[t,k]) with identity experts; with
+    renormalised weights that is x to within one bf16 ulp."""
+    w = wl.make_workload("tiny")
+    spec = w.spec
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R)
+    recv = np.zeros((lay.expert_offset[-1], spec.H), np.uint16)
+    oracle_mod.dispatch(w.x_bits, w.topk_w, lay, recv)
+    out = wl.bf16_bits_to_f32(oracle_mod.combine(recv, w.topk_w, lay, spec.H))
+    x = wl.bf16_bits_to_f32(w.x_bits)
+    assert np.all(np.abs(out - x) <= np.abs(x) * 2.0 ** -7)
+    # unweighted: exactly K * x when K is a power of two
+    out1 = wl.bf16_bits_to_f32(oracle_mod.combine(recv, None, lay, spec.H))
+    assert np.array_equal(out1, x * spec.K)
+    # arbitrary weights: x * sum(w) with exact products
+    w2 = np.random.default_rng(4).random((spec.T, spec.K)).astype(np.float32)
+    out2 = oracle_mod.combine(recv, w2, lay, spec.H)
+    s = w2.astype(np.float64).sum(1)
+    want = np.array([[oracle_mod.double_to_bf16(float(x[t, h]) * float(s[t])) for h in range(0, spec.H, 17)]
+                     for t in range(spec.T)], np.uint16)
+    got = out2[:, ::17]
+    diff = np.abs(wl.bf16_bits_to_f32(got) - wl.bf16_bits_to_f32(want))
+    assert np.all(diff <= np.abs(wl.bf16_bits_to_f32(want)) * 2.0 ** -7)
+    assert (got == want).mean() > 0.98
+
+
+def test_combine_dropped_entries_contribute_zero(oracle_mod):
+    w = wl.make_workload("tiny")
+    spec = w.spec
+    C = 6
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, layout=oracle_mod.LAYOUT_PADDED, C=C)
+    recv = np.zeros((spec.E, C, spec.H), np.uint16)
+    oracle_mod.dispatch(w.x_bits, None, lay, recv)
+    out = wl.bf16_bits_to_f32(oracle_mod.combine(recv, w.topk_w, lay, spec.H))
+    x = wl.bf16_bits_to_f32(w.x_bits).astype(np.float64)
+    keep_w = np.where(lay.dst_row >= 0, w.topk_w, 0).astype(np.float64).sum(1)
+    want = x * keep_w[:, None]
+    assert np.all(np.abs(out - want) <= np.abs(want) * 2.0 ** -7 + 1e-30)
+    assert (lay.dst_row < 0).any()
+
+
+# --------------------------------------------------------------------------- once-per-rank path
+
+
+@pytest.mark.parametrize("mode", ["concat", "padded"])
+def test_dedup_equals_direct(oracle_mod, mode):
+    w = wl.make_workload("ll_decode", T=48, H=128)
+    spec = w.spec
+    topk = w.topk_idx.copy()
+    topk[3, 2] = -1
+    if mode == "padded":
+        C = 3
+        lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, layout=oracle_mod.LAYOUT_PADDED, C=C)
+        shape = (spec.E * C, spec.H)
+        n_slots = spec.R * spec.T
+    else:
+        lay = oracle_mod.layout(topk, E=spec.E, R=spec.R)
+        shape = (lay.expert_offset[-1], spec.H)
+        n_slots = lay.n_msgs
+    direct = np.full(shape, 0x1111, np.uint16)
+    dw = np.full(shape[0], np.float32(-1), np.float32)
+    ds = np.full(shape[0], -9, np.int32)
+    oracle_mod.dispatch(w.x_bits, w.topk_w, lay, direct, dw, ds)
+    win = oracle_mod.dedup_send(w.x_bits, topk, w.topk_w, lay, n_slots)
+    hdr = oracle_mod.msg_header_bytes(spec.K)
+    assert hdr == 80 and hdr % 16 == 0 and win.shape[1] == hdr + 2 * spec.H
+    # header fields and payload of every message; untouched slots keep their fill
+    used = np.zeros(n_slots, bool)
+    L = spec.L
+    for t in range(spec.T):
+        owners = []
+        for k in range(spec.K):
+            e = topk[t, k]
+            if e < 0 or (e // L) in owners:
+                assert lay.rank_row[t, k] == -1
+                continue
+            owners.append(e // L)
+            m = lay.rank_row[t, k]
+            used[m] = True
+            msg = win[m]
+            assert msg[:4].view(np.int32)[0] == t
+            assert np.array_equal(msg[4:4 + 4 * spec.K].view(np.int32), topk[t])
+            assert np.array_equal(msg[4 + 4 * spec.K:4 + 8 * spec.K].view(np.float32), w.topk_w[t])
+            assert np.all(msg[4 + 8 * spec.K:hdr] == 0)
+            assert np.array_equal(msg[hdr:].view(np.uint16), w.x_bits[t])
+    assert used.sum() == lay.n_msgs and np.all(win[~used] == 0xA5)
+    via = np.full(shape, 0x1111, np.uint16)
+    vw = np.full(shape[0], np.float32(-1), np.float32)
+    vs = np.full(shape[0], -9, np.int32)
+    cnt, dropped = oracle_mod.dedup_recv(win, lay, spec.H, via, vw, vs)
+    assert np.array_equal(via, direct) and np.array_equal(vw, dw) and np.array_equal(vs, ds)
+    assert np.array_equal(cnt, lay.expert_kept) and dropped == lay.dropped
+
+
+# --------------------------------------------------------------------------- paper constants
+
+
+def test_paper_constants(oracle_mod):
+    g = _golden("paper_constants.json")
+    assert wl.SPECS["ll_decode"].row_bytes == g["row_bytes_bf16"] == 2 * g["hidden"]
+    assert g["row_bytes_fp8"] == g["hidden"] and g["scale_floats"] * 4 == g["scale_bytes"]
+    assert g["hidden"] // 128 == g["scale_floats"]
+    b = g["ll_benchmark"]
+    s = wl.SPECS["ll_decode"]
+    assert (s.E, s.H, s.T, s.K) == (b["E"], b["H"], b["T"], b["K"])
+    f = g["footprint_example"]
+    for B, P in ((128, 14336), (1, 1), (77, 7168 + 224)):
+        ratio = Fraction(oracle_mod.footprint_per_expert(f["E"], B, P),
+                         oracle_mod.footprint_optimised(f["N"], B, f["K"], P))
+        assert ratio == Fraction(2 * f["E"], f["N"] + f["K"])
+    assert abs(float(ratio) - f["ratio_approx"]) < 0.5
+    assert Fraction(oracle_mod.footprint_per_expert(256, 128, 14336),
+                    oracle_mod.footprint_optimised(32, 128, 8, 14336)) == Fraction(512, 40)
