@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the dispatch/combine hot path on one MI355X.
+
+One step = ep_layout + ep_dispatch + ep_combine (+ handle destroy) over one batch
+of synthetic routing.  Inputs (tokens, top-k ids, gate weights, expert outputs)
+are resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload ht_prefill]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def _traffic(workload: str, kernel: str):
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary was committed."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(w, steps_budget_s: float = 12.0):
+    """The oracle, as it stands, on this host: same three calls, single thread."""
+    import numpy as np
+
+    import oracle
+    from paper_2603_13606_amd import workloads as wl
+
+    spec = w.spec
+    oracle.build()
+    lay = oracle.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=spec.T)
+    rows = int(lay.expert_offset[-1])
+    recv = np.zeros((rows, spec.H), np.uint16)
+    t_total, reps = 0.0, 0
+    while t_total < steps_budget_s and reps < 5:
+        t0 = time.perf_counter()
+        lay = oracle.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=spec.T)
+        oracle.dispatch(w.x_bits, w.topk_w, lay, recv)
+        oracle.combine(recv, w.topk_w, lay, spec.H, acc="f64")
+        t_total += time.perf_counter() - t0
+        reps += 1
+    ab = wl.algorithmic_bytes(spec, rows)
+    nbytes = ab["layout"] + ab["dispatch"] + ab["combine"]
+    return {
+        "value": round(nbytes * reps / t_total / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"{reps} full steps (layout+dispatch+combine, T={spec.T}) of the same workload, "
+                  f"{t_total / reps * 1e3:.0f} ms each, host has {os.cpu_count()} logical cores",
+        "ms_per_step": round(t_total / reps * 1e3, 2),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="ht_prefill")
+    ap.add_argument("--sets", type=int, default=3, help="input/window sets rotated between steps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one rank's share on ONE GPU; this build has no multi-GPU path "
+              "(run with --gpus 1).", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import ep_harness as hx
+    from paper_2603_13606_amd import binding as ep
+    from paper_2603_13606_amd import workloads as wl
+
+    ep.load()  # fails loudly if the HIP library was not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = wl.make_workload(args.workload)
+    spec = w.spec
+    T, K, H, E = spec.T, spec.K, spec.H, spec.E
+    cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, max_handles=2)
+    group = ep.ep_group_create(cfg)
+
+    nsets = max(1, args.sets)
+    sets = []
+    scale = wl.expert_scale_table(spec)
+    for s in range(nsets):
+        ws = w if s == 0 else wl.make_workload(args.workload, seed_offset=10 * s)
+        x = hx.bits_to_dev(ws.x_bits)
+        topk = torch.from_numpy(ws.topk_idx).to(hx.DEV)
+        gate = torch.from_numpy(ws.topk_w).to(hx.DEV)
+        recv = torch.zeros((T * K, H), dtype=torch.bfloat16, device=hx.DEV)
+        out = torch.zeros((T, H), dtype=torch.bfloat16, device=hx.DEV)
+        # expert outputs for combine: stand-in experts applied once to the dispatched rows
+        h = ep.ep_layout(group, topk)
+        ep.ep_dispatch(h, x, recv)
+        info = ep.ep_handle_query(h)
+        counts = ep.read_device_i32(info.expert_count, E).numpy()
+        row_e = torch.from_numpy(np.repeat(np.arange(E), counts)).to(hx.DEV)
+        y = torch.empty_like(recv)
+        step_rows = 8192
+        for r0 in range(0, T * K, step_rows):
+            y[r0:r0 + step_rows] = hx.expert_standin(recv[r0:r0 + step_rows], row_e[r0:r0 + step_rows], scale)
+        rows = int(info.rows_kept)
+        ep.ep_handle_destroy(h)
+        sets.append((x, topk, gate, recv, y, out, rows))
+    torch.cuda.synchronize()
+
+    def step(i, ev=None):
+        x, topk, gate, recv, y, out, _ = sets[i % nsets]
+        if ev:
+            ev[0].record()
+        h = ep.ep_layout(group, topk)
+        if ev:
+            ev[1].record()
+        ep.ep_dispatch(h, x, recv, topk_weights=gate)
+        if ev:
+            ev[2].record()
+        ep.ep_combine(h, y, out, topk_weights=gate)
+        if ev:
+            ev[3].record()
+        ep.ep_handle_destroy(h)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    lay_us = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e3
+    dis_us = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e3
+    com_us = np.array([e[2].elapsed_time(e[3]) for e in events]) * 1e3
+    rows = sets[0][6]
+    ab = wl.algorithmic_bytes(spec, rows)
+    step_bytes = ab["layout"] + ab["dispatch"] + ab["combine"]
+    value = step_bytes * args.steps / elapsed / 1e9
+    dom = "dispatch" if dis_us.mean() >= com_us.mean() else "combine"
+    dom_us = dis_us.mean() if dom == "dispatch" else com_us.mean()
+    kernel_name = {"dispatch": "dispatch_direct_kernel", "combine": "combine_kernel"}[dom]
+    achieved = ab[dom] / (dom_us * 1e-6) / 1e9
+
+    def stats(a):
+        return {"mean": round(float(a.mean()), 2), "p10": round(float(np.percentile(a, 10)), 2),
+                "p50": round(float(np.percentile(a, 50)), 2), "p90": round(float(np.percentile(a, 90)), 2)}
+
+    line = {
+        "metric": "dispatch+combine effective HBM GB/s (layout+dispatch+combine per step), 1 MI355X",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{spec.name}: R={spec.R} T={T} H={H} E={E} K={K} bf16, concatenated layout, "
+                               f"direct dispatch, gate logits N(0,1) prior={spec.prior}",
+                   "rows": rows, "input_sets_rotated": nsets},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "us": {"layout": stats(lay_us), "dispatch": stats(dis_us), "combine": stats(com_us),
+               "dispatch_plus_combine_mean": round(float(dis_us.mean() + com_us.mean()), 2)},
+        "gbps": {"dispatch": round(ab["dispatch"] / (dis_us.mean() * 1e-6) / 1e9, 1),
+                 "combine": round(ab["combine"] / (com_us.mean() * 1e-6) / 1e9, 1),
+                 "dispatch_plus_combine": round((ab["dispatch"] + ab["combine"]) /
+                                                ((dis_us.mean() + com_us.mean()) * 1e-6) / 1e9, 1)},
+        "algorithmic_bytes": ab,
+        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": _traffic(spec.name, kernel_name),
+                     "timing": "HIP events on the launch stream, mean over the timed steps"},
+    }
+    ep.ep_group_destroy(group)
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

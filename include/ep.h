@@ -1,0 +1,257 @@
+/*
+ * ep.h -- C ABI of the MI355X expert-parallel dispatch/combine library.
+ *
+ * One rank's share of MoE dispatch and combine, as the paper's C API states it
+ * (Sec. III-B, Table II: CreateGroup / CreateHandle / Dispatch / Combine /
+ * HandleGetNumRecvTokens and their Destroy calls), on one GPU: the receive
+ * windows of all R ranks are plain regions of this GPU's memory.
+ *
+ * Conventions (Sec. III-A): every function returns an ep_result_t and never
+ * throws; work is enqueued asynchronously on the stream passed in; resources are
+ * created and destroyed explicitly; the caller owns every tensor it passes
+ * ("pre-allocated receive buffers", Sec. III-B) and must keep it alive until the
+ * stream work that uses it has finished.  No entry point takes a PyTorch type.
+ *
+ * All `data` pointers in ep_tensor_t are DEVICE pointers (or pinned host memory
+ * mapped into the device address space) unless a comment says "host".
+ * Pointers to config / info / result structs are HOST pointers.
+ */
+#ifndef EP_MI355X_H
+#define EP_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EP_API __attribute__((visibility("default")))
+
+typedef struct ep_group_s *ep_group_t;   /* long-lived: configuration, buffers (Sec. III-C) */
+typedef struct ep_handle_s *ep_handle_t; /* one routing decision (Sec. III-C)               */
+typedef void *ep_stream_t;               /* a hipStream_t; NULL = the default stream         */
+
+typedef enum {
+    EP_SUCCESS = 0,
+    EP_ERR_INVALID_ARG = 1,     /* bad pointer, shape, stride, dtype, tag or config value      */
+    EP_ERR_INVALID_ROUTING = 2, /* reported by queries when expert ids outside [0,E) were seen */
+    EP_ERR_OVERFLOW = 3,        /* rows did not fit the output tensor given to dispatch        */
+    EP_ERR_UNSUPPORTED = 4,     /* e.g. send_only != 0, dtype other than bf16                  */
+    EP_ERR_BUSY = 5,            /* group destroyed while handles are alive                     */
+    EP_ERR_HIP = 6,             /* a HIP runtime call failed                                   */
+    EP_ERR_NOMEM = 7
+} ep_result_t;
+
+/* Algorithm mode, fixed at group creation (Sec. III-D).  It selects the output
+ * layout of dispatch (Sec. III-E "Tensor Layouts"):
+ *   EP_MODE_LL  3-D expert-major [E, C, H]: C slots per (expert, source rank)
+ *               sub-region; an entry whose slot would be >= C is dropped.
+ *   EP_MODE_HT  2-D concatenated [rows, H] with per-expert counts marking the
+ *               boundaries; rows of expert e start at expert_offset[e].           */
+enum { EP_MODE_LL = 0, EP_MODE_HT = 1 };
+
+/* How dispatch moves rows (Sec. IV-B send phase vs. Sec. IV-D layout optimisation):
+ *   EP_PATH_DIRECT      one row copy per (token, selected expert).
+ *   EP_PATH_RANK_DEDUP  a token is sent once per destination rank into that
+ *                       rank's staging window with its routing vector in the
+ *                       message header; the receiving side fans it out to the
+ *                       local experts.  Same final windows, bit for bit.          */
+enum { EP_PATH_DIRECT = 0, EP_PATH_RANK_DEDUP = 1 };
+
+enum { EP_DTYPE_BF16 = 0, EP_DTYPE_F32 = 1, EP_DTYPE_I32 = 2, EP_DTYPE_U8 = 3 };
+
+/* Tensor roles (Sec. III-E, Table IV).  SCALES is declared for completeness and
+ * rejected with EP_ERR_UNSUPPORTED.  The last three are this library's own. */
+enum {
+    EP_TAG_NONE = 0,
+    EP_TAG_TOKENS = 1,                     /* token data, input or output                 */
+    EP_TAG_TOPK_IDX = 2,                   /* int32 [T, K] expert ids, -1 = not routed    */
+    EP_TAG_TOPK_WEIGHTS = 3,               /* f32 [T, K] gate weights / f32 [rows] output */
+    EP_TAG_SCALES = 4,
+    EP_TAG_RECV_EXPERT_COUNTER_DEVICE = 5, /* int32 [E] rows placed per expert            */
+    EP_TAG_RECV_EXPERT_COUNTER_HOST = 6,   /* same, pinned host memory mapped to device   */
+    EP_TAG_TOKENS_PER_EXPERTS = 7,         /* same as RECV_EXPERT_COUNTER_DEVICE          */
+    EP_TAG_RECV_SRC_TOKEN = 8,             /* int32 [rows] source token index of each row */
+    EP_TAG_EXPERT_BASE = 9                 /* int32 [E], see ep_layout                    */
+};
+
+/* N-d tensor descriptor (Sec. III-E): shape and strides in ELEMENTS, innermost
+ * stride must be 1; rows of bf16 token tensors must start on 16-byte boundaries
+ * (data % 16 == 0 and every outer stride % 8 == 0). */
+typedef struct {
+    void *data;
+    int32_t ndim;
+    int32_t dtype;
+    int32_t tag;
+    int32_t reserved;
+    int64_t shape[4];
+    int64_t stride[4];
+} ep_tensor_t;
+
+/* Group configuration (Sec. III-C "MoE Group").  `size` must be sizeof(ep_group_config_t). */
+typedef struct {
+    uint32_t size;
+    int32_t num_ranks;           /* R >= 1                                                 */
+    int32_t my_rank;             /* in [0, R)                                              */
+    int32_t num_experts;         /* E, multiple of R, <= 1024; expert e lives on rank e/(E/R)
+                                    (block-wise placement, Sec. IV-A)                      */
+    int32_t hidden;              /* H, bf16 elements per token; 2H must be a multiple of 16 */
+    int32_t top_k;               /* K in [1, 64]                                           */
+    int32_t max_tokens_per_rank; /* B: upper bound on T of any ep_layout call              */
+    int32_t dtype;               /* EP_DTYPE_BF16                                          */
+    int32_t mode;                /* EP_MODE_LL / EP_MODE_HT                                */
+    int32_t slots_per_subregion; /* C for EP_MODE_LL; 0 = max_tokens_per_rank (Sec. IV-B:
+                                    each sub-region holds B slots)                         */
+    int32_t dispatch_path;       /* EP_PATH_DIRECT / EP_PATH_RANK_DEDUP                    */
+    int32_t max_handles;         /* handle slabs allocated up front; 0 = 2; more are
+                                    allocated on demand                                    */
+} ep_group_config_t;
+
+/* Allocator callbacks (Sec. III-C): when given, every device allocation of the
+ * group goes through them.  Return 0 on success. */
+typedef int (*ep_alloc_fn)(void **ptr, size_t bytes);
+typedef int (*ep_free_fn)(void *ptr);
+
+typedef struct {
+    int32_t num_ranks, my_rank, num_experts, experts_per_rank, hidden, top_k;
+    int32_t max_tokens_per_rank, mode, slots_per_subregion, dispatch_path;
+    int64_t row_bytes;            /* 2H                                                    */
+    int64_t msg_header_bytes;     /* staging message header: 4 + 8K rounded up to 16       */
+    int64_t msg_bytes;            /* header + 2H                                           */
+    int64_t staging_slots;        /* message slots in the staging windows (0 if DIRECT)    */
+    void *staging;                /* device pointer to the staging windows (borrowed)      */
+    /* Communication-buffer footprints of Sec. IV-D for this configuration, in bytes,
+     * with slot size P = 2H: per-expert sub-regions 2*E*B*P versus the optimised
+     * scheme R*B*P (dispatch) + B*K*P (combine). */
+    int64_t footprint_per_expert_bytes;
+    int64_t footprint_optimised_bytes;
+    int32_t live_handles;
+    int32_t reserved;
+} ep_group_info_t;
+
+/* Result of a layout, host-side copy of the totals plus borrowed DEVICE pointers
+ * to the arrays held by the handle (valid until ep_handle_destroy). */
+typedef struct {
+    int32_t num_tokens;      /* T of this layout                                           */
+    int32_t status;          /* bit 0: ids outside [0,E) seen; bit 1: entries dropped for
+                                capacity; bit 2: a dispatch found rows beyond its output   */
+    int64_t rows_kept;       /* routed entries that own a destination row                  */
+    int64_t rows_dropped;    /* entries cut by the LL capacity C                           */
+    int64_t entries_masked;  /* topk_idx == -1                                             */
+    int64_t entries_invalid; /* other ids outside [0, E)                                   */
+    int64_t entries_sorted;  /* rows_kept + rows_dropped                                   */
+    int64_t rank_messages;   /* (token, destination rank) pairs                            */
+    int64_t rows_end;        /* one past the highest destination row = expert_offset[E]    */
+    const int32_t *expert_count;     /* [E]   demand per expert                            */
+    const int32_t *expert_kept;      /* [E]   rows placed per expert                       */
+    const int32_t *expert_offset;    /* [E+1] first row of each expert                     */
+    const int32_t *rank_pair_count;  /* [R]   entries per destination rank                 */
+    const int32_t *rank_token_count; /* [R]   tokens per destination rank, each once       */
+    const int32_t *rank_offset;      /* [R+1] first staging slot of each destination rank  */
+    const int32_t *slot;             /* [T,K] index among entries naming the same expert   */
+    const int32_t *dst_row;          /* [T,K] destination row, -1 if none                  */
+    const int32_t *rank_row;         /* [T,K] staging slot for the first k naming a rank   */
+    const int32_t *sorted_token;     /* [entries_sorted] token of each entry in (expert,
+                                        slot) order                                        */
+    const int32_t *sorted_k;         /* [entries_sorted] its k                             */
+    const int32_t *sorted_row;       /* [entries_sorted] its destination row or -1         */
+} ep_layout_info_t;
+
+EP_API const char *ep_error_string(ep_result_t code);
+
+/* Library version, major*10000 + minor*100 + patch. */
+EP_API int32_t ep_version(void);
+
+/*
+ * ep_group_create -- Table II "ncclEpCreateGroup" without the communicator.
+ * Validates cfg, computes the window geometry and allocates (through alloc_fn or
+ * hipMalloc) the handle slabs and, for EP_PATH_RANK_DEDUP, the staging windows:
+ * R*B message slots in LL mode, B*min(R,K) in HT mode.  Host-synchronous; may be
+ * called on any thread with the target device current.
+ * Errors: EP_ERR_INVALID_ARG (NULL pointers, size mismatch, E % R != 0, 2H % 16
+ * != 0, limits exceeded), EP_ERR_UNSUPPORTED (dtype), EP_ERR_NOMEM, EP_ERR_HIP.
+ */
+EP_API ep_result_t ep_group_create(ep_group_t *group, const ep_group_config_t *cfg, ep_stream_t stream,
+                            ep_alloc_fn alloc_fn, ep_free_fn free_fn);
+
+/* Table II "ncclEpGroupDestroy".  Fails with EP_ERR_BUSY while handles are alive.
+ * Synchronises `stream` before freeing. */
+EP_API ep_result_t ep_group_destroy(ep_group_t group, ep_stream_t stream);
+
+/* Geometry and footprints of a group (host struct filled synchronously). */
+EP_API ep_result_t ep_group_query(ep_group_t group, ep_group_info_t *info);
+
+/*
+ * ep_layout -- Table II "ncclEpCreateHandle": captures one routing decision.
+ * topk_idx: int32 [T, K], tag EP_TAG_TOPK_IDX, T <= max_tokens_per_rank, entries in
+ * [0, E) or -1.  Runs on `stream`: per-expert and per-destination-rank counts,
+ * prefix offsets, and the stable slot map -- slot(t,k) = number of entries before
+ * (t,k) in flattened t*K+k order that name the same expert, i.e. the "next unused
+ * index" of Sec. IV-B made deterministic: (source rank, token index) order.
+ * expert_base (optional, may be NULL): int32 [E] device array, HT mode only; row
+ * at which this source's rows of expert e start in the receiver's tensor (what the
+ * handle-time metadata exchange of Sec. III-C would deliver).  NULL = exclusive
+ * prefix sum of this source's own counts.
+ * The handle is read-only afterwards and may serve any number of dispatch/combine
+ * calls (forward and backward reuse, Sec. III-C).  Takes a slab from the group's
+ * pool; allocates only if the pool is exhausted.
+ * Errors: EP_ERR_INVALID_ARG, EP_ERR_NOMEM, EP_ERR_HIP.  Bad expert ids are found
+ * on the device and reported by ep_handle_query.
+ */
+EP_API ep_result_t ep_layout(ep_handle_t *handle, ep_group_t group, const ep_tensor_t *topk_idx,
+                      const ep_tensor_t *expert_base, ep_stream_t stream);
+
+/* Synchronises the handle's last stream and fills `info`.  Returns
+ * EP_ERR_INVALID_ROUTING if bad expert ids were seen and EP_ERR_OVERFLOW if a
+ * dispatch ran out of output rows (info is filled in both cases); capacity drops
+ * in LL mode are reported in info->status / rows_dropped only. */
+EP_API ep_result_t ep_handle_query(ep_handle_t handle, ep_layout_info_t *info);
+
+/* Table II "ncclEpHandleGetNumRecvTokens": rows this source places in the
+ * receivers' tensors (rows_kept).  Synchronises like ep_handle_query. */
+EP_API ep_result_t ep_handle_get_num_recv_tokens(ep_handle_t handle, int64_t *num);
+
+/* Table II "ncclEpHandleDestroy".  The caller guarantees that stream work using
+ * the handle has completed (the slab returns to the group's pool at once). */
+EP_API ep_result_t ep_handle_destroy(ep_handle_t handle);
+
+/*
+ * ep_dispatch -- Table II "ncclEpDispatch" (Sec. III-B; data movement of Sec. IV-B/C,
+ * or Sec. IV-D when the group was created with EP_PATH_RANK_DEDUP).
+ * inputs (by tag):  TOKENS x [T, H] bf16 (required);
+ *                   TOPK_WEIGHTS w [T, K] f32 (optional, forwarded per row).
+ * outputs (by tag): TOKENS (required) -- HT: [rows_cap, H]; LL: [E, C, H], possibly a
+ *                     strided view of a larger receiver tensor [E, R*C, H];
+ *                   TOPK_WEIGHTS recv_w [rows_cap] f32 (optional; LL: [E*C]);
+ *                   RECV_SRC_TOKEN recv_src [rows_cap] int32 (optional);
+ *                   RECV_EXPERT_COUNTER_DEVICE / _HOST / TOKENS_PER_EXPERTS [E] int32
+ *                     (optional): rows placed per expert.
+ * For every (t,k) with dst_row >= 0: recv_x[dst_row] = x[t] (byte copy),
+ * recv_w[dst_row] = w[t,k], recv_src[dst_row] = t.  Rows not named by the layout are
+ * left untouched.  A row index >= rows_cap is skipped and flagged (status bit 2).
+ * send_only must be 0 (staged execution is not built): EP_ERR_UNSUPPORTED.
+ */
+EP_API ep_result_t ep_dispatch(ep_handle_t handle, const ep_tensor_t *inputs, int32_t num_inputs,
+                        const ep_tensor_t *outputs, int32_t num_outputs, int32_t send_only,
+                        ep_stream_t stream);
+
+/*
+ * ep_combine -- Table II "ncclEpCombine" (Sec. III-B; reduction of Sec. IV-B/C
+ * "Combine/recv", addressing of Sec. IV-D).
+ * inputs:  TOKENS y with exactly the shape rules of dispatch's TOKENS output
+ *          (Sec. III-E: combine input = dispatch output); TOPK_WEIGHTS w [T, K] f32
+ *          (optional; absent = plain sum).
+ * outputs: TOKENS out [T, H] bf16.
+ * out[t,h] = bf16_rne( sum over k = 0..K-1 in that order of w[t,k] * f32(y[dst_row[t,k], h]) )
+ * with float32 multiply and float32 add, each rounded to nearest even; entries
+ * without a destination row contribute nothing.
+ */
+EP_API ep_result_t ep_combine(ep_handle_t handle, const ep_tensor_t *inputs, int32_t num_inputs,
+                       const ep_tensor_t *outputs, int32_t num_outputs, int32_t send_only,
+                       ep_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EP_MI355X_H */

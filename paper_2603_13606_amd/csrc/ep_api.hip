@@ -1,0 +1,444 @@
+// C-ABI entry points: group / handle lifetime, argument validation, and the
+// translation of tensor descriptors into kernel arguments (Sec. III-A..E).
+// Host code only; every step of the data path runs in the kernels of
+// ep_layout.hip, ep_dispatch.hip, ep_dedup.hip and ep_combine.hip.
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "ep_internal.h"
+
+using namespace ep;
+
+namespace {
+
+constexpr int kSlabAlign = 64;  // ints; every device array starts on a 256-byte boundary
+
+struct Slab {
+    int32_t* base = nullptr;
+    // carved arrays
+    int32_t *totals, *expert_count, *expert_kept, *expert_offset, *own_prefix;
+    int32_t *rank_pair_count, *rank_token_count, *rank_offset, *coltotal, *hist;
+    int32_t *slot, *dst_row, *rank_row, *sorted_token, *sorted_k, *sorted_row;
+};
+
+}  // namespace
+
+struct ep_group_s {
+    ep_group_config_t cfg;
+    int L, L_shift, W, bits_e, bits_r;
+    int C;       // slots per sub-region (LL)
+    int64_t slab_ints;
+    ep_alloc_fn alloc_fn;
+    ep_free_fn free_fn;
+    std::mutex mu;
+    std::vector<Slab> free_slabs;
+    int live_handles = 0;
+    int device = 0;
+    // staging windows of the once-per-rank path
+    uint8_t* staging = nullptr;
+    int64_t staging_slots = 0;
+    int64_t hdr_bytes = 0, msg_bytes = 0;
+};
+
+struct ep_handle_s {
+    ep_group_s* group;
+    Slab slab;
+    int T;
+    hipStream_t last_stream;
+};
+
+namespace {
+
+int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+int bits_for(int n) {  // bits needed to write any value in [0, n)
+    int b = 0;
+    while ((1 << b) < n) ++b;
+    return b;
+}
+
+ep_result_t dev_alloc(ep_group_s* g, void** p, size_t bytes) {
+    if (g->alloc_fn) return g->alloc_fn(p, bytes) == 0 && *p ? EP_SUCCESS : EP_ERR_NOMEM;
+    hipError_t e = hipMalloc(p, bytes);
+    if (e == hipErrorOutOfMemory) return EP_ERR_NOMEM;
+    return e == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+}
+
+void dev_free(ep_group_s* g, void* p) {
+    if (!p) return;
+    if (g->free_fn) g->free_fn(p);
+    else (void)hipFree(p);
+}
+
+int64_t carve(int64_t* cursor, int64_t ints) {
+    const int64_t at = *cursor;
+    *cursor = round_up(at + ints, kSlabAlign);
+    return at;
+}
+
+// Lays the handle arrays out inside one allocation; with base == nullptr only the size is computed.
+int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
+    const int E = g->cfg.num_experts, R = g->cfg.num_ranks;
+    const int64_t nB = (int64_t)g->cfg.max_tokens_per_rank * g->cfg.top_k;
+    int64_t cur = 0;
+    const int64_t o_tot = carve(&cur, kTotalsWords), o_ec = carve(&cur, E), o_ek = carve(&cur, E);
+    const int64_t o_eo = carve(&cur, E + 1), o_op = carve(&cur, E + 1), o_rp = carve(&cur, R);
+    const int64_t o_rt = carve(&cur, R), o_ro = carve(&cur, R + 1), o_ct = carve(&cur, g->W);
+    const int64_t o_h = carve(&cur, (int64_t)kMaxWaveChunks * g->W);
+    const int64_t o_sl = carve(&cur, nB), o_dr = carve(&cur, nB), o_rr = carve(&cur, nB);
+    const int64_t o_st = carve(&cur, nB), o_sk = carve(&cur, nB), o_sr = carve(&cur, nB);
+    if (base && s) {
+        s->base = base;
+        s->totals = base + o_tot; s->expert_count = base + o_ec; s->expert_kept = base + o_ek;
+        s->expert_offset = base + o_eo; s->own_prefix = base + o_op; s->rank_pair_count = base + o_rp;
+        s->rank_token_count = base + o_rt; s->rank_offset = base + o_ro; s->coltotal = base + o_ct;
+        s->hist = base + o_h; s->slot = base + o_sl; s->dst_row = base + o_dr; s->rank_row = base + o_rr;
+        s->sorted_token = base + o_st; s->sorted_k = base + o_sk; s->sorted_row = base + o_sr;
+    }
+    return cur;
+}
+
+ep_result_t new_slab(ep_group_s* g, Slab* s) {
+    void* p = nullptr;
+    ep_result_t r = dev_alloc(g, &p, sizeof(int32_t) * (size_t)g->slab_ints);
+    if (r != EP_SUCCESS) return r;
+    carve_slab(g, s, (int32_t*)p);
+    return EP_SUCCESS;
+}
+
+const ep_tensor_t* find_tag(const ep_tensor_t* ts, int n, int tag, int tag2 = -1, int tag3 = -1) {
+    for (int i = 0; i < n; ++i)
+        if (ts[i].tag == tag || ts[i].tag == tag2 || ts[i].tag == tag3) return &ts[i];
+    return nullptr;
+}
+
+bool has_unsupported(const ep_tensor_t* ts, int n) {
+    for (int i = 0; i < n; ++i)
+        if (ts[i].tag == EP_TAG_SCALES) return true;
+    return false;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// 2-D [rows, cols] tensor of `dtype`, innermost stride 1.
+bool check_2d(const ep_tensor_t* t, int dtype, int64_t rows, int64_t cols, bool rows_exact) {
+    if (!t || t->ndim != 2 || t->dtype != dtype) return false;
+    if (t->shape[1] != cols || t->stride[1] != 1 || t->stride[0] < cols) return false;
+    if (rows_exact ? t->shape[0] != rows : t->shape[0] < rows) return false;
+    if (t->shape[0] > 0 && !t->data) return false;
+    return true;
+}
+
+bool check_1d(const ep_tensor_t* t, int dtype, int64_t n) {
+    if (!t || t->ndim != 1 || t->dtype != dtype || t->shape[0] < n || t->stride[0] != 1) return false;
+    return t->data != nullptr || t->shape[0] == 0;
+}
+
+// Token windows: HT [rows_cap, H]; LL [E, C, H].  Fills a WindowDesc.
+bool window_from_tensor(const ep_group_s* g, const ep_tensor_t* t, WindowDesc* w) {
+    const int H = g->cfg.hidden;
+    if (!t || t->dtype != EP_DTYPE_BF16 || !aligned16(t->data)) return false;
+    if (g->cfg.mode == EP_MODE_LL) {
+        if (t->ndim != 3 || t->shape[0] != g->cfg.num_experts || t->shape[1] != g->C || t->shape[2] != H)
+            return false;
+        if (t->stride[2] != 1 || t->stride[1] < H || t->stride[1] % 8 || t->stride[0] % 8) return false;
+        if (t->stride[0] < 0) return false;
+        if (!t->data) return false;
+        w->stride0 = t->stride[0];
+        w->stride1 = t->stride[1];
+        w->rows_cap = (int64_t)g->cfg.num_experts * g->C;
+        w->padded = 1;
+        w->C = g->C;
+    } else {
+        if (t->ndim != 2 || t->shape[1] != H || t->stride[1] != 1 || t->stride[0] < H || t->stride[0] % 8)
+            return false;
+        if (t->shape[0] < 0 || t->shape[0] > 0x7fffffffLL) return false;
+        if (t->shape[0] > 0 && !t->data) return false;
+        w->stride0 = t->stride[0];
+        w->stride1 = 0;
+        w->rows_cap = t->shape[0];
+        w->padded = 0;
+        w->C = 1;
+    }
+    w->base = (uint16_t*)t->data;
+    return true;
+}
+
+ep_result_t sync_and_read_totals(ep_handle_s* h, int32_t* tot) {
+    if (hipStreamSynchronize(h->last_stream) != hipSuccess) return EP_ERR_HIP;
+    if (hipMemcpy(tot, h->slab.totals, sizeof(int32_t) * kTotalsWords, hipMemcpyDeviceToHost) != hipSuccess)
+        return EP_ERR_HIP;
+    return EP_SUCCESS;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ep_error_string(ep_result_t code) {
+    switch (code) {
+        case EP_SUCCESS: return "success";
+        case EP_ERR_INVALID_ARG: return "invalid argument";
+        case EP_ERR_INVALID_ROUTING: return "expert ids outside [0, num_experts) in topk_idx";
+        case EP_ERR_OVERFLOW: return "destination rows beyond the output tensor";
+        case EP_ERR_UNSUPPORTED: return "unsupported feature";
+        case EP_ERR_BUSY: return "group still has live handles";
+        case EP_ERR_HIP: return "HIP runtime error";
+        case EP_ERR_NOMEM: return "out of device memory";
+    }
+    return "unknown error code";
+}
+
+int32_t ep_version(void) { return 100; }
+
+ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_stream_t stream,
+                            ep_alloc_fn alloc_fn, ep_free_fn free_fn) {
+    (void)stream;
+    if (!group || !cfg || cfg->size != sizeof(ep_group_config_t)) return EP_ERR_INVALID_ARG;
+    if ((alloc_fn == nullptr) != (free_fn == nullptr)) return EP_ERR_INVALID_ARG;
+    const int R = cfg->num_ranks, E = cfg->num_experts, H = cfg->hidden, K = cfg->top_k;
+    if (R < 1 || cfg->my_rank < 0 || cfg->my_rank >= R) return EP_ERR_INVALID_ARG;
+    if (E < 1 || E > kMaxExperts || E % R != 0) return EP_ERR_INVALID_ARG;
+    if (H < 8 || (2 * (int64_t)H) % 16 != 0) return EP_ERR_INVALID_ARG;
+    if (K < 1 || K > kMaxTopK) return EP_ERR_INVALID_ARG;
+    if (cfg->max_tokens_per_rank < 1 || (int64_t)cfg->max_tokens_per_rank * K > (1 << 28)) return EP_ERR_INVALID_ARG;
+    if (cfg->dtype != EP_DTYPE_BF16) return EP_ERR_UNSUPPORTED;
+    if (cfg->mode != EP_MODE_LL && cfg->mode != EP_MODE_HT) return EP_ERR_INVALID_ARG;
+    if (cfg->dispatch_path != EP_PATH_DIRECT && cfg->dispatch_path != EP_PATH_RANK_DEDUP) return EP_ERR_INVALID_ARG;
+    if (cfg->slots_per_subregion < 0 || cfg->max_handles < 0) return EP_ERR_INVALID_ARG;
+    const int C = cfg->slots_per_subregion ? cfg->slots_per_subregion : cfg->max_tokens_per_rank;
+    if (cfg->mode == EP_MODE_LL && (int64_t)E * C > 0x7fffffffLL) return EP_ERR_INVALID_ARG;
+    if (cfg->dispatch_path == EP_PATH_RANK_DEDUP) return EP_ERR_UNSUPPORTED;
+
+    ep_group_s* g = new (std::nothrow) ep_group_s();
+    if (!g) return EP_ERR_NOMEM;
+    g->cfg = *cfg;
+    g->C = C;
+    g->L = E / R;
+    g->L_shift = -1;
+    for (int b = 0; b < 31; ++b)
+        if ((1 << b) == g->L) g->L_shift = b;
+    g->W = E + 2 + R;
+    g->bits_e = bits_for(E);
+    g->bits_r = bits_for(R);
+    g->alloc_fn = alloc_fn;
+    g->free_fn = free_fn;
+    g->slab_ints = carve_slab(g, nullptr, nullptr);
+    g->hdr_bytes = round_up(4 + 8 * (int64_t)K, 16);
+    g->msg_bytes = g->hdr_bytes + 2 * (int64_t)H;
+    if (hipGetDevice(&g->device) != hipSuccess) { delete g; return EP_ERR_HIP; }
+    const int nslabs = cfg->max_handles ? cfg->max_handles : 2;
+    for (int i = 0; i < nslabs; ++i) {
+        Slab s;
+        ep_result_t r = new_slab(g, &s);
+        if (r != EP_SUCCESS) {
+            for (auto& f : g->free_slabs) dev_free(g, f.base);
+            delete g;
+            return r;
+        }
+        g->free_slabs.push_back(s);
+    }
+    *group = g;
+    return EP_SUCCESS;
+}
+
+ep_result_t ep_group_destroy(ep_group_t g, ep_stream_t stream) {
+    if (!g) return EP_ERR_INVALID_ARG;
+    {
+        std::lock_guard<std::mutex> lk(g->mu);
+        if (g->live_handles > 0) return EP_ERR_BUSY;
+    }
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
+    for (auto& s : g->free_slabs) dev_free(g, s.base);
+    dev_free(g, g->staging);
+    delete g;
+    return EP_SUCCESS;
+}
+
+ep_result_t ep_group_query(ep_group_t g, ep_group_info_t* info) {
+    if (!g || !info) return EP_ERR_INVALID_ARG;
+    const ep_group_config_t& c = g->cfg;
+    info->num_ranks = c.num_ranks; info->my_rank = c.my_rank; info->num_experts = c.num_experts;
+    info->experts_per_rank = g->L; info->hidden = c.hidden; info->top_k = c.top_k;
+    info->max_tokens_per_rank = c.max_tokens_per_rank; info->mode = c.mode;
+    info->slots_per_subregion = g->C; info->dispatch_path = c.dispatch_path;
+    info->row_bytes = 2 * (int64_t)c.hidden;
+    info->msg_header_bytes = g->hdr_bytes;
+    info->msg_bytes = g->msg_bytes;
+    info->staging_slots = g->staging_slots;
+    info->staging = g->staging;
+    const int64_t B = c.max_tokens_per_rank, P = info->row_bytes;
+    info->footprint_per_expert_bytes = 2 * (int64_t)c.num_experts * B * P;
+    info->footprint_optimised_bytes = (int64_t)c.num_ranks * B * P + B * c.top_k * P;
+    {
+        std::lock_guard<std::mutex> lk(g->mu);
+        info->live_handles = g->live_handles;
+    }
+    info->reserved = 0;
+    return EP_SUCCESS;
+}
+
+ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk_idx,
+                      const ep_tensor_t* expert_base, ep_stream_t stream) {
+    if (!handle || !g || !topk_idx) return EP_ERR_INVALID_ARG;
+    const ep_group_config_t& c = g->cfg;
+    if (topk_idx->tag != EP_TAG_TOPK_IDX || topk_idx->ndim != 2 || topk_idx->dtype != EP_DTYPE_I32)
+        return EP_ERR_INVALID_ARG;
+    const int64_t T = topk_idx->shape[0];
+    if (T < 0 || T > c.max_tokens_per_rank) return EP_ERR_INVALID_ARG;
+    if (!check_2d(topk_idx, EP_DTYPE_I32, T, c.top_k, true)) return EP_ERR_INVALID_ARG;
+    if (expert_base) {
+        if (c.mode != EP_MODE_HT) return EP_ERR_INVALID_ARG;
+        if (expert_base->tag != EP_TAG_EXPERT_BASE || !check_1d(expert_base, EP_DTYPE_I32, c.num_experts) ||
+            !expert_base->data)
+            return EP_ERR_INVALID_ARG;
+    }
+    ep_handle_s* h = new (std::nothrow) ep_handle_s();
+    if (!h) return EP_ERR_NOMEM;
+    {
+        std::lock_guard<std::mutex> lk(g->mu);
+        if (!g->free_slabs.empty()) {
+            h->slab = g->free_slabs.back();
+            g->free_slabs.pop_back();
+        } else {
+            ep_result_t r = new_slab(g, &h->slab);
+            if (r != EP_SUCCESS) { delete h; return r; }
+        }
+        g->live_handles += 1;
+    }
+    h->group = g;
+    h->T = (int)T;
+    h->last_stream = (hipStream_t)stream;
+
+    LayoutArgs a;
+    a.topk = (const int32_t*)topk_idx->data;
+    a.topk_stride = topk_idx->stride[0];
+    a.expert_base = expert_base ? (const int32_t*)expert_base->data : nullptr;
+    a.T = (int)T; a.K = c.top_k; a.E = c.num_experts; a.R = c.num_ranks; a.L = g->L; a.L_shift = g->L_shift;
+    a.padded = c.mode == EP_MODE_LL; a.C = g->C; a.C_rank = c.max_tokens_per_rank;
+    a.n = (int)(T * c.top_k);
+    plan_layout(a.n, &a.passes, &a.nwc);
+    a.W = g->W; a.bits_e = g->bits_e; a.bits_r = g->bits_r;
+    const Slab& s = h->slab;
+    a.hist = s.hist; a.coltotal = s.coltotal; a.expert_count = s.expert_count; a.expert_kept = s.expert_kept;
+    a.expert_offset = s.expert_offset; a.own_prefix = s.own_prefix; a.rank_pair_count = s.rank_pair_count;
+    a.rank_token_count = s.rank_token_count; a.rank_offset = s.rank_offset; a.totals = s.totals;
+    a.slot = s.slot; a.dst_row = s.dst_row; a.rank_row = s.rank_row; a.sorted_token = s.sorted_token;
+    a.sorted_k = s.sorted_k; a.sorted_row = s.sorted_row;
+    if (launch_layout(a, (hipStream_t)stream) != hipSuccess) {
+        ep_handle_destroy(h);
+        return EP_ERR_HIP;
+    }
+    *handle = h;
+    return EP_SUCCESS;
+}
+
+ep_result_t ep_handle_query(ep_handle_t h, ep_layout_info_t* info) {
+    if (!h || !info) return EP_ERR_INVALID_ARG;
+    int32_t tot[kTotalsWords];
+    ep_result_t r = sync_and_read_totals(h, tot);
+    if (r != EP_SUCCESS) return r;
+    const Slab& s = h->slab;
+    info->num_tokens = h->T;
+    info->status = tot[TOT_STATUS];
+    info->rows_kept = tot[TOT_KEPT]; info->rows_dropped = tot[TOT_DROPPED];
+    info->entries_masked = tot[TOT_MASKED]; info->entries_invalid = tot[TOT_INVALID];
+    info->entries_sorted = tot[TOT_SORTED]; info->rank_messages = tot[TOT_MSGS];
+    info->rows_end = tot[TOT_ROWS_END];
+    info->expert_count = s.expert_count; info->expert_kept = s.expert_kept;
+    info->expert_offset = s.expert_offset; info->rank_pair_count = s.rank_pair_count;
+    info->rank_token_count = s.rank_token_count; info->rank_offset = s.rank_offset;
+    info->slot = s.slot; info->dst_row = s.dst_row; info->rank_row = s.rank_row;
+    info->sorted_token = s.sorted_token; info->sorted_k = s.sorted_k; info->sorted_row = s.sorted_row;
+    if (tot[TOT_STATUS] & STATUS_INVALID_IDS) return EP_ERR_INVALID_ROUTING;
+    if (tot[TOT_STATUS] & STATUS_OUTPUT_OVERFLOW) return EP_ERR_OVERFLOW;
+    return EP_SUCCESS;
+}
+
+ep_result_t ep_handle_get_num_recv_tokens(ep_handle_t h, int64_t* num) {
+    if (!h || !num) return EP_ERR_INVALID_ARG;
+    int32_t tot[kTotalsWords];
+    ep_result_t r = sync_and_read_totals(h, tot);
+    if (r != EP_SUCCESS) return r;
+    *num = tot[TOT_KEPT];
+    return EP_SUCCESS;
+}
+
+ep_result_t ep_handle_destroy(ep_handle_t h) {
+    if (!h) return EP_ERR_INVALID_ARG;
+    ep_group_s* g = h->group;
+    {
+        std::lock_guard<std::mutex> lk(g->mu);
+        g->free_slabs.push_back(h->slab);
+        g->live_handles -= 1;
+    }
+    delete h;
+    return EP_SUCCESS;
+}
+
+ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inputs,
+                        const ep_tensor_t* outputs, int32_t num_outputs, int32_t send_only,
+                        ep_stream_t stream) {
+    if (!h || !inputs || !outputs || num_inputs < 1 || num_outputs < 1) return EP_ERR_INVALID_ARG;
+    if (send_only != 0) return EP_ERR_UNSUPPORTED;
+    if (has_unsupported(inputs, num_inputs) || has_unsupported(outputs, num_outputs)) return EP_ERR_UNSUPPORTED;
+    ep_group_s* g = h->group;
+    const ep_group_config_t& c = g->cfg;
+    const ep_tensor_t* x = find_tag(inputs, num_inputs, EP_TAG_TOKENS);
+    const ep_tensor_t* w = find_tag(inputs, num_inputs, EP_TAG_TOPK_WEIGHTS);
+    const ep_tensor_t* rx = find_tag(outputs, num_outputs, EP_TAG_TOKENS);
+    const ep_tensor_t* rw = find_tag(outputs, num_outputs, EP_TAG_TOPK_WEIGHTS);
+    const ep_tensor_t* rs = find_tag(outputs, num_outputs, EP_TAG_RECV_SRC_TOKEN);
+    const ep_tensor_t* rc = find_tag(outputs, num_outputs, EP_TAG_RECV_EXPERT_COUNTER_DEVICE,
+                                     EP_TAG_RECV_EXPERT_COUNTER_HOST, EP_TAG_TOKENS_PER_EXPERTS);
+    if (!check_2d(x, EP_DTYPE_BF16, h->T, c.hidden, true) || x->stride[0] % 8 || !aligned16(x->data))
+        return EP_ERR_INVALID_ARG;
+    if (w && !check_2d(w, EP_DTYPE_F32, h->T, c.top_k, true)) return EP_ERR_INVALID_ARG;
+    DispatchArgs a;
+    if (!window_from_tensor(g, rx, &a.win)) return EP_ERR_INVALID_ARG;
+    if (rw && !check_1d(rw, EP_DTYPE_F32, a.win.rows_cap)) return EP_ERR_INVALID_ARG;
+    if (rs && !check_1d(rs, EP_DTYPE_I32, a.win.rows_cap)) return EP_ERR_INVALID_ARG;
+    if (rc && !check_1d(rc, EP_DTYPE_I32, c.num_experts)) return EP_ERR_INVALID_ARG;
+    a.x = (const uint16_t*)x->data;
+    a.x_stride = x->stride[0];
+    a.w = w ? (const float*)w->data : nullptr;
+    a.w_stride = w ? w->stride[0] : 0;
+    a.dst_row = h->slab.dst_row;
+    a.recv_w = rw ? (float*)rw->data : nullptr;
+    a.recv_src = rs ? (int32_t*)rs->data : nullptr;
+    a.recv_count = rc ? (int32_t*)rc->data : nullptr;
+    a.expert_kept = h->slab.expert_kept;
+    a.totals = h->slab.totals;
+    a.T = h->T; a.K = c.top_k; a.H = c.hidden; a.E = c.num_experts;
+    h->last_stream = (hipStream_t)stream;
+    return launch_dispatch(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+}
+
+ep_result_t ep_combine(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inputs,
+                       const ep_tensor_t* outputs, int32_t num_outputs, int32_t send_only,
+                       ep_stream_t stream) {
+    if (!h || !inputs || !outputs || num_inputs < 1 || num_outputs < 1) return EP_ERR_INVALID_ARG;
+    if (send_only != 0) return EP_ERR_UNSUPPORTED;
+    if (has_unsupported(inputs, num_inputs) || has_unsupported(outputs, num_outputs)) return EP_ERR_UNSUPPORTED;
+    ep_group_s* g = h->group;
+    const ep_group_config_t& c = g->cfg;
+    const ep_tensor_t* y = find_tag(inputs, num_inputs, EP_TAG_TOKENS);
+    const ep_tensor_t* w = find_tag(inputs, num_inputs, EP_TAG_TOPK_WEIGHTS);
+    const ep_tensor_t* out = find_tag(outputs, num_outputs, EP_TAG_TOKENS);
+    CombineArgs a;
+    if (!window_from_tensor(g, y, &a.win)) return EP_ERR_INVALID_ARG;
+    if (w && !check_2d(w, EP_DTYPE_F32, h->T, c.top_k, true)) return EP_ERR_INVALID_ARG;
+    if (!check_2d(out, EP_DTYPE_BF16, h->T, c.hidden, true) || out->stride[0] % 8 || !aligned16(out->data))
+        return EP_ERR_INVALID_ARG;
+    a.w = w ? (const float*)w->data : nullptr;
+    a.w_stride = w ? w->stride[0] : 0;
+    a.dst_row = h->slab.dst_row;
+    a.out = (uint16_t*)out->data;
+    a.out_stride = out->stride[0];
+    a.T = h->T; a.K = c.top_k; a.H = c.hidden;
+    h->last_stream = (hipStream_t)stream;
+    return launch_combine(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,108 @@
+// Combine: gather the K expert outputs of every token and reduce them with the
+// gate weights (Sec. II-B "Combine"; Sec. IV-B receive phase; Sec. IV-C
+// "Combine/recv"; the (t, k)-indexed addressing of Sec. IV-D).
+//
+//   out[t, h] = bf16_rne( sum_{k = 0..K-1, in order} w[t,k] * f32(y[dst_row[t,k], h]) )
+//
+// float32 multiply and float32 add are separate, each rounded to nearest even
+// (no fused multiply-add), so the result does not depend on the launch shape.
+// Bound by HBM: K rows read, one row written per token.  Work unit = one
+// wavefront reducing one 1 KiB segment of one token: every lane issues up to 8
+// independent 16-byte loads before it starts to accumulate.
+#include "ep_internal.h"
+
+namespace ep {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int KB = 8;  // rows gathered per batch of loads
+
+__device__ __forceinline__ int64_t window_offset(const WindowDesc& w, int row) {
+    if (w.padded) {
+        const int e = row / w.C;
+        const int s = row - e * w.C;
+        return (int64_t)e * w.stride0 + (int64_t)s * w.stride1;
+    }
+    return (int64_t)row * w.stride0;
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t p) { return __uint_as_float(p << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
+
+// float32 -> bfloat16 bits, round to nearest even; every NaN becomes 0x7FC0.
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ void accumulate(float (&acc)[8], const u32x4& v, float w) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        acc[2 * c] = __fadd_rn(acc[2 * c], __fmul_rn(w, bf16_lo(v[c])));
+        acc[2 * c + 1] = __fadd_rn(acc[2 * c + 1], __fmul_rn(w, bf16_hi(v[c])));
+    }
+}
+
+__global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nseg, int units) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t u = (int64_t)blockIdx.x * 4 + wave;
+    if (u >= (int64_t)a.T * nseg) return;
+    const int t = (int)(u / nseg);
+    const int seg = (int)(u - (int64_t)t * nseg);
+    const int unit = seg * kWave + lane;
+    const bool active = unit < units;
+    const int32_t* rows = a.dst_row + (int64_t)t * a.K;
+    const float* wt = a.w ? a.w + (int64_t)t * a.w_stride : nullptr;
+    float acc[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[c] = 0.0f;
+    for (int k0 = 0; k0 < a.K; k0 += KB) {
+        u32x4 v[KB];
+        int row[KB];
+        float wk[KB];
+#pragma unroll
+        for (int j = 0; j < KB; ++j) {
+            const int k = k0 + j;
+            int r = -1;
+            float w = 1.0f;
+            if (k < a.K) {
+                r = __builtin_amdgcn_readfirstlane(rows[k]);
+                if (wt) w = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(wt[k])));
+            }
+            if (r >= a.win.rows_cap) r = -1;
+            row[j] = r;
+            wk[j] = w;
+            v[j] = (u32x4){0u, 0u, 0u, 0u};
+            if (r >= 0 && active)
+                v[j] = __builtin_nontemporal_load((const u32x4*)(a.win.base + window_offset(a.win, r)) + unit);
+        }
+#pragma unroll
+        for (int j = 0; j < KB; ++j)
+            if (row[j] >= 0) accumulate(acc, v[j], wk[j]);
+    }
+    if (active) {
+        u32x4 o;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) o[c] = f32_to_bf16(acc[2 * c]) | (f32_to_bf16(acc[2 * c + 1]) << 16);
+        __builtin_nontemporal_store(o, (u32x4*)(a.out + (int64_t)t * a.out_stride) + unit);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_combine(const CombineArgs& a, hipStream_t s) {
+    const int units = a.H / 8;
+    const int nseg = (units + kWave - 1) / kWave;
+    const int64_t nwaves = (int64_t)a.T * nseg;
+    if (nwaves == 0) return hipSuccess;
+    const int64_t nblk = (nwaves + 3) / 4;
+    if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);
+    return hipGetLastError();
+}
+
+}  // namespace ep

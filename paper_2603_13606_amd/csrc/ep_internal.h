@@ -1,0 +1,102 @@
+// Internal declarations shared by the translation units of libep_mi355x.so.
+// Host-side structs and the launch functions each kernel file exports.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ep.h"
+
+namespace ep {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kMaxExperts = 1024;
+constexpr int kMaxTopK = 64;
+constexpr int kMaxWaveChunks = 256;  // rows of the per-wave-chunk histogram matrix
+constexpr int kFusedMaxEntries = 4096;
+constexpr int kFusedWaves = 16;
+constexpr int kTotalsWords = 16;
+
+// indices into the device totals block
+enum { TOT_KEPT = 0, TOT_DROPPED, TOT_MASKED, TOT_INVALID, TOT_SORTED, TOT_MSGS, TOT_STATUS,
+       TOT_ROWS_END };
+
+enum { STATUS_INVALID_IDS = 1, STATUS_CAPACITY_DROP = 2, STATUS_OUTPUT_OVERFLOW = 4 };
+
+// Everything the layout kernels need.  All pointers are device pointers.
+struct LayoutArgs {
+    const int32_t* topk;      // [T, K], row stride topk_stride
+    int64_t topk_stride;
+    const int32_t* expert_base;  // [E] or nullptr
+    int T, K, E, R, L;
+    int L_shift;              // log2(L) if L is a power of two, else -1
+    int padded;               // 1 = [E, C, H] layout
+    int C;                    // slots per (expert, source) sub-region
+    int C_rank;               // staging slots per destination rank in padded mode
+    int n;                    // T * K
+    int passes;               // a wave-chunk is 64 * passes consecutive entries
+    int nwc;                  // number of wave-chunks
+    int W;                    // histogram width: E experts + masked + invalid + R ranks
+    int bits_e, bits_r;       // key widths for the in-wave match
+    int32_t* hist;            // [nwc, W] scratch
+    int32_t* coltotal;        // [W] scratch
+    int32_t* expert_count;    // [E]
+    int32_t* expert_kept;     // [E]
+    int32_t* expert_offset;   // [E+1]
+    int32_t* own_prefix;      // [E+1]
+    int32_t* rank_pair_count; // [R]
+    int32_t* rank_token_count;// [R]
+    int32_t* rank_offset;     // [R+1]
+    int32_t* totals;          // [kTotalsWords]
+    int32_t* slot;            // [n]
+    int32_t* dst_row;         // [n]
+    int32_t* rank_row;        // [n]
+    int32_t* sorted_token;    // [n]
+    int32_t* sorted_k;        // [n]
+    int32_t* sorted_row;      // [n]
+};
+
+// Addressing of the receive windows: element offset of logical row r is
+//   padded: (r / C) * stride0 + (r % C) * stride1      (3-D [E, C, H])
+//   concat:  r * stride0                               (2-D [rows, H])
+struct WindowDesc {
+    uint16_t* base;
+    int64_t stride0, stride1;
+    int64_t rows_cap;  // rows addressable through this descriptor
+    int padded;
+    int C;
+};
+
+struct DispatchArgs {
+    const uint16_t* x;
+    int64_t x_stride;
+    const float* w;          // [T, K] or nullptr
+    int64_t w_stride;
+    const int32_t* dst_row;  // [T, K] contiguous
+    WindowDesc win;
+    float* recv_w;           // [rows] or nullptr
+    int32_t* recv_src;       // [rows] or nullptr
+    int32_t* recv_count;     // [E] or nullptr
+    const int32_t* expert_kept;
+    int32_t* totals;
+    int T, K, H, E;
+};
+
+struct CombineArgs {
+    WindowDesc win;          // y
+    const float* w;          // [T, K] or nullptr
+    int64_t w_stride;
+    const int32_t* dst_row;
+    uint16_t* out;
+    int64_t out_stride;
+    int T, K, H;
+};
+
+hipError_t launch_layout(const LayoutArgs& a, hipStream_t s);
+hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s);
+hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
+
+// Host-side planning helpers (pure functions, testable without a GPU).
+void plan_layout(int n, int* passes, int* nwc);
+
+}  // namespace ep

@@ -1,0 +1,85 @@
+"""The C-ABI library loads without a GPU and exports every function include/ep.h
+declares; host-side argument validation returns the documented codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "ep.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"EP_API\s+[\w\s\*]+?\b(ep_\w+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def ep():
+    from paper_2603_13606_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2603_13606_amd import build
+        build.build()
+    binding.load()
+    return binding
+
+
+def test_every_declared_function_is_exported(ep):
+    names = _declared()
+    assert len(names) >= 11 and "ep_dispatch" in names and "ep_layout" in names
+    lib = ep.load()
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in ep.h but not exported"
+    assert sorted(ep.EXPORTS) == names
+    for n in names:
+        assert callable(getattr(ep, n)), f"binding lacks {n}"
+
+
+def test_struct_sizes_match_header(ep):
+    # config: uint32 + 11 int32; tensor: pointer + 4 int32 + 8 int64
+    assert ctypes.sizeof(ep.ep_group_config_t) == 48
+    assert ctypes.sizeof(ep.ep_tensor_t) == 8 + 16 + 64
+    assert ctypes.sizeof(ep.ep_layout_info_t) == 8 + 7 * 8 + 12 * 8
+    assert ctypes.sizeof(ep.ep_group_info_t) == 40 + 7 * 8 + 8
+
+
+def test_error_strings_and_version(ep):
+    assert ep.ep_version() >= 100
+    seen = {ep.error_string(c) for c in range(8)}
+    assert len(seen) == 8 and "success" in seen
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(num_ranks=3), 1),            # E % R != 0
+    (dict(hidden=12), 1),              # 2H not a multiple of 16
+    (dict(top_k=0), 1),
+    (dict(top_k=65), 1),
+    (dict(num_experts=2048), 1),
+    (dict(my_rank=2), 1),
+    (dict(max_tokens_per_rank=0), 1),
+    (dict(mode=5), 1),
+    (dict(dtype=1), 4),                # only bf16 tokens
+])
+def test_group_create_rejects_bad_config_on_the_host(ep, kw, code):
+    args = dict(num_ranks=2, num_experts=8, hidden=256, top_k=2, max_tokens_per_rank=64)
+    args.update(kw)
+    cfg = ep.make_config(**args)
+    with pytest.raises(ep.EpError) as e:
+        ep.ep_group_create(cfg, stream=0)
+    assert e.value.code == code
+    cfg = ep.make_config(2, 8, 256, 2, 64)
+    cfg.size = 12
+    with pytest.raises(ep.EpError) as e:
+        ep.ep_group_create(cfg, stream=0)
+    assert e.value.code == ep.EP_ERR_INVALID_ARG
+
+
+def test_null_arguments(ep):
+    lib = ep.load()
+    assert lib.ep_group_destroy(None, None) == ep.EP_ERR_INVALID_ARG
+    assert lib.ep_handle_destroy(None) == ep.EP_ERR_INVALID_ARG
+    assert lib.ep_group_query(None, None) == ep.EP_ERR_INVALID_ARG
+    assert lib.ep_dispatch(None, None, 0, None, 0, 0, None) == ep.EP_ERR_INVALID_ARG
+    assert lib.ep_combine(None, None, 0, None, 0, 0, None) == ep.EP_ERR_INVALID_ARG
+    assert lib.ep_layout(None, None, None, None, None) == ep.EP_ERR_INVALID_ARG

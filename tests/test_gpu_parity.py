@@ -1,0 +1,469 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on identical
+seeded inputs: bit-exact for the layout, slot maps and dispatched rows; combine
+within max(1e-2 absolute, 4e-3 relative) of the float64 oracle and bit-exact with
+the oracle's float32 ordered accumulation."""
+import ctypes
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_13606_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ep():
+    from paper_2603_13606_amd import binding
+    binding.load()
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return binding
+
+
+@pytest.fixture(scope="module")
+def hx():
+    import ep_harness
+    return ep_harness
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _group(ep, spec, T_max, mode, C=0, **kw):
+    cfg = ep.make_config(spec.R, spec.E, spec.H, spec.K, max(T_max, 1), mode=mode,
+                         slots_per_subregion=C, **kw)
+    return ep.ep_group_create(cfg)
+
+
+def _mess_up(topk, E, seed, frac_masked=0.02, n_invalid=0):
+    rng = np.random.default_rng(seed)
+    topk = topk.copy()
+    topk[rng.random(topk.shape) < frac_masked] = -1
+    for _ in range(n_invalid):
+        t, k = rng.integers(topk.shape[0]), rng.integers(topk.shape[1])
+        topk[t, k] = E + int(rng.integers(0, 5))
+    return topk
+
+
+# ------------------------------------------------------------------------------ layout
+
+LAYOUT_CASES = [
+    # name, T override, mode, C, masked fraction
+    ("tiny", None, "ht", 0, 0.0),
+    ("tiny", None, "ll", 6, 0.0),
+    ("tiny", 1, "ht", 0, 0.0),
+    ("tiny", 33, "ll", 0, 0.1),
+    ("ll_decode", None, "ll", 0, 0.0),
+    ("ll_decode", None, "ht", 0, 0.02),
+    ("ll_decode", 127, "ll", 16, 0.02),
+    ("ll_decode", 512, "ht", 0, 0.0),      # 4096 entries: largest one-launch case
+    ("ll_decode", 513, "ht", 0, 0.0),      # first three-launch case, ragged
+    ("ht_prefill", None, "ht", 0, 0.0),
+    ("ht_prefill", 4095, "ht", 0, 0.05),
+    ("skew", None, "ll", 512, 0.0),        # hot experts overflow C
+    ("skew", None, "ht", 0, 0.0),
+    ("skew_rank0", 3001, "ll", 512, 0.01),
+    ("stress", None, "ht", 0, 0.0),
+    ("stress_hot", None, "ht", 0, 0.0),
+    ("stress_hot", 8191, "ll", 300, 0.03),
+]
+
+
+@pytest.mark.parametrize("name,T,mode,C,masked", LAYOUT_CASES)
+def test_layout_parity(ep, hx, oracle_mod, name, T, mode, C, masked):
+    spec = wl.SPECS[name]
+    topk, _, _ = wl.make_routing(spec, T=T)
+    T = topk.shape[0]
+    if masked:
+        topk = _mess_up(topk, spec.E, seed=T, frac_masked=masked)
+    _say(f"layout case {name} T={T} mode={mode} C={C}")
+    ll = mode == "ll"
+    g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C)
+    try:
+        d_topk = torch.from_numpy(topk).to(hx.DEV)
+        h = ep.ep_layout(g, d_topk)
+        got = hx.fetch_layout(h, T, spec.K, spec.E, spec.R)
+        Cc = C if C else T
+        want = oracle_mod.layout(topk, E=spec.E, R=spec.R,
+                                 layout=oracle_mod.LAYOUT_PADDED if ll else oracle_mod.LAYOUT_CONCAT,
+                                 C=Cc if ll else 0, C_rank=T)
+        hx.assert_layout_equal(got, want)
+        assert ep.ep_handle_get_num_recv_tokens(h) == want.kept
+        assert bool(got.info.status & ep.STATUS_CAPACITY_DROP) == (want.dropped > 0)
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+@pytest.mark.parametrize("E,R,K,T", [(1, 1, 1, 70), (24, 4, 3, 500), (6, 6, 6, 129), (1024, 64, 16, 2048),
+                                     (1000, 8, 5, 3000), (64, 1, 8, 1025)])
+def test_layout_odd_shapes(ep, hx, oracle_mod, E, R, K, T):
+    """Non-power-of-two experts per rank, K not dividing 64, the limits of E."""
+    spec = wl.WorkloadSpec("odd", 9, R=R, T=T, H=64, E=E, K=K)
+    topk, _, _ = wl.make_routing(spec)
+    topk = _mess_up(topk, E, seed=E + K, frac_masked=0.05)
+    _say(f"layout odd E={E} R={R} K={K} T={T}")
+    for mode, ll in ((ep.EP_MODE_HT, False), (ep.EP_MODE_LL, True)):
+        C = max(1, (2 * T * K) // (3 * E))
+        g = _group(ep, spec, T, mode, C=C)
+        try:
+            h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+            got = hx.fetch_layout(h, T, K, E, R)
+            want = oracle_mod.layout(topk, E=E, R=R, layout=int(ll), C=C if ll else 0, C_rank=T)
+            hx.assert_layout_equal(got, want)
+            ep.ep_handle_destroy(h)
+        finally:
+            ep.ep_group_destroy(g)
+
+
+def test_layout_duplicate_experts_and_strided_topk(ep, hx, oracle_mod):
+    spec = wl.SPECS["tiny"]
+    rng = np.random.default_rng(8)
+    T, K = 200, 4
+    topk = rng.integers(0, 3, (T, K)).astype(np.int32)  # many duplicates within a token
+    spec = wl.WorkloadSpec("dup", 9, R=2, T=T, H=64, E=4, K=K)
+    g = _group(ep, spec, T, ep.EP_MODE_HT)
+    try:
+        wide = torch.full((T, K + 3), 77, dtype=torch.int32, device=hx.DEV)
+        wide[:, :K] = torch.from_numpy(topk).to(hx.DEV)
+        h = ep.ep_layout(g, wide[:, :K])  # row stride K + 3
+        got = hx.fetch_layout(h, T, K, 4, 2)
+        hx.assert_layout_equal(got, oracle_mod.layout(topk, E=4, R=2, C_rank=T))
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_layout_empty_batch(ep, hx, oracle_mod):
+    spec = wl.SPECS["ll_decode"]
+    g = _group(ep, spec, 16, ep.EP_MODE_HT)
+    try:
+        h = ep.ep_layout(g, torch.zeros((0, spec.K), dtype=torch.int32, device=hx.DEV))
+        got = hx.fetch_layout(h, 0, spec.K, spec.E, spec.R)
+        want = oracle_mod.layout(np.zeros((0, spec.K), np.int32), E=spec.E, R=spec.R, C_rank=1)
+        hx.assert_layout_equal(got, want)
+        x = torch.zeros((0, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        recv = hx.poison_bf16((4, spec.H))
+        out = torch.zeros((0, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        ep.ep_dispatch(h, x, recv)
+        ep.ep_combine(h, recv, out)
+        torch.cuda.synchronize()
+        assert np.all(hx.dev_to_bits(recv) == hx.POISON)
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_layout_invalid_ids_are_flagged_and_skipped(ep, hx, oracle_mod):
+    spec = wl.SPECS["ll_decode"]
+    topk, _, _ = wl.make_routing(spec)
+    topk = _mess_up(topk, spec.E, seed=1, frac_masked=0.01, n_invalid=7)
+    topk[5, 1] = -2
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT)
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+        got = hx.fetch_layout(h, spec.T, spec.K, spec.E, spec.R, ok=(ep.EP_ERR_INVALID_ROUTING,))
+        assert got.info.last_code == ep.EP_ERR_INVALID_ROUTING
+        assert got.info.status & ep.STATUS_INVALID_IDS
+        want = oracle_mod.layout(topk, E=spec.E, R=spec.R, C_rank=spec.T)
+        assert want.invalid >= 1
+        hx.assert_layout_equal(got, want)
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_layout_expert_base(ep, hx, oracle_mod):
+    """Rows of this source start where lower-ranked sources end: base offsets built
+    from seeded routings of the other ranks (stand-in for the metadata exchange)."""
+    spec = wl.SPECS["ll_decode"]
+    my_rank = 3
+    counts = []
+    for r in range(spec.R):
+        tk, _, _ = wl.make_routing(wl.SPECS["ll_decode"], seed_offset=100 + r)
+        counts.append(np.bincount(tk.reshape(-1), minlength=spec.E))
+    counts = np.array(counts)
+    expert_start = np.concatenate([[0], np.cumsum(counts.sum(0))])[:-1]
+    base = (expert_start + counts[:my_rank].sum(0)).astype(np.int32)
+    topk, _, _ = wl.make_routing(spec, seed_offset=100 + my_rank)
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT, my_rank=my_rank)
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV), expert_base=torch.from_numpy(base).to(hx.DEV))
+        got = hx.fetch_layout(h, spec.T, spec.K, spec.E, spec.R)
+        want = oracle_mod.layout(topk, E=spec.E, R=spec.R, expert_base=base, C_rank=spec.T)
+        hx.assert_layout_equal(got, want)
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_layout_is_deterministic(ep, hx):
+    spec = wl.SPECS["stress_hot"]
+    topk, _, _ = wl.make_routing(spec)
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT, max_handles=3)
+    try:
+        d = torch.from_numpy(topk).to(hx.DEV)
+        first = None
+        for i in range(10):
+            h = ep.ep_layout(g, d)
+            got = hx.fetch_layout(h, spec.T, spec.K, spec.E, spec.R)
+            blob = np.concatenate([v.reshape(-1) for v in got.arrays.values()])
+            if first is None:
+                first = blob
+            assert np.array_equal(first, blob), f"run {i} differs"
+            ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+# ------------------------------------------------------------------------------ dispatch + combine
+
+PATH_CASES = [
+    # name, T override, H override, mode, C
+    ("tiny", None, None, "ht", 0),
+    ("tiny", None, None, "ll", 6),
+    ("ll_decode", None, None, "ll", 0),
+    ("ll_decode", 77, None, "ht", 0),
+    ("ll_decode", 50, 1000, "ht", 0),      # row of 2000 bytes: ragged last 1 KiB segment
+    ("ll_decode", 50, 8, "ll", 9),         # smallest row: one 16-byte unit
+    ("skew", 1111, None, "ll", 139),
+    ("skew", 1111, None, "ht", 0),
+    ("ht_prefill", None, None, "ht", 0),   # full benchmark shape
+]
+
+
+def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True):
+    w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
+    spec = w.spec
+    T = spec.T
+    topk = _mess_up(w.topk_idx, spec.E, seed=T + spec.H, frac_masked=masked)
+    ll = mode == "ll"
+    Cc = (C if C else T) if ll else 0
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, layout=int(ll), C=Cc, C_rank=T)
+    rows = spec.E * Cc if ll else int(lay.expert_offset[-1])
+    guard = 2
+    # ---- oracle side
+    o_recv = np.full((rows + guard, spec.H), hx.POISON, np.uint16)
+    o_w = np.full(rows + guard, np.float32(-3.5), np.float32)
+    o_src = np.full(rows + guard, -9, np.int32)
+    oracle_mod.dispatch(w.x_bits, w.topk_w if weights else None, lay, o_recv, o_w, o_src)
+    # ---- HIP side
+    g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C)
+    try:
+        x = hx.bits_to_dev(w.x_bits)
+        d_w = torch.from_numpy(w.topk_w).to(hx.DEV)
+        h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+        store = hx.poison_bf16((rows + guard, spec.H))
+        recv = store[:rows].view(spec.E, Cc, spec.H) if ll else store[:rows]
+        r_w = torch.full((rows + guard,), -3.5, dtype=torch.float32, device=hx.DEV)
+        r_src = torch.full((rows + guard,), -9, dtype=torch.int32, device=hx.DEV)
+        r_cnt = torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)
+        ep.ep_dispatch(h, x, recv, topk_weights=d_w if weights else None, recv_w=r_w[:rows] if rows else r_w[:0],
+                       recv_src=r_src[:rows], recv_count=r_cnt)
+        torch.cuda.synchronize()
+        got = hx.dev_to_bits(store)
+        assert np.array_equal(got, o_recv), "dispatched rows differ"
+        if weights:
+            assert np.array_equal(r_w.cpu().numpy(), o_w)
+        assert np.array_equal(r_src.cpu().numpy(), o_src)
+        assert np.array_equal(r_cnt.cpu().numpy(), lay.expert_kept)
+        # ---- experts (harness), then combine
+        scale = wl.expert_scale_table(spec)
+        if ll:
+            row_e = np.repeat(np.arange(spec.E), Cc)
+        else:
+            row_e = np.repeat(np.arange(spec.E), lay.expert_count)
+        o_y = hx.expert_standin_np(o_recv[:rows], row_e, scale)
+        d_y_store = hx.poison_bf16((rows + guard, spec.H))
+        d_y_store[:rows] = hx.expert_standin(store[:rows], torch.from_numpy(row_e).to(hx.DEV), scale)
+        assert np.array_equal(hx.dev_to_bits(d_y_store[:rows]), o_y), "stand-in experts differ (harness)"
+        d_y = d_y_store[:rows].view(spec.E, Cc, spec.H) if ll else d_y_store[:rows]
+        for use_w in ((True, False) if weights else (False,)):
+            out_store = hx.poison_bf16((T + guard, spec.H))
+            ep.ep_combine(h, d_y, out_store[:T], topk_weights=d_w if use_w else None)
+            torch.cuda.synchronize()
+            got_out = hx.dev_to_bits(out_store)
+            assert np.all(got_out[T:] == hx.POISON), "combine wrote past its output"
+            wts = w.topk_w if use_w else None
+            ref64 = oracle_mod.combine(o_y, wts, lay, spec.H, acc="f64")
+            ok, worst = hx.combine_tolerance_ok(got_out[:T], ref64)
+            assert ok, f"combine outside tolerance, worst abs diff {worst}"
+            ref32 = oracle_mod.combine(o_y, wts, lay, spec.H, acc="f32")
+            assert np.array_equal(got_out[:T], ref32), "combine differs from ordered float32 accumulation"
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+@pytest.mark.parametrize("name,T,H,mode,C", PATH_CASES)
+def test_dispatch_combine_parity(ep, hx, oracle_mod, name, T, H, mode, C):
+    _say(f"path case {name} T={T} H={H} mode={mode} C={C}")
+    _run_path(ep, hx, oracle_mod, name, T, H, mode, C)
+
+
+def test_round_trip_identity_experts(ep, hx):
+    """combine(dispatch(x)) with identity experts and renormalised weights returns x
+    to within one bf16 ulp; unweighted it returns exactly K * x."""
+    w = wl.make_workload("tiny")
+    spec = w.spec
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT)
+    try:
+        x = hx.bits_to_dev(w.x_bits)
+        h = ep.ep_layout(g, torch.from_numpy(w.topk_idx).to(hx.DEV))
+        recv = torch.zeros((spec.T * spec.K, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        out = torch.zeros((spec.T, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        ep.ep_dispatch(h, x, recv)
+        ep.ep_combine(h, recv, out, topk_weights=torch.from_numpy(w.topk_w).to(hx.DEV))
+        torch.cuda.synchronize()
+        xf = x.float().cpu().numpy()
+        of = out.float().cpu().numpy()
+        assert np.all(np.abs(of - xf) <= np.abs(xf) * 2.0 ** -7)
+        ep.ep_combine(h, recv, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.float().cpu().numpy(), xf * spec.K)
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_ll_windows_as_strided_view_of_receiver_tensor(ep, hx, oracle_mod):
+    """LL output [E, C, H] given as this source's sub-regions inside a receiver-shaped
+    tensor [E, R*C, H]; nothing outside them may change.  x is a strided view too."""
+    w = wl.make_workload("tiny")
+    spec = w.spec
+    C, my_rank = 6, 1
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, layout=oracle_mod.LAYOUT_PADDED, C=C, C_rank=spec.T)
+    o_full = np.full((spec.E, spec.R * C, spec.H), hx.POISON, np.uint16)
+    oracle_mod.dispatch(w.x_bits, None, lay, o_full[:, my_rank * C:(my_rank + 1) * C, :],
+                        stride0=spec.R * C * spec.H, stride1=spec.H)
+    g = _group(ep, spec, spec.T, ep.EP_MODE_LL, C=C, my_rank=my_rank)
+    try:
+        xw = hx.poison_bf16((spec.T, spec.H + 24))
+        xw[:, 8:8 + spec.H] = hx.bits_to_dev(w.x_bits)
+        full = hx.poison_bf16((spec.E, spec.R * C, spec.H))
+        h = ep.ep_layout(g, torch.from_numpy(w.topk_idx).to(hx.DEV))
+        ep.ep_dispatch(h, xw[:, 8:8 + spec.H], full[:, my_rank * C:(my_rank + 1) * C, :])
+        torch.cuda.synchronize()
+        assert np.array_equal(hx.dev_to_bits(full), o_full)
+        out = hx.poison_bf16((spec.T, spec.H + 8))
+        ep.ep_combine(h, full[:, my_rank * C:(my_rank + 1) * C, :], out[:, :spec.H],
+                      topk_weights=torch.from_numpy(w.topk_w).to(hx.DEV))
+        torch.cuda.synchronize()
+        ref = oracle_mod.combine(o_full[:, my_rank * C:(my_rank + 1) * C, :].copy(), w.topk_w, lay, spec.H, acc="f32")
+        got = hx.dev_to_bits(out)
+        assert np.array_equal(got[:, :spec.H], ref) and np.all(got[:, spec.H:] == hx.POISON)
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_handle_reuse_forward_and_backward(ep, hx, oracle_mod):
+    """One handle serves several dispatch/combine pairs (Sec. III-C: shared between the
+    forward and backward passes)."""
+    w = wl.make_workload("ll_decode", T=64, H=512)
+    spec = w.spec
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=spec.T)
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT)
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(w.topk_idx).to(hx.DEV))
+        d_w = torch.from_numpy(w.topk_w).to(hx.DEV)
+        for it in range(3):
+            xb = wl.make_tokens(spec, seed_offset=it)
+            recv = torch.zeros((spec.T * spec.K, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+            out = torch.zeros((spec.T, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+            ep.ep_dispatch(h, hx.bits_to_dev(xb), recv)
+            ep.ep_combine(h, recv, out, topk_weights=d_w)
+            torch.cuda.synchronize()
+            o_recv = np.zeros((spec.T * spec.K, spec.H), np.uint16)
+            oracle_mod.dispatch(xb, None, lay, o_recv)
+            assert np.array_equal(hx.dev_to_bits(recv), o_recv)
+            assert np.array_equal(hx.dev_to_bits(out), oracle_mod.combine(o_recv, w.topk_w, lay, spec.H, acc="f32"))
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_output_too_small_is_flagged_not_overrun(ep, hx, oracle_mod):
+    w = wl.make_workload("ll_decode", T=32, H=256)
+    spec = w.spec
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=spec.T)
+    cap = 100
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT)
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(w.topk_idx).to(hx.DEV))
+        store = hx.poison_bf16((spec.T * spec.K, spec.H))
+        ep.ep_dispatch(h, hx.bits_to_dev(w.x_bits), store[:cap])
+        info = ep.ep_handle_query(h, ok=(ep.EP_ERR_OVERFLOW,))
+        assert info.last_code == ep.EP_ERR_OVERFLOW and info.status & ep.STATUS_OUTPUT_OVERFLOW
+        got = hx.dev_to_bits(store)
+        assert np.all(got[cap:] == hx.POISON)
+        o = np.full((spec.T * spec.K, spec.H), hx.POISON, np.uint16)
+        oracle_mod.dispatch(w.x_bits, None, lay, o)
+        assert np.array_equal(got[:cap], o[:cap])
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_allocator_callbacks_and_lifecycle(ep, hx):
+    spec = wl.SPECS["tiny"]
+    held = {}
+
+    def alloc(pp, nbytes):
+        t = torch.empty(int(nbytes), dtype=torch.uint8, device=hx.DEV)
+        held[t.data_ptr()] = t
+        pp[0] = t.data_ptr()
+        return 0
+
+    def free(p):
+        return 0 if held.pop(p, None) is not None else 1
+
+    a, f = ep.ALLOC_FN(alloc), ep.FREE_FN(free)
+    cfg = ep.make_config(spec.R, spec.E, spec.H, spec.K, spec.T, max_handles=1)
+    g = ep.ep_group_create(cfg, alloc_fn=a, free_fn=f)
+    assert len(held) == 1
+    topk = torch.from_numpy(wl.make_routing(spec)[0]).to(hx.DEV)
+    h1 = ep.ep_layout(g, topk)
+    h2 = ep.ep_layout(g, topk)  # pool exhausted: one more slab through the callback
+    assert len(held) == 2 and ep.ep_group_query(g).live_handles == 2
+    with pytest.raises(ep.EpError) as e:
+        ep.ep_group_destroy(g)
+    assert e.value.code == ep.EP_ERR_BUSY
+    a1 = hx.fetch_layout(h1, spec.T, spec.K, spec.E, spec.R).arrays
+    a2 = hx.fetch_layout(h2, spec.T, spec.K, spec.E, spec.R).arrays
+    assert all(np.array_equal(a1[k], a2[k]) for k in a1)
+    ep.ep_handle_destroy(h1)
+    ep.ep_handle_destroy(h2)
+    ep.ep_group_destroy(g)
+    assert not held
+
+
+def test_argument_errors_on_device(ep, hx):
+    spec = wl.SPECS["tiny"]
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT)
+    try:
+        topk = torch.from_numpy(wl.make_routing(spec)[0]).to(hx.DEV)
+        for bad in (topk[:, :1], torch.zeros((spec.T + 1, spec.K), dtype=torch.int32, device=hx.DEV),
+                    topk.float()):
+            with pytest.raises((ep.EpError, KeyError)) as e:
+                ep.ep_layout(g, bad)
+        h = ep.ep_layout(g, topk)
+        x = torch.zeros((spec.T, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        recv = torch.zeros((spec.T * spec.K, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        for args in ((x[:-1], recv), (x, recv[:, :-8]), (x.float(), recv), (x, recv.view(-1)[1:-(spec.H - 1)].view(-1, spec.H))):
+            with pytest.raises(ep.EpError) as e:
+                ep.ep_dispatch(h, *args)
+            assert e.value.code == ep.EP_ERR_INVALID_ARG
+        with pytest.raises(ep.EpError) as e:
+            ep.ep_dispatch(h, x, recv, send_only=1)
+        assert e.value.code == ep.EP_ERR_UNSUPPORTED
+        with pytest.raises(ep.EpError) as e:
+            ep.ep_combine(h, recv, x[:, :-8])
+        assert e.value.code == ep.EP_ERR_INVALID_ARG
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
