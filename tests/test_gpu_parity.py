@@ -1,7 +1,7 @@
 """Parity of the HIP path (through the C ABI) with the CPU oracle on identical
 seeded inputs: bit-exact for the layout, slot maps and dispatched rows; combine
-within max(1e-2 absolute, 4e-3 relative) of the float64 oracle and bit-exact with
-the oracle's float32 ordered accumulation."""
+within 1e-2 absolute or 4e-3 relative of (in fact bit-exact with) the oracle's
+float32 k-ascending accumulation, and within one bf16 ulp of its float64 sum."""
 import ctypes
 import sys
 
@@ -289,11 +289,17 @@ def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True
             got_out = hx.dev_to_bits(out_store)
             assert np.all(got_out[T:] == hx.POISON), "combine wrote past its output"
             wts = w.topk_w if use_w else None
-            ref64 = oracle_mod.combine(o_y, wts, lay, spec.H, acc="f64")
-            ok, worst = hx.combine_tolerance_ok(got_out[:T], ref64)
-            assert ok, f"combine outside tolerance, worst abs diff {worst}"
+            # the accumulation the path is specified with: float32, k ascending
             ref32 = oracle_mod.combine(o_y, wts, lay, spec.H, acc="f32")
+            ok, worst = hx.combine_tolerance_ok(got_out[:T], ref32)
+            assert ok, f"combine outside tolerance, worst abs diff {worst}"
             assert np.array_equal(got_out[:T], ref32), "combine differs from ordered float32 accumulation"
+            # against the float64 definition the float32 sum may land on the other side of a
+            # bf16 rounding boundary: equal or adjacent bf16 values, and only rarely adjacent
+            ref64 = oracle_mod.combine(o_y, wts, lay, spec.H, acc="f64")
+            dist = hx.bf16_ulp_distance(got_out[:T], ref64)
+            assert dist.max(initial=0) <= 1, "combine more than one bf16 ulp from the float64 oracle"
+            assert (dist != 0).mean() < 2e-3 if dist.size else True
         ep.ep_handle_destroy(h)
     finally:
         ep.ep_group_destroy(g)
