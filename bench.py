@@ -24,13 +24,18 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 
 
 def _traffic(workload: str, kernel: str):
-    """HBM bytes per launch measured with rocprofv3 counters, if a summary was committed."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    """HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE + WRITE_SIZE scaled
+    by the calibration copy), read from the committed summary; None if there is none."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     try:
         with open(path) as f:
-            return json.load(f).get(workload, {}).get(kernel)
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == workload and parts[1] == kernel:
+                    return int(parts[2])
     except (OSError, ValueError):
-        return None
+        pass
+    return None
 
 
 def cpu_baseline(w, steps_budget_s: float = 12.0):
@@ -136,6 +141,20 @@ def main() -> int:
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+
+    # reference point: what a plain streaming copy of 512 MiB reaches on this GPU
+    cal_src = torch.empty(512 << 20, dtype=torch.uint8, device=hx.DEV).fill_(1)
+    cal_dst = torch.empty_like(cal_src)
+    cal_ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
+    ep.ep_calibration_copy(cal_dst, cal_src)
+    for j in range(6):
+        cal_ev[j].record()
+        ep.ep_calibration_copy(cal_dst, cal_src)
+    cal_ev[6].record()
+    torch.cuda.synchronize()
+    cal_us = min(cal_ev[j].elapsed_time(cal_ev[j + 1]) for j in range(6)) * 1e3
+    copy_gbps = 2 * cal_src.numel() / (cal_us * 1e-6) / 1e9
+    del cal_src, cal_dst
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -176,6 +195,8 @@ def main() -> int:
                  "dispatch_plus_combine": round((ab["dispatch"] + ab["combine"]) /
                                                 ((dis_us.mean() + com_us.mean()) * 1e-6) / 1e9, 1)},
         "algorithmic_bytes": ab,
+        "hbm_copy_reference": {"gbps": round(copy_gbps, 1), "what": "plain 16-byte-per-lane copy of 512 MiB "
+                               "(read + write bytes / best of 6 launches)"},
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": _traffic(spec.name, kernel_name),

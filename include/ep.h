@@ -164,6 +164,15 @@ EP_API const char *ep_error_string(ep_result_t code);
 EP_API int32_t ep_version(void);
 
 /*
+ * Measurement aid, not part of the paper's API: a plain streaming copy of `bytes`
+ * (multiple of 16; dst and src 16-byte aligned DEVICE pointers, not overlapping)
+ * with the same 16-byte-per-lane accesses the row kernels use.  It is what the
+ * hardware byte counters and "achievable copy bandwidth" are calibrated against.
+ * Errors: EP_ERR_INVALID_ARG, EP_ERR_HIP.
+ */
+EP_API ep_result_t ep_calibration_copy(void *dst, const void *src, size_t bytes, ep_stream_t stream);
+
+/*
  * ep_group_create -- Table II "ncclEpCreateGroup" without the communicator.
  * Validates cfg, computes the window geometry and allocates (through alloc_fn or
  * hipMalloc) the handle slabs and, for EP_PATH_RANK_DEDUP, the staging windows:
@@ -212,8 +221,10 @@ EP_API ep_result_t ep_handle_query(ep_handle_t handle, ep_layout_info_t *info);
  * receivers' tensors (rows_kept).  Synchronises like ep_handle_query. */
 EP_API ep_result_t ep_handle_get_num_recv_tokens(ep_handle_t handle, int64_t *num);
 
-/* Table II "ncclEpHandleDestroy".  The caller guarantees that stream work using
- * the handle has completed (the slab returns to the group's pool at once). */
+/* Table II "ncclEpHandleDestroy".  The handle's device arrays return to the group's
+ * pool at once and the next ep_layout may overwrite them: the caller guarantees that
+ * stream work using the handle has completed, or that every later ep_layout of this
+ * group is enqueued on the same stream as that work (stream order then protects it). */
 EP_API ep_result_t ep_handle_destroy(ep_handle_t handle);
 
 /*

@@ -44,7 +44,7 @@ EP_TAG_EXPERT_BASE = 9
 STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW = 1, 2, 4
 
 EXPORTS = [
-    "ep_error_string", "ep_version", "ep_group_create", "ep_group_destroy", "ep_group_query",
+    "ep_error_string", "ep_version", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
     "ep_layout", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
     "ep_dispatch", "ep_combine",
 ]
@@ -122,6 +122,7 @@ def load() -> ctypes.CDLL:
         lib.ep_handle_destroy.argtypes = [vp]
         for fn in (lib.ep_dispatch, lib.ep_combine):
             fn.argtypes = [vp, ctypes.POINTER(ep_tensor_t), i32, ctypes.POINTER(ep_tensor_t), i32, i32, vp]
+        lib.ep_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         for name in EXPORTS[2:]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -137,6 +138,13 @@ ep_error_string = error_string
 
 def ep_version() -> int:
     return int(load().ep_version())
+
+
+def ep_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes and dst.is_contiguous() and src.is_contiguous()
+    _check(load().ep_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)),
+           "ep_calibration_copy")
 
 
 _DTYPES = {torch.bfloat16: EP_DTYPE_BF16, torch.float32: EP_DTYPE_F32, torch.int32: EP_DTYPE_I32,

@@ -192,6 +192,11 @@ const char* ep_error_string(ep_result_t code) {
 
 int32_t ep_version(void) { return 100; }
 
+ep_result_t ep_calibration_copy(void* dst, const void* src, size_t bytes, ep_stream_t stream) {
+    if (!dst || !src || bytes % 16 || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) return EP_ERR_INVALID_ARG;
+    return launch_calibration_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+}
+
 ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_stream_t stream,
                             ep_alloc_fn alloc_fn, ep_free_fn free_fn) {
     (void)stream;

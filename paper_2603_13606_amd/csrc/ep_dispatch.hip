@@ -54,7 +54,25 @@ __global__ __launch_bounds__(256) void dispatch_direct_kernel(DispatchArgs a, in
     }
 }
 
+// Plain streaming copy, 16 bytes per lane, grid-stride: the yardstick the hardware
+// counters and the achievable copy bandwidth are calibrated against.
+__global__ __launch_bounds__(256) void calibration_copy_kernel(u32x4* dst, const u32x4* src, int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
 }  // namespace
+
+hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+    const int64_t n16 = (int64_t)(bytes / 16);
+    if (n16 == 0) return hipSuccess;
+    int64_t nblk = (n16 + 255) / 256;
+    if (nblk > 256 * 64) nblk = 256 * 64;
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3((unsigned)nblk), dim3(256), 0, s, (u32x4*)dst,
+                       (const u32x4*)src, n16);
+    return hipGetLastError();
+}
 
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s) {
     const int units = a.H / 8;  // 16-byte units per row

@@ -95,6 +95,7 @@ struct CombineArgs {
 hipError_t launch_layout(const LayoutArgs& a, hipStream_t s);
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s);
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
+hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 // Host-side planning helpers (pure functions, testable without a GPU).
 void plan_layout(int n, int* passes, int* nwc);
