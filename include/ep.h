@@ -231,7 +231,9 @@ EP_API ep_result_t ep_handle_destroy(ep_handle_t handle);
  * ep_dispatch -- Table II "ncclEpDispatch" (Sec. III-B; data movement of Sec. IV-B/C,
  * or Sec. IV-D when the group was created with EP_PATH_RANK_DEDUP).
  * inputs (by tag):  TOKENS x [T, H] bf16 (required);
- *                   TOPK_WEIGHTS w [T, K] f32 (optional, forwarded per row).
+ *                   TOPK_WEIGHTS w [T, K] f32 (optional, forwarded per row);
+ *                   TOPK_IDX [T, K] int32, the tensor the handle was built from
+ *                     (required for EP_PATH_RANK_DEDUP: it fills the message headers).
  * outputs (by tag): TOKENS (required) -- HT: [rows_cap, H]; LL: [E, C, H], possibly a
  *                     strided view of a larger receiver tensor [E, R*C, H];
  *                   TOPK_WEIGHTS recv_w [rows_cap] f32 (optional; LL: [E*C]);
@@ -242,6 +244,10 @@ EP_API ep_result_t ep_handle_destroy(ep_handle_t handle);
  * recv_w[dst_row] = w[t,k], recv_src[dst_row] = t.  Rows not named by the layout are
  * left untouched.  A row index >= rows_cap is skipped and flagged (status bit 2).
  * send_only must be 0 (staged execution is not built): EP_ERR_UNSUPPORTED.
+ * EP_PATH_RANK_DEDUP runs three steps on the stream -- send to the group's staging
+ * windows, receiver-side ranking of the header entries, fan-out -- and produces the
+ * same outputs; dispatches of one group must then not overlap (they share the
+ * staging windows).  An expert_base given to ep_layout must stay valid until then.
  */
 EP_API ep_result_t ep_dispatch(ep_handle_t handle, const ep_tensor_t *inputs, int32_t num_inputs,
                         const ep_tensor_t *outputs, int32_t num_outputs, int32_t send_only,

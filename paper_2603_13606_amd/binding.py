@@ -243,10 +243,13 @@ def _descs(pairs) -> "ctypes.Array":
 
 def ep_dispatch(handle, x: torch.Tensor, recv_x: torch.Tensor, topk_weights: Optional[torch.Tensor] = None,
                 recv_w: Optional[torch.Tensor] = None, recv_src: Optional[torch.Tensor] = None,
-                recv_count: Optional[torch.Tensor] = None, send_only: int = 0, stream=None) -> None:
+                recv_count: Optional[torch.Tensor] = None, send_only: int = 0, stream=None,
+                topk_idx: Optional[torch.Tensor] = None) -> None:
     ins = [(x, EP_TAG_TOKENS)]
     if topk_weights is not None:
         ins.append((topk_weights, EP_TAG_TOPK_WEIGHTS))
+    if topk_idx is not None:
+        ins.append((topk_idx, EP_TAG_TOPK_IDX))
     outs = [(recv_x, EP_TAG_TOKENS)]
     if recv_w is not None:
         outs.append((recv_w, EP_TAG_TOPK_WEIGHTS))

@@ -18,8 +18,10 @@ struct Slab {
     int32_t* base = nullptr;
     // carved arrays
     int32_t *totals, *expert_count, *expert_kept, *expert_offset, *own_prefix;
-    int32_t *rank_pair_count, *rank_token_count, *rank_offset, *coltotal, *hist;
+    int32_t *rank_pair_count, *rank_token_count, *rank_offset, *hist;
     int32_t *slot, *dst_row, *rank_row, *sorted_token, *sorted_k, *sorted_row;
+    // receiving side of the once-per-rank path (only carved for EP_PATH_RANK_DEDUP)
+    int32_t *recv_totals, *recv_count, *recv_kept, *recv_offset, *recv_own_prefix, *recv_dst_row;
 };
 
 }  // namespace
@@ -46,6 +48,7 @@ struct ep_handle_s {
     Slab slab;
     int T;
     hipStream_t last_stream;
+    const int32_t* expert_base;  // as given to ep_layout (borrowed), or nullptr
 };
 
 namespace {
@@ -84,17 +87,24 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
     int64_t cur = 0;
     const int64_t o_tot = carve(&cur, kTotalsWords), o_ec = carve(&cur, E), o_ek = carve(&cur, E);
     const int64_t o_eo = carve(&cur, E + 1), o_op = carve(&cur, E + 1), o_rp = carve(&cur, R);
-    const int64_t o_rt = carve(&cur, R), o_ro = carve(&cur, R + 1), o_ct = carve(&cur, g->W);
+    const int64_t o_rt = carve(&cur, R), o_ro = carve(&cur, R + 1);
     const int64_t o_h = carve(&cur, (int64_t)kMaxWaveChunks * g->W);
     const int64_t o_sl = carve(&cur, nB), o_dr = carve(&cur, nB), o_rr = carve(&cur, nB);
     const int64_t o_st = carve(&cur, nB), o_sk = carve(&cur, nB), o_sr = carve(&cur, nB);
+    const bool dedup = g->cfg.dispatch_path == EP_PATH_RANK_DEDUP;
+    const int64_t o_vt = dedup ? carve(&cur, kTotalsWords) : 0, o_vc = dedup ? carve(&cur, E) : 0;
+    const int64_t o_vk = dedup ? carve(&cur, E) : 0, o_vo = dedup ? carve(&cur, E + 1) : 0;
+    const int64_t o_vp = dedup ? carve(&cur, E + 1) : 0;
+    const int64_t o_vr = dedup ? carve(&cur, g->staging_slots * g->cfg.top_k) : 0;
     if (base && s) {
         s->base = base;
         s->totals = base + o_tot; s->expert_count = base + o_ec; s->expert_kept = base + o_ek;
         s->expert_offset = base + o_eo; s->own_prefix = base + o_op; s->rank_pair_count = base + o_rp;
-        s->rank_token_count = base + o_rt; s->rank_offset = base + o_ro; s->coltotal = base + o_ct;
+        s->rank_token_count = base + o_rt; s->rank_offset = base + o_ro;
         s->hist = base + o_h; s->slot = base + o_sl; s->dst_row = base + o_dr; s->rank_row = base + o_rr;
         s->sorted_token = base + o_st; s->sorted_k = base + o_sk; s->sorted_row = base + o_sr;
+        s->recv_totals = base + o_vt; s->recv_count = base + o_vc; s->recv_kept = base + o_vk;
+        s->recv_offset = base + o_vo; s->recv_own_prefix = base + o_vp; s->recv_dst_row = base + o_vr;
     }
     return cur;
 }
@@ -214,7 +224,6 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     if (cfg->slots_per_subregion < 0 || cfg->max_handles < 0) return EP_ERR_INVALID_ARG;
     const int C = cfg->slots_per_subregion ? cfg->slots_per_subregion : cfg->max_tokens_per_rank;
     if (cfg->mode == EP_MODE_LL && (int64_t)E * C > 0x7fffffffLL) return EP_ERR_INVALID_ARG;
-    if (cfg->dispatch_path == EP_PATH_RANK_DEDUP) return EP_ERR_UNSUPPORTED;
 
     ep_group_s* g = new (std::nothrow) ep_group_s();
     if (!g) return EP_ERR_NOMEM;
@@ -229,16 +238,30 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     g->bits_r = bits_for(R);
     g->alloc_fn = alloc_fn;
     g->free_fn = free_fn;
-    g->slab_ints = carve_slab(g, nullptr, nullptr);
     g->hdr_bytes = round_up(4 + 8 * (int64_t)K, 16);
     g->msg_bytes = g->hdr_bytes + 2 * (int64_t)H;
+    if (cfg->dispatch_path == EP_PATH_RANK_DEDUP) {
+        // LL: B slots per destination rank (Sec. IV-D, O(N*B*P)); HT: a token reaches at
+        // most min(R, K) ranks, windows are packed back to back.
+        const int64_t B = cfg->max_tokens_per_rank;
+        g->staging_slots = cfg->mode == EP_MODE_LL ? (int64_t)R * B : B * (R < K ? R : K);
+        if (g->staging_slots * K > (1 << 28)) { delete g; return EP_ERR_INVALID_ARG; }
+    }
+    g->slab_ints = carve_slab(g, nullptr, nullptr);
     if (hipGetDevice(&g->device) != hipSuccess) { delete g; return EP_ERR_HIP; }
+    if (g->staging_slots > 0) {
+        void* p = nullptr;
+        ep_result_t r = dev_alloc(g, &p, (size_t)(g->staging_slots * g->msg_bytes));
+        if (r != EP_SUCCESS) { delete g; return r; }
+        g->staging = (uint8_t*)p;
+    }
     const int nslabs = cfg->max_handles ? cfg->max_handles : 2;
     for (int i = 0; i < nslabs; ++i) {
         Slab s;
         ep_result_t r = new_slab(g, &s);
         if (r != EP_SUCCESS) {
             for (auto& f : g->free_slabs) dev_free(g, f.base);
+            dev_free(g, g->staging);
             delete g;
             return r;
         }
@@ -315,6 +338,7 @@ ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk
     h->group = g;
     h->T = (int)T;
     h->last_stream = (hipStream_t)stream;
+    h->expert_base = expert_base ? (const int32_t*)expert_base->data : nullptr;
 
     LayoutArgs a;
     a.topk = (const int32_t*)topk_idx->data;
@@ -326,11 +350,13 @@ ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk
     plan_layout(a.n, &a.passes, &a.nwc);
     a.W = g->W; a.bits_e = g->bits_e; a.bits_r = g->bits_r;
     const Slab& s = h->slab;
-    a.hist = s.hist; a.coltotal = s.coltotal; a.expert_count = s.expert_count; a.expert_kept = s.expert_kept;
+    a.hist = s.hist; a.expert_count = s.expert_count; a.expert_kept = s.expert_kept;
     a.expert_offset = s.expert_offset; a.own_prefix = s.own_prefix; a.rank_pair_count = s.rank_pair_count;
     a.rank_token_count = s.rank_token_count; a.rank_offset = s.rank_offset; a.totals = s.totals;
     a.slot = s.slot; a.dst_row = s.dst_row; a.rank_row = s.rank_row; a.sorted_token = s.sorted_token;
     a.sorted_k = s.sorted_k; a.sorted_row = s.sorted_row;
+    a.msgs = nullptr; a.msg_bytes = 0; a.msg_total_slots = 0; a.msg_slots_per_rank = 0;
+    a.msg_rank_offset = nullptr; a.msg_rank_count = nullptr;
     if (launch_layout(a, (hipStream_t)stream) != hipSuccess) {
         ep_handle_destroy(h);
         return EP_ERR_HIP;
@@ -417,7 +443,55 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     a.totals = h->slab.totals;
     a.T = h->T; a.K = c.top_k; a.H = c.hidden; a.E = c.num_experts;
     h->last_stream = (hipStream_t)stream;
-    return launch_dispatch(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+    if (c.dispatch_path == EP_PATH_DIRECT)
+        return launch_dispatch(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+
+    // Once per destination rank: send to the staging windows, rank the header entries on
+    // the receiving side, fan out to the expert rows.
+    const ep_tensor_t* ti = find_tag(inputs, num_inputs, EP_TAG_TOPK_IDX);
+    if (!check_2d(ti, EP_DTYPE_I32, h->T, c.top_k, true)) return EP_ERR_INVALID_ARG;
+    const Slab& s = h->slab;
+    DedupSendArgs sa;
+    sa.x = a.x; sa.x_stride = a.x_stride;
+    sa.topk = (const int32_t*)ti->data; sa.topk_stride = ti->stride[0];
+    sa.w = a.w; sa.w_stride = a.w_stride;
+    sa.rank_row = s.rank_row;
+    sa.staging = g->staging; sa.msg_bytes = g->msg_bytes; sa.staging_slots = g->staging_slots;
+    sa.hdr_units = (int)(g->hdr_bytes / 16);
+    sa.totals = s.totals;
+    sa.T = h->T; sa.K = c.top_k; sa.H = c.hidden;
+    if (launch_dedup_send(sa, (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
+
+    LayoutArgs la;
+    la.topk = nullptr; la.topk_stride = 0;
+    la.expert_base = h->expert_base;
+    la.T = (int)g->staging_slots; la.K = c.top_k; la.E = c.num_experts; la.R = c.num_ranks;
+    la.L = g->L; la.L_shift = g->L_shift;
+    la.padded = c.mode == EP_MODE_LL; la.C = g->C; la.C_rank = c.max_tokens_per_rank;
+    la.n = (int)(g->staging_slots * c.top_k);
+    plan_layout(la.n, &la.passes, &la.nwc);
+    la.W = g->W; la.bits_e = g->bits_e; la.bits_r = g->bits_r;
+    la.hist = s.hist;
+    la.expert_count = s.recv_count; la.expert_kept = s.recv_kept; la.expert_offset = s.recv_offset;
+    la.own_prefix = s.recv_own_prefix;
+    la.rank_pair_count = nullptr; la.rank_token_count = nullptr; la.rank_offset = nullptr;
+    la.totals = s.recv_totals;
+    la.slot = nullptr; la.dst_row = s.recv_dst_row; la.rank_row = nullptr;
+    la.sorted_token = nullptr; la.sorted_k = nullptr; la.sorted_row = nullptr;
+    la.msgs = g->staging; la.msg_bytes = g->msg_bytes; la.msg_total_slots = (int)g->staging_slots;
+    la.msg_slots_per_rank = c.mode == EP_MODE_LL ? c.max_tokens_per_rank : 0;
+    la.msg_rank_offset = s.rank_offset; la.msg_rank_count = s.rank_token_count;
+    if (launch_layout(la, (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
+
+    DedupFanoutArgs fa;
+    fa.staging = g->staging; fa.msg_bytes = g->msg_bytes; fa.hdr_bytes = g->hdr_bytes;
+    fa.staging_slots = g->staging_slots; fa.slots_per_rank = la.msg_slots_per_rank;
+    fa.rank_offset = s.rank_offset; fa.rank_count = s.rank_token_count;
+    fa.recv_dst_row = s.recv_dst_row; fa.recv_kept = s.recv_kept;
+    fa.win = a.win; fa.recv_w = a.recv_w; fa.recv_src = a.recv_src; fa.recv_count = a.recv_count;
+    fa.totals = s.totals;
+    fa.K = c.top_k; fa.H = c.hidden; fa.E = c.num_experts; fa.R = c.num_ranks;
+    return launch_dedup_fanout(fa, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
 }
 
 ep_result_t ep_combine(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inputs,

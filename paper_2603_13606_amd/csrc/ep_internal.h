@@ -38,8 +38,7 @@ struct LayoutArgs {
     int nwc;                  // number of wave-chunks
     int W;                    // histogram width: E experts + masked + invalid + R ranks
     int bits_e, bits_r;       // key widths for the in-wave match
-    int32_t* hist;            // [nwc, W] scratch
-    int32_t* coltotal;        // [W] scratch
+    int32_t* hist;            // [chunks, W] scratch, chunks <= kMaxWaveChunks
     int32_t* expert_count;    // [E]
     int32_t* expert_kept;     // [E]
     int32_t* expert_offset;   // [E+1]
@@ -54,6 +53,15 @@ struct LayoutArgs {
     int32_t* sorted_token;    // [n]
     int32_t* sorted_k;        // [n]
     int32_t* sorted_row;      // [n]
+    // Message mode (receiving side of the once-per-rank path): entries are the
+    // routing vectors in the headers of the staged messages; slot, rank_row,
+    // sorted_* and the rank arrays may then be nullptr.
+    const uint8_t* msgs;      // staging windows, or nullptr for the sender-side layout
+    int64_t msg_bytes;        // bytes per message slot
+    int msg_total_slots;      // slots in the staging windows
+    int msg_slots_per_rank;   // > 0: fixed-size window per rank; 0: compact windows
+    const int32_t* msg_rank_offset;  // [R+1] first slot of each rank's window
+    const int32_t* msg_rank_count;   // [R]   messages in each rank's window
 };
 
 // Addressing of the receive windows: element offset of logical row r is
@@ -92,7 +100,42 @@ struct CombineArgs {
     int T, K, H;
 };
 
+struct DedupSendArgs {
+    const uint16_t* x;
+    int64_t x_stride;
+    const int32_t* topk;
+    int64_t topk_stride;
+    const float* w;           // [T, K] or nullptr (header then carries 1.0)
+    int64_t w_stride;
+    const int32_t* rank_row;  // [T, K] staging slot for the first k naming a rank, else -1
+    uint8_t* staging;
+    int64_t msg_bytes;
+    int64_t staging_slots;
+    int hdr_units;            // header size in 16-byte units
+    int32_t* totals;
+    int T, K, H;
+};
+
+struct DedupFanoutArgs {
+    const uint8_t* staging;
+    int64_t msg_bytes, hdr_bytes;
+    int64_t staging_slots;
+    int slots_per_rank;            // > 0: fixed-size window per rank; 0: compact windows
+    const int32_t* rank_offset;    // [R+1]
+    const int32_t* rank_count;     // [R]
+    const int32_t* recv_dst_row;   // [staging_slots, K]
+    const int32_t* recv_kept;      // [E]
+    WindowDesc win;
+    float* recv_w;
+    int32_t* recv_src;
+    int32_t* recv_count;
+    int32_t* totals;
+    int K, H, E, R;
+};
+
 hipError_t launch_layout(const LayoutArgs& a, hipStream_t s);
+hipError_t launch_dedup_send(const DedupSendArgs& a, hipStream_t s);
+hipError_t launch_dedup_fanout(const DedupFanoutArgs& a, hipStream_t s);
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s);
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s);

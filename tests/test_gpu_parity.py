@@ -473,3 +473,97 @@ def test_argument_errors_on_device(ep, hx):
         ep.ep_handle_destroy(h)
     finally:
         ep.ep_group_destroy(g)
+
+
+# ------------------------------------------------------------------------------ once per destination rank
+
+DEDUP_CASES = [
+    # name, T, H, mode, C, weights
+    ("tiny", None, None, "ht", 0, True),
+    ("tiny", None, None, "ll", 6, True),
+    ("ll_decode", None, 512, "ll", 0, True),
+    ("ll_decode", 100, None, "ll", 5, False),
+    ("skew", 700, 1000, "ht", 0, True),
+    ("skew_rank0", 900, 256, "ll", 60, True),
+    ("stress_hot", 600, 128, "ht", 0, True),
+    ("ht_prefill", None, None, "ht", 0, True),   # full benchmark shape
+]
+
+
+@pytest.mark.parametrize("name,T,H,mode,C,weights", DEDUP_CASES)
+def test_once_per_rank_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, weights):
+    """Staging windows byte-for-byte equal to the oracle's messages; final windows equal to
+    the oracle's direct dispatch (and to its own fan-out)."""
+    w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
+    spec = w.spec
+    T = spec.T
+    _say(f"once-per-rank case {name} T={T} H={spec.H} mode={mode} C={C}")
+    topk = _mess_up(w.topk_idx, spec.E, seed=T, frac_masked=0.02)
+    ll = mode == "ll"
+    Cc = (C if C else T) if ll else 0
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, layout=int(ll), C=Cc, C_rank=T)
+    rows = spec.E * Cc if ll else int(lay.expert_offset[-1])
+    n_slots = spec.R * T if ll else T * min(spec.R, spec.K)
+    wts = w.topk_w if weights else None
+    o_win = oracle_mod.dedup_send(w.x_bits, topk, wts, lay, n_slots)
+    o_recv = np.full((rows + 1, spec.H), hx.POISON, np.uint16)
+    o_w = np.full(rows + 1, np.float32(-3.5), np.float32)
+    o_src = np.full(rows + 1, -9, np.int32)
+    oracle_mod.dispatch(w.x_bits, wts, lay, o_recv, o_w, o_src)
+    if not weights:
+        o_w[:rows][o_src[:rows] >= 0] = 1.0  # the header carries 1.0 when no weights are given
+    v_recv = np.full((rows + 1, spec.H), hx.POISON, np.uint16)
+    v_w = np.full(rows + 1, np.float32(-3.5), np.float32)
+    v_src = np.full(rows + 1, -9, np.int32)
+    o_cnt, o_drop = oracle_mod.dedup_recv(o_win, lay, spec.H, v_recv, v_w, v_src)
+    assert np.array_equal(v_recv, o_recv) and np.array_equal(v_src, o_src) and np.array_equal(v_w, o_w)
+
+    held = {}
+
+    def alloc(pp, nbytes):
+        t = torch.full((int(nbytes),), 0xA5, dtype=torch.uint8, device=hx.DEV)
+        held[t.data_ptr()] = t
+        pp[0] = t.data_ptr()
+        return 0
+
+    def free(p):
+        return 0 if held.pop(p, None) is not None else 1
+
+    a_fn, f_fn = ep.ALLOC_FN(alloc), ep.FREE_FN(free)
+    cfg = ep.make_config(spec.R, spec.E, spec.H, spec.K, T, mode=ep.EP_MODE_LL if ll else ep.EP_MODE_HT,
+                         slots_per_subregion=C, dispatch_path=ep.EP_PATH_RANK_DEDUP)
+    g = ep.ep_group_create(cfg, alloc_fn=a_fn, free_fn=f_fn)
+    try:
+        ginfo = ep.ep_group_query(g)
+        assert ginfo.staging_slots == n_slots and ginfo.msg_bytes == o_win.shape[1]
+        assert ginfo.msg_header_bytes == oracle_mod.msg_header_bytes(spec.K)
+        staging = held[ginfo.staging]
+        d_topk = torch.from_numpy(topk).to(hx.DEV)
+        h = ep.ep_layout(g, d_topk)
+        store = hx.poison_bf16((rows + 1, spec.H))
+        recv = store[:rows].view(spec.E, Cc, spec.H) if ll else store[:rows]
+        r_w = torch.full((rows + 1,), -3.5, dtype=torch.float32, device=hx.DEV)
+        r_src = torch.full((rows + 1,), -9, dtype=torch.int32, device=hx.DEV)
+        r_cnt = torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)
+        ep.ep_dispatch(h, hx.bits_to_dev(w.x_bits), recv, topk_weights=torch.from_numpy(w.topk_w).to(hx.DEV) if weights else None,
+                       recv_w=r_w[:rows], recv_src=r_src[:rows], recv_count=r_cnt, topk_idx=d_topk)
+        torch.cuda.synchronize()
+        got_win = staging[: n_slots * ginfo.msg_bytes].cpu().numpy().reshape(n_slots, ginfo.msg_bytes)
+        assert np.array_equal(got_win, o_win), "staging windows differ from the oracle's messages"
+        assert np.array_equal(hx.dev_to_bits(store), o_recv), "fanned-out rows differ"
+        assert np.array_equal(r_src.cpu().numpy(), o_src)
+        assert np.array_equal(r_w.cpu().numpy(), o_w)
+        assert np.array_equal(r_cnt.cpu().numpy(), lay.expert_kept) and np.array_equal(o_cnt, lay.expert_kept)
+        info = ep.ep_handle_query(h)
+        assert int(info.rank_messages) == lay.n_msgs
+        # the direct-path dispatch of another group must give the same windows
+        ep.ep_handle_destroy(h)
+        with pytest.raises(ep.EpError):
+            h2 = ep.ep_layout(g, d_topk)
+            try:
+                ep.ep_dispatch(h2, hx.bits_to_dev(w.x_bits), recv)  # TOPK_IDX is required on this path
+            finally:
+                ep.ep_handle_destroy(h2)
+    finally:
+        ep.ep_group_destroy(g)
+    assert not held
