@@ -12,9 +12,10 @@ namespace ep {
 constexpr int kWave = 64;            // CDNA wavefront width
 constexpr int kMaxExperts = 1024;
 constexpr int kMaxTopK = 64;
-constexpr int kMaxWaveChunks = 256;  // rows of the per-wave-chunk histogram matrix
-constexpr int kFusedMaxEntries = 4096;
-constexpr int kFusedWaves = 16;
+constexpr int kMaxWaveChunks = 256;        // wave-chunks per layout, and rows of the chunk histogram scratch
+constexpr int kLayoutWavesPerBlock = 16;   // wavefronts of the single workgroup that lays out a small input
+constexpr int kLayoutWavesPerChunk = 8;    // wavefronts per workgroup (chunk) for larger inputs
+constexpr int kLayoutOneBlockEntries = 4096;  // inputs up to this size are laid out by one workgroup
 constexpr int kTotalsWords = 16;
 
 // indices into the device totals block

@@ -4,19 +4,21 @@
 //
 // The slot of entry i = t*K + k is the number of entries j < i naming the same
 // expert: a stable counting sort.  The flattened entry list is cut into chunks,
-// one per workgroup, and every chunk into wave-chunks of 64*passes consecutive
-// entries, one per wavefront.
-//   count kernel  each workgroup histograms its chunk (bins: E experts, masked,
-//                 invalid, R destination ranks) with LDS integer atomics --
-//                 counts do not depend on the order of the additions;
-//   slot kernel   each workgroup sums the histograms of the chunks before it
+// one per workgroup of up to 16 wavefronts, and every chunk into wave-chunks of
+// 64*passes consecutive entries, one per wavefront.
+//   count kernel  (only when there is more than one chunk) each workgroup
+//                 histograms its chunk -- bins: E experts, masked, invalid, R
+//                 destination ranks -- with LDS integer atomics; counts do not
+//                 depend on the order of the additions;
+//   slot kernel   each workgroup adds up the histograms of the chunks before it
 //                 (its prefix) and of all chunks (the totals, hence the expert
-//                 offsets), histograms its own wave-chunks again to split the
-//                 prefix per wave, then each wave walks its entries 64 at a
-//                 time: slot = prefix of the bin + number of lower lanes with
-//                 the same key, found with one ballot per key bit.
+//                 offsets), histograms its own wave-chunks to split the prefix
+//                 per wave, then every wave walks its entries 64 at a time:
+//                 slot = prefix of the bin + number of lower lanes holding the
+//                 same key, found with one ballot per key bit.
 // No atomic decides an order anywhere, so the output is a pure function of the
-// input.  Inputs of at most 4096 entries run both steps inside one workgroup.
+// input.  The work is latency bound, so every phase issues all of its global
+// loads before it waits for any of them.
 //
 // The same kernels serve the receiving side of the once-per-rank dispatch
 // (Sec. IV-D): there the entries are the routing vectors found in the headers of
@@ -27,13 +29,23 @@
 namespace ep {
 namespace {
 
-__device__ __forceinline__ int lane_id() {
-    return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+constexpr int PU = 4;  // passes whose loads are issued together
+
+// Workgroup barrier that orders LDS traffic only: global loads issued before it stay
+// in flight across it (a full __syncthreads() would wait for them).
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-__device__ __forceinline__ void wave_fence() {
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+__device__ __forceinline__ void wave_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
     __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ int lane_id() {
+    return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
 }
 
 // Lanes (among those with valid == true) that hold the same key as this lane.
@@ -52,6 +64,7 @@ __device__ __forceinline__ int owner_of(const LayoutArgs& a, int e) {
 }
 
 struct Entry {
+    int i;         // flattened index, or -1 beyond the input
     int t, k, e, d;
     bool ok;       // names an expert that gets a row
     bool masked;   // id == -1
@@ -59,243 +72,30 @@ struct Entry {
     bool lead;     // first k of its token that names destination rank d
 };
 
-// Message mode: which destination rank's window holds staging slot m, and is the
-// slot in use.  mroff / mcnt are LDS copies of rank_offset / rank_token_count.
-__device__ __forceinline__ bool msg_slot_rank(const LayoutArgs& a, int m, const int32_t* mroff,
-                                              const int32_t* mcnt, int* d_out) {
-    if (m >= a.msg_total_slots) return false;
-    if (a.msg_slots_per_rank > 0) {  // fixed-size window per rank
-        const int d = m / a.msg_slots_per_rank;
-        *d_out = d;
-        return (m - d * a.msg_slots_per_rank) < mcnt[d];
-    }
-    if (m >= mroff[a.R]) return false;  // compact windows: [rank_offset[d], rank_offset[d+1])
-    int lo = 0, hi = a.R;               // largest d with rank_offset[d] <= m
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (mroff[mid] <= m) lo = mid; else hi = mid;
-    }
-    *d_out = lo;
-    return true;
-}
-
-__device__ __forceinline__ Entry load_entry(const LayoutArgs& a, int i, const int32_t* mroff,
-                                            const int32_t* mcnt) {
-    Entry en;
-    en.t = 0; en.k = 0; en.e = 0; en.d = 0;
-    en.ok = en.masked = en.invalid = en.lead = false;
-    if (i >= a.n) return en;
-    en.t = i / a.K;
-    en.k = i - en.t * a.K;
-    if (a.msgs) {
-        int d = 0;
-        if (!msg_slot_rank(a, en.t, mroff, mcnt, &d)) return en;
-        const int32_t* hdr = (const int32_t*)(a.msgs + (int64_t)en.t * a.msg_bytes);
-        const int e = hdr[1 + en.k];
-        en.ok = (unsigned)e < (unsigned)a.E && owner_of(a, e) == d;
-        en.e = en.ok ? e : 0;
-        en.d = d;
-        return en;
-    }
-    const int32_t* row = a.topk + (int64_t)en.t * a.topk_stride;
-    en.e = row[en.k];
-    en.ok = (unsigned)en.e < (unsigned)a.E;
-    en.masked = en.e == -1;
-    en.invalid = !en.ok && !en.masked;
-    if (en.ok) {
-        en.d = owner_of(a, en.e);
-        en.lead = true;
-        for (int k2 = 0; k2 < en.k; ++k2) {
-            const int e2 = row[k2];
-            if ((unsigned)e2 < (unsigned)a.E && owner_of(a, e2) == en.d) en.lead = false;
-        }
-    } else {
-        en.e = 0;
-    }
-    return en;
-}
-
-// Histogram of one wave-chunk into h[0..W) with LDS atomics (integer adds: the
-// result does not depend on their order).
-__device__ void wave_hist(const LayoutArgs& a, int wc, int32_t* h, int lane, const int32_t* mroff,
-                          const int32_t* mcnt) {
-    for (int p = 0; p < a.passes; ++p) {
-        const int i = (wc * a.passes + p) * kWave + lane;
-        const Entry en = load_entry(a, i, mroff, mcnt);
-        if (en.ok) atomicAdd(&h[en.e], 1);
-        if (en.masked) atomicAdd(&h[a.E], 1);
-        if (en.invalid) atomicAdd(&h[a.E + 1], 1);
-        if (en.lead) atomicAdd(&h[a.E + 2 + en.d], 1);
-    }
-}
-
-// Slot assignment for one wave-chunk: h holds, per bin, the number of entries of
-// that bin before this wave-chunk; it is advanced as the chunk is walked.
-__device__ void wave_slots(const LayoutArgs& a, int wc, int32_t* h, const int32_t* eoff,
-                           const int32_t* opre, const int32_t* roff, int lane, const int32_t* mroff,
-                           const int32_t* mcnt) {
-    const uint64_t lt = (1ull << lane) - 1ull;
-    for (int p = 0; p < a.passes; ++p) {
-        const int i = (wc * a.passes + p) * kWave + lane;
-        const Entry en = load_entry(a, i, mroff, mcnt);
-        const uint64_t peers = match_key(en.e, en.ok, a.bits_e);
-        const uint64_t peers_r = a.msgs ? 0ull : match_key(en.d, en.lead, a.bits_r);
-        const int rank = __popcll(peers & lt);
-        const int rank_r = __popcll(peers_r & lt);
-        int slot = -1, row = -1, rrow = -1;
-        if (en.ok) {
-            slot = h[en.e] + rank;
-            if (a.padded) row = slot < a.C ? en.e * a.C + slot : -1;
-            else row = eoff[en.e] + slot;
-            if (a.sorted_token) {
-                const int pos = opre[en.e] + slot;
-                a.sorted_token[pos] = en.t;
-                a.sorted_k[pos] = en.k;
-                a.sorted_row[pos] = row;
-            }
-        }
-        if (en.lead) rrow = roff[en.d] + h[a.E + 2 + en.d] + rank_r;
-        if (i < a.n) {
-            if (a.slot) a.slot[i] = slot;
-            a.dst_row[i] = row;
-            if (a.rank_row) a.rank_row[i] = rrow;
-        }
-        wave_fence();
-        if (en.ok && rank == 0) h[en.e] += __popcll(peers);
-        if (en.lead && rank_r == 0) h[a.E + 2 + en.d] += __popcll(peers_r);
-        wave_fence();
-    }
-}
-
-// Exclusive scan of in[0..n) into out[0..n], out[n] = total, by the whole block.
-// tmp needs blockDim.x / 64 + 1 ints.  Ends with a barrier.
-__device__ void block_exclusive_scan(const int32_t* in, int32_t* out, int n, int32_t* tmp) {
-    const int tid = threadIdx.x, nth = blockDim.x;
-    const int lane = tid & (kWave - 1), w = tid >> 6, nw = (nth + kWave - 1) >> 6;
-    const int ipt = (n + nth - 1) / nth;
-    const int start = tid * ipt;
-    int sum = 0;
-    for (int j = 0; j < ipt; ++j) {
-        const int idx = start + j;
-        if (idx < n) sum += in[idx];
-    }
-    int inc = sum;
-    for (int off = 1; off < kWave; off <<= 1) {
-        const int v = __shfl_up(inc, off, kWave);
-        if (lane >= off) inc += v;
-    }
-    if (lane == kWave - 1) tmp[w] = inc;
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int j = 0; j < nw; ++j) { const int v = tmp[j]; tmp[j] = run; run += v; }
-        tmp[nw] = run;
-    }
-    __syncthreads();
-    int run = tmp[w] + inc - sum;
-    for (int j = 0; j < ipt; ++j) {
-        const int idx = start + j;
-        if (idx < n) { const int v = in[idx]; out[idx] = run; run += v; }
-    }
-    if (tid == 0) out[n] = tmp[nw];
-    __syncthreads();
-}
-
-// From the column totals tot[0..W): offsets for the slot walk (in LDS) and, when
-// write_global is set, the per-expert / per-rank arrays and the totals block.
-// red: 4 ints of LDS for reductions.  Ends with a barrier.
-__device__ void finalize_counts(const LayoutArgs& a, const int32_t* tot, int32_t* eoff,
-                                int32_t* opre, int32_t* roff, int32_t* tmp, int32_t* red,
-                                bool write_global) {
-    const int tid = threadIdx.x, nth = blockDim.x;
-    if (tid < 4) red[tid] = 0;
-    block_exclusive_scan(tot, opre, a.E, tmp);  // own_prefix: scan of the demand per expert
-    if (a.padded) {
-        for (int e = tid; e <= a.E; e += nth) eoff[e] = e * a.C;
-    } else if (a.expert_base) {
-        for (int e = tid; e < a.E; e += nth) {
-            const int b = a.expert_base[e];
-            eoff[e] = b;
-            if (tot[e] > 0) atomicMax(&red[2], b + tot[e]);
-        }
-    } else {
-        for (int e = tid; e <= a.E; e += nth) eoff[e] = opre[e];
-    }
-    if (a.padded) {  // staging windows: one region per destination rank
-        for (int d = tid; d <= a.R; d += nth) roff[d] = d * a.C_rank;
-        __syncthreads();
-    } else {
-        block_exclusive_scan(tot + a.E + 2, roff, a.R, tmp);
-    }
-    int kept = 0, dropped = 0;
-    for (int e = tid; e < a.E; e += nth) {
-        const int c = tot[e];
-        const int k = a.padded ? min(c, a.C) : c;
-        kept += k;
-        dropped += c - k;
-        if (write_global) {
-            a.expert_count[e] = c;
-            a.expert_kept[e] = k;
-        }
-    }
-    if (kept) atomicAdd(&red[0], kept);
-    if (dropped) atomicAdd(&red[1], dropped);
-    __syncthreads();
-    if (!a.padded && a.expert_base && tid == 0) eoff[a.E] = red[2];
-    __syncthreads();
-    if (write_global) {
-        for (int e = tid; e <= a.E; e += nth) {
-            a.expert_offset[e] = eoff[e];
-            a.own_prefix[e] = opre[e];
-        }
-        if (a.rank_pair_count) {
-            for (int d = tid; d < a.R; d += nth) {
-                int s = 0;
-                for (int l = 0; l < a.L; ++l) s += tot[d * a.L + l];
-                a.rank_pair_count[d] = s;
-                a.rank_token_count[d] = tot[a.E + 2 + d];
-            }
-            for (int d = tid; d <= a.R; d += nth) a.rank_offset[d] = roff[d];
-        }
-        if (tid == 0) {
-            int msgs = 0;
-            for (int d = 0; d < a.R; ++d) msgs += tot[a.E + 2 + d];
-            const int masked = tot[a.E], invalid = tot[a.E + 1];
-            a.totals[TOT_KEPT] = red[0];
-            a.totals[TOT_DROPPED] = red[1];
-            a.totals[TOT_MASKED] = masked;
-            a.totals[TOT_INVALID] = invalid;
-            a.totals[TOT_SORTED] = opre[a.E];
-            a.totals[TOT_MSGS] = msgs;
-            a.totals[TOT_STATUS] = (invalid ? STATUS_INVALID_IDS : 0) | (red[1] ? STATUS_CAPACITY_DROP : 0);
-            a.totals[TOT_ROWS_END] = eoff[a.E];
-        }
-    }
-    __syncthreads();
-}
-
-// LDS carve-up shared by the kernels: [nw][W] wave histograms, tot[W], eoff[E+1],
-// opre[E+1], roff[R+1], mroff[R+1], mcnt[R], tmp[nw+1], red[4].
+// LDS carve-up shared by the kernels.
 struct Lds {
-    int32_t *wh, *tot, *eoff, *opre, *roff, *mroff, *mcnt, *tmp, *red;
+    int32_t *wh;     // [nw][W] per-wave histograms, later per-wave prefixes
+    int32_t *tot;    // [W] totals over the whole input
+    int32_t *pre;    // [W] entries of each bin in earlier chunks
+    int32_t *eoff, *opre, *roff;  // [E+1], [E+1], [R+1]
+    int32_t *mroff, *mcnt;        // message mode: rank_offset [R+1], rank_token_count [R]
 };
 
 __device__ __forceinline__ Lds carve_lds(int32_t* base, const LayoutArgs& a, int nw) {
     Lds l;
     l.wh = base;
     l.tot = l.wh + nw * a.W;
-    l.eoff = l.tot + a.W;
+    l.pre = l.tot + a.W;
+    l.eoff = l.pre + a.W;
     l.opre = l.eoff + a.E + 1;
     l.roff = l.opre + a.E + 1;
     l.mroff = l.roff + a.R + 1;
     l.mcnt = l.mroff + a.R + 1;
-    l.tmp = l.mcnt + a.R;
-    l.red = l.tmp + nw + 1;
     return l;
 }
 
 size_t lds_bytes(const LayoutArgs& a, int nw) {
-    return sizeof(int32_t) * ((size_t)nw * a.W + a.W + 2 * (a.E + 1) + 2 * (a.R + 1) + a.R + nw + 1 + 4);
+    return sizeof(int32_t) * ((size_t)nw * a.W + 2 * a.W + 2 * (a.E + 1) + 2 * (a.R + 1) + a.R);
 }
 
 __device__ __forceinline__ void stage_msg_tables(const LayoutArgs& a, const Lds& l) {
@@ -304,36 +104,265 @@ __device__ __forceinline__ void stage_msg_tables(const LayoutArgs& a, const Lds&
     for (int d = threadIdx.x; d < a.R; d += blockDim.x) l.mcnt[d] = a.msg_rank_count[d];
 }
 
-// ---- one-launch path: everything inside one workgroup of kFusedWaves waves ----
-__global__ __launch_bounds__(kFusedWaves* kWave) void layout_fused_kernel(LayoutArgs a) {
-    extern __shared__ int32_t lds[];
-    const Lds l = carve_lds(lds, a, kFusedWaves);
-    const int W = a.W;
-    const int tid = threadIdx.x;
-    const int lane = lane_id();
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    for (int j = tid; j < kFusedWaves * W; j += blockDim.x) l.wh[j] = 0;
-    stage_msg_tables(a, l);
-    __syncthreads();
-    if (w < a.nwc) wave_hist(a, w, l.wh + w * W, lane, l.mroff, l.mcnt);
-    __syncthreads();
-    for (int c = tid; c < W; c += blockDim.x) {
-        int run = 0;
-        for (int r = 0; r < kFusedWaves; ++r) {
-            const int v = l.wh[r * W + c];
-            l.wh[r * W + c] = run;
-            run += v;
-        }
-        l.tot[c] = run;
+// Message mode: which destination rank's window holds staging slot m, and is the
+// slot in use.
+__device__ __forceinline__ bool msg_slot_rank(const LayoutArgs& a, int m, const Lds& l, int* d_out) {
+    if (m >= a.msg_total_slots) return false;
+    if (a.msg_slots_per_rank > 0) {  // fixed-size window per rank
+        const int d = m / a.msg_slots_per_rank;
+        *d_out = d;
+        return (m - d * a.msg_slots_per_rank) < l.mcnt[d];
     }
-    __syncthreads();
-    finalize_counts(a, l.tot, l.eoff, l.opre, l.roff, l.tmp, l.red, true);
-    if (w < a.nwc) wave_slots(a, w, l.wh + w * W, l.eoff, l.opre, l.roff, lane, l.mroff, l.mcnt);
+    if (m >= l.mroff[a.R]) return false;  // compact windows: [rank_offset[d], rank_offset[d+1])
+    int lo = 0, hi = a.R;                 // largest d with rank_offset[d] <= m
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (l.mroff[mid] <= m) lo = mid; else hi = mid;
+    }
+    *d_out = lo;
+    return true;
 }
 
-// ---- two-launch path -------------------------------------------------------------
+// Marks the entries that are the first of their token to name their destination
+// rank.  The entries of a token sit in consecutive lanes, so lane l compares its
+// rank with the ranks held by lanes l-1 .. l-k (one cross-lane read each); only
+// when a token began before lane 0 are its earlier entries read from memory.
+// Must be called by all 64 lanes.
+__device__ __forceinline__ void mark_leaders(const LayoutArgs& a, Entry& en, int lane) {
+    const int dkey = en.ok ? en.d : -1;
+    bool lead = en.ok;
+    for (int j = 1; j < a.K; ++j) {
+        const int prev = __shfl_up(dkey, j, kWave);
+        if (j <= en.k && j <= lane && prev == dkey) lead = false;
+    }
+    if (en.ok && en.k > lane) {  // entries of this token that precede lane 0 of this pass
+        const int32_t* row = a.topk + (int64_t)en.t * a.topk_stride;
+        for (int k2 = 0; k2 < en.k - lane; ++k2) {
+            const int e2 = row[k2];
+            if ((unsigned)e2 < (unsigned)a.E && owner_of(a, e2) == en.d) lead = false;
+        }
+    }
+    en.lead = lead;
+}
+
+// Issues the global loads of the ids of passes p0 .. p0+PU-1 of wave-chunk wc
+// (nothing waits on them here).  In message mode the LDS tables must be staged.
+__device__ __forceinline__ void issue_group(const LayoutArgs& a, int wc, int p0, int lane, const Lds& l,
+                                            int (&raw)[PU], int (&dwin)[PU]) {
+#pragma unroll
+    for (int j = 0; j < PU; ++j) {
+        const int p = p0 + j;
+        const int i = (wc * a.passes + p) * kWave + lane;
+        raw[j] = 0;
+        dwin[j] = -1;
+        if (p < a.passes && i < a.n) {
+            const int t = i / a.K, k = i - t * a.K;
+            if (a.msgs) {
+                int d = 0;
+                if (msg_slot_rank(a, t, l, &d)) {
+                    dwin[j] = d;
+                    raw[j] = ((const int32_t*)(a.msgs + (int64_t)t * a.msg_bytes))[1 + k];
+                }
+            } else {
+                raw[j] = a.topk[(int64_t)t * a.topk_stride + k];
+            }
+        }
+    }
+}
+
+// Classifies the ids loaded by issue_group.  Must be called by all 64 lanes.
+__device__ __forceinline__ void classify_group(const LayoutArgs& a, int wc, int p0, int lane,
+                                               const int (&raw)[PU], const int (&dwin)[PU], Entry (&en)[PU]) {
+#pragma unroll
+    for (int j = 0; j < PU; ++j) {
+        Entry& x = en[j];
+        const int p = p0 + j;
+        const int i = (wc * a.passes + p) * kWave + lane;
+        const bool in = p < a.passes && i < a.n;
+        x.i = in ? i : -1;
+        x.t = in ? i / a.K : 0;
+        x.k = in ? i - x.t * a.K : 0;
+        const int e = raw[j];
+        const bool inrange = (unsigned)e < (unsigned)a.E;
+        x.d = inrange ? owner_of(a, e) : 0;
+        if (a.msgs) {
+            x.ok = in && dwin[j] >= 0 && inrange && x.d == dwin[j];
+            x.masked = x.invalid = x.lead = false;
+        } else {
+            x.ok = in && inrange;
+            x.masked = in && e == -1;
+            x.invalid = in && !inrange && e != -1;
+            if (p < a.passes) mark_leaders(a, x, lane);  // wave-uniform condition
+            else x.lead = false;
+        }
+        x.e = x.ok ? e : 0;
+    }
+}
+
+__device__ __forceinline__ void load_group(const LayoutArgs& a, int wc, int p0, int lane, const Lds& l,
+                                           Entry (&en)[PU]) {
+    int raw[PU], dwin[PU];
+    issue_group(a, wc, p0, lane, l, raw, dwin);
+    classify_group(a, wc, p0, lane, raw, dwin, en);
+}
+
+// Histogram of a loaded group into h[0..W) with LDS atomics (integer adds: the
+// result does not depend on their order).
+__device__ __forceinline__ void hist_group(const LayoutArgs& a, const Entry (&en)[PU], int32_t* h) {
+#pragma unroll
+    for (int j = 0; j < PU; ++j) {
+        if (en[j].ok) atomicAdd(&h[en[j].e], 1);
+        if (en[j].masked) atomicAdd(&h[a.E], 1);
+        if (en[j].invalid) atomicAdd(&h[a.E + 1], 1);
+        if (en[j].lead) atomicAdd(&h[a.E + 2 + en[j].d], 1);
+    }
+}
+
+// Slot assignment for a loaded group: h holds, per bin, the number of entries of
+// that bin before the group; it is advanced as the group is walked.  LDS accesses
+// of one wavefront are performed in program order, and the wave barriers keep the
+// compiler from moving them across each other.  Must be called by all 64 lanes.
+__device__ __forceinline__ void slots_group(const LayoutArgs& a, const Entry (&en)[PU], int p0, int32_t* h,
+                                            const Lds& l, int lane) {
+    const uint64_t lt = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int j = 0; j < PU; ++j) {
+        if (p0 + j >= a.passes) break;  // wave-uniform
+        const Entry& x = en[j];
+        const uint64_t peers = match_key(x.e, x.ok, a.bits_e);
+        const uint64_t peers_r = a.msgs ? 0ull : match_key(x.d, x.lead, a.bits_r);
+        const int rank = __popcll(peers & lt);
+        const int rank_r = __popcll(peers_r & lt);
+        int slot = -1, row = -1, rrow = -1;
+        if (x.ok) {
+            slot = h[x.e] + rank;
+            if (a.padded) row = slot < a.C ? x.e * a.C + slot : -1;
+            else row = l.eoff[x.e] + slot;
+        }
+        if (x.lead) rrow = l.roff[x.d] + h[a.E + 2 + x.d] + rank_r;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
+        if (x.ok && rank == 0) h[x.e] += __popcll(peers);
+        if (x.lead && rank_r == 0) h[a.E + 2 + x.d] += __popcll(peers_r);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
+        if (x.ok && a.sorted_token) {
+            const int pos = l.opre[x.e] + slot;
+            a.sorted_token[pos] = x.t;
+            a.sorted_k[pos] = x.k;
+            a.sorted_row[pos] = row;
+        }
+        if (x.i >= 0) {
+            if (a.slot) a.slot[x.i] = slot;
+            a.dst_row[x.i] = row;
+            if (a.rank_row) a.rank_row[x.i] = rrow;
+        }
+    }
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ int wave_max(int v) {
+    for (int off = kWave / 2; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off, kWave));
+    return v;
+}
+
+// From the totals tot[0..W): the offset tables of the slot walk (eoff, opre, roff in
+// LDS) and, when write_global is set, the per-expert / per-rank arrays and the
+// totals block in global memory.  Runs per WAVEFRONT without any workgroup barrier:
+// every wave computes the same values and stores them to the same LDS words, and
+// afterwards reads only words it has stored itself.  One exclusive scan S over all W
+// bins serves both prefix arrays: own_prefix[e] = S[e] and, for compact staging
+// windows, rank_offset[d] = S[E+2+d] - S[E+2].  Must be called by all 64 lanes,
+// after a barrier that makes tot[] final and pre[] free.
+__device__ void wave_offsets(const LayoutArgs& a, const Lds& l, int lane, bool write_global) {
+    const int32_t* tot = l.tot;
+    const int W = a.W, E = a.E, R = a.R;
+    const int ipt = (W + kWave - 1) / kWave;  // bins per lane, consecutive
+    const int start = lane * ipt;
+    int sum = 0;
+    for (int j = 0; j < ipt; ++j) {
+        const int c = start + j;
+        if (c < W) sum += tot[c];
+    }
+    int inc = sum;
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int v = __shfl_up(inc, off, kWave);
+        if (lane >= off) inc += v;
+    }
+    int run = inc - sum;
+    int32_t* S = l.pre;
+    for (int j = 0; j < ipt; ++j) {
+        const int c = start + j;
+        if (c < W) {
+            S[c] = run;
+            run += tot[c];
+        }
+    }
+    wave_lds_fence();
+    const int total_e = S[E];  // bins [0, E) are the experts, so S[E] is their sum
+    const int rbase = S[E + 2];
+    const int msgs = S[E + 1 + R] + tot[E + 1 + R] - rbase;
+    for (int e = lane; e <= E; e += kWave) {
+        const int op = S[e];  // S[E] = total
+        l.opre[e] = op;
+        int eo;
+        if (a.padded) eo = e * a.C;
+        else if (a.expert_base) eo = e < E ? a.expert_base[e] : 0;  // eoff[E] is only reported, see below
+        else eo = op;
+        l.eoff[e] = eo;
+    }
+    for (int d = lane; d <= R; d += kWave) {
+        int ro;
+        if (a.padded) ro = d * a.C_rank;
+        else ro = d < R ? S[E + 2 + d] - rbase : msgs;
+        l.roff[d] = ro;
+    }
+    wave_lds_fence();
+    if (!write_global) return;
+    int kept = 0, dropped = 0, rend = 0;
+    for (int e = lane; e < E; e += kWave) {
+        const int v = tot[e];
+        const int k = a.padded ? min(v, a.C) : v;
+        kept += k;
+        dropped += v - k;
+        if (!a.padded && a.expert_base && v > 0) rend = max(rend, l.eoff[e] + v);
+        a.expert_count[e] = v;
+        a.expert_kept[e] = k;
+        a.expert_offset[e] = l.eoff[e];
+        a.own_prefix[e] = l.opre[e];
+    }
+    kept = wave_sum(kept);
+    dropped = wave_sum(dropped);
+    rend = wave_max(rend);
+    const int rows_end = a.padded ? E * a.C : (a.expert_base ? rend : total_e);
+    if (a.rank_pair_count) {
+        for (int d = lane; d < R; d += kWave) {
+            a.rank_pair_count[d] = S[(d + 1) * a.L] - S[d * a.L];
+            a.rank_token_count[d] = tot[E + 2 + d];
+        }
+        for (int d = lane; d <= R; d += kWave) a.rank_offset[d] = l.roff[d];
+    }
+    if (lane == 0) {
+        const int masked = tot[E], invalid = tot[E + 1];
+        a.expert_offset[E] = rows_end;
+        a.own_prefix[E] = total_e;
+        a.totals[TOT_KEPT] = kept;
+        a.totals[TOT_DROPPED] = dropped;
+        a.totals[TOT_MASKED] = masked;
+        a.totals[TOT_INVALID] = invalid;
+        a.totals[TOT_SORTED] = total_e;
+        a.totals[TOT_MSGS] = msgs;
+        a.totals[TOT_STATUS] = (invalid ? STATUS_INVALID_IDS : 0) | (dropped ? STATUS_CAPACITY_DROP : 0);
+        a.totals[TOT_ROWS_END] = rows_end;
+    }
+}
+
 // Chunk b = wave-chunks [b*wpb, (b+1)*wpb).  Writes hist[b][0..W).
-__global__ void layout_count_kernel(LayoutArgs a) {
+__global__ __launch_bounds__(512) void layout_count_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
     const int wpb = blockDim.x >> 6;
     const Lds l = carve_lds(lds, a, 1);
@@ -342,16 +371,30 @@ __global__ void layout_count_kernel(LayoutArgs a) {
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wc = blockIdx.x * wpb + w;
+    const bool active = wc < a.nwc;
+    int raw[PU], dwin[PU];
+    if (active && !a.msgs) issue_group(a, wc, 0, lane, l, raw, dwin);  // in flight during the LDS set-up
     for (int j = tid; j < W; j += blockDim.x) l.wh[j] = 0;
     stage_msg_tables(a, l);
-    __syncthreads();
-    if (wc < a.nwc) wave_hist(a, wc, l.wh, lane, l.mroff, l.mcnt);
-    __syncthreads();
+    lds_barrier();
+    if (active) {
+        Entry en[PU];
+        for (int p0 = 0; p0 < a.passes; p0 += PU) {
+            if (a.msgs || p0 > 0) issue_group(a, wc, p0, lane, l, raw, dwin);
+            classify_group(a, wc, p0, lane, raw, dwin, en);
+            hist_group(a, en, l.wh);
+        }
+    }
+    lds_barrier();
     int32_t* g = a.hist + (int64_t)blockIdx.x * W;
     for (int j = tid; j < W; j += blockDim.x) g[j] = l.wh[j];
 }
 
-__global__ void layout_slot_kernel(LayoutArgs a) {
+// With one chunk (gridDim.x == 1) this kernel is the whole layout.  MAXT = largest
+// workgroup it is launched with; HB = chunk histograms whose words each thread loads
+// up front (thread = bin).
+template <int MAXT, int HB>
+__global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
     const int wpb = blockDim.x >> 6;
     const Lds l = carve_lds(lds, a, wpb);
@@ -361,67 +404,115 @@ __global__ void layout_slot_kernel(LayoutArgs a) {
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wc = blockIdx.x * wpb + w;
     const int nchunks = gridDim.x;
-    // Row 0 of wh will hold the chunk prefix (entries of each bin in earlier chunks);
-    // rows 1..wpb-1 first receive the histograms of this chunk's waves 0..wpb-2.
-    for (int j = tid; j < (wpb - 1) * W; j += blockDim.x) l.wh[W + j] = 0;
+    const int b = blockIdx.x;
+    const bool active = wc < a.nwc;
+    const bool one_group = a.passes <= PU;
+
+    // (1) issue every global load this workgroup needs up front: its own ids and the
+    //     other chunks' histograms (consumed in (3)); they stay in flight across the
+    //     LDS-only barrier
+    int raw[PU], dwin[PU];
+    if (active && !a.msgs) issue_group(a, wc, 0, lane, l, raw, dwin);
+    int hv[HB];  // column tid of the first HB chunk histograms
+    const int nrows = nchunks > 1 ? nchunks : 0;
+#pragma unroll
+    for (int r = 0; r < HB; ++r) hv[r] = (r < nrows && tid < W) ? a.hist[(int64_t)r * W + tid] : 0;
+    for (int j = tid; j < wpb * W + 2 * W; j += blockDim.x) l.wh[j] = 0;  // wh, tot, pre are contiguous
     stage_msg_tables(a, l);
-    __syncthreads();
-    if (w < wpb - 1 && wc < a.nwc) wave_hist(a, wc, l.wh + (w + 1) * W, lane, l.mroff, l.mcnt);
-    for (int c = tid; c < W; c += blockDim.x) {
-        int before = 0, total = 0;
-        const int32_t* col = a.hist + c;
-#pragma unroll 8
-        for (int r = 0; r < nchunks; ++r) {
-            const int v = col[(int64_t)r * W];
-            total += v;
-            if (r < (int)blockIdx.x) before += v;
+    lds_barrier();
+
+    // (2) per-wave histograms of this chunk
+    Entry en[PU];
+    if (active) {
+        for (int p0 = 0; p0 < a.passes; p0 += PU) {
+            if (a.msgs || p0 > 0) issue_group(a, wc, p0, lane, l, raw, dwin);
+            classify_group(a, wc, p0, lane, raw, dwin, en);
+            hist_group(a, en, l.wh + w * W);
         }
-        l.tot[c] = total;
-        l.wh[c] = before;
     }
-    __syncthreads();
-    // running sum down the rows: row r = entries of the bin before wave r of this chunk
+    // (3) totals over all chunks and the prefix of this chunk, per bin (thread = column)
+    if (nrows > 0) {
+        for (int c = tid; c < W; c += blockDim.x) {
+            int before = 0, total = 0;
+            if (c == tid) {
+#pragma unroll
+                for (int r = 0; r < HB; ++r) {
+                    total += hv[r];
+                    if (r < b) before += hv[r];
+                }
+            }
+            for (int r = (c == tid ? HB : 0); r < nrows; ++r) {
+                const int v = a.hist[(int64_t)r * W + c];
+                total += v;
+                if (r < b) before += v;
+            }
+            l.tot[c] = total;
+            l.pre[c] = before;
+        }
+    }
+    lds_barrier();
+    // (4) running sum down the waves: row r becomes "entries of the bin before wave r"
     for (int c = tid; c < W; c += blockDim.x) {
-        int run = l.wh[c];
-        for (int r = 1; r < wpb; ++r) {
+        int run = l.pre[c];
+        for (int r = 0; r < wpb; ++r) {
             const int v = l.wh[r * W + c];
-            run += v;
             l.wh[r * W + c] = run;
+            run += v;
+        }
+        if (nchunks == 1) l.tot[c] = run;
+    }
+    lds_barrier();
+    // (5) offset tables, per wave; wave 0 of chunk 0 also writes the global arrays
+    wave_offsets(a, l, lane, b == 0 && w == 0);
+    // (6) slots
+    if (active) {
+        for (int p0 = 0; p0 < a.passes; p0 += PU) {
+            if (!one_group) load_group(a, wc, p0, lane, l, en);
+            slots_group(a, en, p0, l.wh + w * W, l, lane);
         }
     }
-    __syncthreads();
-    finalize_counts(a, l.tot, l.eoff, l.opre, l.roff, l.tmp, l.red, blockIdx.x == 0);
-    if (wc < a.nwc) wave_slots(a, wc, l.wh + w * W, l.eoff, l.opre, l.roff, lane, l.mroff, l.mcnt);
 }
 
 constexpr size_t kLdsLimit = 64 * 1024;
 
 }  // namespace
 
-// Wave-chunk plan for n entries: small inputs fit one workgroup of kFusedWaves
-// waves; larger ones use at most kMaxWaveChunks wave-chunks.
+// Wave-chunk plan for n entries.  Up to kLayoutOneBlockEntries: one workgroup of 16
+// waves, 64*passes entries each (one launch).  Beyond: at least two passes per wave so
+// that there are fewer, fuller chunks, and at most kMaxWaveChunks wave-chunks.
 void plan_layout(int n, int* passes, int* nwc) {
-    const int max_wc = n <= kFusedMaxEntries ? kFusedWaves : kMaxWaveChunks;
-    int p = (n + kWave * max_wc - 1) / (kWave * max_wc);
+    int p;
+    if (n <= kLayoutOneBlockEntries) {
+        p = (n + kWave * kLayoutWavesPerBlock - 1) / (kWave * kLayoutWavesPerBlock);
+    } else {
+        p = (n + kWave * kMaxWaveChunks - 1) / (kWave * kMaxWaveChunks);
+        if (p < 2) p = 2;
+    }
     if (p < 1) p = 1;
     *passes = p;
     *nwc = (n + kWave * p - 1) / (kWave * p);
 }
 
 hipError_t launch_layout(const LayoutArgs& a, hipStream_t s) {
-    if (a.n <= kFusedMaxEntries && a.nwc <= kFusedWaves && lds_bytes(a, kFusedWaves) <= kLdsLimit) {
-        hipLaunchKernelGGL(layout_fused_kernel, dim3(1), dim3(kFusedWaves * kWave),
-                           lds_bytes(a, kFusedWaves), s, a);
-        return hipGetLastError();
+    // One workgroup of up to 16 waves when the plan has at most 16 wave-chunks and its
+    // LDS tables fit; otherwise chunks of at most 8 waves so that the walk is spread
+    // over many compute units while one thread per bin can add up the chunk histograms.
+    int wpb;
+    if (a.nwc <= kLayoutWavesPerBlock && lds_bytes(a, kLayoutWavesPerBlock) <= kLdsLimit) {
+        wpb = kLayoutWavesPerBlock;
+    } else {
+        wpb = kLayoutWavesPerChunk;
+        while (wpb > 1 && lds_bytes(a, wpb) > kLdsLimit) wpb >>= 1;
+        if (lds_bytes(a, wpb) > kLdsLimit) return hipErrorInvalidValue;
     }
-    int wpb = 4;
-    while (wpb > 1 && lds_bytes(a, wpb) > kLdsLimit) wpb >>= 1;
-    if (lds_bytes(a, wpb) > kLdsLimit) return hipErrorInvalidValue;
     int nblk = (a.nwc + wpb - 1) / wpb;
     if (nblk < 1) nblk = 1;
     if (nblk > kMaxWaveChunks) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(layout_count_kernel, dim3(nblk), dim3(wpb * kWave), lds_bytes(a, 1), s, a);
-    hipLaunchKernelGGL(layout_slot_kernel, dim3(nblk), dim3(wpb * kWave), lds_bytes(a, wpb), s, a);
+    const dim3 grid(nblk), block(wpb * kWave);
+    const size_t lds = lds_bytes(a, wpb);
+    if (nblk > 1) hipLaunchKernelGGL(layout_count_kernel, grid, block, lds_bytes(a, 1), s, a);
+    if (nblk == 1) hipLaunchKernelGGL((layout_slot_kernel<1024, 1>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((layout_slot_kernel<512, 32>), grid, block, lds, s, a);
     return hipGetLastError();
 }
 
