@@ -271,6 +271,68 @@ def ep_combine(handle, y: torch.Tensor, out: torch.Tensor, topk_weights: Optiona
                              _stream_ptr(stream)), "ep_combine")
 
 
+class PreparedCall:
+    """Descriptors of one ep_dispatch / ep_combine call built once and reused: the
+    per-call cost drops to a single foreign-function call.  The tensors must stay
+    alive and keep their shapes; only the handle and the stream change per call."""
+
+    def __init__(self, fn_name: str, ins, outs, send_only: int = 0):
+        self._fn = getattr(load(), fn_name)
+        self._name = fn_name
+        self._keep = [t for t, _ in ins] + [t for t, _ in outs]
+        self._ins, self._n_in = _descs(ins), len(ins)
+        self._outs, self._n_out = _descs(outs), len(outs)
+        self._send_only = send_only
+
+    def __call__(self, handle, stream_ptr: int = 0) -> None:
+        code = self._fn(handle, self._ins, self._n_in, self._outs, self._n_out, self._send_only, stream_ptr)
+        if code != EP_SUCCESS:
+            raise EpError(code, self._name)
+
+
+def prepare_dispatch(x, recv_x, topk_weights=None, recv_w=None, recv_src=None, recv_count=None,
+                     topk_idx=None) -> PreparedCall:
+    ins = [(x, EP_TAG_TOKENS)]
+    if topk_weights is not None:
+        ins.append((topk_weights, EP_TAG_TOPK_WEIGHTS))
+    if topk_idx is not None:
+        ins.append((topk_idx, EP_TAG_TOPK_IDX))
+    outs = [(recv_x, EP_TAG_TOKENS)]
+    if recv_w is not None:
+        outs.append((recv_w, EP_TAG_TOPK_WEIGHTS))
+    if recv_src is not None:
+        outs.append((recv_src, EP_TAG_RECV_SRC_TOKEN))
+    if recv_count is not None:
+        outs.append((recv_count, EP_TAG_RECV_EXPERT_COUNTER_DEVICE))
+    return PreparedCall("ep_dispatch", ins, outs)
+
+
+def prepare_combine(y, out, topk_weights=None) -> PreparedCall:
+    ins = [(y, EP_TAG_TOKENS)]
+    if topk_weights is not None:
+        ins.append((topk_weights, EP_TAG_TOPK_WEIGHTS))
+    return PreparedCall("ep_combine", ins, [(out, EP_TAG_TOKENS)])
+
+
+class PreparedLayout:
+    """ep_layout with its descriptors built once."""
+
+    def __init__(self, group, topk_idx, expert_base=None):
+        self._fn = load().ep_layout
+        self._group = group
+        self._keep = (topk_idx, expert_base)
+        self._td = tensor_desc(topk_idx, EP_TAG_TOPK_IDX)
+        self._bd = tensor_desc(expert_base, EP_TAG_EXPERT_BASE) if expert_base is not None else None
+
+    def __call__(self, stream_ptr: int = 0) -> ctypes.c_void_p:
+        h = ctypes.c_void_p()
+        code = self._fn(ctypes.byref(h), self._group, ctypes.byref(self._td),
+                        ctypes.byref(self._bd) if self._bd is not None else None, stream_ptr)
+        if code != EP_SUCCESS:
+            raise EpError(code, "ep_layout")
+        return h
+
+
 def read_device_i32(ptr: int, n: int) -> torch.Tensor:
     """Copy n int32 from a borrowed device pointer (as returned by ep_handle_query) to the host."""
     out = torch.empty(max(n, 0), dtype=torch.int32)

@@ -233,6 +233,8 @@ PATH_CASES = [
     ("skew", 1111, None, "ll", 139),
     ("skew", 1111, None, "ht", 0),
     ("ht_prefill", None, None, "ht", 0),   # full benchmark shape
+    ("skew", None, None, "ll", 512),       # full skewed shape, hot experts overflow C = 2*T*K/E
+    ("stress_hot", None, None, "ht", 0),   # full stress shape, 8 of 64 ranks take half the traffic
 ]
 
 
