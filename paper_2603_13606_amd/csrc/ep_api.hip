@@ -28,7 +28,7 @@ struct Slab {
 
 struct ep_group_s {
     ep_group_config_t cfg;
-    int L, L_shift, W, bits_e, bits_r;
+    int L, L_shift, K_shift, W, bits_e, bits_r;
     int C;       // slots per sub-region (LL)
     int64_t slab_ints;
     ep_alloc_fn alloc_fn;
@@ -231,8 +231,11 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     g->C = C;
     g->L = E / R;
     g->L_shift = -1;
-    for (int b = 0; b < 31; ++b)
+    g->K_shift = -1;
+    for (int b = 0; b < 31; ++b) {
         if ((1 << b) == g->L) g->L_shift = b;
+        if ((1 << b) == K) g->K_shift = b;
+    }
     g->W = E + 2 + R;
     g->bits_e = bits_for(E);
     g->bits_r = bits_for(R);
@@ -344,7 +347,7 @@ ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk
     a.topk = (const int32_t*)topk_idx->data;
     a.topk_stride = topk_idx->stride[0];
     a.expert_base = expert_base ? (const int32_t*)expert_base->data : nullptr;
-    a.T = (int)T; a.K = c.top_k; a.E = c.num_experts; a.R = c.num_ranks; a.L = g->L; a.L_shift = g->L_shift;
+    a.T = (int)T; a.K = c.top_k; a.E = c.num_experts; a.R = c.num_ranks; a.L = g->L; a.L_shift = g->L_shift; a.K_shift = g->K_shift;
     a.padded = c.mode == EP_MODE_LL; a.C = g->C; a.C_rank = c.max_tokens_per_rank;
     a.n = (int)(T * c.top_k);
     plan_layout(a.n, &a.passes, &a.nwc);
@@ -466,7 +469,7 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     la.topk = nullptr; la.topk_stride = 0;
     la.expert_base = h->expert_base;
     la.T = (int)g->staging_slots; la.K = c.top_k; la.E = c.num_experts; la.R = c.num_ranks;
-    la.L = g->L; la.L_shift = g->L_shift;
+    la.L = g->L; la.L_shift = g->L_shift; la.K_shift = g->K_shift;
     la.padded = c.mode == EP_MODE_LL; la.C = g->C; la.C_rank = c.max_tokens_per_rank;
     la.n = (int)(g->staging_slots * c.top_k);
     plan_layout(la.n, &la.passes, &la.nwc);

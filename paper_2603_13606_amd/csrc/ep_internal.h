@@ -31,6 +31,7 @@ struct LayoutArgs {
     const int32_t* expert_base;  // [E] or nullptr
     int T, K, E, R, L;
     int L_shift;              // log2(L) if L is a power of two, else -1
+    int K_shift;              // log2(K) if K is a power of two, else -1
     int padded;               // 1 = [E, C, H] layout
     int C;                    // slots per (expert, source) sub-region
     int C_rank;               // staging slots per destination rank in padded mode

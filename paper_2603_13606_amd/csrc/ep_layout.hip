@@ -59,6 +59,11 @@ __device__ __forceinline__ uint64_t match_key(int key, bool valid, int nbits) {
     return valid ? peers : 0ull;
 }
 
+// Token index of flattened entry i (i / K), with a shift when K is a power of two.
+__device__ __forceinline__ int token_of(const LayoutArgs& a, int i) {
+    return a.K_shift >= 0 ? (i >> a.K_shift) : (i / a.K);
+}
+
 __device__ __forceinline__ int owner_of(const LayoutArgs& a, int e) {
     return a.L_shift >= 0 ? (e >> a.L_shift) : (e / a.L);
 }
@@ -98,8 +103,9 @@ size_t lds_bytes(const LayoutArgs& a, int nw) {
     return sizeof(int32_t) * ((size_t)nw * a.W + 2 * a.W + 2 * (a.E + 1) + 2 * (a.R + 1) + a.R);
 }
 
+template <bool MSGS>
 __device__ __forceinline__ void stage_msg_tables(const LayoutArgs& a, const Lds& l) {
-    if (!a.msgs) return;
+    if (!MSGS) return;
     for (int d = threadIdx.x; d <= a.R; d += blockDim.x) l.mroff[d] = a.msg_rank_offset[d];
     for (int d = threadIdx.x; d < a.R; d += blockDim.x) l.mcnt[d] = a.msg_rank_count[d];
 }
@@ -147,6 +153,7 @@ __device__ __forceinline__ void mark_leaders(const LayoutArgs& a, Entry& en, int
 
 // Issues the global loads of the ids of passes p0 .. p0+PU-1 of wave-chunk wc
 // (nothing waits on them here).  In message mode the LDS tables must be staged.
+template <bool MSGS>
 __device__ __forceinline__ void issue_group(const LayoutArgs& a, int wc, int p0, int lane, const Lds& l,
                                             int (&raw)[PU], int (&dwin)[PU]) {
 #pragma unroll
@@ -156,8 +163,8 @@ __device__ __forceinline__ void issue_group(const LayoutArgs& a, int wc, int p0,
         raw[j] = 0;
         dwin[j] = -1;
         if (p < a.passes && i < a.n) {
-            const int t = i / a.K, k = i - t * a.K;
-            if (a.msgs) {
+            const int t = token_of(a, i), k = i - t * a.K;
+            if (MSGS) {
                 int d = 0;
                 if (msg_slot_rank(a, t, l, &d)) {
                     dwin[j] = d;
@@ -171,6 +178,7 @@ __device__ __forceinline__ void issue_group(const LayoutArgs& a, int wc, int p0,
 }
 
 // Classifies the ids loaded by issue_group.  Must be called by all 64 lanes.
+template <bool MSGS>
 __device__ __forceinline__ void classify_group(const LayoutArgs& a, int wc, int p0, int lane,
                                                const int (&raw)[PU], const int (&dwin)[PU], Entry (&en)[PU]) {
 #pragma unroll
@@ -180,12 +188,12 @@ __device__ __forceinline__ void classify_group(const LayoutArgs& a, int wc, int 
         const int i = (wc * a.passes + p) * kWave + lane;
         const bool in = p < a.passes && i < a.n;
         x.i = in ? i : -1;
-        x.t = in ? i / a.K : 0;
+        x.t = in ? token_of(a, i) : 0;
         x.k = in ? i - x.t * a.K : 0;
         const int e = raw[j];
         const bool inrange = (unsigned)e < (unsigned)a.E;
         x.d = inrange ? owner_of(a, e) : 0;
-        if (a.msgs) {
+        if (MSGS) {
             x.ok = in && dwin[j] >= 0 && inrange && x.d == dwin[j];
             x.masked = x.invalid = x.lead = false;
         } else {
@@ -199,11 +207,12 @@ __device__ __forceinline__ void classify_group(const LayoutArgs& a, int wc, int 
     }
 }
 
+template <bool MSGS>
 __device__ __forceinline__ void load_group(const LayoutArgs& a, int wc, int p0, int lane, const Lds& l,
                                            Entry (&en)[PU]) {
     int raw[PU], dwin[PU];
-    issue_group(a, wc, p0, lane, l, raw, dwin);
-    classify_group(a, wc, p0, lane, raw, dwin, en);
+    issue_group<MSGS>(a, wc, p0, lane, l, raw, dwin);
+    classify_group<MSGS>(a, wc, p0, lane, raw, dwin, en);
 }
 
 // Histogram of a loaded group into h[0..W) with LDS atomics (integer adds: the
@@ -222,6 +231,7 @@ __device__ __forceinline__ void hist_group(const LayoutArgs& a, const Entry (&en
 // that bin before the group; it is advanced as the group is walked.  LDS accesses
 // of one wavefront are performed in program order, and the wave barriers keep the
 // compiler from moving them across each other.  Must be called by all 64 lanes.
+template <bool MSGS>
 __device__ __forceinline__ void slots_group(const LayoutArgs& a, const Entry (&en)[PU], int p0, int32_t* h,
                                             const Lds& l, int lane) {
     const uint64_t lt = (1ull << lane) - 1ull;
@@ -230,7 +240,7 @@ __device__ __forceinline__ void slots_group(const LayoutArgs& a, const Entry (&e
         if (p0 + j >= a.passes) break;  // wave-uniform
         const Entry& x = en[j];
         const uint64_t peers = match_key(x.e, x.ok, a.bits_e);
-        const uint64_t peers_r = a.msgs ? 0ull : match_key(x.d, x.lead, a.bits_r);
+        const uint64_t peers_r = MSGS ? 0ull : match_key(x.d, x.lead, a.bits_r);
         const int rank = __popcll(peers & lt);
         const int rank_r = __popcll(peers_r & lt);
         int slot = -1, row = -1, rrow = -1;
@@ -271,58 +281,72 @@ __device__ __forceinline__ int wave_max(int v) {
 }
 
 // From the totals tot[0..W): the offset tables of the slot walk (eoff, opre, roff in
-// LDS) and, when write_global is set, the per-expert / per-rank arrays and the
-// totals block in global memory.  Runs per WAVEFRONT without any workgroup barrier:
+// LDS).  Runs per WAVEFRONT without any workgroup barrier:
 // every wave computes the same values and stores them to the same LDS words, and
 // afterwards reads only words it has stored itself.  One exclusive scan S over all W
 // bins serves both prefix arrays: own_prefix[e] = S[e] and, for compact staging
 // windows, rank_offset[d] = S[E+2+d] - S[E+2].  Must be called by all 64 lanes,
 // after a barrier that makes tot[] final and pre[] free.
-__device__ void wave_offsets(const LayoutArgs& a, const Lds& l, int lane, bool write_global) {
+__device__ void wave_offsets(const LayoutArgs& a, const Lds& l, int lane) {
     const int32_t* tot = l.tot;
     const int W = a.W, E = a.E, R = a.R;
     const int ipt = (W + kWave - 1) / kWave;  // bins per lane, consecutive
     const int start = lane * ipt;
+    constexpr int TV = 8;  // totals of up to TV own bins are kept in registers
+    int tv[TV];
+#pragma unroll
+    for (int j = 0; j < TV; ++j) tv[j] = (j < ipt && start + j < W) ? tot[start + j] : 0;
     int sum = 0;
-    for (int j = 0; j < ipt; ++j) {
-        const int c = start + j;
-        if (c < W) sum += tot[c];
-    }
+#pragma unroll
+    for (int j = 0; j < TV; ++j) sum += tv[j];
+    for (int j = TV; j < ipt; ++j)
+        if (start + j < W) sum += tot[start + j];
     int inc = sum;
     for (int off = 1; off < kWave; off <<= 1) {
         const int v = __shfl_up(inc, off, kWave);
         if (lane >= off) inc += v;
     }
+    // S of the first rank bin is held by the lane that owns bin E+2
+    const int owner = (E + 2) / ipt, jb = (E + 2) - owner * ipt;
+    int my_rbase = inc - sum;
+#pragma unroll
+    for (int j = 0; j < TV; ++j)
+        if (j < jb) my_rbase += tv[j];
+    for (int j = TV; j < jb; ++j) my_rbase += tot[start + j];
+    const int rbase = __shfl(my_rbase, owner, kWave);
+    const int grand = __shfl(inc, kWave - 1, kWave);  // sum over all W bins
     int run = inc - sum;
     int32_t* S = l.pre;
-    for (int j = 0; j < ipt; ++j) {
-        const int c = start + j;
-        if (c < W) {
-            S[c] = run;
-            run += tot[c];
+    auto emit = [&](int c, int v) {
+        S[c] = run;
+        if (c <= E) {  // bin E is "masked": S[E] = number of routed entries
+            l.opre[c] = run;
+            int eo;
+            if (a.padded) eo = c * a.C;
+            else if (a.expert_base) eo = c < E ? a.expert_base[c] : 0;  // eoff[E] is only reported
+            else eo = run;
+            l.eoff[c] = eo;
         }
-    }
+        if (c >= E + 2) l.roff[c - E - 2] = a.padded ? (c - E - 2) * a.C_rank : run - rbase;
+        run += v;
+    };
+#pragma unroll
+    for (int j = 0; j < TV; ++j)
+        if (j < ipt && start + j < W) emit(start + j, tv[j]);
+    for (int j = TV; j < ipt; ++j)
+        if (start + j < W) emit(start + j, tot[start + j]);
+    if (lane == 0) l.roff[R] = a.padded ? R * a.C_rank : grand - rbase;  // rank bins are the last R bins
     wave_lds_fence();
-    const int total_e = S[E];  // bins [0, E) are the experts, so S[E] is their sum
-    const int rbase = S[E + 2];
-    const int msgs = S[E + 1 + R] + tot[E + 1 + R] - rbase;
-    for (int e = lane; e <= E; e += kWave) {
-        const int op = S[e];  // S[E] = total
-        l.opre[e] = op;
-        int eo;
-        if (a.padded) eo = e * a.C;
-        else if (a.expert_base) eo = e < E ? a.expert_base[e] : 0;  // eoff[E] is only reported, see below
-        else eo = op;
-        l.eoff[e] = eo;
-    }
-    for (int d = lane; d <= R; d += kWave) {
-        int ro;
-        if (a.padded) ro = d * a.C_rank;
-        else ro = d < R ? S[E + 2 + d] - rbase : msgs;
-        l.roff[d] = ro;
-    }
-    wave_lds_fence();
-    if (!write_global) return;
+}
+
+// The per-expert / per-rank arrays and the totals block in global memory, from the
+// tables wave_offsets left in LDS.  One wavefront; must be called by all 64 lanes.
+__device__ void wave_write_tables(const LayoutArgs& a, const Lds& l, int lane) {
+    const int32_t* tot = l.tot;
+    const int32_t* S = l.pre;
+    const int E = a.E, R = a.R;
+    const int total_e = S[E];
+    const int msgs = S[E + 1 + R] + tot[E + 1 + R] - S[E + 2];
     int kept = 0, dropped = 0, rend = 0;
     for (int e = lane; e < E; e += kWave) {
         const int v = tot[e];
@@ -362,6 +386,7 @@ __device__ void wave_offsets(const LayoutArgs& a, const Lds& l, int lane, bool w
 }
 
 // Chunk b = wave-chunks [b*wpb, (b+1)*wpb).  Writes hist[b][0..W).
+template <bool MSGS>
 __global__ __launch_bounds__(512) void layout_count_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
     const int wpb = blockDim.x >> 6;
@@ -373,15 +398,15 @@ __global__ __launch_bounds__(512) void layout_count_kernel(LayoutArgs a) {
     const int wc = blockIdx.x * wpb + w;
     const bool active = wc < a.nwc;
     int raw[PU], dwin[PU];
-    if (active && !a.msgs) issue_group(a, wc, 0, lane, l, raw, dwin);  // in flight during the LDS set-up
+    if (active && !MSGS) issue_group<MSGS>(a, wc, 0, lane, l, raw, dwin);  // in flight during the LDS set-up
     for (int j = tid; j < W; j += blockDim.x) l.wh[j] = 0;
-    stage_msg_tables(a, l);
+    stage_msg_tables<MSGS>(a, l);
     lds_barrier();
     if (active) {
         Entry en[PU];
         for (int p0 = 0; p0 < a.passes; p0 += PU) {
-            if (a.msgs || p0 > 0) issue_group(a, wc, p0, lane, l, raw, dwin);
-            classify_group(a, wc, p0, lane, raw, dwin, en);
+            if (MSGS || p0 > 0) issue_group<MSGS>(a, wc, p0, lane, l, raw, dwin);
+            classify_group<MSGS>(a, wc, p0, lane, raw, dwin, en);
             hist_group(a, en, l.wh);
         }
     }
@@ -393,7 +418,7 @@ __global__ __launch_bounds__(512) void layout_count_kernel(LayoutArgs a) {
 // With one chunk (gridDim.x == 1) this kernel is the whole layout.  MAXT = largest
 // workgroup it is launched with; HB = chunk histograms whose words each thread loads
 // up front (thread = bin).
-template <int MAXT, int HB>
+template <int MAXT, int HB, bool MSGS>
 __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
     const int wpb = blockDim.x >> 6;
@@ -412,21 +437,21 @@ __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
     //     other chunks' histograms (consumed in (3)); they stay in flight across the
     //     LDS-only barrier
     int raw[PU], dwin[PU];
-    if (active && !a.msgs) issue_group(a, wc, 0, lane, l, raw, dwin);
+    if (active && !MSGS) issue_group<MSGS>(a, wc, 0, lane, l, raw, dwin);
     int hv[HB];  // column tid of the first HB chunk histograms
     const int nrows = nchunks > 1 ? nchunks : 0;
 #pragma unroll
     for (int r = 0; r < HB; ++r) hv[r] = (r < nrows && tid < W) ? a.hist[(int64_t)r * W + tid] : 0;
     for (int j = tid; j < wpb * W + 2 * W; j += blockDim.x) l.wh[j] = 0;  // wh, tot, pre are contiguous
-    stage_msg_tables(a, l);
+    stage_msg_tables<MSGS>(a, l);
     lds_barrier();
 
     // (2) per-wave histograms of this chunk
     Entry en[PU];
     if (active) {
         for (int p0 = 0; p0 < a.passes; p0 += PU) {
-            if (a.msgs || p0 > 0) issue_group(a, wc, p0, lane, l, raw, dwin);
-            classify_group(a, wc, p0, lane, raw, dwin, en);
+            if (MSGS || p0 > 0) issue_group<MSGS>(a, wc, p0, lane, l, raw, dwin);
+            classify_group<MSGS>(a, wc, p0, lane, raw, dwin, en);
             hist_group(a, en, l.wh + w * W);
         }
     }
@@ -462,15 +487,18 @@ __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
         if (nchunks == 1) l.tot[c] = run;
     }
     lds_barrier();
-    // (5) offset tables, per wave; wave 0 of chunk 0 also writes the global arrays
-    wave_offsets(a, l, lane, b == 0 && w == 0);
+    // (5) offset tables, per wave
+    wave_offsets(a, l, lane);
     // (6) slots
     if (active) {
         for (int p0 = 0; p0 < a.passes; p0 += PU) {
-            if (!one_group) load_group(a, wc, p0, lane, l, en);
-            slots_group(a, en, p0, l.wh + w * W, l, lane);
+            if (!one_group) load_group<MSGS>(a, wc, p0, lane, l, en);
+            slots_group<MSGS>(a, en, p0, l.wh + w * W, l, lane);
         }
     }
+    // (7) one wave publishes the per-expert / per-rank arrays and the totals; it does so
+    //     after its own slot walk so that the walk of the chunk is not held up
+    if (b == 0 && w == 0) wave_write_tables(a, l, lane);
 }
 
 constexpr size_t kLdsLimit = 64 * 1024;
@@ -510,9 +538,15 @@ hipError_t launch_layout(const LayoutArgs& a, hipStream_t s) {
     if (nblk > kMaxWaveChunks) return hipErrorInvalidValue;
     const dim3 grid(nblk), block(wpb * kWave);
     const size_t lds = lds_bytes(a, wpb);
-    if (nblk > 1) hipLaunchKernelGGL(layout_count_kernel, grid, block, lds_bytes(a, 1), s, a);
-    if (nblk == 1) hipLaunchKernelGGL((layout_slot_kernel<1024, 1>), grid, block, lds, s, a);
-    else hipLaunchKernelGGL((layout_slot_kernel<512, 32>), grid, block, lds, s, a);
+    if (a.msgs) {
+        if (nblk > 1) hipLaunchKernelGGL(layout_count_kernel<true>, grid, block, lds_bytes(a, 1), s, a);
+        if (nblk == 1) hipLaunchKernelGGL((layout_slot_kernel<1024, 1, true>), grid, block, lds, s, a);
+        else hipLaunchKernelGGL((layout_slot_kernel<512, 32, true>), grid, block, lds, s, a);
+    } else {
+        if (nblk > 1) hipLaunchKernelGGL(layout_count_kernel<false>, grid, block, lds_bytes(a, 1), s, a);
+        if (nblk == 1) hipLaunchKernelGGL((layout_slot_kernel<1024, 1, false>), grid, block, lds, s, a);
+        else hipLaunchKernelGGL((layout_slot_kernel<512, 32, false>), grid, block, lds, s, a);
+    }
     return hipGetLastError();
 }
 
