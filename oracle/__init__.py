@@ -50,6 +50,12 @@ def lib() -> ctypes.CDLL:
             fn.argtypes = [ctypes.c_int64] * 3
         _lib.ep_oracle_footprint_optimised.restype = ctypes.c_int64
         _lib.ep_oracle_footprint_optimised.argtypes = [ctypes.c_int64] * 4
+        _lib.ep_oracle_e4m3_to_float.restype = ctypes.c_float
+        _lib.ep_oracle_e4m3_to_float.argtypes = [ctypes.c_uint8]
+        _lib.ep_oracle_double_to_e4m3.restype = ctypes.c_uint8
+        _lib.ep_oracle_double_to_e4m3.argtypes = [ctypes.c_double]
+        _lib.ep_oracle_quantize_row.restype = None
+        _lib.ep_oracle_dispatch_fp8.restype = None
         _lib.ep_oracle_layout.restype = None
         _lib.ep_oracle_dispatch.restype = None
         _lib.ep_oracle_combine.restype = None
@@ -202,6 +208,37 @@ def dedup_recv(win: np.ndarray, lay: Layout, H: int, recv_x: np.ndarray,
         ctypes.c_int(max(lay.C, 1)), _p(base), ctypes.c_int64(s0), ctypes.c_int64(s1),
         _p(recv_x), _p(recv_w), _p(recv_src), _p(recv_count), ctypes.byref(dropped))
     return recv_count, int(dropped.value)
+
+
+def double_to_e4m3(v: float) -> int:
+    return int(lib().ep_oracle_double_to_e4m3(ctypes.c_double(v)))
+
+
+def e4m3_to_float(c: int) -> float:
+    return float(lib().ep_oracle_e4m3_to_float(ctypes.c_uint8(c)))
+
+
+def quantize_row(x_bits_row: np.ndarray):
+    """One token row (uint16 bf16 bits, H % 128 == 0) -> (uint8 [H] E4M3 codes, float32 [H/128] scales)."""
+    x = np.ascontiguousarray(x_bits_row, dtype=np.uint16)
+    H = x.shape[0]
+    assert H % 128 == 0
+    q = np.zeros(H, np.uint8)
+    sc = np.zeros(H // 128, np.float32)
+    lib().ep_oracle_quantize_row(_p(x), ctypes.c_int(H), _p(q), _p(sc))
+    return q, sc
+
+
+def dispatch_fp8(x_bits: np.ndarray, lay: Layout, recv_q: np.ndarray, recv_scales: np.ndarray,
+                 stride0: Optional[int] = None, stride1: Optional[int] = None) -> None:
+    """Quantising dispatch: recv_q uint8 windows, recv_scales float32 [rows, H/128] (in place)."""
+    assert x_bits.dtype == np.uint16 and recv_q.dtype == np.uint8 and recv_scales.dtype == np.float32
+    T, H = x_bits.shape
+    s0, s1 = _strides(lay.layout, lay.C, H, stride0, stride1)
+    lib().ep_oracle_dispatch_fp8(
+        _p(x_bits), ctypes.c_int64(x_bits.strides[0] // 2), _p(lay.dst_row), ctypes.c_int(T),
+        ctypes.c_int(lay.K), ctypes.c_int(H), ctypes.c_int(lay.layout), ctypes.c_int(max(lay.C, 1)),
+        ctypes.c_int64(s0), ctypes.c_int64(s1), _p(recv_q), _p(recv_scales))
 
 
 def footprint_per_expert(E: int, B: int, P: int) -> int:

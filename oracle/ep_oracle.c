@@ -380,6 +380,92 @@ void ep_oracle_dedup_recv(const uint8_t *rank_win, const int32_t *rank_offset,
     free(demand); free(start); free(next);
 }
 
+/* ---- FP8 dispatch: in-kernel quantisation with per-128-channel scales ---------- */
+
+/*
+ * The paper only says that dispatch may quantise tokens to FP8 with scales
+ * (Sec. I, Sec. IV-B payload: 7168 B of FP8 data and 56 float scales = 224 B for a
+ * 7168-wide token, i.e. one scale per 128 channels).  Format and scale rule are
+ * this build's reading (parity unpinned by the paper):
+ *   - FP8 is the OCP E4M3 format: 1 sign, 4 exponent (bias 7), 3 mantissa bits,
+ *     no infinity, largest finite value 448, S.1111.111 is NaN.
+ *   - per token and per group of 128 channels: amax = max |x|;
+ *       scale = amax / 448   (float32 division)  -- what a consumer multiplies by
+ *       inv   = 448 / amax   (float32 division)
+ *       q     = e4m3( float32(x) * inv )         (float32 product, then round to
+ *               nearest even; anything above 448 in magnitude saturates to 448)
+ *     amax == 0 gives scale = inv = 1.
+ */
+
+float ep_oracle_e4m3_to_float(uint8_t c) {
+    int s = c >> 7, e = (c >> 3) & 15, m = c & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m / 8.0, -6);
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return (float)(s ? -v : v);
+}
+
+/* Round a real to E4M3: nearest multiple of the quantum of its binade, ties to
+ * even, saturating at 448. */
+uint8_t ep_oracle_double_to_e4m3(double v) {
+    if (isnan(v)) return 0x7F;
+    uint8_t sign = signbit(v) ? 0x80 : 0x00;
+    double a = fabs(v);
+    if (a > 448.0) return sign | 0x7E;
+    if (a == 0.0) return sign;
+    int ex;
+    (void)frexp(a, &ex);
+    int e = ex - 1;
+    if (e < -6) e = -6;                 /* subnormals share the quantum of the lowest binade */
+    double q = ldexp(1.0, e - 3);
+    double r = nearbyint(a / q) * q;    /* to nearest, ties to even */
+    if (r == 0.0) return sign;
+    if (r < ldexp(1.0, -6)) return sign | (uint8_t)(r / ldexp(1.0, -9));
+    (void)frexp(r, &ex);
+    int e2 = ex - 1;
+    int m = (int)((r / ldexp(1.0, e2) - 1.0) * 8.0);
+    return sign | (uint8_t)(((e2 + 7) << 3) | m);
+}
+
+/* Quantise one token row of H bf16 values (H a multiple of 128). */
+void ep_oracle_quantize_row(const uint16_t *x, int H, uint8_t *q, float *scales) {
+    for (int g = 0; g < H / 128; ++g) {
+        float amax = 0.0f;
+        for (int c = 0; c < 128; ++c) {
+            float a = fabsf(bf16_to_float(x[g * 128 + c]));
+            if (a > amax) amax = a;
+        }
+        volatile float scale = 1.0f, inv = 1.0f;
+        if (amax != 0.0f) { scale = amax / 448.0f; inv = 448.0f / amax; }
+        scales[g] = scale;
+        for (int c = 0; c < 128; ++c) {
+            volatile float p = bf16_to_float(x[g * 128 + c]) * inv;
+            q[g * 128 + c] = ep_oracle_double_to_e4m3((double)p);
+        }
+    }
+}
+
+/* Dispatch with quantisation: every routed entry receives the quantised row of
+ * its token and the row's H/128 scales. recv_q is addressed like the bf16 windows
+ * but in bytes (strides in elements of one byte). */
+void ep_oracle_dispatch_fp8(const uint16_t *x, int64_t x_stride, const int32_t *dst_row, int T,
+                            int K, int H, int layout, int C, int64_t stride0, int64_t stride1,
+                            uint8_t *recv_q, float *recv_scales) {
+    uint8_t *q = (uint8_t *)malloc((size_t)H);
+    float *sc = (float *)malloc(sizeof(float) * (size_t)(H / 128));
+    for (int t = 0; t < T; ++t) {
+        ep_oracle_quantize_row(x + (int64_t)t * x_stride, H, q, sc);
+        for (int k = 0; k < K; ++k) {
+            int32_t row = dst_row[t * K + k];
+            if (row < 0) continue;
+            memcpy(recv_q + row_offset(row, layout, C, stride0, stride1), q, (size_t)H);
+            memcpy(recv_scales + (int64_t)row * (H / 128), sc, sizeof(float) * (size_t)(H / 128));
+        }
+    }
+    free(q); free(sc);
+}
+
 /* ---- buffer footprints (Sec. IV-D, footprint equation) ------------------------ */
 
 /* Per-expert sub-region scheme: E sub-regions of B slots of P bytes for dispatch

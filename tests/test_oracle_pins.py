@@ -502,3 +502,107 @@ def test_paper_constants(oracle_mod):
     assert abs(float(ratio) - f["ratio_approx"]) < 0.5
     assert Fraction(oracle_mod.footprint_per_expert(256, 128, 14336),
                     oracle_mod.footprint_optimised(32, 128, 8, 14336)) == Fraction(512, 40)
+
+
+# --------------------------------------------------------------------------- FP8 quantising dispatch
+
+
+def _e4m3_value(c):
+    """OCP E4M3 by its definition: sign, 4 exponent bits (bias 7), 3 mantissa bits."""
+    s, e, m = c >> 7, (c >> 3) & 15, c & 7
+    if e == 15 and m == 7:
+        return float("nan")
+    v = (m / 8.0) * 2.0 ** -6 if e == 0 else (1 + m / 8.0) * 2.0 ** (e - 7)
+    return -v if s else v
+
+
+def test_e4m3_all_codes_and_rounding(oracle_mod):
+    vals = []
+    for c in range(256):
+        v = _e4m3_value(c)
+        got = oracle_mod.e4m3_to_float(c)
+        if v != v:
+            assert got != got
+            continue
+        assert got == v
+        if v == 0.0:
+            continue  # +0 / -0 checked below
+        assert oracle_mod.double_to_e4m3(v) == c
+        if c < 0x7F:
+            vals.append(v)
+    assert max(vals) == 448.0 and min(v for v in vals if v > 0) == 2.0 ** -9
+    assert oracle_mod.double_to_e4m3(0.0) == 0 and oracle_mod.double_to_e4m3(-0.0) == 0x80
+    vals = sorted(vals)
+    # midpoints go to the even code; a hair to either side goes to the nearer code
+    for lo, hi in zip(vals[:-1], vals[1:]):
+        mid = (lo + hi) / 2
+        c_lo, c_hi = oracle_mod.double_to_e4m3(lo), oracle_mod.double_to_e4m3(hi)
+        even = c_lo if c_lo % 2 == 0 else c_hi
+        assert oracle_mod.double_to_e4m3(mid) == even
+        assert oracle_mod.double_to_e4m3(mid * (1 - 1e-9)) == c_lo
+        assert oracle_mod.double_to_e4m3(mid * (1 + 1e-9)) == c_hi
+    # saturation instead of overflow; NaN stays NaN
+    for v, c in ((448.0001, 0x7E), (1e30, 0x7E), (-500.0, 0xFE), (float("inf"), 0x7E)):
+        assert oracle_mod.double_to_e4m3(v) == c
+    assert oracle_mod.double_to_e4m3(float("nan")) == 0x7F
+    assert oracle_mod.double_to_e4m3(2.0 ** -10) == 0 and oracle_mod.double_to_e4m3(2.0 ** -10 * 1.001) == 1
+
+
+def test_e4m3_matches_torch_in_range(oracle_mod):
+    rng = np.random.default_rng(5)
+    a = np.concatenate([rng.standard_normal(20000).astype(np.float32) * 100,
+                        rng.standard_normal(5000).astype(np.float32) * 0.01,
+                        rng.uniform(-448, 448, 5000).astype(np.float32)])
+    a = a[np.abs(a) <= 448.0]
+    want = torch.from_numpy(a).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = np.array([oracle_mod.double_to_e4m3(float(v)) for v in a], np.uint8)
+    assert np.array_equal(got, want)
+
+
+def test_quantize_row_properties(oracle_mod):
+    g = _golden("paper_constants.json")
+    w = wl.make_workload("ll_decode", T=6)
+    H = w.spec.H
+    assert H == g["hidden"]
+    for t in range(6):
+        q, sc = oracle_mod.quantize_row(w.x_bits[t])
+        assert q.nbytes == g["row_bytes_fp8"] and sc.size == g["scale_floats"] and sc.nbytes == g["scale_bytes"]
+        x = wl.bf16_bits_to_f32(w.x_bits[t]).reshape(-1, 128)
+        amax = np.abs(x).max(1)
+        assert np.array_equal(sc, (amax / np.float32(448.0)).astype(np.float32))
+        deq = np.array([_e4m3_value(int(c)) for c in q], np.float64).reshape(-1, 128) * sc[:, None].astype(np.float64)
+        # the largest element of every group maps to +-448 exactly, so it dequantises to itself
+        idx = np.abs(x).argmax(1)
+        rows = np.arange(x.shape[0])
+        assert np.all(np.abs(q.reshape(-1, 128)[rows, idx] & 0x7F) == 0x7E)
+        assert np.allclose(deq[rows, idx], x[rows, idx], rtol=2 ** -22)
+        # 3 mantissa bits: relative error at most 2^-4 in the normal range, absolute 2^-10*scale below it
+        err = np.abs(deq - x)
+        bound = np.maximum(np.abs(x) * 2.0 ** -4, sc[:, None] * 2.0 ** -10) * (1 + 1e-6)
+        assert np.all(err <= bound)
+        # independent re-derivation through torch's E4M3 cast of x * (448 / amax)
+        inv = (np.float32(448.0) / amax).astype(np.float32)
+        p = (x * inv[:, None]).astype(np.float32)
+        p = np.clip(p, -448.0, 448.0)
+        want = torch.from_numpy(p).to(torch.float8_e4m3fn).view(torch.uint8).numpy().reshape(-1)
+        assert np.array_equal(q, want)
+    z = np.zeros(256, np.uint16)
+    z[130] = 0x8000  # -0
+    q, sc = oracle_mod.quantize_row(z)
+    assert np.all(sc == 1.0) and q[130] == 0x80 and np.all(np.delete(q, 130) == 0)
+
+
+def test_dispatch_fp8_places_quantised_rows(oracle_mod):
+    w = wl.make_workload("ll_decode", T=20, H=256)
+    spec = w.spec
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R)
+    rows = lay.expert_offset[-1]
+    rq = np.full((rows + 1, spec.H), 0xAB, np.uint8)
+    rs = np.full((rows + 1, spec.H // 128), np.float32(-2), np.float32)
+    oracle_mod.dispatch_fp8(w.x_bits, lay, rq, rs)
+    assert np.all(rq[rows] == 0xAB) and np.all(rs[rows] == -2)
+    for t in range(spec.T):
+        q, sc = oracle_mod.quantize_row(w.x_bits[t])
+        for k in range(spec.K):
+            r = lay.dst_row[t, k]
+            assert np.array_equal(rq[r], q) and np.array_equal(rs[r], sc)
