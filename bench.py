@@ -68,6 +68,51 @@ def cpu_baseline(w, steps_budget_s: float = 12.0):
     }
 
 
+def extras(ep, hx, wl, torch, np, group, spec, first_set, stream_ptr, iters: int = 20):
+    """Timings of the dispatch variants outside the headline step (HIP events, mean of iters)."""
+    x, topk, gate, recv, y, out, rows = first_set
+    T, K, H, E = spec.T, spec.K, spec.H, spec.E
+    res = {}
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        for i in range(iters):
+            ev[i].record()
+            fn()
+        ev[iters].record()
+        torch.cuda.synchronize()
+        return float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(iters)])) * 1e3
+
+    h = ep.ep_layout(group, topk)
+    if H % 128 == 0:
+        q = torch.empty((T * K, H), dtype=torch.uint8, device=hx.DEV).view(torch.float8_e4m3fn)
+        sc = torch.empty((T * K, H // 128), dtype=torch.float32, device=hx.DEV)
+        call = ep.prepare_dispatch(x, q, topk_weights=gate, recv_scales=sc)
+        us = timed(lambda: call(h, stream_ptr))
+        nbytes = T * 2 * H + rows * (H + 4 * (H // 128)) + 8 * rows
+        res["fp8_dispatch"] = {"us": round(us, 2), "algorithmic_bytes": nbytes,
+                               "gbps": round(nbytes / (us * 1e-6) / 1e9, 1)}
+        del q, sc
+    ep.ep_handle_destroy(h)
+    cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, dispatch_path=ep.EP_PATH_RANK_DEDUP)
+    g2 = ep.ep_group_create(cfg)
+    h2 = ep.ep_layout(g2, topk)
+    info = ep.ep_handle_query(h2)
+    ginfo = ep.ep_group_query(g2)
+    call = ep.prepare_dispatch(x, recv, topk_weights=gate, topk_idx=topk)
+    us = timed(lambda: call(h2, stream_ptr))
+    msgs, P = int(info.rank_messages), int(ginfo.msg_bytes)
+    nbytes = T * 2 * H + msgs * P + msgs * P + rows * 2 * H + 8 * rows
+    res["once_per_rank_dispatch"] = {"us": round(us, 2), "messages": msgs, "algorithmic_bytes": nbytes,
+                                     "gbps": round(nbytes / (us * 1e-6) / 1e9, 1),
+                                     "staging_bytes": int(ginfo.staging_slots) * P}
+    ep.ep_handle_destroy(h2)
+    ep.ep_group_destroy(g2)
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +121,9 @@ def main() -> int:
     ap.add_argument("--workload", default="ht_prefill")
     ap.add_argument("--sets", type=int, default=3, help="input/window sets rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the FP8 quantising dispatch and the once-per-rank dispatch (reported "
+                         "in an 'extras' object; the headline numbers are unaffected)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one rank's share on ONE GPU; this build has no multi-GPU path "
@@ -208,6 +256,8 @@ def main() -> int:
                      "traffic": _traffic(spec.name, kernel_name),
                      "timing": "HIP events on the launch stream, mean over the timed steps"},
     }
+    if args.extras:
+        line["extras"] = extras(ep, hx, wl, torch, np, group, spec, sets[0], stream_ptr)
     ep.ep_group_destroy(group)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)

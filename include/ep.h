@@ -59,16 +59,16 @@ enum { EP_MODE_LL = 0, EP_MODE_HT = 1 };
  *                       local experts.  Same final windows, bit for bit.          */
 enum { EP_PATH_DIRECT = 0, EP_PATH_RANK_DEDUP = 1 };
 
-enum { EP_DTYPE_BF16 = 0, EP_DTYPE_F32 = 1, EP_DTYPE_I32 = 2, EP_DTYPE_U8 = 3 };
+enum { EP_DTYPE_BF16 = 0, EP_DTYPE_F32 = 1, EP_DTYPE_I32 = 2, EP_DTYPE_U8 = 3,
+       EP_DTYPE_FP8_E4M3 = 4 /* OCP E4M3: 1-4-3 bits, bias 7, max 448, no infinity */ };
 
-/* Tensor roles (Sec. III-E, Table IV).  SCALES is declared for completeness and
- * rejected with EP_ERR_UNSUPPORTED.  The last three are this library's own. */
+/* Tensor roles (Sec. III-E, Table IV).  The last three are this library's own. */
 enum {
     EP_TAG_NONE = 0,
     EP_TAG_TOKENS = 1,                     /* token data, input or output                 */
     EP_TAG_TOPK_IDX = 2,                   /* int32 [T, K] expert ids, -1 = not routed    */
     EP_TAG_TOPK_WEIGHTS = 3,               /* f32 [T, K] gate weights / f32 [rows] output */
-    EP_TAG_SCALES = 4,
+    EP_TAG_SCALES = 4,                     /* f32 [rows, H/128] FP8 scales (dispatch output) */
     EP_TAG_RECV_EXPERT_COUNTER_DEVICE = 5, /* int32 [E] rows placed per expert            */
     EP_TAG_RECV_EXPERT_COUNTER_HOST = 6,   /* same, pinned host memory mapped to device   */
     EP_TAG_TOKENS_PER_EXPERTS = 7,         /* same as RECV_EXPERT_COUNTER_DEVICE          */
@@ -244,6 +244,13 @@ EP_API ep_result_t ep_handle_destroy(ep_handle_t handle);
  * recv_w[dst_row] = w[t,k], recv_src[dst_row] = t.  Rows not named by the layout are
  * left untouched.  A row index >= rows_cap is skipped and flagged (status bit 2).
  * send_only must be 0 (staged execution is not built): EP_ERR_UNSUPPORTED.
+ * Quantising dispatch (Sec. I "in-kernel quantization", Sec. IV-B payload: H bytes of FP8
+ * plus H/128 float scales per row): give the TOKENS output the dtype EP_DTYPE_FP8_E4M3
+ * (same shape rules, one byte per element, outer strides multiples of 16) together with a
+ * SCALES output f32 [rows_cap, H/128] (contiguous; LL: rows_cap = E*C).  Requires
+ * H % 128 == 0 and EP_PATH_DIRECT.  Per token and group of 128 channels:
+ * amax = max|x|; scales[row, g] = amax / 448; q = e4m3(f32(x) * (448 / amax)), float32
+ * operations, round to nearest even, magnitudes above 448 saturate; amax == 0 gives scale 1.
  * EP_PATH_RANK_DEDUP runs three steps on the stream -- send to the group's staging
  * windows, receiver-side ranking of the header entries, fan-out -- and produces the
  * same outputs; dispatches of one group must then not overlap (they share the

@@ -28,7 +28,7 @@ EP_ERR_NOMEM = 7
 
 EP_MODE_LL, EP_MODE_HT = 0, 1
 EP_PATH_DIRECT, EP_PATH_RANK_DEDUP = 0, 1
-EP_DTYPE_BF16, EP_DTYPE_F32, EP_DTYPE_I32, EP_DTYPE_U8 = 0, 1, 2, 3
+EP_DTYPE_BF16, EP_DTYPE_F32, EP_DTYPE_I32, EP_DTYPE_U8, EP_DTYPE_FP8_E4M3 = 0, 1, 2, 3, 4
 
 EP_TAG_NONE = 0
 EP_TAG_TOKENS = 1
@@ -148,7 +148,7 @@ def ep_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> No
 
 
 _DTYPES = {torch.bfloat16: EP_DTYPE_BF16, torch.float32: EP_DTYPE_F32, torch.int32: EP_DTYPE_I32,
-           torch.uint8: EP_DTYPE_U8}
+           torch.uint8: EP_DTYPE_U8, torch.float8_e4m3fn: EP_DTYPE_FP8_E4M3}
 
 
 def tensor_desc(t: torch.Tensor, tag: int) -> ep_tensor_t:
@@ -244,7 +244,7 @@ def _descs(pairs) -> "ctypes.Array":
 def ep_dispatch(handle, x: torch.Tensor, recv_x: torch.Tensor, topk_weights: Optional[torch.Tensor] = None,
                 recv_w: Optional[torch.Tensor] = None, recv_src: Optional[torch.Tensor] = None,
                 recv_count: Optional[torch.Tensor] = None, send_only: int = 0, stream=None,
-                topk_idx: Optional[torch.Tensor] = None) -> None:
+                topk_idx: Optional[torch.Tensor] = None, recv_scales: Optional[torch.Tensor] = None) -> None:
     ins = [(x, EP_TAG_TOKENS)]
     if topk_weights is not None:
         ins.append((topk_weights, EP_TAG_TOPK_WEIGHTS))
@@ -257,6 +257,8 @@ def ep_dispatch(handle, x: torch.Tensor, recv_x: torch.Tensor, topk_weights: Opt
         outs.append((recv_src, EP_TAG_RECV_SRC_TOKEN))
     if recv_count is not None:
         outs.append((recv_count, EP_TAG_RECV_EXPERT_COUNTER_DEVICE))
+    if recv_scales is not None:
+        outs.append((recv_scales, EP_TAG_SCALES))
     _check(load().ep_dispatch(handle, _descs(ins), len(ins), _descs(outs), len(outs), send_only,
                               _stream_ptr(stream)), "ep_dispatch")
 
@@ -291,7 +293,7 @@ class PreparedCall:
 
 
 def prepare_dispatch(x, recv_x, topk_weights=None, recv_w=None, recv_src=None, recv_count=None,
-                     topk_idx=None) -> PreparedCall:
+                     topk_idx=None, recv_scales=None) -> PreparedCall:
     ins = [(x, EP_TAG_TOKENS)]
     if topk_weights is not None:
         ins.append((topk_weights, EP_TAG_TOPK_WEIGHTS))
@@ -304,6 +306,8 @@ def prepare_dispatch(x, recv_x, topk_weights=None, recv_w=None, recv_src=None, r
         outs.append((recv_src, EP_TAG_RECV_SRC_TOKEN))
     if recv_count is not None:
         outs.append((recv_count, EP_TAG_RECV_EXPERT_COUNTER_DEVICE))
+    if recv_scales is not None:
+        outs.append((recv_scales, EP_TAG_SCALES))
     return PreparedCall("ep_dispatch", ins, outs)
 
 

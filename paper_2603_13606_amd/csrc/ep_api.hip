@@ -123,7 +123,7 @@ const ep_tensor_t* find_tag(const ep_tensor_t* ts, int n, int tag, int tag2 = -1
     return nullptr;
 }
 
-bool has_unsupported(const ep_tensor_t* ts, int n) {
+bool has_scales(const ep_tensor_t* ts, int n) {
     for (int i = 0; i < n; ++i)
         if (ts[i].tag == EP_TAG_SCALES) return true;
     return false;
@@ -145,14 +145,16 @@ bool check_1d(const ep_tensor_t* t, int dtype, int64_t n) {
     return t->data != nullptr || t->shape[0] == 0;
 }
 
-// Token windows: HT [rows_cap, H]; LL [E, C, H].  Fills a WindowDesc.
-bool window_from_tensor(const ep_group_s* g, const ep_tensor_t* t, WindowDesc* w) {
+// Token windows: HT [rows_cap, H]; LL [E, C, H].  Fills a WindowDesc.  Rows must start on
+// 16-byte boundaries: outer strides are multiples of `align` elements (8 for bf16, 16 for fp8).
+bool window_from_tensor(const ep_group_s* g, const ep_tensor_t* t, WindowDesc* w, int dtype = EP_DTYPE_BF16) {
     const int H = g->cfg.hidden;
-    if (!t || t->dtype != EP_DTYPE_BF16 || !aligned16(t->data)) return false;
+    const int align = dtype == EP_DTYPE_BF16 ? 8 : 16;
+    if (!t || t->dtype != dtype || !aligned16(t->data)) return false;
     if (g->cfg.mode == EP_MODE_LL) {
         if (t->ndim != 3 || t->shape[0] != g->cfg.num_experts || t->shape[1] != g->C || t->shape[2] != H)
             return false;
-        if (t->stride[2] != 1 || t->stride[1] < H || t->stride[1] % 8 || t->stride[0] % 8) return false;
+        if (t->stride[2] != 1 || t->stride[1] < H || t->stride[1] % align || t->stride[0] % align) return false;
         if (t->stride[0] < 0) return false;
         if (!t->data) return false;
         w->stride0 = t->stride[0];
@@ -161,7 +163,7 @@ bool window_from_tensor(const ep_group_s* g, const ep_tensor_t* t, WindowDesc* w
         w->padded = 1;
         w->C = g->C;
     } else {
-        if (t->ndim != 2 || t->shape[1] != H || t->stride[1] != 1 || t->stride[0] < H || t->stride[0] % 8)
+        if (t->ndim != 2 || t->shape[1] != H || t->stride[1] != 1 || t->stride[0] < H || t->stride[0] % align)
             return false;
         if (t->shape[0] < 0 || t->shape[0] > 0x7fffffffLL) return false;
         if (t->shape[0] > 0 && !t->data) return false;
@@ -416,7 +418,7 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
                         ep_stream_t stream) {
     if (!h || !inputs || !outputs || num_inputs < 1 || num_outputs < 1) return EP_ERR_INVALID_ARG;
     if (send_only != 0) return EP_ERR_UNSUPPORTED;
-    if (has_unsupported(inputs, num_inputs) || has_unsupported(outputs, num_outputs)) return EP_ERR_UNSUPPORTED;
+    if (has_scales(inputs, num_inputs)) return EP_ERR_UNSUPPORTED;  // inputs are bf16 tokens
     ep_group_s* g = h->group;
     const ep_group_config_t& c = g->cfg;
     const ep_tensor_t* x = find_tag(inputs, num_inputs, EP_TAG_TOKENS);
@@ -424,13 +426,24 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     const ep_tensor_t* rx = find_tag(outputs, num_outputs, EP_TAG_TOKENS);
     const ep_tensor_t* rw = find_tag(outputs, num_outputs, EP_TAG_TOPK_WEIGHTS);
     const ep_tensor_t* rs = find_tag(outputs, num_outputs, EP_TAG_RECV_SRC_TOKEN);
+    const ep_tensor_t* rq = find_tag(outputs, num_outputs, EP_TAG_SCALES);
     const ep_tensor_t* rc = find_tag(outputs, num_outputs, EP_TAG_RECV_EXPERT_COUNTER_DEVICE,
                                      EP_TAG_RECV_EXPERT_COUNTER_HOST, EP_TAG_TOKENS_PER_EXPERTS);
     if (!check_2d(x, EP_DTYPE_BF16, h->T, c.hidden, true) || x->stride[0] % 8 || !aligned16(x->data))
         return EP_ERR_INVALID_ARG;
     if (w && !check_2d(w, EP_DTYPE_F32, h->T, c.top_k, true)) return EP_ERR_INVALID_ARG;
+    // An FP8 output selects the quantising dispatch (Sec. III-E: the tags tell the library
+    // which tensors to expect -- FP8 tokens come with a SCALES tensor).
+    const bool fp8 = rx && rx->dtype == EP_DTYPE_FP8_E4M3;
+    if (fp8 != (rq != nullptr)) return EP_ERR_INVALID_ARG;
     DispatchArgs a;
-    if (!window_from_tensor(g, rx, &a.win)) return EP_ERR_INVALID_ARG;
+    if (!window_from_tensor(g, rx, &a.win, fp8 ? EP_DTYPE_FP8_E4M3 : EP_DTYPE_BF16)) return EP_ERR_INVALID_ARG;
+    if (fp8) {
+        if (c.hidden % 128 != 0) return EP_ERR_INVALID_ARG;
+        if (c.dispatch_path != EP_PATH_DIRECT) return EP_ERR_UNSUPPORTED;
+        if (!check_2d(rq, EP_DTYPE_F32, a.win.rows_cap, c.hidden / 128, false) || rq->stride[0] != c.hidden / 128)
+            return EP_ERR_INVALID_ARG;
+    }
     if (rw && !check_1d(rw, EP_DTYPE_F32, a.win.rows_cap)) return EP_ERR_INVALID_ARG;
     if (rs && !check_1d(rs, EP_DTYPE_I32, a.win.rows_cap)) return EP_ERR_INVALID_ARG;
     if (rc && !check_1d(rc, EP_DTYPE_I32, c.num_experts)) return EP_ERR_INVALID_ARG;
@@ -446,6 +459,8 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     a.totals = h->slab.totals;
     a.T = h->T; a.K = c.top_k; a.H = c.hidden; a.E = c.num_experts;
     h->last_stream = (hipStream_t)stream;
+    if (fp8)
+        return launch_dispatch_fp8(a, (float*)rq->data, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
     if (c.dispatch_path == EP_PATH_DIRECT)
         return launch_dispatch(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
 
@@ -502,7 +517,7 @@ ep_result_t ep_combine(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inp
                        ep_stream_t stream) {
     if (!h || !inputs || !outputs || num_inputs < 1 || num_outputs < 1) return EP_ERR_INVALID_ARG;
     if (send_only != 0) return EP_ERR_UNSUPPORTED;
-    if (has_unsupported(inputs, num_inputs) || has_unsupported(outputs, num_outputs)) return EP_ERR_UNSUPPORTED;
+    if (has_scales(inputs, num_inputs) || has_scales(outputs, num_outputs)) return EP_ERR_UNSUPPORTED;
     ep_group_s* g = h->group;
     const ep_group_config_t& c = g->cfg;
     const ep_tensor_t* y = find_tag(inputs, num_inputs, EP_TAG_TOKENS);

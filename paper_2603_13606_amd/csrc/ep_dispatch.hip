@@ -54,6 +54,100 @@ __global__ __launch_bounds__(256) void dispatch_direct_kernel(DispatchArgs a, in
     }
 }
 
+// ---- quantising dispatch: FP8 (OCP E4M3) rows with one float scale per 128 channels
+//
+// The paper lets dispatch quantise tokens (Sec. I) and sizes the FP8 row at H bytes
+// plus H/128 float scales (Sec. IV-B payload); format and scale rule are fixed by this
+// library: per token and 128-channel group amax = max|x|, scale = amax / 448,
+// q = e4m3(float(x) * (448 / amax)) rounded to nearest even and saturated at 448;
+// amax == 0 gives scale 1.  Work unit = one wavefront x 1024 channels of one token:
+// a lane owns 16 consecutive channels (32 bytes in, 16 bytes out), a group is 8 lanes.
+// The row is quantised once and stored K times.
+
+// float32 -> E4M3 code: round to nearest even, saturate above 448, NaN -> 0x7F.
+__device__ __forceinline__ uint32_t f32_to_e4m3(float f) {
+    const uint32_t u = __float_as_uint(f);
+    const uint32_t sign = (u >> 24) & 0x80u;
+    uint32_t a = u & 0x7fffffffu;
+    if (a > 0x7f800000u) return 0x7fu;
+    if (a > 0x43e00000u) return sign | 0x7eu;  // above 448
+    if (a < 0x3c800000u) {                      // below 2^-6: multiples of 2^-9
+        const int m = __float2int_rn(__uint_as_float(a) * 512.0f);
+        return sign | (uint32_t)m;
+    }
+    a += 0x0007ffffu + ((a >> 20) & 1u);        // keep 3 mantissa bits, ties to even
+    return sign | ((a >> 20) - (120u << 3));    // rebias the exponent from 127 to 7
+}
+
+__global__ __launch_bounds__(256) void dispatch_fp8_kernel(DispatchArgs a, float* recv_scales, int nseg) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t u = (int64_t)blockIdx.x * 4 + wave;
+    if (blockIdx.x == 0 && a.recv_count) {
+        for (int e = threadIdx.x; e < a.E; e += blockDim.x) a.recv_count[e] = a.expert_kept[e];
+    }
+    if (u >= (int64_t)a.T * nseg) return;
+    const int t = (int)(u / nseg);
+    const int seg = (int)(u - (int64_t)t * nseg);
+    const int ch0 = seg * 1024 + lane * 16;  // first channel of this lane
+    const bool active = ch0 < a.H;
+    u32x4 in0 = {0u, 0u, 0u, 0u}, in1 = {0u, 0u, 0u, 0u};
+    if (active) {
+        const u32x4* src = (const u32x4*)(a.x + (int64_t)t * a.x_stride + ch0);
+        in0 = __builtin_nontemporal_load(src);
+        in1 = __builtin_nontemporal_load(src + 1);
+    }
+    float f[16];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        f[2 * c] = __uint_as_float(in0[c] << 16);
+        f[2 * c + 1] = __uint_as_float(in0[c] & 0xffff0000u);
+        f[8 + 2 * c] = __uint_as_float(in1[c] << 16);
+        f[8 + 2 * c + 1] = __uint_as_float(in1[c] & 0xffff0000u);
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const float v = fabsf(f[c]);
+        amax = v > amax ? v : amax;
+    }
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) {  // the 8 lanes of a 128-channel group
+        const float o = __shfl_xor(amax, off, kWave);
+        amax = o > amax ? o : amax;
+    }
+    float scale = 1.0f, inv = 1.0f;
+    if (amax != 0.0f) {
+        scale = __fdiv_rn(amax, 448.0f);
+        inv = __fdiv_rn(448.0f, amax);
+    }
+    u32x4 q;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        q[c] = f32_to_e4m3(__fmul_rn(f[4 * c], inv)) | (f32_to_e4m3(__fmul_rn(f[4 * c + 1], inv)) << 8) |
+               (f32_to_e4m3(__fmul_rn(f[4 * c + 2], inv)) << 16) | (f32_to_e4m3(__fmul_rn(f[4 * c + 3], inv)) << 24);
+    }
+    const int groups = a.H >> 7;
+    const int32_t* rows = a.dst_row + (int64_t)t * a.K;
+    uint8_t* base = (uint8_t*)a.win.base;  // window strides are in one-byte elements here
+    for (int k = 0; k < a.K; ++k) {
+        const int row = __builtin_amdgcn_readfirstlane(rows[k]);
+        if (row < 0) continue;
+        if (row >= a.win.rows_cap) {
+            if (seg == 0 && lane == 0) atomicOr(&a.totals[TOT_STATUS], STATUS_OUTPUT_OVERFLOW);
+            continue;
+        }
+        if (active) {
+            __builtin_nontemporal_store(q, (u32x4*)(base + window_offset(a.win, row) + ch0));
+            if ((lane & 7) == 0) recv_scales[(int64_t)row * groups + (ch0 >> 7)] = scale;
+        }
+        if (seg == 0 && lane == 0) {
+            if (a.recv_w) a.recv_w[row] = a.w ? a.w[(int64_t)t * a.w_stride + k] : 1.0f;
+            if (a.recv_src) a.recv_src[row] = t;
+        }
+    }
+}
+
 // Plain streaming copy, 16 bytes per lane, grid-stride: the yardstick the hardware
 // counters and the achievable copy bandwidth are calibrated against.
 __global__ __launch_bounds__(256) void calibration_copy_kernel(u32x4* dst, const u32x4* src, int64_t n16) {
@@ -71,6 +165,16 @@ hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hip
     if (nblk > 256 * 64) nblk = 256 * 64;
     hipLaunchKernelGGL(calibration_copy_kernel, dim3((unsigned)nblk), dim3(256), 0, s, (u32x4*)dst,
                        (const u32x4*)src, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStream_t s) {
+    const int nseg = (a.H + 1023) / 1024;
+    const int64_t nwaves = (int64_t)a.T * nseg;
+    int64_t nblk = (nwaves + 3) / 4;
+    if (nblk < 1) nblk = 1;
+    if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dispatch_fp8_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, recv_scales, nseg);
     return hipGetLastError();
 }
 

@@ -69,6 +69,7 @@ struct LayoutArgs {
 // Addressing of the receive windows: element offset of logical row r is
 //   padded: (r / C) * stride0 + (r % C) * stride1      (3-D [E, C, H])
 //   concat:  r * stride0                               (2-D [rows, H])
+// (the quantising dispatch reuses it for one-byte elements: base is then a byte pointer)
 struct WindowDesc {
     uint16_t* base;
     int64_t stride0, stride1;
@@ -139,6 +140,7 @@ hipError_t launch_layout(const LayoutArgs& a, hipStream_t s);
 hipError_t launch_dedup_send(const DedupSendArgs& a, hipStream_t s);
 hipError_t launch_dedup_fanout(const DedupFanoutArgs& a, hipStream_t s);
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s);
+hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStream_t s);
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 

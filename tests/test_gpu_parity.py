@@ -569,3 +569,70 @@ def test_once_per_rank_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, 
     finally:
         ep.ep_group_destroy(g)
     assert not held
+
+
+# ------------------------------------------------------------------------------ quantising dispatch (FP8 + scales)
+
+FP8_CASES = [
+    # name, T, H, mode, C, wide dynamic range
+    ("tiny", None, None, "ht", 0, False),
+    ("tiny", None, 384, "ll", 6, True),
+    ("ll_decode", None, None, "ll", 0, False),
+    ("ll_decode", 90, 1152, "ht", 0, True),     # ragged last 1024-channel segment
+    ("skew", 500, None, "ht", 0, True),
+    ("ht_prefill", None, None, "ht", 0, False),  # full benchmark shape
+]
+
+
+@pytest.mark.parametrize("name,T,H,mode,C,wide", FP8_CASES)
+def test_fp8_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, wide):
+    """E4M3 codes and float scales bit-exact with the oracle; untouched rows keep their fill."""
+    w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
+    spec = w.spec
+    T = spec.T
+    _say(f"fp8 case {name} T={T} H={spec.H} mode={mode} C={C} wide={wide}")
+    x_bits = w.x_bits.copy()
+    if wide:  # spread magnitudes over 2^-24 .. 2^12, plus zero groups and signed zeros
+        rng = np.random.default_rng(T)
+        xf = wl.bf16_bits_to_f32(x_bits) * np.exp2(rng.integers(-24, 13, x_bits.shape)).astype(np.float32)
+        x_bits = wl.f32_to_bf16_bits(xf)
+        x_bits[0, :128] = 0
+        x_bits[1 % T, 128:256] = 0x8000
+        x_bits[2 % T, 5] = 0x7F7F  # largest finite bf16
+    topk = _mess_up(w.topk_idx, spec.E, seed=T + 3, frac_masked=0.01)
+    ll = mode == "ll"
+    Cc = (C if C else T) if ll else 0
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, layout=int(ll), C=Cc, C_rank=T)
+    rows = spec.E * Cc if ll else int(lay.expert_offset[-1])
+    G = spec.H // 128
+    o_q = np.full((rows + 1, spec.H), 0xAB, np.uint8)
+    o_s = np.full((rows + 1, G), np.float32(-2.0), np.float32)
+    oracle_mod.dispatch_fp8(x_bits, lay, o_q, o_s)
+    g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C)
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+        store = torch.full((rows + 1, spec.H), 0xAB, dtype=torch.uint8, device=hx.DEV)
+        recv = store[:rows].view(torch.float8_e4m3fn)
+        recv = recv.view(spec.E, Cc, spec.H) if ll else recv
+        scales = torch.full((rows + 1, G), -2.0, dtype=torch.float32, device=hx.DEV)
+        r_src = torch.full((rows + 1,), -9, dtype=torch.int32, device=hx.DEV)
+        r_cnt = torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)
+        ep.ep_dispatch(h, hx.bits_to_dev(x_bits), recv, recv_scales=scales[:rows], recv_src=r_src[:rows], recv_count=r_cnt)
+        torch.cuda.synchronize()
+        got_q = store.cpu().numpy()
+        got_s = scales.cpu().numpy()
+        assert np.array_equal(got_s.view(np.uint32), o_s.view(np.uint32)), "scales differ"
+        assert np.array_equal(got_q, o_q), "E4M3 codes differ"
+        assert np.array_equal(r_cnt.cpu().numpy(), lay.expert_kept)
+        src = r_src.cpu().numpy()
+        for t in range(0, T, max(1, T // 16)):
+            for k in range(spec.K):
+                if lay.dst_row[t, k] >= 0:
+                    assert src[lay.dst_row[t, k]] == t
+        # FP8 output without scales (or the reverse) is refused
+        with pytest.raises(ep.EpError) as e:
+            ep.ep_dispatch(h, hx.bits_to_dev(x_bits), recv)
+        assert e.value.code == ep.EP_ERR_INVALID_ARG
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
