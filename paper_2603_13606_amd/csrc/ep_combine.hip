@@ -55,8 +55,9 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nseg, i
     const int seg = (int)(u - (int64_t)t * nseg);
     const int unit = seg * kWave + lane;
     const bool active = unit < units;
-    const int32_t* rows = a.dst_row + (int64_t)t * a.K;
-    const float* wt = a.w ? a.w + (int64_t)t * a.w_stride : nullptr;
+    // lane k fetches the k-th row index and weight of the token: one load each for all K
+    const int my_row = lane < a.K ? a.dst_row[(int64_t)t * a.K + lane] : -1;
+    const float my_w = (a.w && lane < a.K) ? a.w[(int64_t)t * a.w_stride + lane] : 1.0f;
     float acc[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) acc[c] = 0.0f;
@@ -70,8 +71,8 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nseg, i
             int r = -1;
             float w = 1.0f;
             if (k < a.K) {
-                r = __builtin_amdgcn_readfirstlane(rows[k]);
-                if (wt) w = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(wt[k])));
+                r = __builtin_amdgcn_readlane(my_row, k);
+                w = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), k));
             }
             if (r >= a.win.rows_cap) r = -1;
             row[j] = r;

@@ -59,9 +59,9 @@ __global__ __launch_bounds__(256) void dedup_send_kernel(DedupSendArgs a, int ns
             v = __builtin_nontemporal_load((const u32x4*)(a.x + (int64_t)t * a.x_stride) + (unit - a.hdr_units));
         }
     }
-    const int32_t* slots = a.rank_row + (int64_t)t * a.K;
+    const int my_slot = lane < a.K ? a.rank_row[(int64_t)t * a.K + lane] : -1;
     for (int k = 0; k < a.K; ++k) {
-        const int m = __builtin_amdgcn_readfirstlane(slots[k]);
+        const int m = __builtin_amdgcn_readlane(my_slot, k);
         if (m < 0) continue;
         if (m >= a.staging_slots) {
             if (seg == 0 && lane == 0) atomicOr(&a.totals[TOT_STATUS], STATUS_OUTPUT_OVERFLOW);
@@ -94,9 +94,9 @@ __global__ __launch_bounds__(256) void dedup_fanout_kernel(DedupFanoutArgs a, in
     const int32_t* hdr = (const int32_t*)msg;
     u32x4 v = {0u, 0u, 0u, 0u};
     if (active) v = __builtin_nontemporal_load((const u32x4*)(msg + a.hdr_bytes) + unit);
-    const int32_t* rows = a.recv_dst_row + (int64_t)m * a.K;
+    const int my_row = lane < a.K ? a.recv_dst_row[(int64_t)m * a.K + lane] : -1;
     for (int k = 0; k < a.K; ++k) {
-        const int row = __builtin_amdgcn_readfirstlane(rows[k]);
+        const int row = __builtin_amdgcn_readlane(my_row, k);
         if (row < 0) continue;
         if (row >= a.win.rows_cap) {
             if (seg == 0 && lane == 0) atomicOr(&a.totals[TOT_STATUS], STATUS_OUTPUT_OVERFLOW);

@@ -37,9 +37,10 @@ __global__ __launch_bounds__(256) void dispatch_direct_kernel(DispatchArgs a, in
     const bool active = unit < units;
     u32x4 v = {0u, 0u, 0u, 0u};
     if (active) v = __builtin_nontemporal_load((const u32x4*)(a.x + (int64_t)t * a.x_stride) + unit);
-    const int32_t* rows = a.dst_row + (int64_t)t * a.K;
+    // lane k fetches the k-th destination row of the token: one load for all K entries
+    const int my_row = lane < a.K ? a.dst_row[(int64_t)t * a.K + lane] : -1;
     for (int k = 0; k < a.K; ++k) {
-        const int row = __builtin_amdgcn_readfirstlane(rows[k]);
+        const int row = __builtin_amdgcn_readlane(my_row, k);
         if (row < 0) continue;
         if (row >= a.win.rows_cap) {
             if (seg == 0 && lane == 0) atomicOr(&a.totals[TOT_STATUS], STATUS_OUTPUT_OVERFLOW);
@@ -128,10 +129,10 @@ __global__ __launch_bounds__(256) void dispatch_fp8_kernel(DispatchArgs a, float
                (f32_to_e4m3(__fmul_rn(f[4 * c + 2], inv)) << 16) | (f32_to_e4m3(__fmul_rn(f[4 * c + 3], inv)) << 24);
     }
     const int groups = a.H >> 7;
-    const int32_t* rows = a.dst_row + (int64_t)t * a.K;
+    const int my_row = lane < a.K ? a.dst_row[(int64_t)t * a.K + lane] : -1;
     uint8_t* base = (uint8_t*)a.win.base;  // window strides are in one-byte elements here
     for (int k = 0; k < a.K; ++k) {
-        const int row = __builtin_amdgcn_readfirstlane(rows[k]);
+        const int row = __builtin_amdgcn_readlane(my_row, k);
         if (row < 0) continue;
         if (row >= a.win.rows_cap) {
             if (seg == 0 && lane == 0) atomicOr(&a.totals[TOT_STATUS], STATUS_OUTPUT_OVERFLOW);
