@@ -116,11 +116,16 @@ def extras(ep, hx, wl, torch, np, group, spec, first_set, stream_ptr, iters: int
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="ht_prefill")
     ap.add_argument("--sets", type=int, default=3, help="input/window sets rotated between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--event-every", type=int, default=4,
+                    help="record the per-op HIP events on every n-th timed step only (four event "
+                         "records cost about 12 us of a step, so they are sampled)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also replay the step from captured HIP graphs (reported in a 'graph' object)")
     ap.add_argument("--extras", action="store_true",
                     help="also time the FP8 quantising dispatch and the once-per-rank dispatch (reported "
                          "in an 'extras' object; the headline numbers are unaffected)")
@@ -143,7 +148,8 @@ def main() -> int:
     w = wl.make_workload(args.workload)
     spec = w.spec
     T, K, H, E = spec.T, spec.K, spec.H, spec.E
-    cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, max_handles=2)
+    nsets = max(1, args.sets)
+    cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, max_handles=nsets + 2)  # no allocation later
     group = ep.ep_group_create(cfg)
 
     nsets = max(1, args.sets)
@@ -213,9 +219,10 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, events[i])
+        step(i, events[i] if i % args.event_every == 0 else None)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    events = [e for i, e in enumerate(events) if i % args.event_every == 0]
 
     lay_us = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e3
     dis_us = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e3
@@ -254,8 +261,37 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": _traffic(spec.name, kernel_name),
-                     "timing": "HIP events on the launch stream, mean over the timed steps"},
+                     "timing": f"HIP events on the launch stream around the kernel, mean over every "
+                               f"{args.event_every}-th step of the timed region ({len(events)} samples)"},
     }
+    if args.graph:
+        # one graph per input set: layout + dispatch + combine captured on a side stream
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        sp = side.cuda_stream
+        graphs, live = [], []
+        for lay, dis, com in prepared:
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                hh = lay(sp)
+                dis(hh, sp)
+                com(hh, sp)
+            graphs.append(gr)
+            live.append(hh)
+        for i in range(args.warmup):
+            graphs[i % nsets].replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % nsets].replay()
+        torch.cuda.synchronize()
+        el = time.perf_counter() - tg
+        line["graph"] = {"ms_per_step": round(el / args.steps * 1e3, 4),
+                         "value": round(step_bytes * args.steps / el / 1e9, 2), "unit": "GB/s",
+                         "what": "the same step replayed from a captured HIP graph (one graph per input set)"}
+        del graphs
+        for hh in live:
+            destroy(hh)
     if args.extras:
         line["extras"] = extras(ep, hx, wl, torch, np, group, spec, sets[0], stream_ptr)
     ep.ep_group_destroy(group)

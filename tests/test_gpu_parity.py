@@ -636,3 +636,63 @@ def test_fp8_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, wide):
         ep.ep_handle_destroy(h)
     finally:
         ep.ep_group_destroy(g)
+
+
+# ------------------------------------------------------------------------------ HIP graph capture
+
+
+def test_graph_capture_and_replay(ep, hx, oracle_mod):
+    """layout + dispatch + combine captured once into a HIP graph and replayed with new
+    token data each time; every replay must equal the eager result and the oracle.  The
+    library records no memset nodes (it never calls one) and allocates nothing while a
+    slab is free in the group's pool, so the three calls are capturable as they are."""
+    w = wl.make_workload("ll_decode", T=96, H=1024)
+    spec = w.spec
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=spec.T)
+    rows = int(lay.expert_offset[-1])
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT, max_handles=2)
+    try:
+        topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
+        gate = torch.from_numpy(w.topk_w).to(hx.DEV)
+        x = hx.bits_to_dev(w.x_bits)
+        recv = torch.zeros((rows, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        out = torch.zeros((spec.T, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):  # warm-up outside capture
+            h0 = ep.ep_layout(g, topk)
+            ep.ep_dispatch(h0, x, recv, topk_weights=gate)
+            ep.ep_combine(h0, recv, out, topk_weights=gate)
+        side.synchronize()
+        ep.ep_handle_destroy(h0)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            h = ep.ep_layout(g, topk)
+            ep.ep_dispatch(h, x, recv, topk_weights=gate)
+            ep.ep_combine(h, recv, out, topk_weights=gate)
+        for it in range(4):
+            xb = wl.make_tokens(spec, seed_offset=50 + it)
+            x.copy_(hx.bits_to_dev(xb))          # eager work between the replays
+            recv.zero_()
+            out.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            o_recv = np.zeros((rows, spec.H), np.uint16)
+            oracle_mod.dispatch(xb, None, lay, o_recv)
+            assert np.array_equal(hx.dev_to_bits(recv), o_recv), f"replay {it}: dispatched rows differ"
+            ref = oracle_mod.combine(o_recv, w.topk_w, lay, spec.H, acc="f32")
+            assert np.array_equal(hx.dev_to_bits(out), ref), f"replay {it}: combine differs"
+            # the same step run eagerly gives the same bits
+            out2 = torch.zeros_like(out)
+            recv2 = torch.zeros_like(recv)
+            h2 = ep.ep_layout(g, topk)
+            ep.ep_dispatch(h2, x, recv2, topk_weights=gate)
+            ep.ep_combine(h2, recv2, out2, topk_weights=gate)
+            torch.cuda.synchronize()
+            ep.ep_handle_destroy(h2)
+            assert torch.equal(out2.view(torch.int16), out.view(torch.int16))
+        del graph
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
