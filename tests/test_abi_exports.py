@@ -83,3 +83,16 @@ def test_null_arguments(ep):
     assert lib.ep_dispatch(None, None, 0, None, 0, 0, None) == ep.EP_ERR_INVALID_ARG
     assert lib.ep_combine(None, None, 0, None, 0, 0, None) == ep.EP_ERR_INVALID_ARG
     assert lib.ep_layout(None, None, None, None, None) == ep.EP_ERR_INVALID_ARG
+
+
+def test_header_is_plain_c_and_cxx(tmp_path):
+    """include/ep.h must compile on its own as C99 and as C++ (no HIP or torch types)."""
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "use_ep.c"
+    src.write_text('#include "ep.h"\nint main(void) { ep_group_config_t c; c.size = sizeof c; '
+                   'return ep_version() > 0 && c.size ? 0 : 1; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    cxx = tmp_path / "use_ep.cpp"
+    cxx.write_text('#include "ep.h"\nint main() { ep_tensor_t t{}; return t.ndim; }\n')
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(cxx)], check=True)
