@@ -40,7 +40,8 @@ typedef enum {
     EP_ERR_UNSUPPORTED = 4,     /* e.g. send_only != 0, dtype other than bf16                  */
     EP_ERR_BUSY = 5,            /* group destroyed while handles are alive                     */
     EP_ERR_HIP = 6,             /* a HIP runtime call failed                                   */
-    EP_ERR_NOMEM = 7
+    EP_ERR_NOMEM = 7,
+    EP_ERR_TIMEOUT = 8          /* ep_complete waited for counters that were never published   */
 } ep_result_t;
 
 /* Algorithm mode, fixed at group creation (Sec. III-D).  It selects the output
@@ -106,6 +107,11 @@ typedef struct {
     int32_t dispatch_path;       /* EP_PATH_DIRECT / EP_PATH_RANK_DEDUP                    */
     int32_t max_handles;         /* handle slabs allocated up front; 0 = 2; more are
                                     allocated on demand                                    */
+    int32_t staged_buffers;      /* 0: send_only calls are refused; 1 or 2: buffer sets for
+                                    staged execution (2 = double buffering, Sec. IV-B): each
+                                    set holds the coordination counters, a (t,k)-indexed
+                                    combine staging of B*K rows and, on the once-per-rank
+                                    path, its own staging windows                          */
 } ep_group_config_t;
 
 /* Allocator callbacks (Sec. III-C): when given, every device allocation of the
@@ -127,7 +133,13 @@ typedef struct {
     int64_t footprint_per_expert_bytes;
     int64_t footprint_optimised_bytes;
     int32_t live_handles;
-    int32_t reserved;
+    int32_t staged_buffers;
+    /* per buffer set (borrowed device pointers, NULL when absent): staging windows,
+     * coordination counters int32 [E dispatch | R once-per-rank | E combine], and the
+     * combine staging bf16 [B*K, H] */
+    void *staging_sets[2];
+    void *signals[2];
+    void *combine_staging[2];
 } ep_group_info_t;
 
 /* Result of a layout, host-side copy of the totals plus borrowed DEVICE pointers
@@ -135,7 +147,8 @@ typedef struct {
 typedef struct {
     int32_t num_tokens;      /* T of this layout                                           */
     int32_t status;          /* bit 0: ids outside [0,E) seen; bit 1: entries dropped for
-                                capacity; bit 2: a dispatch found rows beyond its output   */
+                                capacity; bit 2: a dispatch found rows beyond its output;
+                                bit 3: ep_complete gave up waiting for counters            */
     int64_t rows_kept;       /* routed entries that own a destination row                  */
     int64_t rows_dropped;    /* entries cut by the LL capacity C                           */
     int64_t entries_masked;  /* topk_idx == -1                                             */
@@ -243,7 +256,12 @@ EP_API ep_result_t ep_handle_destroy(ep_handle_t handle);
  * For every (t,k) with dst_row >= 0: recv_x[dst_row] = x[t] (byte copy),
  * recv_w[dst_row] = w[t,k], recv_src[dst_row] = t.  Rows not named by the layout are
  * left untouched.  A row index >= rows_cap is skipped and flagged (status bit 2).
- * send_only must be 0 (staged execution is not built): EP_ERR_UNSUPPORTED.
+ * send_only = 1 (staged execution, Sec. III-B; needs staged_buffers > 0, else
+ * EP_ERR_UNSUPPORTED; a handle can have one staged call pending, else EP_ERR_BUSY): only
+ * the send phase runs -- rows (or once-per-rank messages) are written and the
+ * coordination counters are raised to count + 1 (Sec. IV-B) -- and the call is finished
+ * by ep_complete, which also delivers the per-expert counter output.  The output
+ * tensors must stay valid until then.
  * Quantising dispatch (Sec. I "in-kernel quantization", Sec. IV-B payload: H bytes of FP8
  * plus H/128 float scales per row): give the TOKENS output the dtype EP_DTYPE_FP8_E4M3
  * (same shape rules, one byte per element, outer strides multiples of 16) together with a
@@ -270,10 +288,37 @@ EP_API ep_result_t ep_dispatch(ep_handle_t handle, const ep_tensor_t *inputs, in
  * out[t,h] = bf16_rne( sum over k = 0..K-1 in that order of w[t,k] * f32(y[dst_row[t,k], h]) )
  * with float32 multiply and float32 add, each rounded to nearest even; entries
  * without a destination row contribute nothing.
+ * send_only = 1: the expert side packs the rows into the group's staging at slot
+ * t*K + k (Sec. IV-D) and raises the combine counters to 1; ep_complete waits for them
+ * and reduces from the staging into `out` (same arithmetic, same result).
  */
 EP_API ep_result_t ep_combine(ep_handle_t handle, const ep_tensor_t *inputs, int32_t num_inputs,
                        const ep_tensor_t *outputs, int32_t num_outputs, int32_t send_only,
                        ep_stream_t stream);
+
+/* Options of ep_complete.  `size` must be sizeof(ep_complete_config_t). */
+typedef struct {
+    uint32_t size;
+    int32_t spin_limit; /* polls per counter before giving up; 0 = 1 << 20 */
+} ep_complete_config_t;
+
+/*
+ * ep_complete -- Table II "ncclEpComplete": the receive phase of the staged call pending
+ * on `handle` (Sec. III-B, Sec. IV-B receive phase).  Enqueues on `stream` (which may
+ * differ from the stream of the send phase) a bounded wait until every coordination
+ * counter of the call is non-zero, takes the counts from them, clears them, and then
+ *   dispatch, direct path:   writes the per-expert counter output given to ep_dispatch;
+ *   dispatch, once per rank: ranks the header entries of the staged messages and fans
+ *                            them out to the expert rows;
+ *   combine:                 reduces from the (t,k)-indexed staging into `out`.
+ * cfg may be NULL.  Errors: EP_ERR_INVALID_ARG (no pending call, bad cfg), EP_ERR_HIP.
+ * A wait that runs out sets status bit 3; ep_handle_query then returns EP_ERR_TIMEOUT
+ * and counts of counters that never arrived read as 0.
+ */
+EP_API ep_result_t ep_complete(ep_handle_t handle, const ep_complete_config_t *cfg, ep_stream_t stream);
+
+/* Clears every coordination counter of the group (e.g. after an abandoned staged call). */
+EP_API ep_result_t ep_group_reset_signals(ep_group_t group, ep_stream_t stream);
 
 #ifdef __cplusplus
 }

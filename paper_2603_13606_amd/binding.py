@@ -25,6 +25,7 @@ EP_ERR_UNSUPPORTED = 4
 EP_ERR_BUSY = 5
 EP_ERR_HIP = 6
 EP_ERR_NOMEM = 7
+EP_ERR_TIMEOUT = 8
 
 EP_MODE_LL, EP_MODE_HT = 0, 1
 EP_PATH_DIRECT, EP_PATH_RANK_DEDUP = 0, 1
@@ -41,12 +42,12 @@ EP_TAG_TOKENS_PER_EXPERTS = 7
 EP_TAG_RECV_SRC_TOKEN = 8
 EP_TAG_EXPERT_BASE = 9
 
-STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW = 1, 2, 4
+STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW, STATUS_TIMEOUT = 1, 2, 4, 8
 
 EXPORTS = [
     "ep_error_string", "ep_version", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
     "ep_layout", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
-    "ep_dispatch", "ep_combine",
+    "ep_dispatch", "ep_combine", "ep_complete", "ep_group_reset_signals",
 ]
 
 
@@ -61,7 +62,12 @@ class ep_group_config_t(ctypes.Structure):
                 ("num_experts", ctypes.c_int32), ("hidden", ctypes.c_int32), ("top_k", ctypes.c_int32),
                 ("max_tokens_per_rank", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("mode", ctypes.c_int32), ("slots_per_subregion", ctypes.c_int32),
-                ("dispatch_path", ctypes.c_int32), ("max_handles", ctypes.c_int32)]
+                ("dispatch_path", ctypes.c_int32), ("max_handles", ctypes.c_int32),
+                ("staged_buffers", ctypes.c_int32)]
+
+
+class ep_complete_config_t(ctypes.Structure):
+    _fields_ = [("size", ctypes.c_uint32), ("spin_limit", ctypes.c_int32)]
 
 
 class ep_group_info_t(ctypes.Structure):
@@ -72,7 +78,8 @@ class ep_group_info_t(ctypes.Structure):
         ("msg_bytes", ctypes.c_int64), ("staging_slots", ctypes.c_int64),
         ("staging", ctypes.c_void_p), ("footprint_per_expert_bytes", ctypes.c_int64),
         ("footprint_optimised_bytes", ctypes.c_int64), ("live_handles", ctypes.c_int32),
-        ("reserved", ctypes.c_int32)]
+        ("staged_buffers", ctypes.c_int32), ("staging_sets", ctypes.c_void_p * 2),
+        ("signals", ctypes.c_void_p * 2), ("combine_staging", ctypes.c_void_p * 2)]
 
 
 _INFO_PTRS = ("expert_count", "expert_kept", "expert_offset", "rank_pair_count", "rank_token_count",
@@ -123,6 +130,8 @@ def load() -> ctypes.CDLL:
         for fn in (lib.ep_dispatch, lib.ep_combine):
             fn.argtypes = [vp, ctypes.POINTER(ep_tensor_t), i32, ctypes.POINTER(ep_tensor_t), i32, i32, vp]
         lib.ep_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.ep_complete.argtypes = [vp, ctypes.POINTER(ep_complete_config_t), vp]
+        lib.ep_group_reset_signals.argtypes = [vp, vp]
         for name in EXPORTS[2:]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -181,12 +190,13 @@ def _check(code: int, where: str, ok: Sequence[int] = (EP_SUCCESS,)) -> int:
 def make_config(num_ranks: int, num_experts: int, hidden: int, top_k: int, max_tokens_per_rank: int,
                 mode: int = EP_MODE_HT, my_rank: int = 0, slots_per_subregion: int = 0,
                 dispatch_path: int = EP_PATH_DIRECT, max_handles: int = 0,
-                dtype: int = EP_DTYPE_BF16) -> ep_group_config_t:
+                dtype: int = EP_DTYPE_BF16, staged_buffers: int = 0) -> ep_group_config_t:
     c = ep_group_config_t()
     c.size = ctypes.sizeof(ep_group_config_t)
     c.num_ranks, c.my_rank, c.num_experts, c.hidden, c.top_k = num_ranks, my_rank, num_experts, hidden, top_k
     c.max_tokens_per_rank, c.dtype, c.mode = max_tokens_per_rank, dtype, mode
     c.slots_per_subregion, c.dispatch_path, c.max_handles = slots_per_subregion, dispatch_path, max_handles
+    c.staged_buffers = staged_buffers
     return c
 
 
@@ -232,6 +242,17 @@ def ep_handle_get_num_recv_tokens(handle) -> int:
 
 def ep_handle_destroy(handle) -> None:
     _check(load().ep_handle_destroy(handle), "ep_handle_destroy")
+
+
+def ep_complete(handle, spin_limit: int = 0, stream=None) -> None:
+    cfg = ep_complete_config_t()
+    cfg.size = ctypes.sizeof(ep_complete_config_t)
+    cfg.spin_limit = spin_limit
+    _check(load().ep_complete(handle, ctypes.byref(cfg), _stream_ptr(stream)), "ep_complete")
+
+
+def ep_group_reset_signals(group, stream=None) -> None:
+    _check(load().ep_group_reset_signals(group, _stream_ptr(stream)), "ep_group_reset_signals")
 
 
 def _descs(pairs) -> "ctypes.Array":

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libep_mi355x.so")
-SOURCES = ["ep_api.hip", "ep_layout.hip", "ep_dispatch.hip", "ep_dedup.hip", "ep_combine.hip"]
+SOURCES = ["ep_api.hip", "ep_layout.hip", "ep_dispatch.hip", "ep_dedup.hip", "ep_combine.hip", "ep_staged.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off on purpose: some of their forms have

@@ -22,6 +22,8 @@ struct Slab {
     int32_t *slot, *dst_row, *rank_row, *sorted_token, *sorted_k, *sorted_row;
     // receiving side of the once-per-rank path (only carved for EP_PATH_RANK_DEDUP)
     int32_t *recv_totals, *recv_count, *recv_kept, *recv_offset, *recv_own_prefix, *recv_dst_row;
+    // what the receiving side of a staged call learns from the coordination counters
+    int32_t *recv_rank_count, *recv_rank_offset;
 };
 
 }  // namespace
@@ -37,11 +39,22 @@ struct ep_group_s {
     std::vector<Slab> free_slabs;
     int live_handles = 0;
     int device = 0;
-    // staging windows of the once-per-rank path
-    uint8_t* staging = nullptr;
+    // staging windows of the once-per-rank path, one per buffer set
+    uint8_t* staging[2] = {nullptr, nullptr};
     int64_t staging_slots = 0;
     int64_t hdr_bytes = 0, msg_bytes = 0;
+    // staged execution: buffer sets (0 = not available), coordination counters
+    // [E dispatch | R once-per-rank | E combine] and (t,k)-indexed combine staging per set
+    int nsets = 0, next_set = 0;
+    int32_t* signals[2] = {nullptr, nullptr};
+    uint16_t* comb_stage[2] = {nullptr, nullptr};
+    int sig_ints() const { return 2 * cfg.num_experts + cfg.num_ranks; }
+    int32_t* sig_dispatch(int set) const { return signals[set]; }
+    int32_t* sig_rank(int set) const { return signals[set] + cfg.num_experts; }
+    int32_t* sig_combine(int set) const { return signals[set] + cfg.num_experts + cfg.num_ranks; }
 };
+
+enum { PENDING_NONE = 0, PENDING_DISPATCH_DIRECT, PENDING_DISPATCH_DEDUP, PENDING_COMBINE };
 
 struct ep_handle_s {
     ep_group_s* group;
@@ -49,6 +62,13 @@ struct ep_handle_s {
     int T;
     hipStream_t last_stream;
     const int32_t* expert_base;  // as given to ep_layout (borrowed), or nullptr
+    // receive phase of a staged (send_only) call, run by ep_complete
+    int pending = PENDING_NONE;
+    int pending_set = 0;
+    int32_t* pending_recv_count = nullptr;
+    LayoutArgs pending_layout;
+    DedupFanoutArgs pending_fanout;
+    CombineArgs pending_combine;
 };
 
 namespace {
@@ -96,6 +116,7 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
     const int64_t o_vk = dedup ? carve(&cur, E) : 0, o_vo = dedup ? carve(&cur, E + 1) : 0;
     const int64_t o_vp = dedup ? carve(&cur, E + 1) : 0;
     const int64_t o_vr = dedup ? carve(&cur, g->staging_slots * g->cfg.top_k) : 0;
+    const int64_t o_rc = carve(&cur, R), o_rf = carve(&cur, R + 1);
     if (base && s) {
         s->base = base;
         s->totals = base + o_tot; s->expert_count = base + o_ec; s->expert_kept = base + o_ek;
@@ -105,6 +126,7 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
         s->sorted_token = base + o_st; s->sorted_k = base + o_sk; s->sorted_row = base + o_sr;
         s->recv_totals = base + o_vt; s->recv_count = base + o_vc; s->recv_kept = base + o_vk;
         s->recv_offset = base + o_vo; s->recv_own_prefix = base + o_vp; s->recv_dst_row = base + o_vr;
+        s->recv_rank_count = base + o_rc; s->recv_rank_offset = base + o_rf;
     }
     return cur;
 }
@@ -198,6 +220,7 @@ const char* ep_error_string(ep_result_t code) {
         case EP_ERR_BUSY: return "group still has live handles";
         case EP_ERR_HIP: return "HIP runtime error";
         case EP_ERR_NOMEM: return "out of device memory";
+        case EP_ERR_TIMEOUT: return "coordination counters were not published within the spin limit";
     }
     return "unknown error code";
 }
@@ -211,7 +234,6 @@ ep_result_t ep_calibration_copy(void* dst, const void* src, size_t bytes, ep_str
 
 ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_stream_t stream,
                             ep_alloc_fn alloc_fn, ep_free_fn free_fn) {
-    (void)stream;
     if (!group || !cfg || cfg->size != sizeof(ep_group_config_t)) return EP_ERR_INVALID_ARG;
     if ((alloc_fn == nullptr) != (free_fn == nullptr)) return EP_ERR_INVALID_ARG;
     const int R = cfg->num_ranks, E = cfg->num_experts, H = cfg->hidden, K = cfg->top_k;
@@ -224,6 +246,7 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     if (cfg->mode != EP_MODE_LL && cfg->mode != EP_MODE_HT) return EP_ERR_INVALID_ARG;
     if (cfg->dispatch_path != EP_PATH_DIRECT && cfg->dispatch_path != EP_PATH_RANK_DEDUP) return EP_ERR_INVALID_ARG;
     if (cfg->slots_per_subregion < 0 || cfg->max_handles < 0) return EP_ERR_INVALID_ARG;
+    if (cfg->staged_buffers < 0 || cfg->staged_buffers > 2) return EP_ERR_INVALID_ARG;
     const int C = cfg->slots_per_subregion ? cfg->slots_per_subregion : cfg->max_tokens_per_rank;
     if (cfg->mode == EP_MODE_LL && (int64_t)E * C > 0x7fffffffLL) return EP_ERR_INVALID_ARG;
 
@@ -254,22 +277,36 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     }
     g->slab_ints = carve_slab(g, nullptr, nullptr);
     if (hipGetDevice(&g->device) != hipSuccess) { delete g; return EP_ERR_HIP; }
-    if (g->staging_slots > 0) {
+    g->nsets = cfg->staged_buffers;
+    auto fail = [&](ep_result_t r) {
+        for (int i = 0; i < 2; ++i) { dev_free(g, g->staging[i]); dev_free(g, g->signals[i]); dev_free(g, g->comb_stage[i]); }
+        for (auto& f : g->free_slabs) dev_free(g, f.base);
+        delete g;
+        return r;
+    };
+    const int nstaging = g->staging_slots > 0 ? (g->nsets > 1 ? g->nsets : 1) : 0;
+    for (int i = 0; i < nstaging; ++i) {
         void* p = nullptr;
         ep_result_t r = dev_alloc(g, &p, (size_t)(g->staging_slots * g->msg_bytes));
-        if (r != EP_SUCCESS) { delete g; return r; }
-        g->staging = (uint8_t*)p;
+        if (r != EP_SUCCESS) return fail(r);
+        g->staging[i] = (uint8_t*)p;
     }
+    for (int i = 0; i < g->nsets; ++i) {
+        void* p = nullptr;
+        ep_result_t r = dev_alloc(g, &p, sizeof(int32_t) * (size_t)g->sig_ints());
+        if (r != EP_SUCCESS) return fail(r);
+        g->signals[i] = (int32_t*)p;
+        if (launch_clear_counts(g->signals[i], g->sig_ints(), (hipStream_t)stream) != hipSuccess) return fail(EP_ERR_HIP);
+        r = dev_alloc(g, &p, (size_t)cfg->max_tokens_per_rank * K * H * 2);
+        if (r != EP_SUCCESS) return fail(r);
+        g->comb_stage[i] = (uint16_t*)p;
+    }
+    if (g->nsets > 0 && hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return fail(EP_ERR_HIP);
     const int nslabs = cfg->max_handles ? cfg->max_handles : 2;
     for (int i = 0; i < nslabs; ++i) {
         Slab s;
         ep_result_t r = new_slab(g, &s);
-        if (r != EP_SUCCESS) {
-            for (auto& f : g->free_slabs) dev_free(g, f.base);
-            dev_free(g, g->staging);
-            delete g;
-            return r;
-        }
+        if (r != EP_SUCCESS) return fail(r);
         g->free_slabs.push_back(s);
     }
     *group = g;
@@ -284,7 +321,7 @@ ep_result_t ep_group_destroy(ep_group_t g, ep_stream_t stream) {
     }
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
     for (auto& s : g->free_slabs) dev_free(g, s.base);
-    dev_free(g, g->staging);
+    for (int i = 0; i < 2; ++i) { dev_free(g, g->staging[i]); dev_free(g, g->signals[i]); dev_free(g, g->comb_stage[i]); }
     delete g;
     return EP_SUCCESS;
 }
@@ -300,7 +337,13 @@ ep_result_t ep_group_query(ep_group_t g, ep_group_info_t* info) {
     info->msg_header_bytes = g->hdr_bytes;
     info->msg_bytes = g->msg_bytes;
     info->staging_slots = g->staging_slots;
-    info->staging = g->staging;
+    info->staging = g->staging[0];
+    info->staged_buffers = g->nsets;
+    for (int i = 0; i < 2; ++i) {
+        info->staging_sets[i] = g->staging[i];
+        info->signals[i] = g->signals[i];
+        info->combine_staging[i] = g->comb_stage[i];
+    }
     const int64_t B = c.max_tokens_per_rank, P = info->row_bytes;
     info->footprint_per_expert_bytes = 2 * (int64_t)c.num_experts * B * P;
     info->footprint_optimised_bytes = (int64_t)c.num_ranks * B * P + B * c.top_k * P;
@@ -308,7 +351,6 @@ ep_result_t ep_group_query(ep_group_t g, ep_group_info_t* info) {
         std::lock_guard<std::mutex> lk(g->mu);
         info->live_handles = g->live_handles;
     }
-    info->reserved = 0;
     return EP_SUCCESS;
 }
 
@@ -389,6 +431,7 @@ ep_result_t ep_handle_query(ep_handle_t h, ep_layout_info_t* info) {
     info->sorted_token = s.sorted_token; info->sorted_k = s.sorted_k; info->sorted_row = s.sorted_row;
     if (tot[TOT_STATUS] & STATUS_INVALID_IDS) return EP_ERR_INVALID_ROUTING;
     if (tot[TOT_STATUS] & STATUS_OUTPUT_OVERFLOW) return EP_ERR_OVERFLOW;
+    if (tot[TOT_STATUS] & STATUS_TIMEOUT) return EP_ERR_TIMEOUT;
     return EP_SUCCESS;
 }
 
@@ -417,9 +460,11 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
                         const ep_tensor_t* outputs, int32_t num_outputs, int32_t send_only,
                         ep_stream_t stream) {
     if (!h || !inputs || !outputs || num_inputs < 1 || num_outputs < 1) return EP_ERR_INVALID_ARG;
-    if (send_only != 0) return EP_ERR_UNSUPPORTED;
+    if (send_only != 0 && send_only != 1) return EP_ERR_INVALID_ARG;
     if (has_scales(inputs, num_inputs)) return EP_ERR_UNSUPPORTED;  // inputs are bf16 tokens
     ep_group_s* g = h->group;
+    if (send_only && g->nsets == 0) return EP_ERR_UNSUPPORTED;
+    if (send_only && h->pending != PENDING_NONE) return EP_ERR_BUSY;
     const ep_group_config_t& c = g->cfg;
     const ep_tensor_t* x = find_tag(inputs, num_inputs, EP_TAG_TOKENS);
     const ep_tensor_t* w = find_tag(inputs, num_inputs, EP_TAG_TOPK_WEIGHTS);
@@ -459,10 +504,29 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     a.totals = h->slab.totals;
     a.T = h->T; a.K = c.top_k; a.H = c.hidden; a.E = c.num_experts;
     h->last_stream = (hipStream_t)stream;
-    if (fp8)
-        return launch_dispatch_fp8(a, (float*)rq->data, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
-    if (c.dispatch_path == EP_PATH_DIRECT)
-        return launch_dispatch(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+    int set = 0;
+    if (send_only) {
+        std::lock_guard<std::mutex> lk(g->mu);
+        set = g->next_set;
+        g->next_set = (set + 1) % g->nsets;
+    }
+    if (fp8 || c.dispatch_path == EP_PATH_DIRECT) {
+        // staged: rows go straight to the output windows (they are the receive region), the
+        // per-expert counts are delivered by ep_complete from the coordination counters
+        int32_t* recv_count = a.recv_count;
+        if (send_only) a.recv_count = nullptr;
+        hipError_t e = fp8 ? launch_dispatch_fp8(a, (float*)rq->data, (hipStream_t)stream)
+                           : launch_dispatch(a, (hipStream_t)stream);
+        if (e != hipSuccess) return EP_ERR_HIP;
+        if (send_only) {
+            if (launch_publish_counts(g->sig_dispatch(set), h->slab.expert_kept, c.num_experts, (hipStream_t)stream) != hipSuccess)
+                return EP_ERR_HIP;
+            h->pending = PENDING_DISPATCH_DIRECT;
+            h->pending_set = set;
+            h->pending_recv_count = recv_count;
+        }
+        return EP_SUCCESS;
+    }
 
     // Once per destination rank: send to the staging windows, rank the header entries on
     // the receiving side, fan out to the expert rows.
@@ -474,7 +538,7 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     sa.topk = (const int32_t*)ti->data; sa.topk_stride = ti->stride[0];
     sa.w = a.w; sa.w_stride = a.w_stride;
     sa.rank_row = s.rank_row;
-    sa.staging = g->staging; sa.msg_bytes = g->msg_bytes; sa.staging_slots = g->staging_slots;
+    sa.staging = g->staging[set]; sa.msg_bytes = g->msg_bytes; sa.staging_slots = g->staging_slots;
     sa.hdr_units = (int)(g->hdr_bytes / 16);
     sa.totals = s.totals;
     sa.T = h->T; sa.K = c.top_k; sa.H = c.hidden;
@@ -496,29 +560,77 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     la.totals = s.recv_totals;
     la.slot = nullptr; la.dst_row = s.recv_dst_row; la.rank_row = nullptr;
     la.sorted_token = nullptr; la.sorted_k = nullptr; la.sorted_row = nullptr;
-    la.msgs = g->staging; la.msg_bytes = g->msg_bytes; la.msg_total_slots = (int)g->staging_slots;
+    la.msgs = g->staging[set]; la.msg_bytes = g->msg_bytes; la.msg_total_slots = (int)g->staging_slots;
     la.msg_slots_per_rank = c.mode == EP_MODE_LL ? c.max_tokens_per_rank : 0;
-    la.msg_rank_offset = s.rank_offset; la.msg_rank_count = s.rank_token_count;
-    if (launch_layout(la, (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
+    // a staged call lets the receiving side learn the message counts from the counters
+    la.msg_rank_offset = send_only ? s.recv_rank_offset : s.rank_offset;
+    la.msg_rank_count = send_only ? s.recv_rank_count : s.rank_token_count;
 
     DedupFanoutArgs fa;
-    fa.staging = g->staging; fa.msg_bytes = g->msg_bytes; fa.hdr_bytes = g->hdr_bytes;
+    fa.staging = g->staging[set]; fa.msg_bytes = g->msg_bytes; fa.hdr_bytes = g->hdr_bytes;
     fa.staging_slots = g->staging_slots; fa.slots_per_rank = la.msg_slots_per_rank;
-    fa.rank_offset = s.rank_offset; fa.rank_count = s.rank_token_count;
+    fa.rank_offset = la.msg_rank_offset; fa.rank_count = la.msg_rank_count;
     fa.recv_dst_row = s.recv_dst_row; fa.recv_kept = s.recv_kept;
     fa.win = a.win; fa.recv_w = a.recv_w; fa.recv_src = a.recv_src; fa.recv_count = a.recv_count;
     fa.totals = s.totals;
     fa.K = c.top_k; fa.H = c.hidden; fa.E = c.num_experts; fa.R = c.num_ranks;
+    if (send_only) {
+        if (launch_publish_counts(g->sig_rank(set), s.rank_token_count, c.num_ranks, (hipStream_t)stream) != hipSuccess)
+            return EP_ERR_HIP;
+        h->pending = PENDING_DISPATCH_DEDUP;
+        h->pending_set = set;
+        h->pending_layout = la;
+        h->pending_fanout = fa;
+        return EP_SUCCESS;
+    }
+    if (launch_layout(la, (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
     return launch_dedup_fanout(fa, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+}
+
+ep_result_t ep_complete(ep_handle_t h, const ep_complete_config_t* cfg, ep_stream_t stream) {
+    if (!h) return EP_ERR_INVALID_ARG;
+    if (cfg && cfg->size != sizeof(ep_complete_config_t)) return EP_ERR_INVALID_ARG;
+    if (h->pending == PENDING_NONE) return EP_ERR_INVALID_ARG;
+    ep_group_s* g = h->group;
+    const ep_group_config_t& c = g->cfg;
+    int spin = cfg && cfg->spin_limit > 0 ? cfg->spin_limit : (1 << 20);
+    const int set = h->pending_set;
+    const int kind = h->pending;
+    hipStream_t st = (hipStream_t)stream;
+    h->pending = PENDING_NONE;
+    h->last_stream = st;
+    const Slab& s = h->slab;
+    if (kind == PENDING_DISPATCH_DIRECT) {
+        return launch_await_counts(g->sig_dispatch(set), c.num_experts, spin, h->pending_recv_count, nullptr,
+                                   s.totals, st) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+    }
+    if (kind == PENDING_DISPATCH_DEDUP) {
+        if (launch_await_counts(g->sig_rank(set), c.num_ranks, spin, s.recv_rank_count, s.recv_rank_offset,
+                                s.totals, st) != hipSuccess) return EP_ERR_HIP;
+        if (launch_layout(h->pending_layout, st) != hipSuccess) return EP_ERR_HIP;
+        return launch_dedup_fanout(h->pending_fanout, st) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+    }
+    if (launch_await_counts(g->sig_combine(set), c.num_experts, spin, nullptr, nullptr, s.totals, st) != hipSuccess)
+        return EP_ERR_HIP;
+    return launch_combine(h->pending_combine, st) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+}
+
+ep_result_t ep_group_reset_signals(ep_group_t g, ep_stream_t stream) {
+    if (!g) return EP_ERR_INVALID_ARG;
+    for (int i = 0; i < g->nsets; ++i)
+        if (launch_clear_counts(g->signals[i], g->sig_ints(), (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
+    return EP_SUCCESS;
 }
 
 ep_result_t ep_combine(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inputs,
                        const ep_tensor_t* outputs, int32_t num_outputs, int32_t send_only,
                        ep_stream_t stream) {
     if (!h || !inputs || !outputs || num_inputs < 1 || num_outputs < 1) return EP_ERR_INVALID_ARG;
-    if (send_only != 0) return EP_ERR_UNSUPPORTED;
+    if (send_only != 0 && send_only != 1) return EP_ERR_INVALID_ARG;
     if (has_scales(inputs, num_inputs) || has_scales(outputs, num_outputs)) return EP_ERR_UNSUPPORTED;
     ep_group_s* g = h->group;
+    if (send_only && g->nsets == 0) return EP_ERR_UNSUPPORTED;
+    if (send_only && h->pending != PENDING_NONE) return EP_ERR_BUSY;
     const ep_group_config_t& c = g->cfg;
     const ep_tensor_t* y = find_tag(inputs, num_inputs, EP_TAG_TOKENS);
     const ep_tensor_t* w = find_tag(inputs, num_inputs, EP_TAG_TOPK_WEIGHTS);
@@ -534,8 +646,26 @@ ep_result_t ep_combine(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inp
     a.out = (uint16_t*)out->data;
     a.out_stride = out->stride[0];
     a.T = h->T; a.K = c.top_k; a.H = c.hidden;
+    a.staged = 0;
     h->last_stream = (hipStream_t)stream;
-    return launch_combine(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+    if (!send_only) return launch_combine(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+    // staged: the expert side packs its rows into the (t,k)-indexed staging and raises the
+    // counters; ep_complete reduces from the staging
+    int set;
+    {
+        std::lock_guard<std::mutex> lk(g->mu);
+        set = g->next_set;
+        g->next_set = (set + 1) % g->nsets;
+    }
+    if (launch_combine_pack(a, g->comb_stage[set], (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
+    if (launch_publish_counts(g->sig_combine(set), nullptr, c.num_experts, (hipStream_t)stream) != hipSuccess)
+        return EP_ERR_HIP;
+    h->pending = PENDING_COMBINE;
+    h->pending_set = set;
+    h->pending_combine = a;
+    h->pending_combine.win.base = g->comb_stage[set];
+    h->pending_combine.staged = 1;
+    return EP_SUCCESS;
 }
 
 }  // extern "C"

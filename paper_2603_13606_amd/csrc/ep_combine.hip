@@ -75,11 +75,14 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nseg, i
                 w = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), k));
             }
             if (r >= a.win.rows_cap) r = -1;
+            if (a.staged && r >= 0) r = t * a.K + k;  // (t,k)-indexed staging (Sec. IV-D)
             row[j] = r;
             wk[j] = w;
             v[j] = (u32x4){0u, 0u, 0u, 0u};
-            if (r >= 0 && active)
-                v[j] = __builtin_nontemporal_load((const u32x4*)(a.win.base + window_offset(a.win, r)) + unit);
+            if (r >= 0 && active) {
+                const int64_t off = a.staged ? (int64_t)r * a.H : window_offset(a.win, r);
+                v[j] = __builtin_nontemporal_load((const u32x4*)(a.win.base + off) + unit);
+            }
         }
 #pragma unroll
         for (int j = 0; j < KB; ++j)

@@ -22,7 +22,7 @@ constexpr int kTotalsWords = 16;
 enum { TOT_KEPT = 0, TOT_DROPPED, TOT_MASKED, TOT_INVALID, TOT_SORTED, TOT_MSGS, TOT_STATUS,
        TOT_ROWS_END };
 
-enum { STATUS_INVALID_IDS = 1, STATUS_CAPACITY_DROP = 2, STATUS_OUTPUT_OVERFLOW = 4 };
+enum { STATUS_INVALID_IDS = 1, STATUS_CAPACITY_DROP = 2, STATUS_OUTPUT_OVERFLOW = 4, STATUS_TIMEOUT = 8 };
 
 // Everything the layout kernels need.  All pointers are device pointers.
 struct LayoutArgs {
@@ -101,6 +101,7 @@ struct CombineArgs {
     uint16_t* out;
     int64_t out_stride;
     int T, K, H;
+    int staged;              // 1: y is the (t,k)-indexed staging, entry (t,k) sits in row t*K + k
 };
 
 struct DedupSendArgs {
@@ -142,6 +143,11 @@ hipError_t launch_dedup_fanout(const DedupFanoutArgs& a, hipStream_t s);
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s);
 hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStream_t s);
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
+hipError_t launch_publish_counts(int32_t* sig, const int32_t* counts, int n, hipStream_t s);
+hipError_t launch_await_counts(int32_t* sig, int n, int spin_limit, int32_t* count_out, int32_t* offset_out,
+                               int32_t* totals, hipStream_t s);
+hipError_t launch_clear_counts(int32_t* sig, int n, hipStream_t s);
+hipError_t launch_combine_pack(const CombineArgs& a, uint16_t* stage, hipStream_t s);
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 // Host-side planning helpers (pure functions, testable without a GPU).

@@ -37,17 +37,18 @@ def test_every_declared_function_is_exported(ep):
 
 
 def test_struct_sizes_match_header(ep):
-    # config: uint32 + 11 int32; tensor: pointer + 4 int32 + 8 int64
-    assert ctypes.sizeof(ep.ep_group_config_t) == 48
+    # config: uint32 + 12 int32; tensor: pointer + 4 int32 + 8 int64
+    assert ctypes.sizeof(ep.ep_group_config_t) == 52
     assert ctypes.sizeof(ep.ep_tensor_t) == 8 + 16 + 64
     assert ctypes.sizeof(ep.ep_layout_info_t) == 8 + 7 * 8 + 12 * 8
-    assert ctypes.sizeof(ep.ep_group_info_t) == 40 + 7 * 8 + 8
+    assert ctypes.sizeof(ep.ep_group_info_t) == 40 + 7 * 8 + 8 + 6 * 8
+    assert ctypes.sizeof(ep.ep_complete_config_t) == 8
 
 
 def test_error_strings_and_version(ep):
     assert ep.ep_version() >= 100
-    seen = {ep.error_string(c) for c in range(8)}
-    assert len(seen) == 8 and "success" in seen
+    seen = {ep.error_string(c) for c in range(9)}
+    assert len(seen) == 9 and "success" in seen
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -60,6 +61,7 @@ def test_error_strings_and_version(ep):
     (dict(max_tokens_per_rank=0), 1),
     (dict(mode=5), 1),
     (dict(dtype=1), 4),                # only bf16 tokens
+    (dict(staged_buffers=3), 1),
 ])
 def test_group_create_rejects_bad_config_on_the_host(ep, kw, code):
     args = dict(num_ranks=2, num_experts=8, hidden=256, top_k=2, max_tokens_per_rank=64)
@@ -83,6 +85,8 @@ def test_null_arguments(ep):
     assert lib.ep_dispatch(None, None, 0, None, 0, 0, None) == ep.EP_ERR_INVALID_ARG
     assert lib.ep_combine(None, None, 0, None, 0, 0, None) == ep.EP_ERR_INVALID_ARG
     assert lib.ep_layout(None, None, None, None, None) == ep.EP_ERR_INVALID_ARG
+    assert lib.ep_complete(None, None, None) == ep.EP_ERR_INVALID_ARG
+    assert lib.ep_group_reset_signals(None, None) == ep.EP_ERR_INVALID_ARG
 
 
 def test_header_is_plain_c_and_cxx(tmp_path):

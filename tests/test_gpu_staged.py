@@ -1,0 +1,213 @@
+"""Staged execution (send_only + ep_complete), coordination counters and double
+buffering: counters carry count + 1 after the send phase (the value the paper states),
+and the completed calls give the same outputs as the one-shot calls, i.e. the oracle's."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_13606_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ep():
+    from paper_2603_13606_amd import binding
+    binding.load()
+    assert torch.cuda.is_available()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def hx():
+    import ep_harness
+    return ep_harness
+
+
+def _signals(ep, g, spec, which):
+    info = ep.ep_group_query(g)
+    n = 2 * spec.E + spec.R
+    return ep.read_device_i32(info.signals[which], n).numpy()
+
+
+def _setup(ep, hx, oracle_mod, name, T, H, mode, path, sets=2, C=0):
+    w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
+    spec = w.spec
+    ll = mode == "ll"
+    Cc = (C if C else spec.T) if ll else 0
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, layout=int(ll), C=Cc, C_rank=spec.T)
+    cfg = ep.make_config(spec.R, spec.E, spec.H, spec.K, spec.T, mode=ep.EP_MODE_LL if ll else ep.EP_MODE_HT,
+                         slots_per_subregion=C, dispatch_path=path, staged_buffers=sets, max_handles=3)
+    g = ep.ep_group_create(cfg)
+    rows = spec.E * Cc if ll else int(lay.expert_offset[-1])
+    return w, spec, lay, g, rows, Cc
+
+
+@pytest.mark.parametrize("mode,C", [("ht", 0), ("ll", 20)])
+def test_staged_direct_dispatch_and_combine(ep, hx, oracle_mod, mode, C):
+    w, spec, lay, g, rows, Cc = _setup(ep, hx, oracle_mod, "ll_decode", 96, 1024, mode, ep.EP_PATH_DIRECT, C=C)
+    ll = mode == "ll"
+    try:
+        topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
+        gate = torch.from_numpy(w.topk_w).to(hx.DEV)
+        x = hx.bits_to_dev(w.x_bits)
+        h = ep.ep_layout(g, topk)
+        store = hx.poison_bf16((rows, spec.H))
+        recv = store.view(spec.E, Cc, spec.H) if ll else store
+        cnt = torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)
+        ep.ep_dispatch(h, x, recv, topk_weights=gate, recv_count=cnt, send_only=1)
+        torch.cuda.synchronize()
+        sig = _signals(ep, g, spec, 0)
+        assert np.array_equal(sig[:spec.E], lay.expert_kept + 1)     # V = m + 1
+        assert np.all(sig[spec.E:] == 0) and np.all(_signals(ep, g, spec, 1) == 0)
+        assert np.all(cnt.cpu().numpy() == -1)                        # delivered by ep_complete
+        with pytest.raises(ep.EpError) as e:
+            ep.ep_dispatch(h, x, recv, send_only=1)
+        assert e.value.code == ep.EP_ERR_BUSY
+        ep.ep_complete(h)
+        torch.cuda.synchronize()
+        assert np.array_equal(cnt.cpu().numpy(), lay.expert_kept)
+        assert np.all(_signals(ep, g, spec, 0) == 0)
+        o_recv = np.full((rows, spec.H), hx.POISON, np.uint16)
+        oracle_mod.dispatch(w.x_bits, None, lay, o_recv)
+        assert np.array_equal(hx.dev_to_bits(store), o_recv)
+        with pytest.raises(ep.EpError) as e:
+            ep.ep_complete(h)
+        assert e.value.code == ep.EP_ERR_INVALID_ARG
+        # staged combine: pack into the (t,k)-indexed staging, then reduce
+        out = hx.poison_bf16((spec.T, spec.H))
+        ep.ep_combine(h, recv, out, topk_weights=gate, send_only=1)
+        torch.cuda.synchronize()
+        sig = _signals(ep, g, spec, 1)                                # second buffer set
+        assert np.all(sig[spec.E + spec.R:] == 1) and np.all(sig[:spec.E + spec.R] == 0)
+        assert np.all(hx.dev_to_bits(out) == hx.POISON)
+        ginfo = ep.ep_group_query(g)
+        stage = ep.read_device_i32(ginfo.combine_staging[1], spec.T * spec.K * spec.H // 2).numpy().view(np.uint16)
+        stage = stage.reshape(spec.T * spec.K, spec.H)
+        flat = lay.dst_row.reshape(-1)
+        valid = flat >= 0
+        assert np.array_equal(stage[valid], o_recv[flat[valid]])
+        ep.ep_complete(h)
+        torch.cuda.synchronize()
+        assert np.array_equal(hx.dev_to_bits(out), oracle_mod.combine(o_recv, w.topk_w, lay, spec.H, acc="f32"))
+        assert np.all(_signals(ep, g, spec, 1) == 0)
+        info = ep.ep_handle_query(h)
+        assert not info.status & ep.STATUS_TIMEOUT
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+@pytest.mark.parametrize("mode,C", [("ht", 0), ("ll", 7)])
+def test_staged_once_per_rank_dispatch(ep, hx, oracle_mod, mode, C):
+    w, spec, lay, g, rows, Cc = _setup(ep, hx, oracle_mod, "ll_decode", 80, 512, mode, ep.EP_PATH_RANK_DEDUP, C=C)
+    ll = mode == "ll"
+    try:
+        topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
+        gate = torch.from_numpy(w.topk_w).to(hx.DEV)
+        h = ep.ep_layout(g, topk)
+        store = hx.poison_bf16((rows, spec.H))
+        recv = store.view(spec.E, Cc, spec.H) if ll else store
+        r_w = torch.full((rows,), -3.5, dtype=torch.float32, device=hx.DEV)
+        r_src = torch.full((rows,), -9, dtype=torch.int32, device=hx.DEV)
+        cnt = torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)
+        ep.ep_dispatch(h, hx.bits_to_dev(w.x_bits), recv, topk_weights=gate, recv_w=r_w, recv_src=r_src,
+                       recv_count=cnt, topk_idx=topk, send_only=1)
+        torch.cuda.synchronize()
+        sig = _signals(ep, g, spec, 0)
+        assert np.array_equal(sig[spec.E:spec.E + spec.R], lay.rank_token_count + 1)
+        assert np.all(hx.dev_to_bits(store) == hx.POISON)           # nothing fanned out yet
+        ginfo = ep.ep_group_query(g)
+        n_slots = int(ginfo.staging_slots)
+        o_win = oracle_mod.dedup_send(w.x_bits, w.topk_idx, w.topk_w, lay, n_slots)
+        got = ep.read_device_i32(ginfo.staging_sets[0], n_slots * int(ginfo.msg_bytes) // 4).numpy().view(np.uint8)
+        got = got.reshape(n_slots, -1)
+        used = np.zeros(n_slots, bool)
+        used[lay.rank_row[lay.rank_row >= 0]] = True
+        assert np.array_equal(got[used], o_win[used])
+        ep.ep_complete(h)
+        torch.cuda.synchronize()
+        o_recv = np.full((rows, spec.H), hx.POISON, np.uint16)
+        o_w = np.full(rows, np.float32(-3.5), np.float32)
+        o_src = np.full(rows, -9, np.int32)
+        oracle_mod.dispatch(w.x_bits, w.topk_w, lay, o_recv, o_w, o_src)
+        assert np.array_equal(hx.dev_to_bits(store), o_recv)
+        assert np.array_equal(r_w.cpu().numpy(), o_w) and np.array_equal(r_src.cpu().numpy(), o_src)
+        assert np.array_equal(cnt.cpu().numpy(), lay.expert_kept)
+        assert np.all(_signals(ep, g, spec, 0) == 0)
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_two_micro_batches_in_flight_on_two_streams(ep, hx, oracle_mod):
+    """The decode pattern of Sec. III-F: dispatch of micro-batch 1 is sent while micro-batch 0
+    is being completed and combined; sends run on one stream, receive phases on another."""
+    w0, spec, lay0, g, rows0, _ = _setup(ep, hx, oracle_mod, "ll_decode", 128, 1024, "ht", ep.EP_PATH_DIRECT)
+    w1 = wl.make_workload("ll_decode", T=128, H=1024, seed_offset=7)
+    lay1 = oracle_mod.layout(w1.topk_idx, E=spec.E, R=spec.R, C_rank=spec.T)
+    try:
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        batches = []
+        for w, lay in ((w0, lay0), (w1, lay1)):
+            rows = int(lay.expert_offset[-1])
+            batches.append(dict(w=w, lay=lay, rows=rows, topk=torch.from_numpy(w.topk_idx).to(hx.DEV),
+                                gate=torch.from_numpy(w.topk_w).to(hx.DEV), x=hx.bits_to_dev(w.x_bits),
+                                recv=hx.poison_bf16((rows, spec.H)), out=hx.poison_bf16((spec.T, spec.H)),
+                                cnt=torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)))
+        torch.cuda.synchronize()
+        for b in batches:  # both sends are enqueued before any receive phase
+            b["h"] = ep.ep_layout(g, b["topk"], stream=sa)
+            ep.ep_dispatch(b["h"], b["x"], b["recv"], recv_count=b["cnt"], send_only=1, stream=sa)
+        for b in batches:  # receive phases on the other stream; the wait happens on the device
+            ep.ep_complete(b["h"], stream=sb)
+            ep.ep_combine(b["h"], b["recv"], b["out"], topk_weights=b["gate"], stream=sb)
+        torch.cuda.synchronize()
+        for b in batches:
+            info = ep.ep_handle_query(b["h"])
+            assert not info.status & ep.STATUS_TIMEOUT
+            o_recv = np.full((b["rows"], spec.H), hx.POISON, np.uint16)
+            oracle_mod.dispatch(b["w"].x_bits, None, b["lay"], o_recv)
+            assert np.array_equal(hx.dev_to_bits(b["recv"]), o_recv)
+            assert np.array_equal(b["cnt"].cpu().numpy(), b["lay"].expert_kept)
+            assert np.array_equal(hx.dev_to_bits(b["out"]),
+                                  oracle_mod.combine(o_recv, b["w"].topk_w, b["lay"], spec.H, acc="f32"))
+            ep.ep_handle_destroy(b["h"])
+        assert np.all(_signals(ep, g, spec, 0) == 0) and np.all(_signals(ep, g, spec, 1) == 0)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_complete_gives_up_when_counters_never_arrive(ep, hx, oracle_mod):
+    """The wait is bounded: with the counters cleared behind its back, ep_complete flags a
+    time-out, reports zero counts, and every kernel still exits normally."""
+    w, spec, lay, g, rows, _ = _setup(ep, hx, oracle_mod, "tiny", None, None, "ht", ep.EP_PATH_DIRECT, sets=1)
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(w.topk_idx).to(hx.DEV))
+        recv = hx.poison_bf16((rows, spec.H))
+        cnt = torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)
+        ep.ep_dispatch(h, hx.bits_to_dev(w.x_bits), recv, recv_count=cnt, send_only=1)
+        ep.ep_group_reset_signals(g)          # the "peer" never signals
+        ep.ep_complete(h, spin_limit=4)
+        info = ep.ep_handle_query(h, ok=(ep.EP_ERR_TIMEOUT,))
+        assert info.last_code == ep.EP_ERR_TIMEOUT and info.status & ep.STATUS_TIMEOUT
+        assert np.all(cnt.cpu().numpy() == 0)
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_send_only_needs_buffer_sets(ep, hx):
+    spec = wl.SPECS["tiny"]
+    g = ep.ep_group_create(ep.make_config(spec.R, spec.E, spec.H, spec.K, spec.T))
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(wl.make_routing(spec)[0]).to(hx.DEV))
+        x = torch.zeros((spec.T, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        recv = torch.zeros((spec.T * spec.K, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        for call in (lambda: ep.ep_dispatch(h, x, recv, send_only=1), lambda: ep.ep_combine(h, recv, x, send_only=1)):
+            with pytest.raises(ep.EpError) as e:
+                call()
+            assert e.value.code == ep.EP_ERR_UNSUPPORTED
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
