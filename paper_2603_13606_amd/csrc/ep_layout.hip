@@ -227,6 +227,28 @@ __device__ __forceinline__ void hist_group(const LayoutArgs& a, const Entry (&en
     }
 }
 
+// Writes what the layout records for one entry, given its slot among the entries of its
+// expert and (for a leader) its slot among the tokens of its destination rank.
+__device__ __forceinline__ void emit_entry(const LayoutArgs& a, const Entry& x, int slot, int rslot, const Lds& l) {
+    int row = -1, rrow = -1;
+    if (x.ok) {
+        if (a.padded) row = slot < a.C ? x.e * a.C + slot : -1;
+        else row = l.eoff[x.e] + slot;
+        if (a.sorted_token) {
+            const int pos = l.opre[x.e] + slot;
+            a.sorted_token[pos] = x.t;
+            a.sorted_k[pos] = x.k;
+            a.sorted_row[pos] = row;
+        }
+    }
+    if (x.lead) rrow = l.roff[x.d] + rslot;
+    if (x.i >= 0) {
+        if (a.slot) a.slot[x.i] = slot;
+        a.dst_row[x.i] = row;
+        if (a.rank_row) a.rank_row[x.i] = rrow;
+    }
+}
+
 // Slot assignment for a loaded group: h holds, per bin, the number of entries of
 // that bin before the group; it is advanced as the group is walked.  LDS accesses
 // of one wavefront are performed in program order, and the wave barriers keep the
@@ -243,30 +265,15 @@ __device__ __forceinline__ void slots_group(const LayoutArgs& a, const Entry (&e
         const uint64_t peers_r = MSGS ? 0ull : match_key(x.d, x.lead, a.bits_r);
         const int rank = __popcll(peers & lt);
         const int rank_r = __popcll(peers_r & lt);
-        int slot = -1, row = -1, rrow = -1;
-        if (x.ok) {
-            slot = h[x.e] + rank;
-            if (a.padded) row = slot < a.C ? x.e * a.C + slot : -1;
-            else row = l.eoff[x.e] + slot;
-        }
-        if (x.lead) rrow = l.roff[x.d] + h[a.E + 2 + x.d] + rank_r;
+        const int slot = x.ok ? h[x.e] + rank : -1;
+        const int rslot = x.lead ? h[a.E + 2 + x.d] + rank_r : -1;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
         __builtin_amdgcn_wave_barrier();
         if (x.ok && rank == 0) h[x.e] += __popcll(peers);
         if (x.lead && rank_r == 0) h[a.E + 2 + x.d] += __popcll(peers_r);
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
         __builtin_amdgcn_wave_barrier();
-        if (x.ok && a.sorted_token) {
-            const int pos = l.opre[x.e] + slot;
-            a.sorted_token[pos] = x.t;
-            a.sorted_k[pos] = x.k;
-            a.sorted_row[pos] = row;
-        }
-        if (x.i >= 0) {
-            if (a.slot) a.slot[x.i] = slot;
-            a.dst_row[x.i] = row;
-            if (a.rank_row) a.rank_row[x.i] = rrow;
-        }
+        emit_entry(a, x, slot, rslot, l);
     }
 }
 
@@ -501,6 +508,76 @@ __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
     if (b == 0 && w == 0) wave_write_tables(a, l, lane);
 }
 
+// ---- inputs of at most 1024 entries: one workgroup, one entry per thread, bitmaps ----
+//
+// Every bin keeps one bit per entry (a 64-bit word per wavefront).  An entry sets its bit;
+// its slot is the number of set bits below its own position in the bitmap of its bin --
+// a handful of independent LDS reads and popcounts instead of a histogram, a scan across
+// waves and a ballot walk.  Bits are set with atomic ORs, whose result does not depend on
+// their order.
+constexpr int kBitmapWords = 16;   // words per bitmap: one per wavefront of a 1024-thread workgroup
+constexpr int kBitmapStride = 17;  // row stride in words: odd, so that the rows start in different LDS banks
+
+size_t bitmap_lds_bytes(const LayoutArgs& a) {
+    return 8 * (size_t)(a.E + a.R) * kBitmapStride + sizeof(int32_t) * (2 * (size_t)a.W + 2 * (a.E + 1) + (a.R + 1));
+}
+
+// Set bits of a bitmap row below position (w, lane): all 16 words are read at once.
+__device__ __forceinline__ int bits_below(const uint64_t* row, int w, uint64_t below_in_word) {
+    uint64_t v[kBitmapWords];
+#pragma unroll
+    for (int j = 0; j < kBitmapWords; ++j) v[j] = row[j];
+    int n = 0;
+#pragma unroll
+    for (int j = 0; j < kBitmapWords; ++j) {
+        const uint64_t m = j < w ? ~0ull : (j == w ? below_in_word : 0ull);
+        n += __popcll(v[j] & m);
+    }
+    return n;
+}
+
+__global__ __launch_bounds__(1024) void layout_bitmap_kernel(LayoutArgs a) {
+    extern __shared__ int32_t lds[];
+    const int nbins = a.E + a.R;  // expert bitmaps, then destination-rank bitmaps
+    uint64_t* bm = (uint64_t*)lds;
+    Lds l;
+    l.wh = nullptr;
+    l.tot = lds + 2 * nbins * kBitmapStride;
+    l.pre = l.tot + a.W;
+    l.eoff = l.pre + a.W;
+    l.opre = l.eoff + a.E + 1;
+    l.roff = l.opre + a.E + 1;
+    l.mroff = l.mcnt = nullptr;
+    const int tid = threadIdx.x;
+    const int lane = lane_id();
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int raw[PU], dwin[PU];
+    issue_group<false>(a, w, 0, lane, l, raw, dwin);  // one pass: the entry of this thread
+    for (int j = tid; j < nbins * kBitmapStride; j += blockDim.x) bm[j] = 0ull;
+    for (int j = tid; j < a.W; j += blockDim.x) l.tot[j] = 0;
+    lds_barrier();
+    Entry en[PU];
+    classify_group<false>(a, w, 0, lane, raw, dwin, en);
+    const Entry& x = en[0];
+    const uint64_t bit = 1ull << lane;
+    if (x.ok) atomicOr((unsigned long long*)&bm[x.e * kBitmapStride + w], (unsigned long long)bit);
+    if (x.lead) atomicOr((unsigned long long*)&bm[(a.E + x.d) * kBitmapStride + w], (unsigned long long)bit);
+    const uint64_t bmask = __ballot(x.masked), binv = __ballot(x.invalid);
+    if (lane == 0) {
+        if (bmask) atomicAdd(&l.tot[a.E], __popcll(bmask));
+        if (binv) atomicAdd(&l.tot[a.E + 1], __popcll(binv));
+    }
+    lds_barrier();
+    for (int c = tid; c < nbins; c += blockDim.x)  // totals per bin
+        l.tot[c < a.E ? c : c + 2] = bits_below(bm + c * kBitmapStride, kBitmapWords, 0ull);
+    const int slot = x.ok ? bits_below(bm + x.e * kBitmapStride, w, bit - 1) : -1;
+    const int rslot = x.lead ? bits_below(bm + (a.E + x.d) * kBitmapStride, w, bit - 1) : -1;
+    lds_barrier();
+    wave_offsets(a, l, lane);
+    emit_entry(a, x, slot, rslot, l);
+    if (w == 0) wave_write_tables(a, l, lane);
+}
+
 constexpr size_t kLdsLimit = 64 * 1024;
 
 }  // namespace
@@ -522,6 +599,10 @@ void plan_layout(int n, int* passes, int* nwc) {
 }
 
 hipError_t launch_layout(const LayoutArgs& a, hipStream_t s) {
+    if (!a.msgs && a.passes == 1 && a.nwc >= 1 && a.nwc <= kLayoutWavesPerBlock && bitmap_lds_bytes(a) <= kLdsLimit) {
+        hipLaunchKernelGGL(layout_bitmap_kernel, dim3(1), dim3(a.nwc * kWave), bitmap_lds_bytes(a), s, a);
+        return hipGetLastError();
+    }
     // One workgroup of up to 16 waves when the plan has at most 16 wave-chunks and its
     // LDS tables fit; otherwise chunks of at most 8 waves so that the walk is spread
     // over many compute units while one thread per bin can add up the chunk histograms.
