@@ -59,6 +59,7 @@ def lib() -> ctypes.CDLL:
         _lib.ep_oracle_layout.restype = None
         _lib.ep_oracle_dispatch.restype = None
         _lib.ep_oracle_combine.restype = None
+        _lib.ep_oracle_combine_hier.restype = None
         _lib.ep_oracle_dedup_send.restype = None
         _lib.ep_oracle_dedup_recv.restype = None
     return _lib
@@ -173,6 +174,21 @@ def combine(y_bits: np.ndarray, w: Optional[np.ndarray], lay: Layout, H: int,
         _p(y_bits), ctypes.c_int(lay.layout), ctypes.c_int(max(lay.C, 1)), ctypes.c_int64(s0),
         ctypes.c_int64(s1), _p(wc), _p(lay.dst_row), ctypes.c_int(T), ctypes.c_int(lay.K),
         ctypes.c_int(H), _p(out), ctypes.c_int64(H), ctypes.c_int({"f64": 0, "f32": 1}[acc]))
+    return out
+
+
+def combine_hier(y_bits: np.ndarray, w: Optional[np.ndarray], lay: Layout, topk_idx: np.ndarray, H: int,
+                 ranks_per_node: int, stride0: Optional[int] = None, stride1: Optional[int] = None) -> np.ndarray:
+    """Combine with the two-level (per node, then across nodes) float32 summation order."""
+    assert y_bits.dtype == np.uint16
+    s0, s1 = _strides(lay.layout, lay.C, H, stride0, stride1)
+    out = np.zeros((lay.T, H), np.uint16)
+    wc = None if w is None else np.ascontiguousarray(w, dtype=np.float32)
+    lib().ep_oracle_combine_hier(
+        _p(y_bits), ctypes.c_int(lay.layout), ctypes.c_int(max(lay.C, 1)), ctypes.c_int64(s0),
+        ctypes.c_int64(s1), _p(wc), _p(lay.dst_row), _p(_i32(topk_idx)), ctypes.c_int(lay.T),
+        ctypes.c_int(lay.K), ctypes.c_int(H), ctypes.c_int(lay.E // lay.R), ctypes.c_int(lay.R),
+        ctypes.c_int(ranks_per_node), _p(out), ctypes.c_int64(H))
     return out
 
 

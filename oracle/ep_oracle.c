@@ -278,6 +278,42 @@ void ep_oracle_combine(const uint16_t *y, int layout, int C, int64_t stride0, in
     }
 }
 
+/* Hierarchical reduction order (Sec. V-A: partial results are accumulated within a
+ * node first, then reduced across nodes; Table III "Reduction: Hierarchical").  The
+ * ranks are grouped into nodes of ranks_per_node consecutive ranks; expert e lives on
+ * rank e / L.  For every token: for each node in ascending order, the products of the
+ * entries whose expert lives in that node are summed in ascending k (float32 multiply,
+ * float32 add); the node sums are then added in ascending node order (float32), and the
+ * result is rounded once to bf16.  Precision of the partial sums is this build's
+ * reading: the paper does not say in which type they travel. */
+void ep_oracle_combine_hier(const uint16_t *y, int layout, int C, int64_t stride0, int64_t stride1,
+                            const float *w, const int32_t *dst_row, const int32_t *topk_idx, int T,
+                            int K, int H, int L, int R, int ranks_per_node, uint16_t *out,
+                            int64_t out_stride) {
+    const int nodes = (R + ranks_per_node - 1) / ranks_per_node;
+    for (int t = 0; t < T; ++t) {
+        for (int h = 0; h < H; ++h) {
+            volatile float total = 0.0f;
+            for (int n = 0; n < nodes; ++n) {
+                volatile float part = 0.0f;
+                int any = 0;
+                for (int k = 0; k < K; ++k) {
+                    int32_t row = dst_row[t * K + k];
+                    if (row < 0) continue;
+                    if ((topk_idx[t * K + k] / L) / ranks_per_node != n) continue;
+                    float wk = w ? w[t * K + k] : 1.0f;
+                    float v = bf16_to_float(y[row_offset(row, layout, C, stride0, stride1) + h]);
+                    volatile float prod = wk * v;
+                    part = part + prod;
+                    any = 1;
+                }
+                if (any) total = total + part;
+            }
+            out[(int64_t)t * out_stride + h] = double_to_bf16((double)total);
+        }
+    }
+}
+
 /* ---- footprint-optimised dispatch: once per destination rank ------------------ */
 
 int64_t ep_oracle_msg_header_bytes(int K) {

@@ -606,3 +606,46 @@ def test_dispatch_fp8_places_quantised_rows(oracle_mod):
         for k in range(spec.K):
             r = lay.dst_row[t, k]
             assert np.array_equal(rq[r], q) and np.array_equal(rs[r], sc)
+
+
+# --------------------------------------------------------------------------- hierarchical combine order
+
+
+def test_combine_hier_order(oracle_mod):
+    w = wl.make_workload("ll_decode", T=40, H=96)
+    spec = w.spec
+    topk = w.topk_idx.copy()
+    topk[2, 3] = -1
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R)
+    rows = lay.expert_offset[-1]
+    y = wl.f32_to_bf16_bits(np.random.default_rng(9).standard_normal((rows, spec.H)).astype(np.float32) * 3)
+    flat = oracle_mod.combine(y, w.topk_w, lay, spec.H, acc="f32")
+    # one node holding every rank: the two-level order degenerates to the flat one
+    assert np.array_equal(oracle_mod.combine_hier(y, w.topk_w, lay, topk, spec.H, ranks_per_node=spec.R), flat)
+    rpn = 8
+    hier = oracle_mod.combine_hier(y, w.topk_w, lay, topk, spec.H, ranks_per_node=rpn)
+    # the same two-level order written with numpy float32 scalars (IEEE, round to nearest even)
+    yf = wl.bf16_bits_to_f32(y)
+    L = spec.L
+    want = np.zeros((spec.T, spec.H), np.float32)
+    for t in range(spec.T):
+        total = np.zeros(spec.H, np.float32)
+        for n in range(spec.R // rpn):
+            part, has = np.zeros(spec.H, np.float32), False
+            for k in range(spec.K):
+                if lay.dst_row[t, k] < 0 or (topk[t, k] // L) // rpn != n:
+                    continue
+                part = (part + (np.float32(w.topk_w[t, k]) * yf[lay.dst_row[t, k]]).astype(np.float32)).astype(np.float32)
+                has = True
+            if has:
+                total = (total + part).astype(np.float32)
+        want[t] = total
+    assert np.array_equal(hier, wl.f32_to_bf16_bits(want))
+    # a different association of the same sum: equal or adjacent bf16 values, and not always equal
+    def ordered(b):
+        b = b.astype(np.int32)
+        return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+    d = np.abs(ordered(hier) - ordered(flat))
+    assert d.max() <= 1
+    f64 = oracle_mod.combine(y, w.topk_w, lay, spec.H, acc="f64")
+    assert np.abs(ordered(hier) - ordered(f64)).max() <= 1
