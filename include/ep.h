@@ -112,6 +112,10 @@ typedef struct {
                                     set holds the coordination counters, a (t,k)-indexed
                                     combine staging of B*K rows and, on the once-per-rank
                                     path, its own staging windows                          */
+    int32_t ranks_per_node;      /* 0 or >= R: combine sums in flat k order; otherwise ranks
+                                    d with equal d / ranks_per_node form a node and combine
+                                    sums per node first, then across nodes (the HT
+                                    "hierarchical" reduction of Sec. III-D / V-A)          */
 } ep_group_config_t;
 
 /* Allocator callbacks (Sec. III-C): when given, every device allocation of the
@@ -169,6 +173,7 @@ typedef struct {
                                         slot) order                                        */
     const int32_t *sorted_k;         /* [entries_sorted] its k                             */
     const int32_t *sorted_row;       /* [entries_sorted] its destination row or -1         */
+    const int32_t *entry_rank;       /* [T,K] destination rank of the entry, -1 = not routed */
 } ep_layout_info_t;
 
 EP_API const char *ep_error_string(ep_result_t code);
@@ -287,7 +292,9 @@ EP_API ep_result_t ep_dispatch(ep_handle_t handle, const ep_tensor_t *inputs, in
  * outputs: TOKENS out [T, H] bf16.
  * out[t,h] = bf16_rne( sum over k = 0..K-1 in that order of w[t,k] * f32(y[dst_row[t,k], h]) )
  * with float32 multiply and float32 add, each rounded to nearest even; entries
- * without a destination row contribute nothing.
+ * without a destination row contribute nothing.  With ranks_per_node set (see the group
+ * configuration) the same products are summed per node in ascending k and the node sums
+ * are then added in ascending node order, still in float32 with one final rounding.
  * send_only = 1: the expert side packs the rows into the group's staging at slot
  * t*K + k (Sec. IV-D) and raises the combine counters to 1; ep_complete waits for them
  * and reduces from the staging into `out` (same arithmetic, same result).

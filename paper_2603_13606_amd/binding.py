@@ -63,7 +63,7 @@ class ep_group_config_t(ctypes.Structure):
                 ("max_tokens_per_rank", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("mode", ctypes.c_int32), ("slots_per_subregion", ctypes.c_int32),
                 ("dispatch_path", ctypes.c_int32), ("max_handles", ctypes.c_int32),
-                ("staged_buffers", ctypes.c_int32)]
+                ("staged_buffers", ctypes.c_int32), ("ranks_per_node", ctypes.c_int32)]
 
 
 class ep_complete_config_t(ctypes.Structure):
@@ -83,7 +83,8 @@ class ep_group_info_t(ctypes.Structure):
 
 
 _INFO_PTRS = ("expert_count", "expert_kept", "expert_offset", "rank_pair_count", "rank_token_count",
-              "rank_offset", "slot", "dst_row", "rank_row", "sorted_token", "sorted_k", "sorted_row")
+              "rank_offset", "slot", "dst_row", "rank_row", "sorted_token", "sorted_k", "sorted_row",
+              "entry_rank")
 
 
 class ep_layout_info_t(ctypes.Structure):
@@ -190,13 +191,14 @@ def _check(code: int, where: str, ok: Sequence[int] = (EP_SUCCESS,)) -> int:
 def make_config(num_ranks: int, num_experts: int, hidden: int, top_k: int, max_tokens_per_rank: int,
                 mode: int = EP_MODE_HT, my_rank: int = 0, slots_per_subregion: int = 0,
                 dispatch_path: int = EP_PATH_DIRECT, max_handles: int = 0,
-                dtype: int = EP_DTYPE_BF16, staged_buffers: int = 0) -> ep_group_config_t:
+                dtype: int = EP_DTYPE_BF16, staged_buffers: int = 0, ranks_per_node: int = 0) -> ep_group_config_t:
     c = ep_group_config_t()
     c.size = ctypes.sizeof(ep_group_config_t)
     c.num_ranks, c.my_rank, c.num_experts, c.hidden, c.top_k = num_ranks, my_rank, num_experts, hidden, top_k
     c.max_tokens_per_rank, c.dtype, c.mode = max_tokens_per_rank, dtype, mode
     c.slots_per_subregion, c.dispatch_path, c.max_handles = slots_per_subregion, dispatch_path, max_handles
     c.staged_buffers = staged_buffers
+    c.ranks_per_node = ranks_per_node
     return c
 
 

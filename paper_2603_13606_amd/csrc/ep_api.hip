@@ -19,7 +19,7 @@ struct Slab {
     // carved arrays
     int32_t *totals, *expert_count, *expert_kept, *expert_offset, *own_prefix;
     int32_t *rank_pair_count, *rank_token_count, *rank_offset, *hist;
-    int32_t *slot, *dst_row, *rank_row, *sorted_token, *sorted_k, *sorted_row;
+    int32_t *slot, *dst_row, *rank_row, *sorted_token, *sorted_k, *sorted_row, *entry_rank;
     // receiving side of the once-per-rank path (only carved for EP_PATH_RANK_DEDUP)
     int32_t *recv_totals, *recv_count, *recv_kept, *recv_offset, *recv_own_prefix, *recv_dst_row;
     // what the receiving side of a staged call learns from the coordination counters
@@ -110,7 +110,7 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
     const int64_t o_rt = carve(&cur, R), o_ro = carve(&cur, R + 1);
     const int64_t o_h = carve(&cur, (int64_t)kMaxWaveChunks * g->W);
     const int64_t o_sl = carve(&cur, nB), o_dr = carve(&cur, nB), o_rr = carve(&cur, nB);
-    const int64_t o_st = carve(&cur, nB), o_sk = carve(&cur, nB), o_sr = carve(&cur, nB);
+    const int64_t o_st = carve(&cur, nB), o_sk = carve(&cur, nB), o_sr = carve(&cur, nB), o_er = carve(&cur, nB);
     const bool dedup = g->cfg.dispatch_path == EP_PATH_RANK_DEDUP;
     const int64_t o_vt = dedup ? carve(&cur, kTotalsWords) : 0, o_vc = dedup ? carve(&cur, E) : 0;
     const int64_t o_vk = dedup ? carve(&cur, E) : 0, o_vo = dedup ? carve(&cur, E + 1) : 0;
@@ -124,6 +124,7 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
         s->rank_token_count = base + o_rt; s->rank_offset = base + o_ro;
         s->hist = base + o_h; s->slot = base + o_sl; s->dst_row = base + o_dr; s->rank_row = base + o_rr;
         s->sorted_token = base + o_st; s->sorted_k = base + o_sk; s->sorted_row = base + o_sr;
+        s->entry_rank = base + o_er;
         s->recv_totals = base + o_vt; s->recv_count = base + o_vc; s->recv_kept = base + o_vk;
         s->recv_offset = base + o_vo; s->recv_own_prefix = base + o_vp; s->recv_dst_row = base + o_vr;
         s->recv_rank_count = base + o_rc; s->recv_rank_offset = base + o_rf;
@@ -247,6 +248,7 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     if (cfg->dispatch_path != EP_PATH_DIRECT && cfg->dispatch_path != EP_PATH_RANK_DEDUP) return EP_ERR_INVALID_ARG;
     if (cfg->slots_per_subregion < 0 || cfg->max_handles < 0) return EP_ERR_INVALID_ARG;
     if (cfg->staged_buffers < 0 || cfg->staged_buffers > 2) return EP_ERR_INVALID_ARG;
+    if (cfg->ranks_per_node < 0) return EP_ERR_INVALID_ARG;
     const int C = cfg->slots_per_subregion ? cfg->slots_per_subregion : cfg->max_tokens_per_rank;
     if (cfg->mode == EP_MODE_LL && (int64_t)E * C > 0x7fffffffLL) return EP_ERR_INVALID_ARG;
 
@@ -402,6 +404,7 @@ ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk
     a.rank_token_count = s.rank_token_count; a.rank_offset = s.rank_offset; a.totals = s.totals;
     a.slot = s.slot; a.dst_row = s.dst_row; a.rank_row = s.rank_row; a.sorted_token = s.sorted_token;
     a.sorted_k = s.sorted_k; a.sorted_row = s.sorted_row;
+    a.entry_rank = s.entry_rank;
     a.msgs = nullptr; a.msg_bytes = 0; a.msg_total_slots = 0; a.msg_slots_per_rank = 0;
     a.msg_rank_offset = nullptr; a.msg_rank_count = nullptr;
     if (launch_layout(a, (hipStream_t)stream) != hipSuccess) {
@@ -427,7 +430,7 @@ ep_result_t ep_handle_query(ep_handle_t h, ep_layout_info_t* info) {
     info->expert_count = s.expert_count; info->expert_kept = s.expert_kept;
     info->expert_offset = s.expert_offset; info->rank_pair_count = s.rank_pair_count;
     info->rank_token_count = s.rank_token_count; info->rank_offset = s.rank_offset;
-    info->slot = s.slot; info->dst_row = s.dst_row; info->rank_row = s.rank_row;
+    info->slot = s.slot; info->dst_row = s.dst_row; info->rank_row = s.rank_row; info->entry_rank = s.entry_rank;
     info->sorted_token = s.sorted_token; info->sorted_k = s.sorted_k; info->sorted_row = s.sorted_row;
     if (tot[TOT_STATUS] & STATUS_INVALID_IDS) return EP_ERR_INVALID_ROUTING;
     if (tot[TOT_STATUS] & STATUS_OUTPUT_OVERFLOW) return EP_ERR_OVERFLOW;
@@ -558,7 +561,7 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     la.own_prefix = s.recv_own_prefix;
     la.rank_pair_count = nullptr; la.rank_token_count = nullptr; la.rank_offset = nullptr;
     la.totals = s.recv_totals;
-    la.slot = nullptr; la.dst_row = s.recv_dst_row; la.rank_row = nullptr;
+    la.slot = nullptr; la.dst_row = s.recv_dst_row; la.rank_row = nullptr; la.entry_rank = nullptr;
     la.sorted_token = nullptr; la.sorted_k = nullptr; la.sorted_row = nullptr;
     la.msgs = g->staging[set]; la.msg_bytes = g->msg_bytes; la.msg_total_slots = (int)g->staging_slots;
     la.msg_slots_per_rank = c.mode == EP_MODE_LL ? c.max_tokens_per_rank : 0;
@@ -647,6 +650,10 @@ ep_result_t ep_combine(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inp
     a.out_stride = out->stride[0];
     a.T = h->T; a.K = c.top_k; a.H = c.hidden;
     a.staged = 0;
+    // two-level order only when it differs from the flat one (more than one node)
+    a.ranks_per_node = (c.ranks_per_node > 0 && c.ranks_per_node < c.num_ranks) ? c.ranks_per_node : 0;
+    a.nodes = a.ranks_per_node ? (c.num_ranks + a.ranks_per_node - 1) / a.ranks_per_node : 1;
+    a.entry_rank = h->slab.entry_rank;
     h->last_stream = (hipStream_t)stream;
     if (!send_only) return launch_combine(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
     // staged: the expert side packs its rows into the (t,k)-indexed staging and raises the

@@ -96,6 +96,68 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nseg, i
     }
 }
 
+// Two-level summation order (Sec. V-A: partial results are accumulated within a node
+// first, then reduced across nodes): for every node in ascending order the products of
+// the entries whose expert lives in that node are summed in ascending k, and the node
+// sums are added in ascending node order; all in float32, one rounding to bf16 at the
+// end.  Same bytes moved as the flat kernel.
+__global__ __launch_bounds__(256) void combine_hier_kernel(CombineArgs a, int nseg, int units) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t u = (int64_t)blockIdx.x * 4 + wave;
+    if (u >= (int64_t)a.T * nseg) return;
+    const int t = (int)(u / nseg);
+    const int seg = (int)(u - (int64_t)t * nseg);
+    const int unit = seg * kWave + lane;
+    const bool active = unit < units;
+    int my_row = lane < a.K ? a.dst_row[(int64_t)t * a.K + lane] : -1;
+    if (my_row >= a.win.rows_cap) my_row = -1;
+    const float my_w = (a.w && lane < a.K) ? a.w[(int64_t)t * a.w_stride + lane] : 1.0f;
+    const int my_rank = lane < a.K ? a.entry_rank[(int64_t)t * a.K + lane] : -1;
+    const int my_node = (my_row >= 0 && my_rank >= 0) ? my_rank / a.ranks_per_node : -1;
+    float total[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) total[c] = 0.0f;
+    for (int n = 0; n < a.nodes; ++n) {
+        uint64_t members = __ballot(my_node == n);  // the k's of this node, ascending = bit order
+        if (members == 0) continue;
+        float part[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) part[c] = 0.0f;
+        while (members) {
+            u32x4 v[KB];
+            float wk[KB];
+            bool has[KB];
+#pragma unroll
+            for (int j = 0; j < KB; ++j) {
+                has[j] = members != 0;
+                v[j] = (u32x4){0u, 0u, 0u, 0u};
+                wk[j] = 0.0f;
+                if (has[j]) {
+                    const int k = __builtin_ctzll(members);
+                    members &= members - 1;
+                    int r = __builtin_amdgcn_readlane(my_row, k);
+                    wk[j] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), k));
+                    if (a.staged) r = t * a.K + k;
+                    const int64_t off = a.staged ? (int64_t)r * a.H : window_offset(a.win, r);
+                    if (active) v[j] = __builtin_nontemporal_load((const u32x4*)(a.win.base + off) + unit);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < KB; ++j)
+                if (has[j]) accumulate(part, v[j], wk[j]);
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) total[c] = __fadd_rn(total[c], part[c]);
+    }
+    if (active) {
+        u32x4 o;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) o[c] = f32_to_bf16(total[2 * c]) | (f32_to_bf16(total[2 * c + 1]) << 16);
+        __builtin_nontemporal_store(o, (u32x4*)(a.out + (int64_t)t * a.out_stride) + unit);
+    }
+}
+
 }  // namespace
 
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s) {
@@ -105,7 +167,10 @@ hipError_t launch_combine(const CombineArgs& a, hipStream_t s) {
     if (nwaves == 0) return hipSuccess;
     const int64_t nblk = (nwaves + 3) / 4;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(combine_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);
+    if (a.ranks_per_node > 0)
+        hipLaunchKernelGGL(combine_hier_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);
+    else
+        hipLaunchKernelGGL(combine_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);
     return hipGetLastError();
 }
 

@@ -52,6 +52,7 @@ struct LayoutArgs {
     int32_t* slot;            // [n]
     int32_t* dst_row;         // [n]
     int32_t* rank_row;        // [n]
+    int32_t* entry_rank;      // [n] destination rank of the entry, -1 if not routed (may be nullptr)
     int32_t* sorted_token;    // [n]
     int32_t* sorted_k;        // [n]
     int32_t* sorted_row;      // [n]
@@ -102,6 +103,9 @@ struct CombineArgs {
     int64_t out_stride;
     int T, K, H;
     int staged;              // 1: y is the (t,k)-indexed staging, entry (t,k) sits in row t*K + k
+    const int32_t* entry_rank;  // [T, K] destination rank per entry (two-level order only)
+    int ranks_per_node;      // > 0: sum per node first, then across nodes; 0: flat k order
+    int nodes;
 };
 
 struct DedupSendArgs {

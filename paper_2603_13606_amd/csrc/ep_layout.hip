@@ -246,6 +246,7 @@ __device__ __forceinline__ void emit_entry(const LayoutArgs& a, const Entry& x, 
         if (a.slot) a.slot[x.i] = slot;
         a.dst_row[x.i] = row;
         if (a.rank_row) a.rank_row[x.i] = rrow;
+        if (a.entry_rank) a.entry_rank[x.i] = x.ok ? x.d : -1;
     }
 }
 

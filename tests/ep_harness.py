@@ -44,11 +44,11 @@ def fetch_layout(handle, T: int, K: int, E: int, R: int, ok=(ep.EP_SUCCESS,)) ->
     info = ep.ep_handle_query(handle, ok=ok)
     n = T * K
     sizes = dict(expert_count=E, expert_kept=E, expert_offset=E + 1, rank_pair_count=R,
-                 rank_token_count=R, rank_offset=R + 1, slot=n, dst_row=n, rank_row=n,
+                 rank_token_count=R, rank_offset=R + 1, slot=n, dst_row=n, rank_row=n, entry_rank=n,
                  sorted_token=int(info.entries_sorted), sorted_k=int(info.entries_sorted),
                  sorted_row=int(info.entries_sorted))
     arrays = {k: ep.read_device_i32(getattr(info, k), v).numpy() for k, v in sizes.items()}
-    for k in ("slot", "dst_row", "rank_row"):
+    for k in ("slot", "dst_row", "rank_row", "entry_rank"):
         arrays[k] = arrays[k].reshape(T, K)
     return GpuLayout(info=info, arrays=arrays)
 

@@ -37,10 +37,10 @@ def test_every_declared_function_is_exported(ep):
 
 
 def test_struct_sizes_match_header(ep):
-    # config: uint32 + 12 int32; tensor: pointer + 4 int32 + 8 int64
-    assert ctypes.sizeof(ep.ep_group_config_t) == 52
+    # config: uint32 + 13 int32; tensor: pointer + 4 int32 + 8 int64
+    assert ctypes.sizeof(ep.ep_group_config_t) == 56
     assert ctypes.sizeof(ep.ep_tensor_t) == 8 + 16 + 64
-    assert ctypes.sizeof(ep.ep_layout_info_t) == 8 + 7 * 8 + 12 * 8
+    assert ctypes.sizeof(ep.ep_layout_info_t) == 8 + 7 * 8 + 13 * 8
     assert ctypes.sizeof(ep.ep_group_info_t) == 40 + 7 * 8 + 8 + 6 * 8
     assert ctypes.sizeof(ep.ep_complete_config_t) == 8
 

@@ -92,6 +92,8 @@ def test_layout_parity(ep, hx, oracle_mod, name, T, mode, C, masked):
                                  layout=oracle_mod.LAYOUT_PADDED if ll else oracle_mod.LAYOUT_CONCAT,
                                  C=Cc if ll else 0, C_rank=T)
         hx.assert_layout_equal(got, want)
+        routed = (topk >= 0) & (topk < spec.E)
+        assert np.array_equal(got.arrays["entry_rank"], np.where(routed, topk // spec.L, -1))
         assert ep.ep_handle_get_num_recv_tokens(h) == want.kept
         assert bool(got.info.status & ep.STATUS_CAPACITY_DROP) == (want.dropped > 0)
         ep.ep_handle_destroy(h)
@@ -693,6 +695,65 @@ def test_graph_capture_and_replay(ep, hx, oracle_mod):
             ep.ep_handle_destroy(h2)
             assert torch.equal(out2.view(torch.int16), out.view(torch.int16))
         del graph
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+# ------------------------------------------------------------------------------ two-level combine order
+
+
+@pytest.mark.parametrize("name,T,H,rpn,mode", [("ll_decode", None, 512, 8, "ht"), ("ll_decode", 77, 1000, 4, "ll"),
+                                               ("stress_hot", 300, 256, 8, "ht"), ("skew", 200, 512, 2, "ht"),
+                                               ("ht_prefill", None, None, 8, "ht")])
+def test_combine_two_level_order(ep, hx, oracle_mod, name, T, H, rpn, mode):
+    """Sum per node of rpn ranks first, then across nodes: bit-exact with the oracle's
+    two-level float32 order, within one bf16 ulp of the flat order and of the float64 sum."""
+    w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
+    spec = w.spec
+    T = spec.T
+    _say(f"two-level combine {name} T={T} H={spec.H} ranks_per_node={rpn} mode={mode}")
+    topk = _mess_up(w.topk_idx, spec.E, seed=T, frac_masked=0.02)
+    ll = mode == "ll"
+    Cc = T if ll else 0
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, layout=int(ll), C=Cc, C_rank=T)
+    rows = spec.E * Cc if ll else int(lay.expert_offset[-1])
+    y_bits = wl.f32_to_bf16_bits(np.random.default_rng(T).standard_normal((rows, spec.H)).astype(np.float32) * 2)
+    ref = oracle_mod.combine_hier(y_bits, w.topk_w, lay, topk, spec.H, ranks_per_node=rpn)
+    cfg = ep.make_config(spec.R, spec.E, spec.H, spec.K, T, mode=ep.EP_MODE_LL if ll else ep.EP_MODE_HT,
+                         ranks_per_node=rpn, staged_buffers=1 if T <= 300 else 0)
+    g = ep.ep_group_create(cfg)
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+        y = hx.bits_to_dev(y_bits)
+        y = y.view(spec.E, Cc, spec.H) if ll else y
+        gate = torch.from_numpy(w.topk_w).to(hx.DEV)
+        out = hx.poison_bf16((T, spec.H))
+        ep.ep_combine(h, y, out, topk_weights=gate)
+        torch.cuda.synchronize()
+        got = hx.dev_to_bits(out)
+        assert np.array_equal(got, ref), "differs from the two-level float32 order"
+        if T <= 300:
+            # another association of the same float32 sum: equal or adjacent bf16 values, except
+            # where the terms cancel -- there the difference is bounded by the float32 rounding
+            # of the terms, (K + 1) * 2^-24 * sum_k |w_k y_k|
+            yf = wl.bf16_bits_to_f32(y_bits)
+            rows_k = np.clip(lay.dst_row, 0, None)
+            terms = np.abs(w.topk_w)[:, :, None] * np.abs(yf[rows_k]) * (lay.dst_row >= 0)[:, :, None]
+            bound = terms.sum(1) * (spec.K + 1) * 2.0 ** -24
+            for other in (oracle_mod.combine(y_bits, w.topk_w, lay, spec.H, acc="f32"),
+                          oracle_mod.combine(y_bits, w.topk_w, lay, spec.H, acc="f64")):
+                near = hx.bf16_ulp_distance(got, other) <= 1
+                diff = np.abs(wl.bf16_bits_to_f32(got).astype(np.float64) - wl.bf16_bits_to_f32(other))
+                assert np.all(near | (diff <= 2 * bound + 1e-30))
+            out2 = hx.poison_bf16((T, spec.H))   # the staged combine uses the same order
+            ep.ep_combine(h, y, out2, topk_weights=gate, send_only=1)
+            ep.ep_complete(h)
+            torch.cuda.synchronize()
+            assert np.array_equal(hx.dev_to_bits(out2), ref)
+            ep.ep_combine(h, y, out2)            # unweighted
+            torch.cuda.synchronize()
+            assert np.array_equal(hx.dev_to_bits(out2), oracle_mod.combine_hier(y_bits, None, lay, topk, spec.H, rpn))
         ep.ep_handle_destroy(h)
     finally:
         ep.ep_group_destroy(g)
