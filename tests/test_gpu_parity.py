@@ -757,3 +757,51 @@ def test_combine_two_level_order(ep, hx, oracle_mod, name, T, H, rpn, mode):
         ep.ep_handle_destroy(h)
     finally:
         ep.ep_group_destroy(g)
+
+
+# ------------------------------------------------------------------------------ randomised shapes
+
+
+def test_random_shapes_end_to_end(ep, hx, oracle_mod):
+    """Forty seeded random configurations (E, R, K, T, H, mode, capacity, masked fraction):
+    layout, dispatch and combine against the oracle in each."""
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        R = int(rng.choice([1, 2, 3, 4, 8, 16, 32, 64]))
+        L = int(rng.choice([1, 2, 3, 4, 8, 13]))
+        E = R * L
+        if E > 1024:
+            continue
+        K = int(rng.integers(1, min(E, 12) + 1))
+        T = int(rng.choice([1, 2, 7, 63, 64, 65, 127, 129, 500, 513, 1000, 2049]))
+        H = int(rng.choice([8, 64, 200, 512, 520, 1024, 1536]))
+        ll = bool(rng.integers(0, 2))
+        C = int(rng.integers(1, max(2, (3 * T * K) // (2 * E) + 2))) if ll else 0
+        spec = wl.WorkloadSpec(f"rand{case}", 40 + case, R=R, T=T, H=H, E=E, K=K)
+        w = wl.make_workload(spec)
+        topk = _mess_up(w.topk_idx, E, seed=case, frac_masked=float(rng.choice([0.0, 0.05, 0.5])),
+                        n_invalid=int(rng.integers(0, 3)))
+        _say(f"random case {case}: E={E} R={R} K={K} T={T} H={H} ll={ll} C={C}")
+        lay = oracle_mod.layout(topk, E=E, R=R, layout=int(ll), C=C if ll else 0, C_rank=T)
+        rows = E * C if ll else int(lay.expert_offset[-1])
+        o_recv = np.full((rows + 1, H), hx.POISON, np.uint16)
+        oracle_mod.dispatch(w.x_bits, None, lay, o_recv)
+        g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C)
+        try:
+            h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+            ok_codes = (ep.EP_SUCCESS, ep.EP_ERR_INVALID_ROUTING)
+            got = hx.fetch_layout(h, T, K, E, R, ok=ok_codes)
+            hx.assert_layout_equal(got, lay)
+            store = hx.poison_bf16((rows + 1, H))
+            recv = store[:rows].view(E, C, H) if ll else store[:rows]
+            ep.ep_dispatch(h, hx.bits_to_dev(w.x_bits), recv)
+            out = hx.poison_bf16((T, H))
+            gate = torch.from_numpy(w.topk_w).to(hx.DEV)
+            ep.ep_combine(h, recv, out, topk_weights=gate)
+            torch.cuda.synchronize()
+            assert np.array_equal(hx.dev_to_bits(store), o_recv), f"case {case}: rows differ"
+            ref = oracle_mod.combine(o_recv[:rows], w.topk_w, lay, H, acc="f32")
+            assert np.array_equal(hx.dev_to_bits(out), ref), f"case {case}: combine differs"
+            ep.ep_handle_destroy(h)
+        finally:
+            ep.ep_group_destroy(g)
