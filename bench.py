@@ -110,6 +110,37 @@ def extras(ep, hx, wl, torch, np, group, spec, first_set, stream_ptr, iters: int
                                      "staging_bytes": int(ginfo.staging_slots) * P}
     ep.ep_handle_destroy(h2)
     ep.ep_group_destroy(g2)
+
+    # staged execution (send phase + ep_complete) and the two-level combine order
+    cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, staged_buffers=2, ranks_per_node=8)
+    g3 = ep.ep_group_create(cfg)
+    h3 = ep.ep_layout(g3, topk)
+    dis = ep.prepare_dispatch(x, recv, topk_weights=gate)
+    dis.__init__("ep_dispatch", [(x, ep.EP_TAG_TOKENS), (gate, ep.EP_TAG_TOPK_WEIGHTS)], [(recv, ep.EP_TAG_TOKENS)], send_only=1)
+    complete = ep.load().ep_complete
+
+    def staged_dispatch():
+        dis(h3, stream_ptr)
+        complete(h3, None, stream_ptr)
+
+    res["staged_dispatch_plus_complete"] = {"us": round(timed(staged_dispatch), 2)}
+    com = ep.PreparedCall("ep_combine", [(y, ep.EP_TAG_TOKENS), (gate, ep.EP_TAG_TOPK_WEIGHTS)], [(out, ep.EP_TAG_TOKENS)], send_only=1)
+
+    def staged_combine():
+        com(h3, stream_ptr)
+        complete(h3, None, stream_ptr)
+
+    us = timed(staged_combine)
+    nbytes = 2 * rows * 2 * H + rows * 2 * H + T * 2 * H + 16 * rows
+    res["staged_combine_plus_complete"] = {"us": round(us, 2), "algorithmic_bytes": nbytes,
+                                           "gbps": round(nbytes / (us * 1e-6) / 1e9, 1)}
+    hier = ep.prepare_combine(y, out, topk_weights=gate)
+    us = timed(lambda: hier(h3, stream_ptr))
+    nbytes = rows * 2 * H + T * 2 * H + 12 * rows
+    res["two_level_combine"] = {"us": round(us, 2), "ranks_per_node": 8, "algorithmic_bytes": nbytes,
+                                "gbps": round(nbytes / (us * 1e-6) / 1e9, 1)}
+    ep.ep_handle_destroy(h3)
+    ep.ep_group_destroy(g3)
     return res
 
 
