@@ -115,8 +115,8 @@ def extras(ep, hx, wl, torch, np, group, spec, first_set, stream_ptr, iters: int
     cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, staged_buffers=2, ranks_per_node=8)
     g3 = ep.ep_group_create(cfg)
     h3 = ep.ep_layout(g3, topk)
-    dis = ep.prepare_dispatch(x, recv, topk_weights=gate)
-    dis.__init__("ep_dispatch", [(x, ep.EP_TAG_TOKENS), (gate, ep.EP_TAG_TOPK_WEIGHTS)], [(recv, ep.EP_TAG_TOKENS)], send_only=1)
+    dis = ep.PreparedCall("ep_dispatch", [(x, ep.EP_TAG_TOKENS), (gate, ep.EP_TAG_TOPK_WEIGHTS)],
+                          [(recv, ep.EP_TAG_TOKENS)], send_only=1)
     complete = ep.load().ep_complete
 
     def staged_dispatch():
