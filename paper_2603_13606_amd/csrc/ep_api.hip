@@ -1,7 +1,7 @@
 // C-ABI entry points: group / handle lifetime, argument validation, and the
 // translation of tensor descriptors into kernel arguments (Sec. III-A..E).
 // Host code only; every step of the data path runs in the kernels of
-// ep_layout.hip, ep_dispatch.hip, ep_dedup.hip and ep_combine.hip.
+// ep_layout.hip, ep_dispatch.hip, ep_dedup.hip, ep_combine.hip and ep_staged.hip.
 #include <mutex>
 #include <new>
 #include <vector>

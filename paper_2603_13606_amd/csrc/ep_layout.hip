@@ -3,22 +3,28 @@
 // Count"; the slot rule of Sec. IV-B made deterministic).
 //
 // The slot of entry i = t*K + k is the number of entries j < i naming the same
-// expert: a stable counting sort.  The flattened entry list is cut into chunks,
-// one per workgroup of up to 16 wavefronts, and every chunk into wave-chunks of
-// 64*passes consecutive entries, one per wavefront.
+// expert: a stable counting sort.  No atomic decides an order anywhere (atomics
+// only add counts or set bits), so the output is a pure function of the input.
+//
+// Up to 1024 entries (the decode regime): one workgroup, one entry per thread, one
+// bitmap per bin; slot = popcount of the bits below the entry (layout_bitmap_kernel).
+//
+// Larger inputs: the flattened entry list is cut into chunks, one per workgroup of up
+// to 16 wavefronts, and every chunk into wave-chunks of 64*passes consecutive entries,
+// one per wavefront.
 //   count kernel  (only when there is more than one chunk) each workgroup
 //                 histograms its chunk -- bins: E experts, masked, invalid, R
-//                 destination ranks -- with LDS integer atomics; counts do not
-//                 depend on the order of the additions;
-//   slot kernel   each workgroup adds up the histograms of the chunks before it
-//                 (its prefix) and of all chunks (the totals, hence the expert
-//                 offsets), histograms its own wave-chunks to split the prefix
-//                 per wave, then every wave walks its entries 64 at a time:
+//                 destination ranks -- with LDS integer atomics;
+//   slot kernel   one thread per bin adds up the histograms of the chunks before
+//                 this one (its prefix) and of all chunks (the totals, hence the
+//                 expert offsets); the workgroup histograms its own wave-chunks
+//                 to split the prefix per wave; every wave builds the offset
+//                 tables for itself and then walks its entries 64 at a time:
 //                 slot = prefix of the bin + number of lower lanes holding the
 //                 same key, found with one ballot per key bit.
-// No atomic decides an order anywhere, so the output is a pure function of the
-// input.  The work is latency bound, so every phase issues all of its global
-// loads before it waits for any of them.
+// The work is latency bound (a chain of dependent LDS and global round trips per
+// wave), so every phase issues all of its global loads before it waits for any of
+// them and the workgroup barriers order LDS traffic only.
 //
 // The same kernels serve the receiving side of the once-per-rank dispatch
 // (Sec. IV-D): there the entries are the routing vectors found in the headers of
