@@ -182,6 +182,13 @@ EP_API const char *ep_error_string(ep_result_t code);
 EP_API int32_t ep_version(void);
 
 /*
+ * Diagnostic: how ep_layout would cut `num_entries` = T*K routing entries into wave-chunks
+ * (64 * passes consecutive entries per wavefront).  Host-only, no GPU needed.
+ * Errors: EP_ERR_INVALID_ARG (NULL pointers, negative count).
+ */
+EP_API ep_result_t ep_layout_plan(int64_t num_entries, int32_t *passes, int32_t *wave_chunks);
+
+/*
  * Measurement aid, not part of the paper's API: a plain streaming copy of `bytes`
  * (multiple of 16; dst and src 16-byte aligned DEVICE pointers, not overlapping)
  * with the same 16-byte-per-lane accesses the row kernels use.  It is what the

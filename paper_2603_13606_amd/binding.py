@@ -45,7 +45,7 @@ EP_TAG_EXPERT_BASE = 9
 STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW, STATUS_TIMEOUT = 1, 2, 4, 8
 
 EXPORTS = [
-    "ep_error_string", "ep_version", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
+    "ep_error_string", "ep_version", "ep_layout_plan", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
     "ep_layout", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
     "ep_dispatch", "ep_combine", "ep_complete", "ep_group_reset_signals",
 ]
@@ -133,6 +133,7 @@ def load() -> ctypes.CDLL:
         lib.ep_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.ep_complete.argtypes = [vp, ctypes.POINTER(ep_complete_config_t), vp]
         lib.ep_group_reset_signals.argtypes = [vp, vp]
+        lib.ep_layout_plan.argtypes = [ctypes.c_int64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         for name in EXPORTS[2:]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -148,6 +149,13 @@ ep_error_string = error_string
 
 def ep_version() -> int:
     return int(load().ep_version())
+
+
+def ep_layout_plan(num_entries: int):
+    """(passes, wave_chunks) ep_layout would use for num_entries = T*K routing entries."""
+    p, w = ctypes.c_int32(), ctypes.c_int32()
+    _check(load().ep_layout_plan(num_entries, ctypes.byref(p), ctypes.byref(w)), "ep_layout_plan")
+    return int(p.value), int(w.value)
 
 
 def ep_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

@@ -228,6 +228,15 @@ const char* ep_error_string(ep_result_t code) {
 
 int32_t ep_version(void) { return 100; }
 
+ep_result_t ep_layout_plan(int64_t num_entries, int32_t* passes, int32_t* wave_chunks) {
+    if (!passes || !wave_chunks || num_entries < 0 || num_entries > (1 << 28)) return EP_ERR_INVALID_ARG;
+    int p = 0, w = 0;
+    plan_layout((int)num_entries, &p, &w);
+    *passes = p;
+    *wave_chunks = w;
+    return EP_SUCCESS;
+}
+
 ep_result_t ep_calibration_copy(void* dst, const void* src, size_t bytes, ep_stream_t stream) {
     if (!dst || !src || bytes % 16 || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) return EP_ERR_INVALID_ARG;
     return launch_calibration_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;

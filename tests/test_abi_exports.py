@@ -100,3 +100,22 @@ def test_header_is_plain_c_and_cxx(tmp_path):
     cxx = tmp_path / "use_ep.cpp"
     cxx.write_text('#include "ep.h"\nint main() { ep_tensor_t t{}; return t.ndim; }\n')
     subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(cxx)], check=True)
+
+
+def test_layout_plan_covers_every_entry(ep):
+    """Host-side planning: the wave-chunks cover the input, stay within the scratch the
+    handle holds (256 rows), and small inputs fit one workgroup of 16 waves."""
+    for n in [0, 1, 63, 64, 65, 1023, 1024, 1025, 4095, 4096, 4097, 16384, 32768, 65536, 65537,
+              160000, 262144, 1 << 20, (1 << 28)]:
+        passes, chunks = ep.ep_layout_plan(n)
+        assert passes >= 1 and 0 <= chunks <= 256
+        assert chunks * passes * 64 >= n
+        assert (chunks - 1) * passes * 64 < n or n == 0
+        if n <= 1024:
+            assert passes == 1
+        if n <= 4096:
+            assert chunks <= 16
+        else:
+            assert passes >= 2
+    with pytest.raises(ep.EpError):
+        ep.ep_layout_plan(-1)

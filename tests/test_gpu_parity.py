@@ -70,6 +70,8 @@ LAYOUT_CASES = [
     ("stress", None, "ht", 0, 0.0),
     ("stress_hot", None, "ht", 0, 0.0),
     ("stress_hot", 8191, "ll", 300, 0.03),
+    ("ht_prefill", 20000, "ht", 0, 0.01),  # 160000 entries: several load groups per wave
+    ("stress", 33333, "ll", 700, 0.0),     # 266664 entries
 ]
 
 
