@@ -173,7 +173,7 @@ def main() -> int:
     from paper_2603_13606_amd import binding as ep
     from paper_2603_13606_amd import workloads as wl
 
-    ep.load()  # fails loudly if the HIP library was not built
+    hx.ensure_built()  # builds only if no library is in the tree; there is no fallback path
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = wl.make_workload(args.workload)

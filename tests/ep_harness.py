@@ -14,6 +14,16 @@ import torch
 from paper_2603_13606_amd import binding as ep
 from paper_2603_13606_amd import workloads as wl
 
+def ensure_built() -> None:
+    """Build the HIP library if no built one is in the tree (harness convenience; the
+    binding itself never builds and never falls back)."""
+    import os
+    if not os.path.exists(ep.LIB_PATH):
+        from paper_2603_13606_amd import build
+        build.build()
+    ep.load()
+
+
 DEV = "cuda:0"
 POISON = 0x4B4B  # a finite bf16 bit pattern (about 1.3e7) no seeded input contains
 

@@ -12,6 +12,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(scope="module")
 def hx():
     import ep_harness
+    ep_harness.ensure_built()
     assert torch.cuda.is_available()
     return ep_harness
 

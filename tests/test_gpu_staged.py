@@ -13,7 +13,8 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(scope="module")
 def ep():
     from paper_2603_13606_amd import binding
-    binding.load()
+    import ep_harness
+    ep_harness.ensure_built()
     assert torch.cuda.is_available()
     return binding
 
