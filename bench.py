@@ -111,6 +111,20 @@ def extras(ep, hx, wl, torch, np, group, spec, first_set, stream_ptr, iters: int
     ep.ep_handle_destroy(h2)
     ep.ep_group_destroy(g2)
 
+    # destination-ordered dispatch: with its read pass, and without it for cache-resident tokens
+    for order, key in ((ep.EP_ORDER_DESTINATION, "dispatch_destination_order"),
+                       (ep.EP_ORDER_DESTINATION_RESIDENT, "dispatch_destination_order_resident")):
+        cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, dispatch_order=order)
+        g4 = ep.ep_group_create(cfg)
+        h4 = ep.ep_layout(g4, topk)
+        call = ep.prepare_dispatch(x, recv, topk_weights=gate)
+        us = timed(lambda: call(h4, stream_ptr))
+        nbytes = T * 2 * H + rows * 2 * H + 8 * rows
+        res[key] = {"us": round(us, 2), "algorithmic_bytes": nbytes, "gbps": round(nbytes / (us * 1e-6) / 1e9, 1),
+                    "note": "same tokens every iteration: they are resident in the memory-side cache"}
+        ep.ep_handle_destroy(h4)
+        ep.ep_group_destroy(g4)
+
     # staged execution (send phase + ep_complete) and the two-level combine order
     cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, staged_buffers=2, ranks_per_node=8)
     g3 = ep.ep_group_create(cfg)
@@ -151,6 +165,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="ht_prefill")
     ap.add_argument("--sets", type=int, default=3, help="input/window sets rotated between steps")
+    ap.add_argument("--dispatch-order", type=int, default=0, choices=(0, 1, 2),
+                    help="EP_ORDER_TOKEN (0), EP_ORDER_DESTINATION (1), EP_ORDER_DESTINATION_RESIDENT (2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--event-every", type=int, default=4,
                     help="record the per-op HIP events on every n-th timed step only (four event "
@@ -180,7 +196,8 @@ def main() -> int:
     spec = w.spec
     T, K, H, E = spec.T, spec.K, spec.H, spec.E
     nsets = max(1, args.sets)
-    cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, max_handles=nsets + 2)  # no allocation later
+    cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, max_handles=nsets + 2,  # no allocation later
+                         dispatch_order=args.dispatch_order)
     group = ep.ep_group_create(cfg)
 
     nsets = max(1, args.sets)

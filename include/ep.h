@@ -60,6 +60,22 @@ enum { EP_MODE_LL = 0, EP_MODE_HT = 1 };
  *                       local experts.  Same final windows, bit for bit.          */
 enum { EP_PATH_DIRECT = 0, EP_PATH_RANK_DEDUP = 1 };
 
+/* Order in which the direct dispatch walks its work (a tuning knob: every order writes
+ * the same bytes to the same places).
+ *   EP_ORDER_TOKEN        token by token: a row is read once and stored to its
+ *                         destinations.  Insensitive to what the caches hold.  Default.
+ *   EP_ORDER_DESTINATION  in the order of the destination rows, for inputs of at least
+ *                         8192 routed entries (smaller ones use the token order): rows
+ *                         that end up next to each other are written close in time,
+ *                         which the memory system rewards.  A read pass over the tokens
+ *                         (in pieces of at most 64 MiB) precedes the copy so that the
+ *                         copy finds them in the memory-side cache.
+ *   EP_ORDER_DESTINATION_RESIDENT  the same without the read pass: for callers whose
+ *                         tokens were produced or read just before the call and are at
+ *                         most a fraction of the 256 MiB memory-side cache.  When the
+ *                         tokens are not resident this order is the slowest of the three. */
+enum { EP_ORDER_TOKEN = 0, EP_ORDER_DESTINATION = 1, EP_ORDER_DESTINATION_RESIDENT = 2 };
+
 enum { EP_DTYPE_BF16 = 0, EP_DTYPE_F32 = 1, EP_DTYPE_I32 = 2, EP_DTYPE_U8 = 3,
        EP_DTYPE_FP8_E4M3 = 4 /* OCP E4M3: 1-4-3 bits, bias 7, max 448, no infinity */ };
 
@@ -116,6 +132,8 @@ typedef struct {
                                     d with equal d / ranks_per_node form a node and combine
                                     sums per node first, then across nodes (the HT
                                     "hierarchical" reduction of Sec. III-D / V-A)          */
+    int32_t dispatch_order;      /* EP_ORDER_TOKEN / EP_ORDER_DESTINATION /
+                                    EP_ORDER_DESTINATION_RESIDENT (EP_PATH_DIRECT only)     */
 } ep_group_config_t;
 
 /* Allocator callbacks (Sec. III-C): when given, every device allocation of the

@@ -29,6 +29,7 @@ EP_ERR_TIMEOUT = 8
 
 EP_MODE_LL, EP_MODE_HT = 0, 1
 EP_PATH_DIRECT, EP_PATH_RANK_DEDUP = 0, 1
+EP_ORDER_TOKEN, EP_ORDER_DESTINATION, EP_ORDER_DESTINATION_RESIDENT = 0, 1, 2
 EP_DTYPE_BF16, EP_DTYPE_F32, EP_DTYPE_I32, EP_DTYPE_U8, EP_DTYPE_FP8_E4M3 = 0, 1, 2, 3, 4
 
 EP_TAG_NONE = 0
@@ -63,7 +64,8 @@ class ep_group_config_t(ctypes.Structure):
                 ("max_tokens_per_rank", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("mode", ctypes.c_int32), ("slots_per_subregion", ctypes.c_int32),
                 ("dispatch_path", ctypes.c_int32), ("max_handles", ctypes.c_int32),
-                ("staged_buffers", ctypes.c_int32), ("ranks_per_node", ctypes.c_int32)]
+                ("staged_buffers", ctypes.c_int32), ("ranks_per_node", ctypes.c_int32),
+                ("dispatch_order", ctypes.c_int32)]
 
 
 class ep_complete_config_t(ctypes.Structure):
@@ -199,7 +201,8 @@ def _check(code: int, where: str, ok: Sequence[int] = (EP_SUCCESS,)) -> int:
 def make_config(num_ranks: int, num_experts: int, hidden: int, top_k: int, max_tokens_per_rank: int,
                 mode: int = EP_MODE_HT, my_rank: int = 0, slots_per_subregion: int = 0,
                 dispatch_path: int = EP_PATH_DIRECT, max_handles: int = 0,
-                dtype: int = EP_DTYPE_BF16, staged_buffers: int = 0, ranks_per_node: int = 0) -> ep_group_config_t:
+                dtype: int = EP_DTYPE_BF16, staged_buffers: int = 0, ranks_per_node: int = 0,
+                dispatch_order: int = 0) -> ep_group_config_t:
     c = ep_group_config_t()
     c.size = ctypes.sizeof(ep_group_config_t)
     c.num_ranks, c.my_rank, c.num_experts, c.hidden, c.top_k = num_ranks, my_rank, num_experts, hidden, top_k
@@ -207,6 +210,7 @@ def make_config(num_ranks: int, num_experts: int, hidden: int, top_k: int, max_t
     c.slots_per_subregion, c.dispatch_path, c.max_handles = slots_per_subregion, dispatch_path, max_handles
     c.staged_buffers = staged_buffers
     c.ranks_per_node = ranks_per_node
+    c.dispatch_order = dispatch_order
     return c
 
 

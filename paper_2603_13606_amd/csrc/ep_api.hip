@@ -19,7 +19,7 @@ struct Slab {
     // carved arrays
     int32_t *totals, *expert_count, *expert_kept, *expert_offset, *own_prefix;
     int32_t *rank_pair_count, *rank_token_count, *rank_offset, *hist;
-    int32_t *slot, *dst_row, *rank_row, *sorted_token, *sorted_k, *sorted_row, *entry_rank;
+    int32_t *slot, *dst_row, *rank_row, *sorted_token, *sorted_k, *sorted_row, *entry_rank, *run_start;
     // receiving side of the once-per-rank path (only carved for EP_PATH_RANK_DEDUP)
     int32_t *recv_totals, *recv_count, *recv_kept, *recv_offset, *recv_own_prefix, *recv_dst_row;
     // what the receiving side of a staged call learns from the coordination counters
@@ -62,6 +62,9 @@ struct ep_handle_s {
     int T;
     hipStream_t last_stream;
     const int32_t* expert_base;  // as given to ep_layout (borrowed), or nullptr
+    bool has_runs = false;       // the layout filled slab.run_start
+    int nwc = 0;                 // wave-chunks of the layout plan
+    int chunk_entries = 0;       // entries per wave-chunk
     // receive phase of a staged (send_only) call, run by ep_complete
     int pending = PENDING_NONE;
     int pending_set = 0;
@@ -109,6 +112,8 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
     const int64_t o_eo = carve(&cur, E + 1), o_op = carve(&cur, E + 1), o_rp = carve(&cur, R);
     const int64_t o_rt = carve(&cur, R), o_ro = carve(&cur, R + 1);
     const int64_t o_h = carve(&cur, (int64_t)kMaxWaveChunks * g->W);
+    const bool runs = g->cfg.dispatch_order != EP_ORDER_TOKEN && g->cfg.dispatch_path == EP_PATH_DIRECT;
+    const int64_t o_rn = runs ? carve(&cur, (int64_t)(kMaxWaveChunks + 1) * E) : 0;
     const int64_t o_sl = carve(&cur, nB), o_dr = carve(&cur, nB), o_rr = carve(&cur, nB);
     const int64_t o_st = carve(&cur, nB), o_sk = carve(&cur, nB), o_sr = carve(&cur, nB), o_er = carve(&cur, nB);
     const bool dedup = g->cfg.dispatch_path == EP_PATH_RANK_DEDUP;
@@ -124,7 +129,7 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
         s->rank_token_count = base + o_rt; s->rank_offset = base + o_ro;
         s->hist = base + o_h; s->slot = base + o_sl; s->dst_row = base + o_dr; s->rank_row = base + o_rr;
         s->sorted_token = base + o_st; s->sorted_k = base + o_sk; s->sorted_row = base + o_sr;
-        s->entry_rank = base + o_er;
+        s->entry_rank = base + o_er; s->run_start = base + o_rn;
         s->recv_totals = base + o_vt; s->recv_count = base + o_vc; s->recv_kept = base + o_vk;
         s->recv_offset = base + o_vo; s->recv_own_prefix = base + o_vp; s->recv_dst_row = base + o_vr;
         s->recv_rank_count = base + o_rc; s->recv_rank_offset = base + o_rf;
@@ -258,6 +263,7 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     if (cfg->slots_per_subregion < 0 || cfg->max_handles < 0) return EP_ERR_INVALID_ARG;
     if (cfg->staged_buffers < 0 || cfg->staged_buffers > 2) return EP_ERR_INVALID_ARG;
     if (cfg->ranks_per_node < 0) return EP_ERR_INVALID_ARG;
+    if (cfg->dispatch_order < EP_ORDER_TOKEN || cfg->dispatch_order > EP_ORDER_DESTINATION_RESIDENT) return EP_ERR_INVALID_ARG;
     const int C = cfg->slots_per_subregion ? cfg->slots_per_subregion : cfg->max_tokens_per_rank;
     if (cfg->mode == EP_MODE_LL && (int64_t)E * C > 0x7fffffffLL) return EP_ERR_INVALID_ARG;
 
@@ -414,8 +420,13 @@ ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk
     a.slot = s.slot; a.dst_row = s.dst_row; a.rank_row = s.rank_row; a.sorted_token = s.sorted_token;
     a.sorted_k = s.sorted_k; a.sorted_row = s.sorted_row;
     a.entry_rank = s.entry_rank;
+    // the table of run starts is only wanted by the destination-ordered dispatch
+    a.run_start = (c.dispatch_order != EP_ORDER_TOKEN && c.dispatch_path == EP_PATH_DIRECT) ? s.run_start : nullptr;
     a.msgs = nullptr; a.msg_bytes = 0; a.msg_total_slots = 0; a.msg_slots_per_rank = 0;
     a.msg_rank_offset = nullptr; a.msg_rank_count = nullptr;
+    h->has_runs = layout_writes_runs(a);
+    h->nwc = a.nwc;
+    h->chunk_entries = a.passes * kWave;
     if (launch_layout(a, (hipStream_t)stream) != hipSuccess) {
         ep_handle_destroy(h);
         return EP_ERR_HIP;
@@ -515,6 +526,10 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     a.expert_kept = h->slab.expert_kept;
     a.totals = h->slab.totals;
     a.T = h->T; a.K = c.top_k; a.H = c.hidden; a.E = c.num_experts;
+    a.sorted_token = h->slab.sorted_token; a.sorted_k = h->slab.sorted_k; a.sorted_row = h->slab.sorted_row;
+    a.run_start = h->has_runs ? h->slab.run_start : nullptr;
+    a.nwc = h->nwc; a.chunk_entries = h->chunk_entries;
+    a.order = c.dispatch_order;
     h->last_stream = (hipStream_t)stream;
     int set = 0;
     if (send_only) {
@@ -571,7 +586,7 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     la.rank_pair_count = nullptr; la.rank_token_count = nullptr; la.rank_offset = nullptr;
     la.totals = s.recv_totals;
     la.slot = nullptr; la.dst_row = s.recv_dst_row; la.rank_row = nullptr; la.entry_rank = nullptr;
-    la.sorted_token = nullptr; la.sorted_k = nullptr; la.sorted_row = nullptr;
+    la.sorted_token = nullptr; la.sorted_k = nullptr; la.sorted_row = nullptr; la.run_start = nullptr;
     la.msgs = g->staging[set]; la.msg_bytes = g->msg_bytes; la.msg_total_slots = (int)g->staging_slots;
     la.msg_slots_per_rank = c.mode == EP_MODE_LL ? c.max_tokens_per_rank : 0;
     // a staged call lets the receiving side learn the message counts from the counters

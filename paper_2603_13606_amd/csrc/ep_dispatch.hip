@@ -9,6 +9,8 @@
 // routing entries of the token are wave-uniform and come through scalar loads.
 #include "ep_internal.h"
 
+#include <algorithm>
+
 namespace ep {
 namespace {
 
@@ -53,6 +55,124 @@ __global__ __launch_bounds__(256) void dispatch_direct_kernel(DispatchArgs a, in
             if (a.recv_src) a.recv_src[row] = t;
         }
     }
+}
+
+// ---- run-ordered variant for large inputs
+//
+// Writes that land next to each other within a short time are served much faster by the
+// memory system than rows scattered at random (measured on this part: 6.3 TB/s against
+// 4.9 TB/s), so large inputs are walked in the order of the destination rows instead of
+// the order of the tokens.  The layout's expert-sorted entry list is cut into runs: the
+// entries of one expert that come from one block of consecutive wave-chunks of the input
+// (the layout records where those start).  A workgroup copies one run; consecutive
+// workgroups take the experts of one block in order, so the copy sweeps over all expert
+// regions once per block and every region grows by a few adjacent rows each time.
+//
+// A row is read once from HBM and up to K-1 more times from the L2 cache: the 16-byte
+// units of a row are split into kSlices equal pieces and workgroup index mod kSlices picks
+// the piece, which on this part is also the accelerator die the workgroup runs on, so each
+// die's L2 only ever holds its own piece of the tokens of the current block.
+constexpr int kSlices = 8;
+constexpr int kRunUnroll = 2;
+
+struct RunPlan {
+    int group;      // wave-chunks per block
+    int nblocks;    // blocks of the input
+    int piece;      // 16-byte units per slice
+    int units;      // 16-byte units per row
+    int tpr_shift;  // log2(threads that share one row piece)
+    int first_block;  // this launch covers blocks first_block .. first_block + gridDim.y - 1
+};
+
+// TPR_SHIFT = log2(threads that share one row piece); PADDED = window addressing mode.
+template <int TPR_SHIFT, bool PADDED>
+__global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunPlan p) {
+    if (blockIdx.x == 0 && blockIdx.y == 0 && p.first_block == 0 && a.recv_count) {
+        for (int e = threadIdx.x; e < a.E; e += blockDim.x) a.recv_count[e] = a.expert_kept[e];
+    }
+    constexpr int tpr = 1 << TPR_SHIFT, nsub = 256 >> TPR_SHIFT;
+    // grid = (kSlices * E, blocks): x runs fastest, so workgroups are handed out slice by
+    // slice, expert by expert, block by block
+    const int xs = blockIdx.x & (kSlices - 1);
+    const int e = blockIdx.x / kSlices;
+    const int blk = p.first_block + blockIdx.y;
+    const int c0 = blk * p.group, c1 = min(c0 + p.group, a.nwc);
+    // wave-uniform: the run of expert e in block blk, as positions of the sorted entry list
+    const int lo = __builtin_amdgcn_readfirstlane(max(a.run_start[(int64_t)c0 * a.E + e], 0));
+    const int hi = __builtin_amdgcn_readfirstlane(min(a.run_start[(int64_t)c1 * a.E + e], a.T * a.K));
+    if (lo >= hi) return;
+    const int sub = threadIdx.x >> TPR_SHIFT, u = threadIdx.x & (tpr - 1);
+    const int u0 = xs * p.piece, u1 = min(p.units, u0 + p.piece);
+    const bool side = xs == 0 && u == 0;  // one lane per row fills the side arrays
+    for (int pos0 = lo + sub; pos0 < hi; pos0 += nsub * kRunUnroll) {
+        int t[kRunUnroll], row[kRunUnroll];
+#pragma unroll
+        for (int q = 0; q < kRunUnroll; ++q) {
+            const int pos = pos0 + q * nsub;
+            t[q] = 0;
+            row[q] = -1;
+            if (pos < hi) {
+                t[q] = a.sorted_token[pos];
+                row[q] = a.sorted_row[pos];
+                if (row[q] >= a.win.rows_cap) {
+                    if (side) atomicOr(&a.totals[TOT_STATUS], STATUS_OUTPUT_OVERFLOW);
+                    row[q] = -1;
+                }
+            }
+        }
+        for (int col = u0 + u; col < u1; col += tpr) {
+            u32x4 v[kRunUnroll];
+#pragma unroll
+            for (int q = 0; q < kRunUnroll; ++q)
+                if (row[q] >= 0) v[q] = *((const u32x4*)(a.x + (int64_t)t[q] * a.x_stride) + col);
+#pragma unroll
+            for (int q = 0; q < kRunUnroll; ++q) {
+                if (row[q] < 0) continue;
+                const int64_t off = PADDED ? window_offset(a.win, row[q]) : (int64_t)row[q] * a.win.stride0;
+                __builtin_nontemporal_store(v[q], (u32x4*)(a.win.base + off) + col);
+            }
+        }
+        if (side) {
+#pragma unroll
+            for (int q = 0; q < kRunUnroll; ++q) {
+                if (row[q] < 0) continue;
+                if (a.recv_src) a.recv_src[row[q]] = t[q];
+                if (a.recv_w) {
+                    const int k = a.sorted_k[pos0 + q * nsub];
+                    a.recv_w[row[q]] = a.w ? a.w[(int64_t)t[q] * a.w_stride + k] : 1.0f;
+                }
+            }
+        }
+    }
+}
+
+// Reads token rows [t0, t1) (and, when asked, the index arrays of the layout) once, front
+// to back, with ordinary cached loads, so that the run-ordered copy that follows finds
+// them in the memory-side cache and the DRAM sees a read phase and then a write phase.
+__global__ __launch_bounds__(256) void dispatch_warm_kernel(DispatchArgs a, int units, int t0, int t1, int with_index) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t acc = 0;
+    const int64_t total = (int64_t)(t1 - t0) * units;
+    for (int64_t i = gid; i < total; i += stride) {
+        const int64_t t = i / units;
+        const int col = (int)(i - t * units);
+        const u32x4 v = *((const u32x4*)(a.x + (t0 + t) * a.x_stride) + col);
+        acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+    }
+    if (with_index) {
+        const int n = a.T * a.K, table = (a.nwc + 1) * a.E;
+        for (int64_t i = gid; i < n; i += stride) acc ^= (uint32_t)(a.sorted_token[i] ^ a.sorted_row[i]);
+        for (int64_t i = gid; i < table; i += stride) acc ^= (uint32_t)a.run_start[i];
+    }
+    if (acc == 0x9e3779b9u) atomicOr(&a.totals[TOT_STATUS], 0);  // keeps the loads; changes nothing
+}
+
+template <int TPR_SHIFT>
+void launch_runs(const DispatchArgs& a, const RunPlan& p, int nblocks, hipStream_t s) {
+    const dim3 grid((unsigned)(kSlices * a.E), (unsigned)nblocks);
+    if (a.win.padded) hipLaunchKernelGGL((dispatch_runs_kernel<TPR_SHIFT, true>), grid, dim3(256), 0, s, a, p);
+    else hipLaunchKernelGGL((dispatch_runs_kernel<TPR_SHIFT, false>), grid, dim3(256), 0, s, a, p);
 }
 
 // ---- quantising dispatch: FP8 (OCP E4M3) rows with one float scale per 128 channels
@@ -179,8 +299,51 @@ hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStr
     return hipGetLastError();
 }
 
+// Inputs from this many entries on can be copied in run order (when the layout recorded
+// the runs); smaller ones are bound by latency and keep the shorter token-ordered kernel.
+constexpr int kRunOrderMinEntries = 8192;
+// Tokens warmed per read pass: a piece must stay in the 256 MiB memory-side cache, next to
+// whatever else lives there, while the copy of that piece runs.
+constexpr int64_t kWarmBytes = 64ll << 20;
+
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s) {
     const int units = a.H / 8;  // 16-byte units per row
+    if (a.order != EP_ORDER_TOKEN && a.run_start && (int64_t)a.T * a.K >= kRunOrderMinEntries && units >= kSlices) {
+        RunPlan p;
+        // a block holds about three rows per expert (and at least 768 entries)
+        const int want = max(768, 3 * a.E);
+        p.group = max(1, want / a.chunk_entries);
+        p.nblocks = (a.nwc + p.group - 1) / p.group;
+        p.units = units;
+        p.piece = (units + kSlices - 1) / kSlices;
+        p.tpr_shift = 4;
+        while ((1 << p.tpr_shift) < p.piece && p.tpr_shift < 8) ++p.tpr_shift;
+        const bool warm = a.order == EP_ORDER_DESTINATION;
+        const int64_t block_entries = (int64_t)p.group * a.chunk_entries;
+        // blocks per launch: all of them, or as many as cover kWarmBytes of tokens
+        int per = p.nblocks;
+        if (warm) {
+            const int64_t block_bytes = (block_entries + a.K - 1) / a.K * a.H * 2;
+            per = (int)std::max<int64_t>(1, std::min<int64_t>(p.nblocks, kWarmBytes / std::max<int64_t>(block_bytes, 1)));
+        }
+        for (int b0 = 0; b0 < p.nblocks; b0 += per) {
+            const int nb = min(per, p.nblocks - b0);
+            if (warm) {
+                const int t0 = (int)std::min<int64_t>(a.T, b0 * block_entries / a.K);
+                const int t1 = (int)std::min<int64_t>(a.T, ((b0 + nb) * block_entries + a.K - 1) / a.K);
+                hipLaunchKernelGGL(dispatch_warm_kernel, dim3(2048), dim3(256), 0, s, a, units, t0, t1, b0 == 0 ? 1 : 0);
+            }
+            p.first_block = b0;
+            switch (p.tpr_shift) {
+                case 4: launch_runs<4>(a, p, nb, s); break;
+                case 5: launch_runs<5>(a, p, nb, s); break;
+                case 6: launch_runs<6>(a, p, nb, s); break;
+                case 7: launch_runs<7>(a, p, nb, s); break;
+                default: launch_runs<8>(a, p, nb, s); break;
+            }
+        }
+        return hipGetLastError();
+    }
     const int nseg = (units + kWave - 1) / kWave;
     const int64_t nwaves = (int64_t)a.T * nseg;
     int64_t nblk = (nwaves + 3) / 4;

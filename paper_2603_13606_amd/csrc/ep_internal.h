@@ -56,6 +56,8 @@ struct LayoutArgs {
     int32_t* sorted_token;    // [n]
     int32_t* sorted_k;        // [n]
     int32_t* sorted_row;      // [n]
+    int32_t* run_start;       // [nwc+1, E] or nullptr: first sorted position of expert e among the entries
+                              // of wave-chunks >= c (row c); only the histogram kernels fill it
     // Message mode (receiving side of the once-per-rank path): entries are the
     // routing vectors in the headers of the staged messages; slot, rank_row,
     // sorted_* and the rank arrays may then be nullptr.
@@ -92,6 +94,15 @@ struct DispatchArgs {
     const int32_t* expert_kept;
     int32_t* totals;
     int T, K, H, E;
+    // run-ordered kernel only (see launch_dispatch): the expert-sorted entry list of the
+    // layout and the table of where each wave-chunk's entries start inside it
+    const int32_t* sorted_token;  // [n]
+    const int32_t* sorted_k;      // [n]
+    const int32_t* sorted_row;    // [n]
+    const int32_t* run_start;     // [nwc+1, E], or nullptr: the layout did not produce one
+    int nwc;                      // wave-chunks of the layout
+    int chunk_entries;            // entries per wave-chunk
+    int order;                    // EP_ORDER_*
 };
 
 struct CombineArgs {
@@ -156,5 +167,7 @@ hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hip
 
 // Host-side planning helpers (pure functions, testable without a GPU).
 void plan_layout(int n, int* passes, int* nwc);
+// True when launch_layout fills LayoutArgs::run_start for this plan.
+bool layout_writes_runs(const LayoutArgs& a);
 
 }  // namespace ep

@@ -372,6 +372,7 @@ __device__ void wave_write_tables(const LayoutArgs& a, const Lds& l, int lane) {
         a.expert_kept[e] = k;
         a.expert_offset[e] = l.eoff[e];
         a.own_prefix[e] = l.opre[e];
+        if (a.run_start) a.run_start[e] = l.opre[e];  // row 0: nothing precedes the first wave-chunk
     }
     kept = wave_sum(kept);
     dropped = wave_sum(dropped);
@@ -509,6 +510,14 @@ __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
             if (!one_group) load_group<MSGS>(a, wc, p0, lane, l, en);
             slots_group<MSGS>(a, en, p0, l.wh + w * W, l, lane);
         }
+        // the walk has advanced the wave's prefixes past its own entries: they are now the
+        // positions at which the next wave-chunk's entries start in the expert-sorted list
+        if (a.run_start) {
+            wave_lds_fence();
+            int32_t* rs = a.run_start + (int64_t)(wc + 1) * a.E;
+            const int32_t* h = l.wh + w * W;
+            for (int e = lane; e < a.E; e += kWave) rs[e] = l.opre[e] + h[e];
+        }
     }
     // (7) one wave publishes the per-expert / per-rank arrays and the totals; it does so
     //     after its own slot walk so that the walk of the chunk is not held up
@@ -605,8 +614,14 @@ void plan_layout(int n, int* passes, int* nwc) {
     *nwc = (n + kWave * p - 1) / (kWave * p);
 }
 
+static bool use_bitmap(const LayoutArgs& a) {
+    return !a.msgs && a.passes == 1 && a.nwc >= 1 && a.nwc <= kLayoutWavesPerBlock && bitmap_lds_bytes(a) <= kLdsLimit;
+}
+
+bool layout_writes_runs(const LayoutArgs& a) { return a.run_start != nullptr && !use_bitmap(a); }
+
 hipError_t launch_layout(const LayoutArgs& a, hipStream_t s) {
-    if (!a.msgs && a.passes == 1 && a.nwc >= 1 && a.nwc <= kLayoutWavesPerBlock && bitmap_lds_bytes(a) <= kLdsLimit) {
+    if (use_bitmap(a)) {
         hipLaunchKernelGGL(layout_bitmap_kernel, dim3(1), dim3(a.nwc * kWave), bitmap_lds_bytes(a), s, a);
         return hipGetLastError();
     }

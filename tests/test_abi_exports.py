@@ -37,8 +37,8 @@ def test_every_declared_function_is_exported(ep):
 
 
 def test_struct_sizes_match_header(ep):
-    # config: uint32 + 13 int32; tensor: pointer + 4 int32 + 8 int64
-    assert ctypes.sizeof(ep.ep_group_config_t) == 56
+    # config: uint32 + 14 int32; tensor: pointer + 4 int32 + 8 int64
+    assert ctypes.sizeof(ep.ep_group_config_t) == 60
     assert ctypes.sizeof(ep.ep_tensor_t) == 8 + 16 + 64
     assert ctypes.sizeof(ep.ep_layout_info_t) == 8 + 7 * 8 + 13 * 8
     assert ctypes.sizeof(ep.ep_group_info_t) == 40 + 7 * 8 + 8 + 6 * 8
@@ -62,6 +62,8 @@ def test_error_strings_and_version(ep):
     (dict(mode=5), 1),
     (dict(dtype=1), 4),                # only bf16 tokens
     (dict(staged_buffers=3), 1),
+    (dict(dispatch_order=3), 1),
+    (dict(dispatch_order=-1), 1),
 ])
 def test_group_create_rejects_bad_config_on_the_host(ep, kw, code):
     args = dict(num_ranks=2, num_experts=8, hidden=256, top_k=2, max_tokens_per_rank=64)

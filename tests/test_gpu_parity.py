@@ -243,7 +243,7 @@ PATH_CASES = [
 ]
 
 
-def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True):
+def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True, order=0):
     w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
     spec = w.spec
     T = spec.T
@@ -259,7 +259,7 @@ def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True
     o_src = np.full(rows + guard, -9, np.int32)
     oracle_mod.dispatch(w.x_bits, w.topk_w if weights else None, lay, o_recv, o_w, o_src)
     # ---- HIP side
-    g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C)
+    g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C, dispatch_order=order)
     try:
         x = hx.bits_to_dev(w.x_bits)
         d_w = torch.from_numpy(w.topk_w).to(hx.DEV)
@@ -316,6 +316,50 @@ def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True
 def test_dispatch_combine_parity(ep, hx, oracle_mod, name, T, H, mode, C):
     _say(f"path case {name} T={T} H={H} mode={mode} C={C}")
     _run_path(ep, hx, oracle_mod, name, T, H, mode, C)
+
+
+ORDER_CASES = [
+    # inputs of at least 8192 routed entries take the destination-ordered kernel
+    ("ht_prefill", None, None, "ht", 0),
+    ("skew", None, None, "ll", 512),        # padded windows, capacity drops, 8 KiB rows
+    ("skew", 1111, None, "ht", 0),          # 8888 entries: just above the switch, ragged last chunk
+    ("ll_decode", 1100, 1000, "ht", 0),     # 125 units per row: uneven slices, the last one short
+    ("ll_decode", 1030, 64, "ll", 40),      # one unit per slice, heavy drops
+    ("stress_hot", None, None, "ht", 0),    # 117 MB of tokens: two read passes
+    ("ll_decode", 200, None, "ht", 0),      # below the switch: token order whatever the setting
+]
+
+
+@pytest.mark.parametrize("order", [1, 2])
+@pytest.mark.parametrize("name,T,H,mode,C", ORDER_CASES)
+def test_dispatch_destination_order_parity(ep, hx, oracle_mod, name, T, H, mode, C, order):
+    """The destination-ordered dispatch (with and without its read pass) writes exactly the
+    bytes of the oracle's dispatch, side arrays and counts included, and leaves the rest of the
+    windows untouched; combine on top of it is unchanged."""
+    _say(f"order case {name} T={T} H={H} mode={mode} C={C} order={order}")
+    _run_path(ep, hx, oracle_mod, name, T, H, mode, C, order=order)
+
+
+def test_destination_order_output_too_small_is_flagged_not_overrun(ep, hx, oracle_mod):
+    w = wl.make_workload("ll_decode", T=1100, H=256)
+    spec = w.spec
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=spec.T)
+    cap = 5000
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT, dispatch_order=ep.EP_ORDER_DESTINATION)
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(w.topk_idx).to(hx.DEV))
+        store = hx.poison_bf16((spec.T * spec.K, spec.H))
+        ep.ep_dispatch(h, hx.bits_to_dev(w.x_bits), store[:cap])
+        info = ep.ep_handle_query(h, ok=(ep.EP_ERR_OVERFLOW,))
+        assert info.last_code == ep.EP_ERR_OVERFLOW and info.status & ep.STATUS_OUTPUT_OVERFLOW
+        got = hx.dev_to_bits(store)
+        assert np.all(got[cap:] == hx.POISON)
+        o = np.full((spec.T * spec.K, spec.H), hx.POISON, np.uint16)
+        oracle_mod.dispatch(w.x_bits, None, lay, o)
+        assert np.array_equal(got[:cap], o[:cap])
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
 
 
 def test_round_trip_identity_experts(ep, hx):
