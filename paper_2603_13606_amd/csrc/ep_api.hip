@@ -21,7 +21,7 @@ struct Slab {
     int32_t *rank_pair_count, *rank_token_count, *rank_offset, *hist;
     int32_t *slot, *dst_row, *rank_row, *sorted_token, *sorted_k, *sorted_row, *entry_rank, *run_start;
     // receiving side of the once-per-rank path (only carved for EP_PATH_RANK_DEDUP)
-    int32_t *recv_totals, *recv_count, *recv_kept, *recv_offset, *recv_own_prefix, *recv_dst_row;
+    int32_t *recv_count, *recv_kept, *recv_dst_row;
     // what the receiving side of a staged call learns from the coordination counters
     int32_t *recv_rank_count, *recv_rank_offset;
 };
@@ -69,7 +69,7 @@ struct ep_handle_s {
     int pending = PENDING_NONE;
     int pending_set = 0;
     int32_t* pending_recv_count = nullptr;
-    LayoutArgs pending_layout;
+    DedupRankArgs pending_rank;
     DedupFanoutArgs pending_fanout;
     CombineArgs pending_combine;
 };
@@ -117,9 +117,7 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
     const int64_t o_sl = carve(&cur, nB), o_dr = carve(&cur, nB), o_rr = carve(&cur, nB);
     const int64_t o_st = carve(&cur, nB), o_sk = carve(&cur, nB), o_sr = carve(&cur, nB), o_er = carve(&cur, nB);
     const bool dedup = g->cfg.dispatch_path == EP_PATH_RANK_DEDUP;
-    const int64_t o_vt = dedup ? carve(&cur, kTotalsWords) : 0, o_vc = dedup ? carve(&cur, E) : 0;
-    const int64_t o_vk = dedup ? carve(&cur, E) : 0, o_vo = dedup ? carve(&cur, E + 1) : 0;
-    const int64_t o_vp = dedup ? carve(&cur, E + 1) : 0;
+    const int64_t o_vc = dedup ? carve(&cur, E) : 0, o_vk = dedup ? carve(&cur, E) : 0;
     const int64_t o_vr = dedup ? carve(&cur, g->staging_slots * g->cfg.top_k) : 0;
     const int64_t o_rc = carve(&cur, R), o_rf = carve(&cur, R + 1);
     if (base && s) {
@@ -130,8 +128,7 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
         s->hist = base + o_h; s->slot = base + o_sl; s->dst_row = base + o_dr; s->rank_row = base + o_rr;
         s->sorted_token = base + o_st; s->sorted_k = base + o_sk; s->sorted_row = base + o_sr;
         s->entry_rank = base + o_er; s->run_start = base + o_rn;
-        s->recv_totals = base + o_vt; s->recv_count = base + o_vc; s->recv_kept = base + o_vk;
-        s->recv_offset = base + o_vo; s->recv_own_prefix = base + o_vp; s->recv_dst_row = base + o_vr;
+        s->recv_count = base + o_vc; s->recv_kept = base + o_vk; s->recv_dst_row = base + o_vr;
         s->recv_rank_count = base + o_rc; s->recv_rank_offset = base + o_rf;
     }
     return cur;
@@ -422,8 +419,6 @@ ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk
     a.entry_rank = s.entry_rank;
     // the table of run starts is only wanted by the destination-ordered dispatch
     a.run_start = (c.dispatch_order != EP_ORDER_TOKEN && c.dispatch_path == EP_PATH_DIRECT) ? s.run_start : nullptr;
-    a.msgs = nullptr; a.msg_bytes = 0; a.msg_total_slots = 0; a.msg_slots_per_rank = 0;
-    a.msg_rank_offset = nullptr; a.msg_rank_count = nullptr;
     h->has_runs = layout_writes_runs(a);
     h->nwc = a.nwc;
     h->chunk_entries = a.passes * kWave;
@@ -571,32 +566,22 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     sa.T = h->T; sa.K = c.top_k; sa.H = c.hidden;
     if (launch_dedup_send(sa, (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
 
-    LayoutArgs la;
-    la.topk = nullptr; la.topk_stride = 0;
-    la.expert_base = h->expert_base;
-    la.T = (int)g->staging_slots; la.K = c.top_k; la.E = c.num_experts; la.R = c.num_ranks;
-    la.L = g->L; la.L_shift = g->L_shift; la.K_shift = g->K_shift;
-    la.padded = c.mode == EP_MODE_LL; la.C = g->C; la.C_rank = c.max_tokens_per_rank;
-    la.n = (int)(g->staging_slots * c.top_k);
-    plan_layout(la.n, &la.passes, &la.nwc);
-    la.W = g->W; la.bits_e = g->bits_e; la.bits_r = g->bits_r;
-    la.hist = s.hist;
-    la.expert_count = s.recv_count; la.expert_kept = s.recv_kept; la.expert_offset = s.recv_offset;
-    la.own_prefix = s.recv_own_prefix;
-    la.rank_pair_count = nullptr; la.rank_token_count = nullptr; la.rank_offset = nullptr;
-    la.totals = s.recv_totals;
-    la.slot = nullptr; la.dst_row = s.recv_dst_row; la.rank_row = nullptr; la.entry_rank = nullptr;
-    la.sorted_token = nullptr; la.sorted_k = nullptr; la.sorted_row = nullptr; la.run_start = nullptr;
-    la.msgs = g->staging[set]; la.msg_bytes = g->msg_bytes; la.msg_total_slots = (int)g->staging_slots;
-    la.msg_slots_per_rank = c.mode == EP_MODE_LL ? c.max_tokens_per_rank : 0;
+    DedupRankArgs ra;
+    ra.staging = g->staging[set]; ra.msg_bytes = g->msg_bytes; ra.staging_slots = g->staging_slots;
+    ra.slots_per_rank = c.mode == EP_MODE_LL ? c.max_tokens_per_rank : 0;
     // a staged call lets the receiving side learn the message counts from the counters
-    la.msg_rank_offset = send_only ? s.recv_rank_offset : s.rank_offset;
-    la.msg_rank_count = send_only ? s.recv_rank_count : s.rank_token_count;
+    ra.rank_offset = send_only ? s.recv_rank_offset : s.rank_offset;
+    ra.rank_count = send_only ? s.recv_rank_count : s.rank_token_count;
+    ra.expert_offset = s.expert_offset;
+    ra.recv_dst_row = s.recv_dst_row; ra.recv_count = s.recv_count; ra.recv_kept = s.recv_kept;
+    ra.K = c.top_k; ra.E = c.num_experts; ra.R = c.num_ranks; ra.L = g->L; ra.L_shift = g->L_shift;
+    ra.K_shift = g->K_shift; ra.bits_l = bits_for(g->L);
+    ra.padded = c.mode == EP_MODE_LL; ra.C = g->C;
 
     DedupFanoutArgs fa;
     fa.staging = g->staging[set]; fa.msg_bytes = g->msg_bytes; fa.hdr_bytes = g->hdr_bytes;
-    fa.staging_slots = g->staging_slots; fa.slots_per_rank = la.msg_slots_per_rank;
-    fa.rank_offset = la.msg_rank_offset; fa.rank_count = la.msg_rank_count;
+    fa.staging_slots = g->staging_slots; fa.slots_per_rank = ra.slots_per_rank;
+    fa.rank_offset = ra.rank_offset; fa.rank_count = ra.rank_count;
     fa.recv_dst_row = s.recv_dst_row; fa.recv_kept = s.recv_kept;
     fa.win = a.win; fa.recv_w = a.recv_w; fa.recv_src = a.recv_src; fa.recv_count = a.recv_count;
     fa.totals = s.totals;
@@ -606,11 +591,11 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
             return EP_ERR_HIP;
         h->pending = PENDING_DISPATCH_DEDUP;
         h->pending_set = set;
-        h->pending_layout = la;
+        h->pending_rank = ra;
         h->pending_fanout = fa;
         return EP_SUCCESS;
     }
-    if (launch_layout(la, (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
+    if (launch_dedup_rank(ra, (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
     return launch_dedup_fanout(fa, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
 }
 
@@ -634,7 +619,7 @@ ep_result_t ep_complete(ep_handle_t h, const ep_complete_config_t* cfg, ep_strea
     if (kind == PENDING_DISPATCH_DEDUP) {
         if (launch_await_counts(g->sig_rank(set), c.num_ranks, spin, s.recv_rank_count, s.recv_rank_offset,
                                 s.totals, st) != hipSuccess) return EP_ERR_HIP;
-        if (launch_layout(h->pending_layout, st) != hipSuccess) return EP_ERR_HIP;
+        if (launch_dedup_rank(h->pending_rank, st) != hipSuccess) return EP_ERR_HIP;
         return launch_dedup_fanout(h->pending_fanout, st) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
     }
     if (launch_await_counts(g->sig_combine(set), c.num_experts, spin, nullptr, nullptr, s.totals, st) != hipSuccess)

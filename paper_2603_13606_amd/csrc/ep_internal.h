@@ -58,15 +58,6 @@ struct LayoutArgs {
     int32_t* sorted_row;      // [n]
     int32_t* run_start;       // [nwc+1, E] or nullptr: first sorted position of expert e among the entries
                               // of wave-chunks >= c (row c); only the histogram kernels fill it
-    // Message mode (receiving side of the once-per-rank path): entries are the
-    // routing vectors in the headers of the staged messages; slot, rank_row,
-    // sorted_* and the rank arrays may then be nullptr.
-    const uint8_t* msgs;      // staging windows, or nullptr for the sender-side layout
-    int64_t msg_bytes;        // bytes per message slot
-    int msg_total_slots;      // slots in the staging windows
-    int msg_slots_per_rank;   // > 0: fixed-size window per rank; 0: compact windows
-    const int32_t* msg_rank_offset;  // [R+1] first slot of each rank's window
-    const int32_t* msg_rank_count;   // [R]   messages in each rank's window
 };
 
 // Addressing of the receive windows: element offset of logical row r is
@@ -152,7 +143,26 @@ struct DedupFanoutArgs {
     int K, H, E, R;
 };
 
+// Receiving side of the once-per-rank path: ranks the header entries of every staging
+// window among the entries of the same expert, in slot order.
+struct DedupRankArgs {
+    const uint8_t* staging;
+    int64_t msg_bytes;
+    int64_t staging_slots;
+    int slots_per_rank;              // > 0: fixed-size window per rank; 0: compact windows
+    const int32_t* rank_offset;      // [R+1] first slot of each rank's window
+    const int32_t* rank_count;       // [R]   messages in each rank's window
+    const int32_t* expert_offset;    // [E+1] first row of each expert (concat layout)
+    int32_t* recv_dst_row;           // [staging_slots, K] out: row of each header entry, -1 if none
+    int32_t* recv_count;             // [E] out: entries per expert
+    int32_t* recv_kept;              // [E] out: rows per expert (capped at C in the padded layout)
+    int K, E, R, L, L_shift, K_shift;
+    int bits_l;                      // bits of a local expert index
+    int padded, C;
+};
+
 hipError_t launch_layout(const LayoutArgs& a, hipStream_t s);
+hipError_t launch_dedup_rank(const DedupRankArgs& a, hipStream_t s);
 hipError_t launch_dedup_send(const DedupSendArgs& a, hipStream_t s);
 hipError_t launch_dedup_fanout(const DedupFanoutArgs& a, hipStream_t s);
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s);

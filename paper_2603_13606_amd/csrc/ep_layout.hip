@@ -25,11 +25,6 @@
 // The work is latency bound (a chain of dependent LDS and global round trips per
 // wave), so every phase issues all of its global loads before it waits for any of
 // them and the workgroup barriers order LDS traffic only.
-//
-// The same kernels serve the receiving side of the once-per-rank dispatch
-// (Sec. IV-D): there the entries are the routing vectors found in the headers of
-// the staged messages, in window order, filtered to the experts the window's
-// rank hosts (Sec. IV-C "Dispatch/recv").
 #include "ep_internal.h"
 
 namespace ep {
@@ -89,7 +84,6 @@ struct Lds {
     int32_t *tot;    // [W] totals over the whole input
     int32_t *pre;    // [W] entries of each bin in earlier chunks
     int32_t *eoff, *opre, *roff;  // [E+1], [E+1], [R+1]
-    int32_t *mroff, *mcnt;        // message mode: rank_offset [R+1], rank_token_count [R]
 };
 
 __device__ __forceinline__ Lds carve_lds(int32_t* base, const LayoutArgs& a, int nw) {
@@ -100,39 +94,11 @@ __device__ __forceinline__ Lds carve_lds(int32_t* base, const LayoutArgs& a, int
     l.eoff = l.pre + a.W;
     l.opre = l.eoff + a.E + 1;
     l.roff = l.opre + a.E + 1;
-    l.mroff = l.roff + a.R + 1;
-    l.mcnt = l.mroff + a.R + 1;
     return l;
 }
 
 size_t lds_bytes(const LayoutArgs& a, int nw) {
-    return sizeof(int32_t) * ((size_t)nw * a.W + 2 * a.W + 2 * (a.E + 1) + 2 * (a.R + 1) + a.R);
-}
-
-template <bool MSGS>
-__device__ __forceinline__ void stage_msg_tables(const LayoutArgs& a, const Lds& l) {
-    if (!MSGS) return;
-    for (int d = threadIdx.x; d <= a.R; d += blockDim.x) l.mroff[d] = a.msg_rank_offset[d];
-    for (int d = threadIdx.x; d < a.R; d += blockDim.x) l.mcnt[d] = a.msg_rank_count[d];
-}
-
-// Message mode: which destination rank's window holds staging slot m, and is the
-// slot in use.
-__device__ __forceinline__ bool msg_slot_rank(const LayoutArgs& a, int m, const Lds& l, int* d_out) {
-    if (m >= a.msg_total_slots) return false;
-    if (a.msg_slots_per_rank > 0) {  // fixed-size window per rank
-        const int d = m / a.msg_slots_per_rank;
-        *d_out = d;
-        return (m - d * a.msg_slots_per_rank) < l.mcnt[d];
-    }
-    if (m >= l.mroff[a.R]) return false;  // compact windows: [rank_offset[d], rank_offset[d+1])
-    int lo = 0, hi = a.R;                 // largest d with rank_offset[d] <= m
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (l.mroff[mid] <= m) lo = mid; else hi = mid;
-    }
-    *d_out = lo;
-    return true;
+    return sizeof(int32_t) * ((size_t)nw * a.W + 2 * a.W + 2 * (a.E + 1) + (a.R + 1));
 }
 
 // Marks the entries that are the first of their token to name their destination
@@ -158,35 +124,23 @@ __device__ __forceinline__ void mark_leaders(const LayoutArgs& a, Entry& en, int
 }
 
 // Issues the global loads of the ids of passes p0 .. p0+PU-1 of wave-chunk wc
-// (nothing waits on them here).  In message mode the LDS tables must be staged.
-template <bool MSGS>
-__device__ __forceinline__ void issue_group(const LayoutArgs& a, int wc, int p0, int lane, const Lds& l,
-                                            int (&raw)[PU], int (&dwin)[PU]) {
+// (nothing waits on them here).
+__device__ __forceinline__ void issue_group(const LayoutArgs& a, int wc, int p0, int lane, int (&raw)[PU]) {
 #pragma unroll
     for (int j = 0; j < PU; ++j) {
         const int p = p0 + j;
         const int i = (wc * a.passes + p) * kWave + lane;
         raw[j] = 0;
-        dwin[j] = -1;
         if (p < a.passes && i < a.n) {
             const int t = token_of(a, i), k = i - t * a.K;
-            if (MSGS) {
-                int d = 0;
-                if (msg_slot_rank(a, t, l, &d)) {
-                    dwin[j] = d;
-                    raw[j] = ((const int32_t*)(a.msgs + (int64_t)t * a.msg_bytes))[1 + k];
-                }
-            } else {
-                raw[j] = a.topk[(int64_t)t * a.topk_stride + k];
-            }
+            raw[j] = a.topk[(int64_t)t * a.topk_stride + k];
         }
     }
 }
 
 // Classifies the ids loaded by issue_group.  Must be called by all 64 lanes.
-template <bool MSGS>
 __device__ __forceinline__ void classify_group(const LayoutArgs& a, int wc, int p0, int lane,
-                                               const int (&raw)[PU], const int (&dwin)[PU], Entry (&en)[PU]) {
+                                               const int (&raw)[PU], Entry (&en)[PU]) {
 #pragma unroll
     for (int j = 0; j < PU; ++j) {
         Entry& x = en[j];
@@ -199,26 +153,19 @@ __device__ __forceinline__ void classify_group(const LayoutArgs& a, int wc, int 
         const int e = raw[j];
         const bool inrange = (unsigned)e < (unsigned)a.E;
         x.d = inrange ? owner_of(a, e) : 0;
-        if (MSGS) {
-            x.ok = in && dwin[j] >= 0 && inrange && x.d == dwin[j];
-            x.masked = x.invalid = x.lead = false;
-        } else {
-            x.ok = in && inrange;
-            x.masked = in && e == -1;
-            x.invalid = in && !inrange && e != -1;
-            if (p < a.passes) mark_leaders(a, x, lane);  // wave-uniform condition
-            else x.lead = false;
-        }
+        x.ok = in && inrange;
+        x.masked = in && e == -1;
+        x.invalid = in && !inrange && e != -1;
+        if (p < a.passes) mark_leaders(a, x, lane);  // wave-uniform condition
+        else x.lead = false;
         x.e = x.ok ? e : 0;
     }
 }
 
-template <bool MSGS>
-__device__ __forceinline__ void load_group(const LayoutArgs& a, int wc, int p0, int lane, const Lds& l,
-                                           Entry (&en)[PU]) {
-    int raw[PU], dwin[PU];
-    issue_group<MSGS>(a, wc, p0, lane, l, raw, dwin);
-    classify_group<MSGS>(a, wc, p0, lane, raw, dwin, en);
+__device__ __forceinline__ void load_group(const LayoutArgs& a, int wc, int p0, int lane, Entry (&en)[PU]) {
+    int raw[PU];
+    issue_group(a, wc, p0, lane, raw);
+    classify_group(a, wc, p0, lane, raw, en);
 }
 
 // Histogram of a loaded group into h[0..W) with LDS atomics (integer adds: the
@@ -260,7 +207,6 @@ __device__ __forceinline__ void emit_entry(const LayoutArgs& a, const Entry& x, 
 // that bin before the group; it is advanced as the group is walked.  LDS accesses
 // of one wavefront are performed in program order, and the wave barriers keep the
 // compiler from moving them across each other.  Must be called by all 64 lanes.
-template <bool MSGS>
 __device__ __forceinline__ void slots_group(const LayoutArgs& a, const Entry (&en)[PU], int p0, int32_t* h,
                                             const Lds& l, int lane) {
     const uint64_t lt = (1ull << lane) - 1ull;
@@ -269,7 +215,7 @@ __device__ __forceinline__ void slots_group(const LayoutArgs& a, const Entry (&e
         if (p0 + j >= a.passes) break;  // wave-uniform
         const Entry& x = en[j];
         const uint64_t peers = match_key(x.e, x.ok, a.bits_e);
-        const uint64_t peers_r = MSGS ? 0ull : match_key(x.d, x.lead, a.bits_r);
+        const uint64_t peers_r = match_key(x.d, x.lead, a.bits_r);
         const int rank = __popcll(peers & lt);
         const int rank_r = __popcll(peers_r & lt);
         const int slot = x.ok ? h[x.e] + rank : -1;
@@ -401,7 +347,6 @@ __device__ void wave_write_tables(const LayoutArgs& a, const Lds& l, int lane) {
 }
 
 // Chunk b = wave-chunks [b*wpb, (b+1)*wpb).  Writes hist[b][0..W).
-template <bool MSGS>
 __global__ __launch_bounds__(512) void layout_count_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
     const int wpb = blockDim.x >> 6;
@@ -412,16 +357,15 @@ __global__ __launch_bounds__(512) void layout_count_kernel(LayoutArgs a) {
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wc = blockIdx.x * wpb + w;
     const bool active = wc < a.nwc;
-    int raw[PU], dwin[PU];
-    if (active && !MSGS) issue_group<MSGS>(a, wc, 0, lane, l, raw, dwin);  // in flight during the LDS set-up
+    int raw[PU];
+    if (active) issue_group(a, wc, 0, lane, raw);  // in flight during the LDS set-up
     for (int j = tid; j < W; j += blockDim.x) l.wh[j] = 0;
-    stage_msg_tables<MSGS>(a, l);
     lds_barrier();
     if (active) {
         Entry en[PU];
         for (int p0 = 0; p0 < a.passes; p0 += PU) {
-            if (MSGS || p0 > 0) issue_group<MSGS>(a, wc, p0, lane, l, raw, dwin);
-            classify_group<MSGS>(a, wc, p0, lane, raw, dwin, en);
+            if (p0 > 0) issue_group(a, wc, p0, lane, raw);
+            classify_group(a, wc, p0, lane, raw, en);
             hist_group(a, en, l.wh);
         }
     }
@@ -433,7 +377,7 @@ __global__ __launch_bounds__(512) void layout_count_kernel(LayoutArgs a) {
 // With one chunk (gridDim.x == 1) this kernel is the whole layout.  MAXT = largest
 // workgroup it is launched with; HB = chunk histograms whose words each thread loads
 // up front (thread = bin).
-template <int MAXT, int HB, bool MSGS>
+template <int MAXT, int HB>
 __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
     const int wpb = blockDim.x >> 6;
@@ -451,22 +395,21 @@ __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
     // (1) issue every global load this workgroup needs up front: its own ids and the
     //     other chunks' histograms (consumed in (3)); they stay in flight across the
     //     LDS-only barrier
-    int raw[PU], dwin[PU];
-    if (active && !MSGS) issue_group<MSGS>(a, wc, 0, lane, l, raw, dwin);
+    int raw[PU];
+    if (active) issue_group(a, wc, 0, lane, raw);
     int hv[HB];  // column tid of the first HB chunk histograms
     const int nrows = nchunks > 1 ? nchunks : 0;
 #pragma unroll
     for (int r = 0; r < HB; ++r) hv[r] = (r < nrows && tid < W) ? a.hist[(int64_t)r * W + tid] : 0;
     for (int j = tid; j < wpb * W + 2 * W; j += blockDim.x) l.wh[j] = 0;  // wh, tot, pre are contiguous
-    stage_msg_tables<MSGS>(a, l);
     lds_barrier();
 
     // (2) per-wave histograms of this chunk
     Entry en[PU];
     if (active) {
         for (int p0 = 0; p0 < a.passes; p0 += PU) {
-            if (MSGS || p0 > 0) issue_group<MSGS>(a, wc, p0, lane, l, raw, dwin);
-            classify_group<MSGS>(a, wc, p0, lane, raw, dwin, en);
+            if (p0 > 0) issue_group(a, wc, p0, lane, raw);
+            classify_group(a, wc, p0, lane, raw, en);
             hist_group(a, en, l.wh + w * W);
         }
     }
@@ -507,8 +450,8 @@ __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
     // (6) slots
     if (active) {
         for (int p0 = 0; p0 < a.passes; p0 += PU) {
-            if (!one_group) load_group<MSGS>(a, wc, p0, lane, l, en);
-            slots_group<MSGS>(a, en, p0, l.wh + w * W, l, lane);
+            if (!one_group) load_group(a, wc, p0, lane, en);
+            slots_group(a, en, p0, l.wh + w * W, l, lane);
         }
         // the walk has advanced the wave's prefixes past its own entries: they are now the
         // positions at which the next wave-chunk's entries start in the expert-sorted list
@@ -563,17 +506,16 @@ __global__ __launch_bounds__(1024) void layout_bitmap_kernel(LayoutArgs a) {
     l.eoff = l.pre + a.W;
     l.opre = l.eoff + a.E + 1;
     l.roff = l.opre + a.E + 1;
-    l.mroff = l.mcnt = nullptr;
     const int tid = threadIdx.x;
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    int raw[PU], dwin[PU];
-    issue_group<false>(a, w, 0, lane, l, raw, dwin);  // one pass: the entry of this thread
+    int raw[PU];
+    issue_group(a, w, 0, lane, raw);  // one pass: the entry of this thread
     for (int j = tid; j < nbins * kBitmapStride; j += blockDim.x) bm[j] = 0ull;
     for (int j = tid; j < a.W; j += blockDim.x) l.tot[j] = 0;
     lds_barrier();
     Entry en[PU];
-    classify_group<false>(a, w, 0, lane, raw, dwin, en);
+    classify_group(a, w, 0, lane, raw, en);
     const Entry& x = en[0];
     const uint64_t bit = 1ull << lane;
     if (x.ok) atomicOr((unsigned long long*)&bm[x.e * kBitmapStride + w], (unsigned long long)bit);
@@ -615,7 +557,7 @@ void plan_layout(int n, int* passes, int* nwc) {
 }
 
 static bool use_bitmap(const LayoutArgs& a) {
-    return !a.msgs && a.passes == 1 && a.nwc >= 1 && a.nwc <= kLayoutWavesPerBlock && bitmap_lds_bytes(a) <= kLdsLimit;
+    return a.passes == 1 && a.nwc >= 1 && a.nwc <= kLayoutWavesPerBlock && bitmap_lds_bytes(a) <= kLdsLimit;
 }
 
 bool layout_writes_runs(const LayoutArgs& a) { return a.run_start != nullptr && !use_bitmap(a); }
@@ -641,15 +583,9 @@ hipError_t launch_layout(const LayoutArgs& a, hipStream_t s) {
     if (nblk > kMaxWaveChunks) return hipErrorInvalidValue;
     const dim3 grid(nblk), block(wpb * kWave);
     const size_t lds = lds_bytes(a, wpb);
-    if (a.msgs) {
-        if (nblk > 1) hipLaunchKernelGGL(layout_count_kernel<true>, grid, block, lds_bytes(a, 1), s, a);
-        if (nblk == 1) hipLaunchKernelGGL((layout_slot_kernel<1024, 1, true>), grid, block, lds, s, a);
-        else hipLaunchKernelGGL((layout_slot_kernel<512, 32, true>), grid, block, lds, s, a);
-    } else {
-        if (nblk > 1) hipLaunchKernelGGL(layout_count_kernel<false>, grid, block, lds_bytes(a, 1), s, a);
-        if (nblk == 1) hipLaunchKernelGGL((layout_slot_kernel<1024, 1, false>), grid, block, lds, s, a);
-        else hipLaunchKernelGGL((layout_slot_kernel<512, 32, false>), grid, block, lds, s, a);
-    }
+    if (nblk > 1) hipLaunchKernelGGL(layout_count_kernel, grid, block, lds_bytes(a, 1), s, a);
+    if (nblk == 1) hipLaunchKernelGGL((layout_slot_kernel<1024, 1>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((layout_slot_kernel<512, 32>), grid, block, lds, s, a);
     return hipGetLastError();
 }
 

@@ -538,6 +538,11 @@ DEDUP_CASES = [
     ("skew_rank0", 900, 256, "ll", 60, True),
     ("stress_hot", 600, 128, "ht", 0, True),
     ("ht_prefill", None, None, "ht", 0, True),   # full benchmark shape
+    ("stress_hot", None, 256, "ht", 0, True),    # 8192 tokens: hot ranks' windows take several passes per wave
+    (("ll_decode", dict(R=1, E=64, K=4)), 300, 128, "ht", 0, True),   # one window, 64 local experts
+    (("ll_decode", dict(R=4, E=24, K=3)), 333, 64, "ll", 50, True),   # K and L not powers of two, drops
+    (("ll_decode", dict(R=8, E=1024, K=16)), 200, 64, "ht", 0, False),  # 128 local experts, 16 ids per header
+    (("tiny", dict(dup=True)), 64, None, "ht", 0, True),              # a token naming one expert twice
 ]
 
 
@@ -545,11 +550,17 @@ DEDUP_CASES = [
 def test_once_per_rank_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, weights):
     """Staging windows byte-for-byte equal to the oracle's messages; final windows equal to
     the oracle's direct dispatch (and to its own fan-out)."""
-    w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
+    over = {}
+    if isinstance(name, tuple):
+        name, over = name[0], dict(name[1])
+    dup = over.pop("dup", False)
+    w = wl.make_workload(name, T=T, **({"H": H} if H else {}), **over)
     spec = w.spec
     T = spec.T
-    _say(f"once-per-rank case {name} T={T} H={spec.H} mode={mode} C={C}")
+    _say(f"once-per-rank case {name} {over} T={T} H={spec.H} mode={mode} C={C}")
     topk = _mess_up(w.topk_idx, spec.E, seed=T, frac_masked=0.02)
+    if dup:
+        topk[::3, 1] = topk[::3, 0]  # duplicates: each occurrence gets its own row
     ll = mode == "ll"
     Cc = (C if C else T) if ll else 0
     lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, layout=int(ll), C=Cc, C_rank=T)
