@@ -107,7 +107,7 @@ def extras(ep, hx, wl, torch, np, group, spec, first_set, stream_ptr, iters: int
     nbytes = T * 2 * H + msgs * P + msgs * P + rows * 2 * H + 8 * rows
     res["once_per_rank_dispatch"] = {"us": round(us, 2), "messages": msgs, "algorithmic_bytes": nbytes,
                                      "gbps": round(nbytes / (us * 1e-6) / 1e9, 1),
-                                     "staging_bytes": int(ginfo.staging_slots) * P}
+                                     "staging_bytes": int(ginfo.staging_slots) * int(ginfo.msg_stride)}
     ep.ep_handle_destroy(h2)
     ep.ep_group_destroy(g2)
 

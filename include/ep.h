@@ -162,6 +162,12 @@ typedef struct {
     void *staging_sets[2];
     void *signals[2];
     void *combine_staging[2];
+    /* Staging slot s occupies bytes [s * msg_stride, (s+1) * msg_stride) of a staging window
+     * set; its message (msg_bytes: header, then token data) starts msg_lead bytes in, which
+     * puts the token data on a 256-byte boundary.  The other bytes of a slot are never
+     * written. */
+    int64_t msg_stride;
+    int64_t msg_lead;
 } ep_group_info_t;
 
 /* Result of a layout, host-side copy of the totals plus borrowed DEVICE pointers

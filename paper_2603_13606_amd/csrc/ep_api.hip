@@ -42,7 +42,8 @@ struct ep_group_s {
     // staging windows of the once-per-rank path, one per buffer set
     uint8_t* staging[2] = {nullptr, nullptr};
     int64_t staging_slots = 0;
-    int64_t hdr_bytes = 0, msg_bytes = 0;
+    int64_t hdr_bytes = 0, msg_bytes = 0;   // header and whole message (header + 2H)
+    int64_t msg_stride = 0, msg_lead = 0;    // slot pitch, and where the message starts in its slot
     // staged execution: buffer sets (0 = not available), coordination counters
     // [E dispatch | R once-per-rank | E combine] and (t,k)-indexed combine staging per set
     int nsets = 0, next_set = 0;
@@ -282,6 +283,9 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     g->free_fn = free_fn;
     g->hdr_bytes = round_up(4 + 8 * (int64_t)K, 16);
     g->msg_bytes = g->hdr_bytes + 2 * (int64_t)H;
+    // the token data of a message starts on a 256-byte boundary of its slot
+    g->msg_lead = round_up(g->hdr_bytes, 256) - g->hdr_bytes;
+    g->msg_stride = round_up(g->msg_lead + g->msg_bytes, 256);
     if (cfg->dispatch_path == EP_PATH_RANK_DEDUP) {
         // LL: B slots per destination rank (Sec. IV-D, O(N*B*P)); HT: a token reaches at
         // most min(R, K) ranks, windows are packed back to back.
@@ -301,7 +305,7 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     const int nstaging = g->staging_slots > 0 ? (g->nsets > 1 ? g->nsets : 1) : 0;
     for (int i = 0; i < nstaging; ++i) {
         void* p = nullptr;
-        ep_result_t r = dev_alloc(g, &p, (size_t)(g->staging_slots * g->msg_bytes));
+        ep_result_t r = dev_alloc(g, &p, (size_t)(g->staging_slots * g->msg_stride));
         if (r != EP_SUCCESS) return fail(r);
         g->staging[i] = (uint8_t*)p;
     }
@@ -350,6 +354,8 @@ ep_result_t ep_group_query(ep_group_t g, ep_group_info_t* info) {
     info->row_bytes = 2 * (int64_t)c.hidden;
     info->msg_header_bytes = g->hdr_bytes;
     info->msg_bytes = g->msg_bytes;
+    info->msg_stride = g->msg_stride;
+    info->msg_lead = g->msg_lead;
     info->staging_slots = g->staging_slots;
     info->staging = g->staging[0];
     info->staged_buffers = g->nsets;
@@ -560,14 +566,16 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     sa.topk = (const int32_t*)ti->data; sa.topk_stride = ti->stride[0];
     sa.w = a.w; sa.w_stride = a.w_stride;
     sa.rank_row = s.rank_row;
-    sa.staging = g->staging[set]; sa.msg_bytes = g->msg_bytes; sa.staging_slots = g->staging_slots;
+    sa.staging = g->staging[set]; sa.msg_stride = g->msg_stride; sa.msg_lead = g->msg_lead;
+    sa.staging_slots = g->staging_slots;
     sa.hdr_units = (int)(g->hdr_bytes / 16);
     sa.totals = s.totals;
     sa.T = h->T; sa.K = c.top_k; sa.H = c.hidden;
     if (launch_dedup_send(sa, (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
 
     DedupRankArgs ra;
-    ra.staging = g->staging[set]; ra.msg_bytes = g->msg_bytes; ra.staging_slots = g->staging_slots;
+    ra.staging = g->staging[set]; ra.msg_stride = g->msg_stride; ra.msg_lead = g->msg_lead;
+    ra.staging_slots = g->staging_slots;
     ra.slots_per_rank = c.mode == EP_MODE_LL ? c.max_tokens_per_rank : 0;
     // a staged call lets the receiving side learn the message counts from the counters
     ra.rank_offset = send_only ? s.recv_rank_offset : s.rank_offset;
@@ -579,7 +587,8 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     ra.padded = c.mode == EP_MODE_LL; ra.C = g->C;
 
     DedupFanoutArgs fa;
-    fa.staging = g->staging[set]; fa.msg_bytes = g->msg_bytes; fa.hdr_bytes = g->hdr_bytes;
+    fa.staging = g->staging[set]; fa.msg_stride = g->msg_stride; fa.msg_lead = g->msg_lead;
+    fa.hdr_bytes = g->hdr_bytes;
     fa.staging_slots = g->staging_slots; fa.slots_per_rank = ra.slots_per_rank;
     fa.rank_offset = ra.rank_offset; fa.rank_count = ra.rank_count;
     fa.recv_dst_row = s.recv_dst_row; fa.recv_kept = s.recv_kept;

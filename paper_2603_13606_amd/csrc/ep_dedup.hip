@@ -3,12 +3,15 @@
 // vector and the gate weights in the message header; the receiving side expands
 // each message to the local experts its header names (Sec. IV-C "Dispatch/recv").
 //
-// Message slot = { int32 src_token; int32 route[K]; float w[K]; zero padding to a
-// multiple of 16 bytes; 2H bytes of token data }.
+// Message = { int32 src_token; int32 route[K]; float w[K]; zero padding to a
+// multiple of 16 bytes; 2H bytes of token data }.  Slots are msg_stride bytes apart
+// (a multiple of 256) and a message starts msg_lead bytes into its slot, so that its
+// token data starts on a 256-byte boundary: every 1 KiB wave access to the data covers
+// whole memory lines, and the short header sits in the line before.
 //
-//   send kernel    work unit = one wavefront x one 1 KiB segment of one token's
-//                  message: a lane builds its 16 bytes once (header words or row
-//                  data) and stores them to every destination rank's slot.
+//   send kernel    work unit = one wavefront x one 1 KiB segment of one token's data,
+//                  loaded once and stored to every destination rank's slot; the wave
+//                  of segment 0 also builds and stores the header.
 //   rank kernel    the receiving side: one workgroup per staging window ranks the
 //                  header entries that name one of the window's local experts among
 //                  the entries of the same expert, in slot order (a stable counting
@@ -41,24 +44,22 @@ __global__ __launch_bounds__(256) void dedup_send_kernel(DedupSendArgs a, int ns
     if (u >= (int64_t)a.T * nseg) return;
     const int t = (int)(u / nseg);
     const int seg = (int)(u - (int64_t)t * nseg);
-    const int unit = seg * kWave + lane;  // 16-byte unit inside the message
+    const int unit = seg * kWave + lane;  // 16-byte unit inside the token data
     const bool active = unit < units;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (active) {
-        if (unit < a.hdr_units) {
-            const int32_t* route = a.topk + (int64_t)t * a.topk_stride;
-            const float* wt = a.w ? a.w + (int64_t)t * a.w_stride : nullptr;
+    u32x4 v = {0u, 0u, 0u, 0u}, hv = {0u, 0u, 0u, 0u};
+    if (active) v = __builtin_nontemporal_load((const u32x4*)(a.x + (int64_t)t * a.x_stride) + unit);
+    const bool header = seg == 0 && lane < a.hdr_units;  // this lane holds 16 bytes of the header
+    if (header) {
+        const int32_t* route = a.topk + (int64_t)t * a.topk_stride;
+        const float* wt = a.w ? a.w + (int64_t)t * a.w_stride : nullptr;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int j = unit * 4 + c;  // header word index
-                uint32_t word = 0u;
-                if (j == 0) word = (uint32_t)t;
-                else if (j <= a.K) word = (uint32_t)route[j - 1];
-                else if (j <= 2 * a.K) word = wt ? __float_as_uint(wt[j - 1 - a.K]) : __float_as_uint(1.0f);
-                v[c] = word;
-            }
-        } else {
-            v = __builtin_nontemporal_load((const u32x4*)(a.x + (int64_t)t * a.x_stride) + (unit - a.hdr_units));
+        for (int c = 0; c < 4; ++c) {
+            const int j = lane * 4 + c;  // header word index
+            uint32_t word = 0u;
+            if (j == 0) word = (uint32_t)t;
+            else if (j <= a.K) word = (uint32_t)route[j - 1];
+            else if (j <= 2 * a.K) word = wt ? __float_as_uint(wt[j - 1 - a.K]) : __float_as_uint(1.0f);
+            hv[c] = word;
         }
     }
     const int my_slot = lane < a.K ? a.rank_row[(int64_t)t * a.K + lane] : -1;
@@ -69,7 +70,9 @@ __global__ __launch_bounds__(256) void dedup_send_kernel(DedupSendArgs a, int ns
             if (seg == 0 && lane == 0) atomicOr(&a.totals[TOT_STATUS], STATUS_OUTPUT_OVERFLOW);
             continue;
         }
-        if (active) __builtin_nontemporal_store(v, (u32x4*)(a.staging + (int64_t)m * a.msg_bytes) + unit);
+        u32x4* msg = (u32x4*)(a.staging + (int64_t)m * a.msg_stride + a.msg_lead);
+        if (header) msg[lane] = hv;
+        if (active) __builtin_nontemporal_store(v, msg + a.hdr_units + unit);
     }
 }
 
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(256) void dedup_fanout_kernel(DedupFanoutArgs a, in
     }
     const int unit = seg * kWave + lane;  // 16-byte unit inside the payload
     const bool active = unit < units;
-    const uint8_t* msg = a.staging + (int64_t)m * a.msg_bytes;
+    const uint8_t* msg = a.staging + (int64_t)m * a.msg_stride + a.msg_lead;
     const int32_t* hdr = (const int32_t*)msg;
     u32x4 v = {0u, 0u, 0u, 0u};
     if (active) v = __builtin_nontemporal_load((const u32x4*)(msg + a.hdr_bytes) + unit);
@@ -165,7 +168,7 @@ __global__ __launch_bounds__(kRankWaves * kWave) void dedup_rank_kernel(DedupRan
     auto load_id = [&](int i) -> int {  // expert id named by entry i of the window
         const int mi = a.K_shift >= 0 ? (i >> a.K_shift) : (i / a.K);
         const int k = i - mi * a.K;
-        return ((const int32_t*)(a.staging + (int64_t)(m0 + mi) * a.msg_bytes))[1 + k];
+        return ((const int32_t*)(a.staging + (int64_t)(m0 + mi) * a.msg_stride + a.msg_lead))[1 + k];
     };
     auto local = [&](int e, int* le) -> bool {  // is e one of this window's experts, and which
         if ((unsigned)e >= (unsigned)a.E) return false;
@@ -250,10 +253,11 @@ hipError_t launch_dedup_rank(const DedupRankArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_dedup_send(const DedupSendArgs& a, hipStream_t s) {
-    const int units = a.hdr_units + a.H / 8;
+    const int units = a.H / 8;
     const int nseg = (units + kWave - 1) / kWave;
     const int64_t nwaves = (int64_t)a.T * nseg;
     if (nwaves == 0) return hipSuccess;
+    if (a.hdr_units > kWave) return hipErrorInvalidValue;  // the header is built by one wavefront
     const int64_t nblk = (nwaves + 3) / 4;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(dedup_send_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);

@@ -119,7 +119,8 @@ struct DedupSendArgs {
     int64_t w_stride;
     const int32_t* rank_row;  // [T, K] staging slot for the first k naming a rank, else -1
     uint8_t* staging;
-    int64_t msg_bytes;
+    int64_t msg_stride;       // bytes from one staging slot to the next
+    int64_t msg_lead;         // bytes between the start of a slot and its message
     int64_t staging_slots;
     int hdr_units;            // header size in 16-byte units
     int32_t* totals;
@@ -128,7 +129,7 @@ struct DedupSendArgs {
 
 struct DedupFanoutArgs {
     const uint8_t* staging;
-    int64_t msg_bytes, hdr_bytes;
+    int64_t msg_stride, msg_lead, hdr_bytes;
     int64_t staging_slots;
     int slots_per_rank;            // > 0: fixed-size window per rank; 0: compact windows
     const int32_t* rank_offset;    // [R+1]
@@ -147,7 +148,7 @@ struct DedupFanoutArgs {
 // window among the entries of the same expert, in slot order.
 struct DedupRankArgs {
     const uint8_t* staging;
-    int64_t msg_bytes;
+    int64_t msg_stride, msg_lead;
     int64_t staging_slots;
     int slots_per_rank;              // > 0: fixed-size window per rank; 0: compact windows
     const int32_t* rank_offset;      // [R+1] first slot of each rank's window

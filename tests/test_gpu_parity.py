@@ -610,8 +610,11 @@ def test_once_per_rank_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, 
         ep.ep_dispatch(h, hx.bits_to_dev(w.x_bits), recv, topk_weights=torch.from_numpy(w.topk_w).to(hx.DEV) if weights else None,
                        recv_w=r_w[:rows], recv_src=r_src[:rows], recv_count=r_cnt, topk_idx=d_topk)
         torch.cuda.synchronize()
-        got_win = staging[: n_slots * ginfo.msg_bytes].cpu().numpy().reshape(n_slots, ginfo.msg_bytes)
-        assert np.array_equal(got_win, o_win), "staging windows differ from the oracle's messages"
+        stride, lead = int(ginfo.msg_stride), int(ginfo.msg_lead)
+        assert stride % 256 == 0 and (lead + ginfo.msg_header_bytes) % 256 == 0 and lead + ginfo.msg_bytes <= stride
+        slots = staging[: n_slots * stride].cpu().numpy().reshape(n_slots, stride)
+        assert np.array_equal(slots[:, lead:lead + ginfo.msg_bytes], o_win), "staging windows differ from the oracle's messages"
+        assert np.all(slots[:, :lead] == 0xA5) and np.all(slots[:, lead + ginfo.msg_bytes:] == 0xA5), "slot padding was written"
         assert np.array_equal(hx.dev_to_bits(store), o_recv), "fanned-out rows differ"
         assert np.array_equal(r_src.cpu().numpy(), o_src)
         assert np.array_equal(r_w.cpu().numpy(), o_w)

@@ -121,8 +121,9 @@ def test_staged_once_per_rank_dispatch(ep, hx, oracle_mod, mode, C):
         ginfo = ep.ep_group_query(g)
         n_slots = int(ginfo.staging_slots)
         o_win = oracle_mod.dedup_send(w.x_bits, w.topk_idx, w.topk_w, lay, n_slots)
-        got = ep.read_device_i32(ginfo.staging_sets[0], n_slots * int(ginfo.msg_bytes) // 4).numpy().view(np.uint8)
-        got = got.reshape(n_slots, -1)
+        stride, lead = int(ginfo.msg_stride), int(ginfo.msg_lead)
+        got = ep.read_device_i32(ginfo.staging_sets[0], n_slots * stride // 4).numpy().view(np.uint8)
+        got = got.reshape(n_slots, stride)[:, lead:lead + int(ginfo.msg_bytes)]
         used = np.zeros(n_slots, bool)
         used[lay.rank_row[lay.rank_row >= 0]] = True
         assert np.array_equal(got[used], o_win[used])
