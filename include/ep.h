@@ -137,7 +137,9 @@ typedef struct {
 } ep_group_config_t;
 
 /* Allocator callbacks (Sec. III-C): when given, every device allocation of the
- * group goes through them.  Return 0 on success. */
+ * group goes through them.  Return 0 on success; the memory must be device memory
+ * aligned to 256 bytes (ep_group_create / ep_layout fail with EP_ERR_INVALID_ARG
+ * otherwise and hand the block back through the free callback). */
 typedef int (*ep_alloc_fn)(void **ptr, size_t bytes);
 typedef int (*ep_free_fn)(void *ptr);
 

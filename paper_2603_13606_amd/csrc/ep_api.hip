@@ -86,7 +86,15 @@ int bits_for(int n) {  // bits needed to write any value in [0, n)
 }
 
 ep_result_t dev_alloc(ep_group_s* g, void** p, size_t bytes) {
-    if (g->alloc_fn) return g->alloc_fn(p, bytes) == 0 && *p ? EP_SUCCESS : EP_ERR_NOMEM;
+    if (g->alloc_fn) {
+        if (g->alloc_fn(p, bytes) != 0 || !*p) return EP_ERR_NOMEM;
+        if ((uintptr_t)*p & 255u) {  // the kernels rely on 256-byte aligned arrays
+            g->free_fn(*p);
+            *p = nullptr;
+            return EP_ERR_INVALID_ARG;
+        }
+        return EP_SUCCESS;
+    }
     hipError_t e = hipMalloc(p, bytes);
     if (e == hipErrorOutOfMemory) return EP_ERR_NOMEM;
     return e == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
@@ -128,8 +136,9 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
         s->rank_token_count = base + o_rt; s->rank_offset = base + o_ro;
         s->hist = base + o_h; s->slot = base + o_sl; s->dst_row = base + o_dr; s->rank_row = base + o_rr;
         s->sorted_token = base + o_st; s->sorted_k = base + o_sk; s->sorted_row = base + o_sr;
-        s->entry_rank = base + o_er; s->run_start = base + o_rn;
-        s->recv_count = base + o_vc; s->recv_kept = base + o_vk; s->recv_dst_row = base + o_vr;
+        s->entry_rank = base + o_er; s->run_start = runs ? base + o_rn : nullptr;
+        s->recv_count = dedup ? base + o_vc : nullptr; s->recv_kept = dedup ? base + o_vk : nullptr;
+        s->recv_dst_row = dedup ? base + o_vr : nullptr;
         s->recv_rank_count = base + o_rc; s->recv_rank_offset = base + o_rf;
     }
     return cur;
