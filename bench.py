@@ -281,7 +281,9 @@ def main() -> int:
     value = step_bytes * args.steps / elapsed / 1e9
     dom = "dispatch" if dis_us.mean() >= com_us.mean() else "combine"
     dom_us = dis_us.mean() if dom == "dispatch" else com_us.mean()
-    kernel_name = {"dispatch": "dispatch_direct_kernel", "combine": "combine_kernel"}[dom]
+    kernel_name = {"dispatch": "dispatch_runs_kernel" if args.dispatch_order else "dispatch_direct_kernel",
+                   "combine": "combine_kernel"}[dom]
+    traffic_key = spec.name + ("_destination_order" if args.dispatch_order else "")
     achieved = ab[dom] / (dom_us * 1e-6) / 1e9
 
     def stats(a):
@@ -296,7 +298,8 @@ def main() -> int:
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{spec.name}: R={spec.R} T={T} H={H} E={E} K={K} bf16, concatenated layout, "
-                               f"direct dispatch, gate logits N(0,1) prior={spec.prior}",
+                               f"direct dispatch{['', ' (EP_ORDER_DESTINATION)', ' (EP_ORDER_DESTINATION_RESIDENT)'][args.dispatch_order]}, "
+                               f"gate logits N(0,1) prior={spec.prior}",
                    "rows": rows, "input_sets_rotated": nsets},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "us": {"layout": stats(lay_us), "dispatch": stats(dis_us), "combine": stats(com_us),
@@ -310,7 +313,7 @@ def main() -> int:
                                "(read + write bytes / best of 6 launches)"},
         "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": _traffic(spec.name, kernel_name),
+                     "traffic": _traffic(traffic_key, kernel_name),
                      "timing": f"HIP events on the launch stream around the kernel, mean over every "
                                f"{args.event_every}-th step of the timed region ({len(events)} samples)"},
     }
