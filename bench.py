@@ -5,6 +5,10 @@ One step = ep_layout + ep_dispatch + ep_combine (+ handle destroy) over one batc
 of synthetic routing.  Inputs (tokens, top-k ids, gate weights, expert outputs)
 are resident in HBM before the timed region.  Prints ONE JSON line.
 
+By default the group is configured with EP_ORDER_DESTINATION and the layout call is
+ep_layout_prefetch (the tokens are announced to it); --dispatch-order 0 times the
+token-ordered dispatch with plain ep_layout.
+
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload ht_prefill]
 """
 from __future__ import annotations
@@ -165,8 +169,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="ht_prefill")
     ap.add_argument("--sets", type=int, default=3, help="input/window sets rotated between steps")
-    ap.add_argument("--dispatch-order", type=int, default=0, choices=(0, 1, 2),
-                    help="EP_ORDER_TOKEN (0), EP_ORDER_DESTINATION (1), EP_ORDER_DESTINATION_RESIDENT (2)")
+    ap.add_argument("--dispatch-order", type=int, default=1, choices=(0, 1, 2),
+                    help="EP_ORDER_TOKEN (0); EP_ORDER_DESTINATION with the tokens announced to the layout "
+                         "call, ep_layout_prefetch (1, default); EP_ORDER_DESTINATION_RESIDENT (2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--event-every", type=int, default=4,
                     help="record the per-op HIP events on every n-th timed step only (four event "
@@ -228,7 +233,7 @@ def main() -> int:
     # descriptors are built once per input set; a step is then four foreign-function calls
     stream_ptr = torch.cuda.current_stream().cuda_stream
     destroy = ep.load().ep_handle_destroy
-    prepared = [(ep.PreparedLayout(group, topk), ep.prepare_dispatch(x, recv, topk_weights=gate),
+    prepared = [(ep.PreparedLayout(group, topk, tokens=x if args.dispatch_order == 1 else None), ep.prepare_dispatch(x, recv, topk_weights=gate),
                  ep.prepare_combine(y, out, topk_weights=gate)) for (x, topk, gate, recv, y, out, _) in sets]
 
     def step(i, ev=None):
@@ -283,7 +288,7 @@ def main() -> int:
     dom_us = dis_us.mean() if dom == "dispatch" else com_us.mean()
     kernel_name = {"dispatch": "dispatch_runs_kernel" if args.dispatch_order else "dispatch_direct_kernel",
                    "combine": "combine_kernel"}[dom]
-    traffic_key = spec.name + ("_destination_order" if args.dispatch_order else "")
+    traffic_key = spec.name + ["_token_order", "", "_destination_order_resident"][args.dispatch_order]
     achieved = ab[dom] / (dom_us * 1e-6) / 1e9
 
     def stats(a):
@@ -298,7 +303,7 @@ def main() -> int:
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{spec.name}: R={spec.R} T={T} H={H} E={E} K={K} bf16, concatenated layout, "
-                               f"direct dispatch{['', ' (EP_ORDER_DESTINATION)', ' (EP_ORDER_DESTINATION_RESIDENT)'][args.dispatch_order]}, "
+                               f"direct dispatch {['EP_ORDER_TOKEN', 'EP_ORDER_DESTINATION + ep_layout_prefetch', 'EP_ORDER_DESTINATION_RESIDENT'][args.dispatch_order]}, "
                                f"gate logits N(0,1) prior={spec.prior}",
                    "rows": rows, "input_sets_rotated": nsets},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),

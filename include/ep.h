@@ -69,7 +69,8 @@ enum { EP_PATH_DIRECT = 0, EP_PATH_RANK_DEDUP = 1 };
  *                         that end up next to each other are written close in time,
  *                         which the memory system rewards.  A read pass over the tokens
  *                         (in pieces of at most 64 MiB) precedes the copy so that the
- *                         copy finds them in the memory-side cache.
+ *                         copy finds them in the memory-side cache (ep_layout_prefetch
+ *                         can do that reading in the shadow of the layout kernels).
  *   EP_ORDER_DESTINATION_RESIDENT  the same without the read pass: for callers whose
  *                         tokens were produced or read just before the call and are at
  *                         most a fraction of the 256 MiB memory-side cache.  When the
@@ -261,6 +262,20 @@ EP_API ep_result_t ep_group_query(ep_group_t group, ep_group_info_t *info);
  */
 EP_API ep_result_t ep_layout(ep_handle_t *handle, ep_group_t group, const ep_tensor_t *topk_idx,
                       const ep_tensor_t *expert_base, ep_stream_t stream);
+
+/*
+ * ep_layout with a hint: `tokens` is the bf16 [T, H] tensor (tag EP_TAG_TOKENS, rows on
+ * 16-byte boundaries) that the caller is going to hand to ep_dispatch next.  The layout
+ * kernels keep only a few compute units busy; for a group whose dispatch_order is
+ * EP_ORDER_DESTINATION and an input of at least 8192 routed entries, the same launch
+ * therefore also reads the tokens (the first 64 MiB of them) into the memory-side cache
+ * on the idle units, and ep_dispatch, when it is given the same tensor (data pointer and
+ * row stride), leaves out its own read pass over those rows.  In every other case the
+ * hint is ignored.  The handle, its arrays and all results are those of ep_layout.
+ */
+EP_API ep_result_t ep_layout_prefetch(ep_handle_t *handle, ep_group_t group, const ep_tensor_t *topk_idx,
+                               const ep_tensor_t *expert_base, const ep_tensor_t *tokens,
+                               ep_stream_t stream);
 
 /* Synchronises the handle's last stream and fills `info`.  Returns
  * EP_ERR_INVALID_ROUTING if bad expert ids were seen and EP_ERR_OVERFLOW if a

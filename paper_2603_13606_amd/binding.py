@@ -47,7 +47,7 @@ STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW, STATUS_TIMEOUT
 
 EXPORTS = [
     "ep_error_string", "ep_version", "ep_layout_plan", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
-    "ep_layout", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
+    "ep_layout", "ep_layout_prefetch", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
     "ep_dispatch", "ep_combine", "ep_complete", "ep_group_reset_signals",
 ]
 
@@ -128,6 +128,8 @@ def load() -> ctypes.CDLL:
         lib.ep_group_query.argtypes = [vp, ctypes.POINTER(ep_group_info_t)]
         lib.ep_layout.argtypes = [ctypes.POINTER(vp), vp, ctypes.POINTER(ep_tensor_t),
                                   ctypes.POINTER(ep_tensor_t), vp]
+        lib.ep_layout_prefetch.argtypes = [ctypes.POINTER(vp), vp, ctypes.POINTER(ep_tensor_t),
+                                           ctypes.POINTER(ep_tensor_t), ctypes.POINTER(ep_tensor_t), vp]
         lib.ep_handle_query.argtypes = [vp, ctypes.POINTER(ep_layout_info_t)]
         lib.ep_handle_get_num_recv_tokens.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
         lib.ep_handle_destroy.argtypes = [vp]
@@ -243,6 +245,17 @@ def ep_layout(group, topk_idx: torch.Tensor, expert_base: Optional[torch.Tensor]
     return h
 
 
+def ep_layout_prefetch(group, topk_idx: torch.Tensor, tokens: torch.Tensor,
+                       expert_base: Optional[torch.Tensor] = None, stream=None) -> ctypes.c_void_p:
+    h = ctypes.c_void_p()
+    td = tensor_desc(topk_idx, EP_TAG_TOPK_IDX)
+    bd = ctypes.byref(tensor_desc(expert_base, EP_TAG_EXPERT_BASE)) if expert_base is not None else None
+    xd = tensor_desc(tokens, EP_TAG_TOKENS)
+    _check(load().ep_layout_prefetch(ctypes.byref(h), group, ctypes.byref(td), bd, ctypes.byref(xd),
+                                     _stream_ptr(stream)), "ep_layout_prefetch")
+    return h
+
+
 def ep_handle_query(handle, ok: Sequence[int] = (EP_SUCCESS,)) -> ep_layout_info_t:
     info = ep_layout_info_t()
     info.last_code = _check(load().ep_handle_query(handle, ctypes.byref(info)), "ep_handle_query", ok)
@@ -355,19 +368,21 @@ def prepare_combine(y, out, topk_weights=None) -> PreparedCall:
 
 
 class PreparedLayout:
-    """ep_layout with its descriptors built once."""
+    """ep_layout (ep_layout_prefetch when tokens are given) with its descriptors built once."""
 
-    def __init__(self, group, topk_idx, expert_base=None):
-        self._fn = load().ep_layout
+    def __init__(self, group, topk_idx, expert_base=None, tokens=None):
+        self._fn = load().ep_layout_prefetch
         self._group = group
-        self._keep = (topk_idx, expert_base)
+        self._keep = (topk_idx, expert_base, tokens)
         self._td = tensor_desc(topk_idx, EP_TAG_TOPK_IDX)
         self._bd = tensor_desc(expert_base, EP_TAG_EXPERT_BASE) if expert_base is not None else None
+        self._xd = tensor_desc(tokens, EP_TAG_TOKENS) if tokens is not None else None
 
     def __call__(self, stream_ptr: int = 0) -> ctypes.c_void_p:
         h = ctypes.c_void_p()
         code = self._fn(ctypes.byref(h), self._group, ctypes.byref(self._td),
-                        ctypes.byref(self._bd) if self._bd is not None else None, stream_ptr)
+                        ctypes.byref(self._bd) if self._bd is not None else None,
+                        ctypes.byref(self._xd) if self._xd is not None else None, stream_ptr)
         if code != EP_SUCCESS:
             raise EpError(code, "ep_layout")
         return h

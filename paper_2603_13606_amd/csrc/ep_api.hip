@@ -2,6 +2,7 @@
 // translation of tensor descriptors into kernel arguments (Sec. III-A..E).
 // Host code only; every step of the data path runs in the kernels of
 // ep_layout.hip, ep_dispatch.hip, ep_dedup.hip, ep_combine.hip and ep_staged.hip.
+#include <algorithm>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -66,6 +67,9 @@ struct ep_handle_s {
     bool has_runs = false;       // the layout filled slab.run_start
     int nwc = 0;                 // wave-chunks of the layout plan
     int chunk_entries = 0;       // entries per wave-chunk
+    const void* warm_x = nullptr;  // tokens the layout launch has read into cache (ep_layout_prefetch)
+    int64_t warm_stride = 0;
+    int warm_rows = 0;
     // receive phase of a staged (send_only) call, run by ep_complete
     int pending = PENDING_NONE;
     int pending_set = 0;
@@ -385,6 +389,11 @@ ep_result_t ep_group_query(ep_group_t g, ep_group_info_t* info) {
 
 ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk_idx,
                       const ep_tensor_t* expert_base, ep_stream_t stream) {
+    return ep_layout_prefetch(handle, g, topk_idx, expert_base, nullptr, stream);
+}
+
+ep_result_t ep_layout_prefetch(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk_idx,
+                               const ep_tensor_t* expert_base, const ep_tensor_t* tokens, ep_stream_t stream) {
     if (!handle || !g || !topk_idx) return EP_ERR_INVALID_ARG;
     const ep_group_config_t& c = g->cfg;
     if (topk_idx->tag != EP_TAG_TOPK_IDX || topk_idx->ndim != 2 || topk_idx->dtype != EP_DTYPE_I32)
@@ -396,6 +405,11 @@ ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk
         if (c.mode != EP_MODE_HT) return EP_ERR_INVALID_ARG;
         if (expert_base->tag != EP_TAG_EXPERT_BASE || !check_1d(expert_base, EP_DTYPE_I32, c.num_experts) ||
             !expert_base->data)
+            return EP_ERR_INVALID_ARG;
+    }
+    if (tokens) {
+        if (tokens->tag != EP_TAG_TOKENS || !check_2d(tokens, EP_DTYPE_BF16, T, c.hidden, true) ||
+            tokens->stride[0] % 8 || !aligned16(tokens->data))
             return EP_ERR_INVALID_ARG;
     }
     ep_handle_s* h = new (std::nothrow) ep_handle_s();
@@ -434,6 +448,17 @@ ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk
     a.entry_rank = s.entry_rank;
     // the table of run starts is only wanted by the destination-ordered dispatch
     a.run_start = (c.dispatch_order != EP_ORDER_TOKEN && c.dispatch_path == EP_PATH_DIRECT) ? s.run_start : nullptr;
+    a.warm_x = nullptr; a.warm_stride = 0; a.warm_rows = 0; a.warm_units = c.hidden / 8; a.nchunks = 1;
+    if (tokens && a.run_start && c.dispatch_order == EP_ORDER_DESTINATION) {
+        a.warm_x = (const uint16_t*)tokens->data;
+        a.warm_stride = tokens->stride[0];
+        a.warm_rows = (int)std::min<int64_t>(T, kWarmBytes / (2 * (int64_t)c.hidden));
+        if (layout_prefetches(a)) {
+            h->warm_x = tokens->data; h->warm_stride = a.warm_stride; h->warm_rows = a.warm_rows;
+        } else {
+            a.warm_x = nullptr;
+        }
+    }
     h->has_runs = layout_writes_runs(a);
     h->nwc = a.nwc;
     h->chunk_entries = a.passes * kWave;
@@ -540,6 +565,7 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     a.run_start = h->has_runs ? h->slab.run_start : nullptr;
     a.nwc = h->nwc; a.chunk_entries = h->chunk_entries;
     a.order = c.dispatch_order;
+    a.prefetched_rows = (h->warm_x == x->data && h->warm_stride == x->stride[0]) ? h->warm_rows : 0;
     h->last_stream = (hipStream_t)stream;
     int set = 0;
     if (send_only) {

@@ -165,7 +165,7 @@ __global__ __launch_bounds__(256) void dispatch_warm_kernel(DispatchArgs a, int 
         for (int64_t i = gid; i < n; i += stride) acc ^= (uint32_t)(a.sorted_token[i] ^ a.sorted_row[i]);
         for (int64_t i = gid; i < table; i += stride) acc ^= (uint32_t)a.run_start[i];
     }
-    if (acc == 0x9e3779b9u) atomicOr(&a.totals[TOT_STATUS], 0);  // keeps the loads; changes nothing
+    if (acc == 0x9e3779b9u) a.totals[kTotalsWords - 1] = (int32_t)acc;  // keeps the loads; the word is unused
 }
 
 template <int TPR_SHIFT>
@@ -299,12 +299,10 @@ hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStr
     return hipGetLastError();
 }
 
-// Inputs from this many entries on can be copied in run order (when the layout recorded
-// the runs); smaller ones are bound by latency and keep the shorter token-ordered kernel.
-constexpr int kRunOrderMinEntries = 8192;
-// Tokens warmed per read pass: a piece must stay in the 256 MiB memory-side cache, next to
-// whatever else lives there, while the copy of that piece runs.
-constexpr int64_t kWarmBytes = 64ll << 20;
+// Inputs from kRunOrderMinEntries entries on can be copied in run order (when the layout
+// recorded the runs); smaller ones are bound by latency and keep the shorter token-ordered
+// kernel.  A read pass covers kWarmBytes of tokens: a piece must stay in the 256 MiB
+// memory-side cache, next to whatever else lives there, while the copy of that piece runs.
 
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s) {
     const int units = a.H / 8;  // 16-byte units per row
@@ -328,9 +326,9 @@ hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s) {
         }
         for (int b0 = 0; b0 < p.nblocks; b0 += per) {
             const int nb = min(per, p.nblocks - b0);
-            if (warm) {
-                const int t0 = (int)std::min<int64_t>(a.T, b0 * block_entries / a.K);
-                const int t1 = (int)std::min<int64_t>(a.T, ((b0 + nb) * block_entries + a.K - 1) / a.K);
+            const int t0 = (int)std::min<int64_t>(a.T, b0 * block_entries / a.K);
+            const int t1 = (int)std::min<int64_t>(a.T, ((b0 + nb) * block_entries + a.K - 1) / a.K);
+            if (warm && t1 > a.prefetched_rows) {  // unless the layout launch has read these rows already
                 hipLaunchKernelGGL(dispatch_warm_kernel, dim3(2048), dim3(256), 0, s, a, units, t0, t1, b0 == 0 ? 1 : 0);
             }
             p.first_block = b0;

@@ -56,6 +56,11 @@ struct LayoutArgs {
     int32_t* sorted_token;    // [n]
     int32_t* sorted_k;        // [n]
     int32_t* sorted_row;      // [n]
+    // optional: token rows to read into the memory-side cache on otherwise idle compute units
+    const uint16_t* warm_x;   // [warm_rows, H] bf16, row stride warm_stride elements, or nullptr
+    int64_t warm_stride;
+    int warm_rows, warm_units;  // rows to read, 16-byte units per row
+    int nchunks;              // workgroups of the slot kernel that lay out (set by launch_layout)
     int32_t* run_start;       // [nwc+1, E] or nullptr: first sorted position of expert e among the entries
                               // of wave-chunks >= c (row c); only the histogram kernels fill it
 };
@@ -94,6 +99,7 @@ struct DispatchArgs {
     int nwc;                      // wave-chunks of the layout
     int chunk_entries;            // entries per wave-chunk
     int order;                    // EP_ORDER_*
+    int prefetched_rows;          // leading token rows the layout launch has already read into cache
 };
 
 struct CombineArgs {
@@ -180,5 +186,11 @@ hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hip
 void plan_layout(int n, int* passes, int* nwc);
 // True when launch_layout fills LayoutArgs::run_start for this plan.
 bool layout_writes_runs(const LayoutArgs& a);
+// True when launch_layout reads LayoutArgs::warm_x for this plan.
+bool layout_prefetches(const LayoutArgs& a);
+// Token bytes one read pass of the destination-ordered dispatch covers.
+constexpr int64_t kWarmBytes = 64ll << 20;
+// Inputs from this many routed entries on may be dispatched in destination order.
+constexpr int kRunOrderMinEntries = 8192;
 
 }  // namespace ep

@@ -346,6 +346,24 @@ __device__ void wave_write_tables(const LayoutArgs& a, const Lds& l, int lane) {
     }
 }
 
+// Extra workgroups of the slot kernel (blockIdx >= nchunks): read the token rows the caller
+// announced, with ordinary cached loads, while the layout workgroups -- a few dozen on a
+// part with 256 compute units -- do their latency-bound work.  wb of nwb.
+// Rows [r0, r1), 16 bytes per thread and step, the workgroups side by side.
+__device__ void warm_tokens(const LayoutArgs& a, int wb, int nwb, int r0, int r1) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int64_t total = (int64_t)(r1 - r0) * a.warm_units;
+    const int64_t stride = (int64_t)nwb * blockDim.x;
+    uint32_t acc = 0;
+    for (int64_t i = (int64_t)wb * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int64_t t = r0 + i / a.warm_units;
+        const int col = (int)(i % a.warm_units);
+        const u32x4 v = *((const u32x4*)(a.warm_x + t * a.warm_stride) + col);
+        acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
+    }
+    if (acc == 0x9e3779b9u) a.totals[kTotalsWords - 1] = (int32_t)acc;  // keeps the loads; the word is unused
+}
+
 // Chunk b = wave-chunks [b*wpb, (b+1)*wpb).  Writes hist[b][0..W).
 __global__ __launch_bounds__(512) void layout_count_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
@@ -380,6 +398,10 @@ __global__ __launch_bounds__(512) void layout_count_kernel(LayoutArgs a) {
 template <int MAXT, int HB>
 __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
+    if ((int)blockIdx.x >= a.nchunks) {  // a whole workgroup: no barrier below is reached by part of one
+        warm_tokens(a, blockIdx.x - a.nchunks, gridDim.x - a.nchunks, 0, a.warm_rows);
+        return;
+    }
     const int wpb = blockDim.x >> 6;
     const Lds l = carve_lds(lds, a, wpb);
     const int W = a.W;
@@ -387,7 +409,7 @@ __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wc = blockIdx.x * wpb + w;
-    const int nchunks = gridDim.x;
+    const int nchunks = a.nchunks;
     const int b = blockIdx.x;
     const bool active = wc < a.nwc;
     const bool one_group = a.passes <= PU;
@@ -562,7 +584,17 @@ static bool use_bitmap(const LayoutArgs& a) {
 
 bool layout_writes_runs(const LayoutArgs& a) { return a.run_start != nullptr && !use_bitmap(a); }
 
-hipError_t launch_layout(const LayoutArgs& a, hipStream_t s) {
+// The read-ahead rides on the slot kernel of inputs that are laid out by several workgroups.
+bool layout_prefetches(const LayoutArgs& a) {
+    return a.warm_x != nullptr && a.warm_rows > 0 && a.n >= kRunOrderMinEntries && !use_bitmap(a) &&
+           a.nwc > kLayoutWavesPerBlock;
+}
+
+constexpr int kWarmBlocks = 2048;  // extra workgroups of the slot kernel that read tokens
+
+hipError_t launch_layout(const LayoutArgs& a_in, hipStream_t s) {
+    LayoutArgs a = a_in;
+    a.nchunks = 1;
     if (use_bitmap(a)) {
         hipLaunchKernelGGL(layout_bitmap_kernel, dim3(1), dim3(a.nwc * kWave), bitmap_lds_bytes(a), s, a);
         return hipGetLastError();
@@ -583,9 +615,11 @@ hipError_t launch_layout(const LayoutArgs& a, hipStream_t s) {
     if (nblk > kMaxWaveChunks) return hipErrorInvalidValue;
     const dim3 grid(nblk), block(wpb * kWave);
     const size_t lds = lds_bytes(a, wpb);
+    a.nchunks = nblk;
+    const bool pf = layout_prefetches(a);
     if (nblk > 1) hipLaunchKernelGGL(layout_count_kernel, grid, block, lds_bytes(a, 1), s, a);
     if (nblk == 1) hipLaunchKernelGGL((layout_slot_kernel<1024, 1>), grid, block, lds, s, a);
-    else hipLaunchKernelGGL((layout_slot_kernel<512, 32>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((layout_slot_kernel<512, 32>), dim3(nblk + (pf ? kWarmBlocks : 0)), block, lds, s, a);
     return hipGetLastError();
 }
 

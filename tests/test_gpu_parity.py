@@ -243,7 +243,7 @@ PATH_CASES = [
 ]
 
 
-def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True, order=0):
+def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True, order=0, prefetch=False):
     w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
     spec = w.spec
     T = spec.T
@@ -263,7 +263,11 @@ def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True
     try:
         x = hx.bits_to_dev(w.x_bits)
         d_w = torch.from_numpy(w.topk_w).to(hx.DEV)
-        h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+        if prefetch:
+            h = ep.ep_layout_prefetch(g, torch.from_numpy(topk).to(hx.DEV), x)
+            hx.assert_layout_equal(hx.fetch_layout(h, T, spec.K, spec.E, spec.R, ok=(ep.EP_SUCCESS, ep.EP_ERR_INVALID_ROUTING)), lay)
+        else:
+            h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
         store = hx.poison_bf16((rows + guard, spec.H))
         recv = store[:rows].view(spec.E, Cc, spec.H) if ll else store[:rows]
         r_w = torch.full((rows + guard,), -3.5, dtype=torch.float32, device=hx.DEV)
@@ -330,14 +334,15 @@ ORDER_CASES = [
 ]
 
 
-@pytest.mark.parametrize("order", [1, 2])
+@pytest.mark.parametrize("order", [1, 2, "1 with ep_layout_prefetch", "0 with ep_layout_prefetch"])
 @pytest.mark.parametrize("name,T,H,mode,C", ORDER_CASES)
 def test_dispatch_destination_order_parity(ep, hx, oracle_mod, name, T, H, mode, C, order):
     """The destination-ordered dispatch (with and without its read pass) writes exactly the
     bytes of the oracle's dispatch, side arrays and counts included, and leaves the rest of the
     windows untouched; combine on top of it is unchanged."""
     _say(f"order case {name} T={T} H={H} mode={mode} C={C} order={order}")
-    _run_path(ep, hx, oracle_mod, name, T, H, mode, C, order=order)
+    prefetch = isinstance(order, str)  # the layout launch also reads the tokens (a hint: same results)
+    _run_path(ep, hx, oracle_mod, name, T, H, mode, C, order=int(str(order)[0]), prefetch=prefetch)
 
 
 def test_destination_order_output_too_small_is_flagged_not_overrun(ep, hx, oracle_mod):
@@ -357,6 +362,24 @@ def test_destination_order_output_too_small_is_flagged_not_overrun(ep, hx, oracl
         o = np.full((spec.T * spec.K, spec.H), hx.POISON, np.uint16)
         oracle_mod.dispatch(w.x_bits, None, lay, o)
         assert np.array_equal(got[:cap], o[:cap])
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_layout_prefetch_rejects_a_wrong_tokens_tensor(ep, hx):
+    w = wl.make_workload("ll_decode", T=1100, H=256)
+    spec = w.spec
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT, dispatch_order=ep.EP_ORDER_DESTINATION)
+    try:
+        topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
+        x = hx.bits_to_dev(w.x_bits)
+        for bad in (x[:-1], x[:, :128], x.float()):
+            with pytest.raises(ep.EpError) as ei:
+                ep.ep_layout_prefetch(g, topk, bad)
+            assert ei.value.code == ep.EP_ERR_INVALID_ARG
+        assert ep.ep_group_query(g).live_handles == 0
+        h = ep.ep_layout_prefetch(g, topk, x)
         ep.ep_handle_destroy(h)
     finally:
         ep.ep_group_destroy(g)
