@@ -109,7 +109,9 @@ class EPBuffer:
         with torch.cuda.stream(self.comm_stream):
             if handle is None:
                 assert topk_idx is not None
-                raw = ep.ep_layout(self.group, topk_idx, stream=sp)
+                # the tokens are about to be dispatched: let the layout launch read them ahead
+                # (only a destination-ordered group makes use of the hint)
+                raw = ep.ep_layout_prefetch(self.group, topk_idx, x, stream=sp)
                 handle = EPHandle(raw, topk_idx, T)
             rows = self.E * self.C if self.ll else T * self.K
             dt = torch.float8_e4m3fn if fp8 else torch.bfloat16

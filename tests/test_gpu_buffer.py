@@ -95,3 +95,31 @@ def test_buffer_autograd_reuses_handle(hx, mode):
         buf.destroy_handle(h)
     finally:
         buf.close()
+
+
+def test_buffer_destination_order_gives_the_same_tensors(hx):
+    """A buffer configured for the destination order (its dispatch announces the tokens to the
+    layout call) returns bit for bit what the default buffer returns."""
+    from paper_2603_13606_amd import binding as ep
+    from paper_2603_13606_amd.buffer import EPBuffer
+    w = wl.make_workload("ll_decode", T=1100, H=512)
+    spec = w.spec
+    topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
+    x = hx.bits_to_dev(w.x_bits)
+    gate = torch.from_numpy(w.topk_w).to(hx.DEV)
+    got = []
+    for order in (ep.EP_ORDER_TOKEN, ep.EP_ORDER_DESTINATION):
+        buf = EPBuffer(spec.R, spec.E, spec.H, spec.K, max_tokens_per_rank=spec.T, mode="ht", dispatch_order=order)
+        try:
+            recv_x, recv_src, recv_w, h, _ = buf.dispatch(x, topk, gate)
+            n = sum(buf.get_tokens_per_expert_list())
+            out, _ = buf.combine(recv_x, h, gate)
+            torch.cuda.synchronize()
+            got.append((hx.dev_to_bits(recv_x[:n]), recv_src[:n].cpu().numpy(), recv_w[:n].cpu().numpy(),
+                        hx.dev_to_bits(out), n))
+            buf.destroy_handle(h)
+        finally:
+            buf.close()
+    assert got[0][4] == got[1][4] == spec.T * spec.K
+    for a, b in zip(got[0][:4], got[1][:4]):
+        assert np.array_equal(a, b)
