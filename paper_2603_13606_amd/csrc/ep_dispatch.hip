@@ -82,6 +82,7 @@ struct RunPlan {
     int units;      // 16-byte units per row
     int tpr_shift;  // log2(threads that share one row piece)
     int first_block;  // this launch covers blocks first_block .. first_block + gridDim.y - 1
+    int splits;       // workgroups that share one run
 };
 
 // TPR_SHIFT = log2(threads that share one row piece); PADDED = window addressing mode.
@@ -94,7 +95,8 @@ __global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunP
     // grid = (kSlices * E, blocks): x runs fastest, so workgroups are handed out slice by
     // slice, expert by expert, block by block
     const int xs = blockIdx.x & (kSlices - 1);
-    const int e = blockIdx.x / kSlices;
+    const int es = blockIdx.x / kSlices;
+    const int e = es / p.splits, sp = es - e * p.splits;
     const int blk = p.first_block + blockIdx.y;
     const int c0 = blk * p.group, c1 = min(c0 + p.group, a.nwc);
     // wave-uniform: the run of expert e in block blk, as positions of the sorted entry list
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunP
     const int sub = threadIdx.x >> TPR_SHIFT, u = threadIdx.x & (tpr - 1);
     const int u0 = xs * p.piece, u1 = min(p.units, u0 + p.piece);
     const bool side = xs == 0 && u == 0;  // one lane per row fills the side arrays
-    for (int pos0 = lo + sub; pos0 < hi; pos0 += nsub * kRunUnroll) {
+    for (int pos0 = lo + sp * (nsub * kRunUnroll) + sub; pos0 < hi; pos0 += p.splits * nsub * kRunUnroll) {
         int t[kRunUnroll], row[kRunUnroll];
 #pragma unroll
         for (int q = 0; q < kRunUnroll; ++q) {
@@ -170,7 +172,7 @@ __global__ __launch_bounds__(256) void dispatch_warm_kernel(DispatchArgs a, int 
 
 template <int TPR_SHIFT>
 void launch_runs(const DispatchArgs& a, const RunPlan& p, int nblocks, hipStream_t s) {
-    const dim3 grid((unsigned)(kSlices * a.E), (unsigned)nblocks);
+    const dim3 grid((unsigned)(kSlices * a.E * p.splits), (unsigned)nblocks);
     if (a.win.padded) hipLaunchKernelGGL((dispatch_runs_kernel<TPR_SHIFT, true>), grid, dim3(256), 0, s, a, p);
     else hipLaunchKernelGGL((dispatch_runs_kernel<TPR_SHIFT, false>), grid, dim3(256), 0, s, a, p);
 }
@@ -309,13 +311,25 @@ hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s) {
     if (a.order != EP_ORDER_TOKEN && a.run_start && (int64_t)a.T * a.K >= kRunOrderMinEntries && units >= kSlices) {
         RunPlan p;
         // a block holds about three rows per expert (and at least 768 entries)
-        const int want = max(768, 3 * a.E);
+        // A block holds about 12 rows per expert, and no more tokens than keep one slice of
+        // them (2H/8 bytes each) within 2 MiB, half of an XCD's L2.  Longer runs are rewarded
+        // by the memory system when the routing is even (32 rows per expert: 86 instead of
+        // 88 us at the prefill shape) but lose more when a few experts are hot, because the
+        // workgroups of a long hot run then loop while the others idle; 8 to 16 rows are
+        // within 1 % of the best on every shape measured.  A workgroup
+        // copies nsub * kRunUnroll rows at a time, so a run of average length is shared by
+        // `splits` workgroups, one step each.
+        const int64_t l2_tokens = (2ll << 20) / max(2 * a.H / kSlices, 1);
+        const int want = (int)std::max<int64_t>(768, std::min<int64_t>(12ll * a.E, l2_tokens * a.K));
         p.group = max(1, want / a.chunk_entries);
         p.nblocks = (a.nwc + p.group - 1) / p.group;
         p.units = units;
         p.piece = (units + kSlices - 1) / kSlices;
         p.tpr_shift = 4;
         while ((1 << p.tpr_shift) < p.piece && p.tpr_shift < 8) ++p.tpr_shift;
+        const int rows_per_step = (256 >> p.tpr_shift) * kRunUnroll;
+        const int avg_run = (p.group * a.chunk_entries + a.E - 1) / a.E;
+        p.splits = max(1, (avg_run + rows_per_step - 1) / rows_per_step);
         const bool warm = a.order == EP_ORDER_DESTINATION;
         const int64_t block_entries = (int64_t)p.group * a.chunk_entries;
         // blocks per launch: all of them, or as many as cover kWarmBytes of tokens
