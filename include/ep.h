@@ -215,6 +215,24 @@ EP_API int32_t ep_version(void);
  */
 EP_API ep_result_t ep_layout_plan(int64_t num_entries, int32_t *passes, int32_t *wave_chunks);
 
+/* Diagnostic: how the direct dispatch of a group configured like `cfg` would walk an input
+ * of `num_tokens` tokens, `prefetched_rows` of which ep_layout_prefetch has already read.
+ * Pure host arithmetic (no device is touched); the same function plans the real launches. */
+typedef struct {
+    int32_t run_order;          /* 1: destination order; 0: token order, the rest is 0       */
+    int32_t group;              /* wave-chunks of the layout per block                       */
+    int32_t blocks;             /* blocks the input is cut into                              */
+    int32_t block_entries;      /* routed entries per block                                  */
+    int32_t splits;             /* workgroups that share the run of one (block, expert)      */
+    int32_t slice_units;        /* 16-byte units of a row per slice (8 slices per row)       */
+    int32_t threads_per_piece;  /* threads that copy one row piece                           */
+    int32_t blocks_per_launch;  /* blocks per copy launch                                    */
+    int32_t launches;           /* copy launches                                             */
+    int32_t read_passes;        /* token read passes (at most one per copy launch)           */
+} ep_dispatch_plan_t;
+EP_API ep_result_t ep_dispatch_plan(const ep_group_config_t *cfg, int64_t num_tokens, int64_t prefetched_rows,
+                             ep_dispatch_plan_t *plan);
+
 /*
  * Measurement aid, not part of the paper's API: a plain streaming copy of `bytes`
  * (multiple of 16; dst and src 16-byte aligned DEVICE pointers, not overlapping)

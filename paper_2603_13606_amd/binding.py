@@ -46,7 +46,7 @@ EP_TAG_EXPERT_BASE = 9
 STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW, STATUS_TIMEOUT = 1, 2, 4, 8
 
 EXPORTS = [
-    "ep_error_string", "ep_version", "ep_layout_plan", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
+    "ep_error_string", "ep_version", "ep_layout_plan", "ep_dispatch_plan", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
     "ep_layout", "ep_layout_prefetch", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
     "ep_dispatch", "ep_combine", "ep_complete", "ep_group_reset_signals",
 ]
@@ -88,6 +88,12 @@ class ep_group_info_t(ctypes.Structure):
 _INFO_PTRS = ("expert_count", "expert_kept", "expert_offset", "rank_pair_count", "rank_token_count",
               "rank_offset", "slot", "dst_row", "rank_row", "sorted_token", "sorted_k", "sorted_row",
               "entry_rank")
+
+
+class ep_dispatch_plan_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("run_order", "group", "blocks", "block_entries", "splits", "slice_units", "threads_per_piece",
+                 "blocks_per_launch", "launches", "read_passes")]
 
 
 class ep_layout_info_t(ctypes.Structure):
@@ -139,6 +145,8 @@ def load() -> ctypes.CDLL:
         lib.ep_complete.argtypes = [vp, ctypes.POINTER(ep_complete_config_t), vp]
         lib.ep_group_reset_signals.argtypes = [vp, vp]
         lib.ep_layout_plan.argtypes = [ctypes.c_int64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        lib.ep_dispatch_plan.argtypes = [ctypes.POINTER(ep_group_config_t), ctypes.c_int64, ctypes.c_int64,
+                                         ctypes.POINTER(ep_dispatch_plan_t)]
         for name in EXPORTS[2:]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -154,6 +162,14 @@ ep_error_string = error_string
 
 def ep_version() -> int:
     return int(load().ep_version())
+
+
+def ep_dispatch_plan(cfg: "ep_group_config_t", num_tokens: int, prefetched_rows: int = 0) -> ep_dispatch_plan_t:
+    """How ep_dispatch of a group configured like cfg would walk num_tokens tokens (host arithmetic)."""
+    plan = ep_dispatch_plan_t()
+    _check(load().ep_dispatch_plan(ctypes.byref(cfg), num_tokens, prefetched_rows, ctypes.byref(plan)),
+           "ep_dispatch_plan")
+    return plan
 
 
 def ep_layout_plan(num_entries: int):

@@ -253,6 +253,24 @@ ep_result_t ep_layout_plan(int64_t num_entries, int32_t* passes, int32_t* wave_c
     return EP_SUCCESS;
 }
 
+ep_result_t ep_dispatch_plan(const ep_group_config_t* cfg, int64_t num_tokens, int64_t prefetched_rows,
+                             ep_dispatch_plan_t* plan) {
+    if (!cfg || !plan || cfg->size != sizeof(ep_group_config_t)) return EP_ERR_INVALID_ARG;
+    if (num_tokens < 0 || prefetched_rows < 0 || cfg->top_k < 1 || cfg->hidden < 8 || cfg->num_experts < 1 ||
+        num_tokens * cfg->top_k > (1 << 28))
+        return EP_ERR_INVALID_ARG;
+    DispatchPlan d;
+    // layouts of more than 1024 entries record the runs whenever the group asks for them
+    const bool have_runs = cfg->dispatch_order != EP_ORDER_TOKEN && cfg->dispatch_path == EP_PATH_DIRECT;
+    plan_dispatch((int)num_tokens, cfg->top_k, cfg->hidden, cfg->num_experts, cfg->dispatch_order, have_runs,
+                  (int)std::min<int64_t>(prefetched_rows, num_tokens), &d);
+    plan->run_order = d.run_order; plan->group = d.group; plan->blocks = d.blocks;
+    plan->block_entries = d.block_entries; plan->splits = d.splits; plan->slice_units = d.piece;
+    plan->threads_per_piece = d.run_order ? 1 << d.tpr_shift : 0;
+    plan->blocks_per_launch = d.blocks_per_launch; plan->launches = d.launches; plan->read_passes = d.read_passes;
+    return EP_SUCCESS;
+}
+
 ep_result_t ep_calibration_copy(void* dst, const void* src, size_t bytes, ep_stream_t stream) {
     if (!dst || !src || bytes % 16 || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) return EP_ERR_INVALID_ARG;
     return launch_calibration_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;

@@ -305,46 +305,64 @@ hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStr
 // recorded the runs); smaller ones are bound by latency and keep the shorter token-ordered
 // kernel.  A read pass covers kWarmBytes of tokens: a piece must stay in the 256 MiB
 // memory-side cache, next to whatever else lives there, while the copy of that piece runs.
+//
+// A block holds about 12 rows per expert, and no more tokens than keep one slice of them
+// (2H/8 bytes each) within 2 MiB, half of an XCD's L2.  Longer runs are rewarded by the
+// memory system when the routing is even (32 rows per expert: 86 instead of 88 us at the
+// prefill shape) but lose more when a few experts are hot, because the workgroups of a long
+// hot run then loop while the others idle; 8 to 16 rows are within 1 % of the best on every
+// shape measured.  A workgroup copies nsub * kRunUnroll rows at a time, so a run of average
+// length is shared by `splits` workgroups, one step each.
+bool plan_dispatch(int T, int K, int H, int E, int order, bool have_runs, int prefetched_rows, DispatchPlan* out) {
+    DispatchPlan d = {};
+    const int units = H / 8;  // 16-byte units per row
+    const int64_t n = (int64_t)T * K;
+    d.run_order = order != EP_ORDER_TOKEN && have_runs && n >= kRunOrderMinEntries && units >= kSlices;
+    if (!d.run_order) { *out = d; return false; }
+    int passes = 0, nwc = 0;
+    plan_layout((int)n, &passes, &nwc);
+    const int chunk_entries = passes * kWave;
+    const int64_t l2_tokens = (2ll << 20) / std::max(2 * H / kSlices, 1);
+    const int want = (int)std::max<int64_t>(768, std::min<int64_t>(12ll * E, l2_tokens * K));
+    d.group = std::max(1, want / chunk_entries);
+    d.blocks = (nwc + d.group - 1) / d.group;
+    d.piece = (units + kSlices - 1) / kSlices;
+    d.tpr_shift = 4;
+    while ((1 << d.tpr_shift) < d.piece && d.tpr_shift < 8) ++d.tpr_shift;
+    const int rows_per_step = (256 >> d.tpr_shift) * kRunUnroll;
+    const int avg_run = (int)(((int64_t)d.group * chunk_entries + E - 1) / E);
+    d.splits = std::max(1, (avg_run + rows_per_step - 1) / rows_per_step);
+    d.block_entries = d.group * chunk_entries;
+    // blocks per launch: all of them, or as many as cover kWarmBytes of tokens
+    d.blocks_per_launch = d.blocks;
+    if (order == EP_ORDER_DESTINATION) {
+        const int64_t block_bytes = ((int64_t)d.block_entries + K - 1) / K * H * 2;
+        d.blocks_per_launch = (int)std::max<int64_t>(1, std::min<int64_t>(d.blocks, kWarmBytes / std::max<int64_t>(block_bytes, 1)));
+    }
+    for (int b0 = 0; b0 < d.blocks; b0 += d.blocks_per_launch) {
+        const int nb = std::min(d.blocks_per_launch, d.blocks - b0);
+        const int t1 = (int)std::min<int64_t>(T, ((int64_t)(b0 + nb) * d.block_entries + K - 1) / K);
+        d.launches += 1;
+        if (order == EP_ORDER_DESTINATION && t1 > prefetched_rows) d.read_passes += 1;
+    }
+    *out = d;
+    return true;
+}
 
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s) {
     const int units = a.H / 8;  // 16-byte units per row
-    if (a.order != EP_ORDER_TOKEN && a.run_start && (int64_t)a.T * a.K >= kRunOrderMinEntries && units >= kSlices) {
+    DispatchPlan d;
+    if (plan_dispatch(a.T, a.K, a.H, a.E, a.order, a.run_start != nullptr, a.prefetched_rows, &d)) {
         RunPlan p;
-        // a block holds about three rows per expert (and at least 768 entries)
-        // A block holds about 12 rows per expert, and no more tokens than keep one slice of
-        // them (2H/8 bytes each) within 2 MiB, half of an XCD's L2.  Longer runs are rewarded
-        // by the memory system when the routing is even (32 rows per expert: 86 instead of
-        // 88 us at the prefill shape) but lose more when a few experts are hot, because the
-        // workgroups of a long hot run then loop while the others idle; 8 to 16 rows are
-        // within 1 % of the best on every shape measured.  A workgroup
-        // copies nsub * kRunUnroll rows at a time, so a run of average length is shared by
-        // `splits` workgroups, one step each.
-        const int64_t l2_tokens = (2ll << 20) / max(2 * a.H / kSlices, 1);
-        const int want = (int)std::max<int64_t>(768, std::min<int64_t>(12ll * a.E, l2_tokens * a.K));
-        p.group = max(1, want / a.chunk_entries);
-        p.nblocks = (a.nwc + p.group - 1) / p.group;
-        p.units = units;
-        p.piece = (units + kSlices - 1) / kSlices;
-        p.tpr_shift = 4;
-        while ((1 << p.tpr_shift) < p.piece && p.tpr_shift < 8) ++p.tpr_shift;
-        const int rows_per_step = (256 >> p.tpr_shift) * kRunUnroll;
-        const int avg_run = (p.group * a.chunk_entries + a.E - 1) / a.E;
-        p.splits = max(1, (avg_run + rows_per_step - 1) / rows_per_step);
-        const bool warm = a.order == EP_ORDER_DESTINATION;
-        const int64_t block_entries = (int64_t)p.group * a.chunk_entries;
-        // blocks per launch: all of them, or as many as cover kWarmBytes of tokens
-        int per = p.nblocks;
-        if (warm) {
-            const int64_t block_bytes = (block_entries + a.K - 1) / a.K * a.H * 2;
-            per = (int)std::max<int64_t>(1, std::min<int64_t>(p.nblocks, kWarmBytes / std::max<int64_t>(block_bytes, 1)));
-        }
-        for (int b0 = 0; b0 < p.nblocks; b0 += per) {
-            const int nb = min(per, p.nblocks - b0);
-            const int t0 = (int)std::min<int64_t>(a.T, b0 * block_entries / a.K);
-            const int t1 = (int)std::min<int64_t>(a.T, ((b0 + nb) * block_entries + a.K - 1) / a.K);
-            if (warm && t1 > a.prefetched_rows) {  // unless the layout launch has read these rows already
+        p.group = d.group; p.nblocks = d.blocks; p.units = units; p.piece = d.piece; p.tpr_shift = d.tpr_shift;
+        p.splits = d.splits;
+        for (int b0 = 0; b0 < d.blocks; b0 += d.blocks_per_launch) {
+            const int nb = std::min(d.blocks_per_launch, d.blocks - b0);
+            const int t0 = (int)std::min<int64_t>(a.T, (int64_t)b0 * d.block_entries / a.K);
+            const int t1 = (int)std::min<int64_t>(a.T, ((int64_t)(b0 + nb) * d.block_entries + a.K - 1) / a.K);
+            // a read pass, unless the layout launch has read these rows already
+            if (a.order == EP_ORDER_DESTINATION && t1 > a.prefetched_rows)
                 hipLaunchKernelGGL(dispatch_warm_kernel, dim3(2048), dim3(256), 0, s, a, units, t0, t1, b0 == 0 ? 1 : 0);
-            }
             p.first_block = b0;
             switch (p.tpr_shift) {
                 case 4: launch_runs<4>(a, p, nb, s); break;

@@ -184,6 +184,21 @@ hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hip
 
 // Host-side planning helpers (pure functions, testable without a GPU).
 void plan_layout(int n, int* passes, int* nwc);
+
+// How launch_dispatch walks an input (see ep_dispatch.hip).
+struct DispatchPlan {
+    int run_order;          // 1: destination order; 0: token order (nothing else is set then)
+    int group;              // wave-chunks of the layout per block
+    int blocks;             // blocks of the input
+    int block_entries;      // routed entries per block
+    int splits;             // workgroups that share the run of one (block, expert)
+    int piece;              // 16-byte units of a row per XCD slice
+    int tpr_shift;          // log2(threads that share one row piece)
+    int blocks_per_launch;  // blocks per copy launch
+    int launches;           // copy launches
+    int read_passes;        // token read passes (at most one per copy launch)
+};
+bool plan_dispatch(int T, int K, int H, int E, int order, bool have_runs, int prefetched_rows, DispatchPlan* out);
 // True when launch_layout fills LayoutArgs::run_start for this plan.
 bool layout_writes_runs(const LayoutArgs& a);
 // True when launch_layout reads LayoutArgs::warm_x for this plan.

@@ -121,3 +121,44 @@ def test_layout_plan_covers_every_entry(ep):
             assert passes >= 2
     with pytest.raises(ep.EpError):
         ep.ep_layout_plan(-1)
+
+
+def test_dispatch_plan_covers_the_input_and_fits_the_launch_limits(ep):
+    """Host arithmetic of the destination-ordered dispatch: the blocks cover every wave-chunk of
+    the layout, the copy launches cover every block, a read pass is planned per launch unless the
+    rows were announced to the layout call, and small inputs or the token order plan nothing."""
+    import ctypes
+    shapes = [(32, 256, 7168, 8, 4096), (64, 256, 7168, 8, 8192), (16, 128, 4096, 8, 4096), (1, 1024, 7168, 16, 4096),
+              (8, 8, 64, 1, 9000), (4, 24, 1000, 3, 3000), (64, 1024, 8192, 64, 100000), (2, 2, 8, 2, 5000)]
+    for R, E, H, K, T in shapes:
+        for order in (ep.EP_ORDER_DESTINATION, ep.EP_ORDER_DESTINATION_RESIDENT):
+            cfg = ep.make_config(R, E, H, K, T, dispatch_order=order)
+            p = ep.ep_dispatch_plan(cfg, T)
+            passes, nwc = ep.ep_layout_plan(T * K)
+            if T * K < 8192 or H // 8 < 8:
+                assert p.run_order == 0 and p.blocks == 0
+                continue
+            assert p.run_order == 1
+            assert p.group >= 1 and p.blocks * p.group >= nwc > (p.blocks - 1) * p.group
+            assert p.block_entries == p.group * passes * 64
+            assert 1 <= p.splits and 8 * E * p.splits < 2 ** 31 and p.blocks <= 65535
+            assert p.slice_units * 8 >= H // 8 > (p.slice_units - 1) * 8
+            assert p.threads_per_piece in (16, 32, 64, 128, 256)
+            assert p.launches == -(-p.blocks // p.blocks_per_launch)
+            # one slice of a block's tokens stays within 2 MiB (half of an XCD's L2), or the block is
+            # a single wave-chunk, which cannot be cut
+            assert p.group == 1 or (p.block_entries // K) * (2 * H // 8) <= 2 << 20 or p.block_entries <= 768
+            if order == ep.EP_ORDER_DESTINATION:
+                assert p.read_passes == p.launches
+                tokens_per_launch = -(-p.blocks_per_launch * p.block_entries // K)
+                assert p.blocks_per_launch == 1 or tokens_per_launch * 2 * H <= (64 << 20) + 2 * H
+                # rows announced to the layout call (at most 64 MiB of them) need no read pass
+                first = min(T, (64 << 20) // (2 * H))
+                q = ep.ep_dispatch_plan(cfg, T, first)
+                assert q.read_passes == p.read_passes - (1 if first >= min(T, tokens_per_launch) else 0)
+            else:
+                assert p.read_passes == 0 and p.launches == 1
+        cfg = ep.make_config(R, E, H, K, T)
+        assert ep.ep_dispatch_plan(cfg, T).run_order == 0
+    with pytest.raises(ep.EpError):
+        ep.ep_dispatch_plan(ep.make_config(2, 8, 256, 2, 64), -1)
