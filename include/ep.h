@@ -287,8 +287,8 @@ EP_API ep_result_t ep_layout(ep_handle_t *handle, ep_group_t group, const ep_ten
  * kernels keep only a few compute units busy; for a group whose dispatch_order is
  * EP_ORDER_DESTINATION and an input of at least 8192 routed entries, the same launch
  * therefore also reads the tokens (the first 64 MiB of them) into the memory-side cache
- * on the idle units, and ep_dispatch, when it is given the same tensor (data pointer and
- * row stride), leaves out its own read pass over those rows.  In every other case the
+ * on the idle units, and the first ep_dispatch of the handle, when it is given the same
+ * tensor (data pointer and row stride), leaves out its own read pass over those rows.  In every other case the
  * hint is ignored.  The handle, its arrays and all results are those of ep_layout.
  */
 EP_API ep_result_t ep_layout_prefetch(ep_handle_t *handle, ep_group_t group, const ep_tensor_t *topk_idx,

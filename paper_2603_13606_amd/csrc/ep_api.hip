@@ -583,7 +583,10 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     a.run_start = h->has_runs ? h->slab.run_start : nullptr;
     a.nwc = h->nwc; a.chunk_entries = h->chunk_entries;
     a.order = c.dispatch_order;
+    // the read-ahead of the layout call is good for the dispatch that follows it, once
     a.prefetched_rows = (h->warm_x == x->data && h->warm_stride == x->stride[0]) ? h->warm_rows : 0;
+    h->warm_x = nullptr;
+    h->warm_rows = 0;
     h->last_stream = (hipStream_t)stream;
     int set = 0;
     if (send_only) {

@@ -31,22 +31,25 @@ def _signals(ep, g, spec, which):
     return ep.read_device_i32(info.signals[which], n).numpy()
 
 
-def _setup(ep, hx, oracle_mod, name, T, H, mode, path, sets=2, C=0):
+def _setup(ep, hx, oracle_mod, name, T, H, mode, path, sets=2, C=0, order=0):
     w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
     spec = w.spec
     ll = mode == "ll"
     Cc = (C if C else spec.T) if ll else 0
     lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, layout=int(ll), C=Cc, C_rank=spec.T)
     cfg = ep.make_config(spec.R, spec.E, spec.H, spec.K, spec.T, mode=ep.EP_MODE_LL if ll else ep.EP_MODE_HT,
-                         slots_per_subregion=C, dispatch_path=path, staged_buffers=sets, max_handles=3)
+                         slots_per_subregion=C, dispatch_path=path, staged_buffers=sets, max_handles=3,
+                         dispatch_order=order)
     g = ep.ep_group_create(cfg)
     rows = spec.E * Cc if ll else int(lay.expert_offset[-1])
     return w, spec, lay, g, rows, Cc
 
 
-@pytest.mark.parametrize("mode,C", [("ht", 0), ("ll", 20)])
-def test_staged_direct_dispatch_and_combine(ep, hx, oracle_mod, mode, C):
-    w, spec, lay, g, rows, Cc = _setup(ep, hx, oracle_mod, "ll_decode", 96, 1024, mode, ep.EP_PATH_DIRECT, C=C)
+@pytest.mark.parametrize("mode,C,T,order", [("ht", 0, 96, 0), ("ll", 20, 96, 0),
+                                             ("ht", 0, 1100, 1), ("ll", 300, 1100, 2)])  # destination-ordered send phase
+def test_staged_direct_dispatch_and_combine(ep, hx, oracle_mod, mode, C, T, order):
+    w, spec, lay, g, rows, Cc = _setup(ep, hx, oracle_mod, "ll_decode", T, 1024, mode, ep.EP_PATH_DIRECT, C=C,
+                                       order=order)
     ll = mode == "ll"
     try:
         topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
