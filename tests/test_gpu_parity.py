@@ -889,3 +889,60 @@ def test_random_shapes_end_to_end(ep, hx, oracle_mod):
             ep.ep_handle_destroy(h)
         finally:
             ep.ep_group_destroy(g)
+
+
+def test_random_large_shapes_destination_order(ep, hx, oracle_mod):
+    """Twenty-four seeded random configurations of at least 8192 routed entries (so that the
+    destination-ordered kernel runs), odd row sizes, expert counts and top-k included; every other
+    case announces its tokens to the layout call.  Layout and dispatched rows, side arrays and
+    counts against the oracle."""
+    rng = np.random.default_rng(777)
+    done = 0
+    case = 0
+    while done < 24:
+        case += 1
+        R = int(rng.choice([1, 2, 4, 8, 16, 32, 64]))
+        L = int(rng.choice([1, 2, 3, 4, 8]))
+        E = R * L
+        K = int(rng.integers(1, min(E, 9) + 1))
+        T = int(rng.choice([8192 // K + 1, 9001 // K + 3, 20000 // K, 3000, 4099]))
+        if T * K < 8192 or T * K > 70000:
+            continue
+        H = int(rng.choice([64, 72, 200, 512, 1000, 1536, 2048]))
+        ll = bool(rng.integers(0, 2))
+        C = int(rng.integers(max(1, (T * K) // (2 * E)), (3 * T * K) // (2 * E) + 2)) if ll else 0
+        order = int(rng.choice([1, 2]))
+        spec = wl.WorkloadSpec(f"randbig{case}", 140 + case, R=R, T=T, H=H, E=E, K=K,
+                               prior=str(rng.choice(["uniform", "zipf"])))
+        w = wl.make_workload(spec)
+        topk = _mess_up(w.topk_idx, E, seed=case, frac_masked=float(rng.choice([0.0, 0.03])),
+                        n_invalid=int(rng.integers(0, 2)))
+        _say(f"random large case {case}: E={E} R={R} K={K} T={T} H={H} ll={ll} C={C} order={order}")
+        lay = oracle_mod.layout(topk, E=E, R=R, layout=int(ll), C=C if ll else 0, C_rank=T)
+        rows = E * C if ll else int(lay.expert_offset[-1])
+        o_recv = np.full((rows + 1, H), hx.POISON, np.uint16)
+        o_w = np.full(rows + 1, np.float32(-3.5), np.float32)
+        o_src = np.full(rows + 1, -9, np.int32)
+        oracle_mod.dispatch(w.x_bits, w.topk_w, lay, o_recv, o_w, o_src)
+        g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C, dispatch_order=order)
+        try:
+            x = hx.bits_to_dev(w.x_bits)
+            d_topk = torch.from_numpy(topk).to(hx.DEV)
+            h = ep.ep_layout_prefetch(g, d_topk, x) if case % 2 else ep.ep_layout(g, d_topk)
+            got = hx.fetch_layout(h, T, K, E, R, ok=(ep.EP_SUCCESS, ep.EP_ERR_INVALID_ROUTING))
+            hx.assert_layout_equal(got, lay)
+            store = hx.poison_bf16((rows + 1, H))
+            recv = store[:rows].view(E, C, H) if ll else store[:rows]
+            r_w = torch.full((rows + 1,), -3.5, dtype=torch.float32, device=hx.DEV)
+            r_src = torch.full((rows + 1,), -9, dtype=torch.int32, device=hx.DEV)
+            r_cnt = torch.full((E,), -1, dtype=torch.int32, device=hx.DEV)
+            ep.ep_dispatch(h, x, recv, topk_weights=torch.from_numpy(w.topk_w).to(hx.DEV), recv_w=r_w[:rows],
+                           recv_src=r_src[:rows], recv_count=r_cnt)
+            torch.cuda.synchronize()
+            assert np.array_equal(hx.dev_to_bits(store), o_recv), f"case {case}: rows differ"
+            assert np.array_equal(r_w.cpu().numpy(), o_w) and np.array_equal(r_src.cpu().numpy(), o_src)
+            assert np.array_equal(r_cnt.cpu().numpy(), lay.expert_kept)
+            ep.ep_handle_destroy(h)
+        finally:
+            ep.ep_group_destroy(g)
+        done += 1
