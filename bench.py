@@ -204,6 +204,10 @@ def main() -> int:
     ap.add_argument("--dispatch-order", type=int, default=1, choices=(0, 1, 2),
                     help="EP_ORDER_TOKEN (0); EP_ORDER_DESTINATION with the tokens announced to the layout "
                          "call, ep_layout_prefetch (1, default); EP_ORDER_DESTINATION_RESIDENT (2)")
+    ap.add_argument("--mode", choices=("ht", "ll"), default="ht",
+                    help="window layout: ht = concatenated [rows, H] (default), ll = padded [E, C, H]")
+    ap.add_argument("--slots", type=int, default=0,
+                    help="C of the padded layout (default: twice the mean rows per expert, 2*T*K/E)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--event-every", type=int, default=4,
                     help="record the per-op HIP events on every n-th timed step only (four event "
@@ -233,7 +237,10 @@ def main() -> int:
     spec = w.spec
     T, K, H, E = spec.T, spec.K, spec.H, spec.E
     nsets = max(1, args.sets)
-    cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, max_handles=nsets + 2,  # no allocation later
+    ll = args.mode == "ll"
+    C = (args.slots or max(1, 2 * T * K // E)) if ll else 0
+    cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_LL if ll else ep.EP_MODE_HT, slots_per_subregion=C,
+                         max_handles=nsets + 2,  # no allocation later
                          dispatch_order=args.dispatch_order)
     group = ep.ep_group_create(cfg)
 
@@ -245,18 +252,19 @@ def main() -> int:
         x = hx.bits_to_dev(ws.x_bits)
         topk = torch.from_numpy(ws.topk_idx).to(hx.DEV)
         gate = torch.from_numpy(ws.topk_w).to(hx.DEV)
-        recv = torch.zeros((T * K, H), dtype=torch.bfloat16, device=hx.DEV)
+        recv = torch.zeros((E, C, H) if ll else (T * K, H), dtype=torch.bfloat16, device=hx.DEV)
         out = torch.zeros((T, H), dtype=torch.bfloat16, device=hx.DEV)
         # expert outputs for combine: stand-in experts applied once to the dispatched rows
         h = ep.ep_layout(group, topk)
         ep.ep_dispatch(h, x, recv)
         info = ep.ep_handle_query(h)
         counts = ep.read_device_i32(info.expert_count, E).numpy()
-        row_e = torch.from_numpy(np.repeat(np.arange(E), counts)).to(hx.DEV)
+        row_e = torch.from_numpy(np.repeat(np.arange(E), C if ll else counts)).to(hx.DEV)
         y = torch.empty_like(recv)
+        flat_in, flat_out = recv.view(-1, H), y.view(-1, H)
         step_rows = 8192
-        for r0 in range(0, T * K, step_rows):
-            y[r0:r0 + step_rows] = hx.expert_standin(recv[r0:r0 + step_rows], row_e[r0:r0 + step_rows], scale)
+        for r0 in range(0, flat_in.shape[0], step_rows):
+            flat_out[r0:r0 + step_rows] = hx.expert_standin(flat_in[r0:r0 + step_rows], row_e[r0:r0 + step_rows], scale)
         rows = int(info.rows_kept)
         ep.ep_handle_destroy(h)
         sets.append((x, topk, gate, recv, y, out, rows))
@@ -334,7 +342,8 @@ def main() -> int:
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{spec.name}: R={spec.R} T={T} H={H} E={E} K={K} bf16, concatenated layout, "
+        "config": {"workload": f"{spec.name}: R={spec.R} T={T} H={H} E={E} K={K} bf16, "
+                               f"{'padded layout [E, C=%d, H]' % C if ll else 'concatenated layout'}, "
                                f"direct dispatch {['EP_ORDER_TOKEN', 'EP_ORDER_DESTINATION + ep_layout_prefetch', 'EP_ORDER_DESTINATION_RESIDENT'][args.dispatch_order]}, "
                                f"gate logits N(0,1) prior={spec.prior}",
                    "rows": rows, "input_sets_rotated": nsets},
@@ -382,9 +391,9 @@ def main() -> int:
         del graphs
         for hh in live:
             destroy(hh)
-    if spec.T * spec.K >= 1024:
+    if spec.T * spec.K >= 1024 and not ll:
         line["once_per_rank"] = once_per_rank(ep, torch, np, spec, sets, stream_ptr)
-    if args.extras:
+    if args.extras and not ll:
         line["extras"] = extras(ep, hx, wl, torch, np, group, spec, sets[0], stream_ptr)
     ep.ep_group_destroy(group)
     if not args.no_cpu_baseline:

@@ -580,6 +580,7 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     a.totals = h->slab.totals;
     a.T = h->T; a.K = c.top_k; a.H = c.hidden; a.E = c.num_experts;
     a.sorted_token = h->slab.sorted_token; a.sorted_k = h->slab.sorted_k; a.sorted_row = h->slab.sorted_row;
+    a.own_prefix = h->slab.own_prefix;
     a.run_start = h->has_runs ? h->slab.run_start : nullptr;
     a.nwc = h->nwc; a.chunk_entries = h->chunk_entries;
     a.order = c.dispatch_order;

@@ -101,7 +101,9 @@ __global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunP
     const int c0 = blk * p.group, c1 = min(c0 + p.group, a.nwc);
     // wave-uniform: the run of expert e in block blk, as positions of the sorted entry list
     const int lo = __builtin_amdgcn_readfirstlane(max(a.run_start[(int64_t)c0 * a.E + e], 0));
-    const int hi = __builtin_amdgcn_readfirstlane(min(a.run_start[(int64_t)c1 * a.E + e], a.T * a.K));
+    int hi = __builtin_amdgcn_readfirstlane(min(a.run_start[(int64_t)c1 * a.E + e], a.T * a.K));
+    // padded windows keep the first C entries of an expert: the rest of its sorted range has no row
+    if (PADDED) hi = min(hi, __builtin_amdgcn_readfirstlane(a.own_prefix[e]) + a.win.C);
     if (lo >= hi) return;
     const int sub = threadIdx.x >> TPR_SHIFT, u = threadIdx.x & (tpr - 1);
     const int u0 = xs * p.piece, u1 = min(p.units, u0 + p.piece);

@@ -95,6 +95,7 @@ struct DispatchArgs {
     const int32_t* sorted_token;  // [n]
     const int32_t* sorted_k;      // [n]
     const int32_t* sorted_row;    // [n]
+    const int32_t* own_prefix;    // [E+1] first sorted position of each expert
     const int32_t* run_start;     // [nwc+1, E], or nullptr: the layout did not produce one
     int nwc;                      // wave-chunks of the layout
     int chunk_entries;            // entries per wave-chunk
