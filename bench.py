@@ -119,6 +119,55 @@ def once_per_rank(ep, torch, np, spec, sets, stream_ptr):
     return res
 
 
+def decode_shape(ep, hx, wl, torch, np, stream_ptr, steps: int = 200):
+    """The low-latency decode shape (R=32, T=128, H=7168, E=256, K=8) in the padded [E, C, H] window
+    layout: microseconds per call (HIP events on every 4th step) and per whole step (wall clock)."""
+    w = wl.make_workload("ll_decode")
+    spec = w.spec
+    T, K, H, E = spec.T, spec.K, spec.H, spec.E
+    C = T
+    g = ep.ep_group_create(ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_LL, slots_per_subregion=C, max_handles=4))
+    x = hx.bits_to_dev(w.x_bits)
+    topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
+    gate = torch.from_numpy(w.topk_w).to(hx.DEV)
+    recv = torch.zeros((E, C, H), dtype=torch.bfloat16, device=hx.DEV)
+    out = torch.zeros((T, H), dtype=torch.bfloat16, device=hx.DEV)
+    lay, dis, com = ep.PreparedLayout(g, topk), ep.prepare_dispatch(x, recv, topk_weights=gate), \
+        ep.prepare_combine(recv, out, topk_weights=gate)
+    destroy = ep.load().ep_handle_destroy
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        h = lay(stream_ptr)
+        if ev:
+            ev[1].record()
+        dis(h, stream_ptr)
+        if ev:
+            ev[2].record()
+        com(h, stream_ptr)
+        if ev:
+            ev[3].record()
+        destroy(h)
+
+    for _ in range(20):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps // 4)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(events[i // 4] if i % 4 == 0 else None)
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    us = lambda a, b: round(float(np.mean([e[a].elapsed_time(e[b]) for e in events])) * 1e3, 2)
+    ab = wl.algorithmic_bytes(spec, T * K)
+    res = {"workload": f"ll_decode: R={spec.R} T={T} H={H} E={E} K={K} bf16, padded layout [E, C={C}, H], token order",
+           "step_us": round(el / steps * 1e6, 2), "layout_us": us(0, 1), "dispatch_us": us(1, 2), "combine_us": us(2, 3),
+           "algorithmic_bytes": ab, "note": "launch and latency bound: 16.5 MB per call is 2 us at the HBM peak"}
+    ep.ep_group_destroy(g)
+    return res
+
+
 def extras(ep, hx, wl, torch, np, group, spec, first_set, stream_ptr, iters: int = 20):
     """Timings of the dispatch variants outside the headline step (HIP events, mean of iters)."""
     x, topk, gate, recv, y, out, rows = first_set
@@ -391,6 +440,8 @@ def main() -> int:
         del graphs
         for hh in live:
             destroy(hh)
+    if spec.name == "ht_prefill":
+        line["decode_shape"] = decode_shape(ep, hx, wl, torch, np, stream_ptr)
     if spec.T * spec.K >= 1024 and not ll:
         line["once_per_rank"] = once_per_rank(ep, torch, np, spec, sets, stream_ptr)
     if args.extras and not ll:
