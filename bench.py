@@ -72,6 +72,58 @@ def cpu_baseline(w, steps_budget_s: float = 12.0):
     }
 
 
+def cpu_baseline_all_cores(w, threads: int, budget_s: float = 4.0):
+    """The same oracle calls with the tokens cut into `threads` contiguous ranges, one Python thread
+    per range (the C loops release the interpreter lock): dispatch and combine of different tokens
+    touch different rows, the layout stays sequential.  Nothing in the oracle is changed for this."""
+    import dataclasses
+    from concurrent.futures import ThreadPoolExecutor
+
+    import numpy as np
+
+    import oracle
+    from paper_2603_13606_amd import workloads as wl
+
+    spec = w.spec
+    T, H = spec.T, spec.H
+    oracle.build()
+    lay = oracle.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=T)
+    rows = int(lay.expert_offset[-1])
+    recv = np.zeros((rows, H), np.uint16)
+    out = np.zeros((T, H), np.uint16)
+    cuts = [T * i // threads for i in range(threads + 1)]
+    parts = [(a, b) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+
+    def part(ab, lay):
+        a, b = ab
+        sub = dataclasses.replace(lay, T=b - a, dst_row=lay.dst_row[a:b])
+        oracle.dispatch(w.x_bits[a:b], w.topk_w[a:b], sub, recv)
+
+    def part2(ab, lay):
+        a, b = ab
+        sub = dataclasses.replace(lay, T=b - a, dst_row=lay.dst_row[a:b])
+        out[a:b] = oracle.combine(recv, w.topk_w[a:b], sub, H, acc="f64")
+
+    t_total, reps = 0.0, 0
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        while t_total < budget_s and reps < 40:
+            t0 = time.perf_counter()
+            lay = oracle.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=T)
+            list(pool.map(lambda ab: part(ab, lay), parts))
+            list(pool.map(lambda ab: part2(ab, lay), parts))
+            t_total += time.perf_counter() - t0
+            reps += 1
+    # the threaded result must be the sequential one
+    ref = oracle.combine(recv, w.topk_w, lay, H, acc="f64")
+    assert np.array_equal(out, ref)
+    ab = wl.algorithmic_bytes(spec, rows)
+    nbytes = ab["layout"] + ab["dispatch"] + ab["combine"]
+    return {"value": round(nbytes * reps / t_total / 1e9, 4), "unit": "GB/s", "cores": len(parts), "kind": "oracle",
+            "sample": f"{reps} full steps, dispatch and combine cut into {len(parts)} token ranges run by as many "
+                      f"threads, layout sequential; {t_total / reps * 1e3:.0f} ms each",
+            "ms_per_step": round(t_total / reps * 1e3, 2)}
+
+
 def _timed_us(torch, np, fn, iters: int = 20) -> float:
     for _ in range(3):
         fn()
@@ -449,6 +501,8 @@ def main() -> int:
     ep.ep_group_destroy(group)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
+        # box share of one GPU: 16 cores, whatever os.cpu_count() shows
+        line["cpu_baseline_all_cores"] = cpu_baseline_all_cores(w, threads=min(16, os.cpu_count() or 1))
     print(json.dumps(line))
     return 0
 
