@@ -64,9 +64,10 @@ __global__ __launch_bounds__(256) void dispatch_direct_kernel(DispatchArgs a, in
 // 4.9 TB/s), so large inputs are walked in the order of the destination rows instead of
 // the order of the tokens.  The layout's expert-sorted entry list is cut into runs: the
 // entries of one expert that come from one block of consecutive wave-chunks of the input
-// (the layout records where those start).  A workgroup copies one run; consecutive
-// workgroups take the experts of one block in order, so the copy sweeps over all expert
-// regions once per block and every region grows by a few adjacent rows each time.
+// (the layout records where those start).  A run is copied by `splits` workgroups, a few
+// rows each per step; consecutive workgroups take the runs of one block expert by expert,
+// so the copy sweeps over all expert regions once per block and every region grows by about
+// a dozen adjacent rows each time.
 //
 // A row is read once from HBM and up to K-1 more times from the L2 cache: the 16-byte
 // units of a row are split into kSlices equal pieces and workgroup index mod kSlices picks
@@ -92,8 +93,8 @@ __global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunP
         for (int e = threadIdx.x; e < a.E; e += blockDim.x) a.recv_count[e] = a.expert_kept[e];
     }
     constexpr int tpr = 1 << TPR_SHIFT, nsub = 256 >> TPR_SHIFT;
-    // grid = (kSlices * E, blocks): x runs fastest, so workgroups are handed out slice by
-    // slice, expert by expert, block by block
+    // grid = (kSlices * splits * E, blocks): x runs fastest, so workgroups are handed out
+    // slice by slice, then share by share of a run, expert by expert, block by block
     const int xs = blockIdx.x & (kSlices - 1);
     const int es = blockIdx.x / kSlices;
     const int e = es / p.splits, sp = es - e * p.splits;
