@@ -727,16 +727,18 @@ def test_fp8_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, wide):
 # ------------------------------------------------------------------------------ HIP graph capture
 
 
-def test_graph_capture_and_replay(ep, hx, oracle_mod):
+@pytest.mark.parametrize("T,order", [(96, 0), (1100, 1)])
+def test_graph_capture_and_replay(ep, hx, oracle_mod, T, order):
     """layout + dispatch + combine captured once into a HIP graph and replayed with new
     token data each time; every replay must equal the eager result and the oracle.  The
     library records no memset nodes (it never calls one) and allocates nothing while a
-    slab is free in the group's pool, so the three calls are capturable as they are."""
-    w = wl.make_workload("ll_decode", T=96, H=1024)
+    slab is free in the group's pool, so the three calls are capturable as they are.  The
+    second case captures the read-ahead layout call and the destination-ordered dispatch."""
+    w = wl.make_workload("ll_decode", T=T, H=1024)
     spec = w.spec
     lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=spec.T)
     rows = int(lay.expert_offset[-1])
-    g = _group(ep, spec, spec.T, ep.EP_MODE_HT, max_handles=2)
+    g = _group(ep, spec, spec.T, ep.EP_MODE_HT, max_handles=2, dispatch_order=order)
     try:
         topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
         gate = torch.from_numpy(w.topk_w).to(hx.DEV)
@@ -753,7 +755,7 @@ def test_graph_capture_and_replay(ep, hx, oracle_mod):
         ep.ep_handle_destroy(h0)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            h = ep.ep_layout(g, topk)
+            h = ep.ep_layout_prefetch(g, topk, x) if order else ep.ep_layout(g, topk)
             ep.ep_dispatch(h, x, recv, topk_weights=gate)
             ep.ep_combine(h, recv, out, topk_weights=gate)
         for it in range(4):
