@@ -311,6 +311,9 @@ def main() -> int:
     ap.add_argument("--slots", type=int, default=0,
                     help="C of the padded layout (default: twice the mean rows per expert, 2*T*K/E)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--step-only", action="store_true",
+                    help="leave out the add-on measurements (decode_shape, once_per_rank, CPU baselines): only the "
+                         "kernels of the headline step run, which is what the rocprofv3 summaries are taken with")
     ap.add_argument("--event-every", type=int, default=4,
                     help="record the per-op HIP events on every n-th timed step only (four event "
                          "records cost about 12 us of a step, so they are sampled)")
@@ -493,14 +496,14 @@ def main() -> int:
         del graphs
         for hh in live:
             destroy(hh)
-    if spec.name == "ht_prefill":
+    if spec.name == "ht_prefill" and not args.step_only:
         line["decode_shape"] = decode_shape(ep, hx, wl, torch, np, stream_ptr)
-    if spec.T * spec.K >= 1024 and not ll:
+    if spec.T * spec.K >= 1024 and not ll and not args.step_only:
         line["once_per_rank"] = once_per_rank(ep, torch, np, spec, sets, stream_ptr)
     if args.extras and not ll:
         line["extras"] = extras(ep, hx, wl, torch, np, group, spec, sets[0], stream_ptr)
     ep.ep_group_destroy(group)
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.step_only:
         line["cpu_baseline"] = cpu_baseline(w)
         # box share of one GPU: 16 cores, whatever os.cpu_count() shows
         line["cpu_baseline_all_cores"] = cpu_baseline_all_cores(w, threads=min(16, os.cpu_count() or 1))
