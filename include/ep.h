@@ -208,6 +208,11 @@ EP_API const char *ep_error_string(ep_result_t code);
 /* Library version, major*10000 + minor*100 + patch. */
 EP_API int32_t ep_version(void);
 
+/* Identifies the sources and compiler flags this library was built from (16 hex digits
+ * computed by the build script; "unknown" for a build that bypassed it).  Benchmarks print
+ * it so that a number can be tied to the code that produced it. */
+EP_API const char *ep_build_id(void);
+
 /*
  * Diagnostic: how ep_layout would cut `num_entries` = T*K routing entries into wave-chunks
  * (64 * passes consecutive entries per wavefront).  Host-only, no GPU needed.

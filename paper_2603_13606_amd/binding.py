@@ -46,7 +46,7 @@ EP_TAG_EXPERT_BASE = 9
 STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW, STATUS_TIMEOUT = 1, 2, 4, 8
 
 EXPORTS = [
-    "ep_error_string", "ep_version", "ep_layout_plan", "ep_dispatch_plan", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
+    "ep_error_string", "ep_version", "ep_build_id", "ep_layout_plan", "ep_dispatch_plan", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
     "ep_layout", "ep_layout_prefetch", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
     "ep_dispatch", "ep_combine", "ep_complete", "ep_group_reset_signals",
 ]
@@ -129,6 +129,8 @@ def load() -> ctypes.CDLL:
         lib.ep_error_string.argtypes = [ctypes.c_int]
         lib.ep_version.restype = i32
         lib.ep_version.argtypes = []
+        lib.ep_build_id.restype = ctypes.c_char_p
+        lib.ep_build_id.argtypes = []
         lib.ep_group_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(ep_group_config_t), vp, vp, vp]
         lib.ep_group_destroy.argtypes = [vp, vp]
         lib.ep_group_query.argtypes = [vp, ctypes.POINTER(ep_group_info_t)]
@@ -147,7 +149,7 @@ def load() -> ctypes.CDLL:
         lib.ep_layout_plan.argtypes = [ctypes.c_int64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         lib.ep_dispatch_plan.argtypes = [ctypes.POINTER(ep_group_config_t), ctypes.c_int64, ctypes.c_int64,
                                          ctypes.POINTER(ep_dispatch_plan_t)]
-        for name in EXPORTS[2:]:
+        for name in EXPORTS[3:]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -162,6 +164,10 @@ ep_error_string = error_string
 
 def ep_version() -> int:
     return int(load().ep_version())
+
+
+def ep_build_id() -> str:
+    return load().ep_build_id().decode()
 
 
 def ep_dispatch_plan(cfg: "ep_group_config_t", num_tokens: int, prefetched_rows: int = 0) -> ep_dispatch_plan_t:

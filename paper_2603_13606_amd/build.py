@@ -21,9 +21,43 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
+HEADERS = [os.path.join(CSRC, "ep_internal.h"), os.path.join(ROOT, "include", "ep.h")]
+_ID_MARK = b"EP_BUILD_ID="
+
+
+def source_id() -> str:
+    """16 hex digits naming the sources and flags the library is built from."""
+    import hashlib
+    h = hashlib.sha256()
+    for path in [os.path.join(CSRC, s) for s in SOURCES] + HEADERS:
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+    h.update(" ".join(FLAGS[:-4]).encode())  # the include paths differ from tree to tree
+    return h.hexdigest()[:16]
+
+
+def built_id(lib: str = LIB):
+    """The source id a built library carries (read from the file, which is not loaded), or None."""
+    try:
+        with open(lib, "rb") as f:
+            data = f.read()
+    except OSError:
+        return None
+    at = data.find(_ID_MARK)
+    if at < 0:
+        return None
+    return data[at + len(_ID_MARK): at + len(_ID_MARK) + 16].decode("ascii", "replace")
+
+
+def is_current() -> bool:
+    """True when the library in the tree was built from the sources in the tree."""
+    return built_id() == source_id()
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, f'-DEP_BUILD_ID_STRING="{source_id()}"', "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")

@@ -216,6 +216,33 @@ bool window_from_tensor(const ep_group_s* g, const ep_tensor_t* t, WindowDesc* w
     return true;
 }
 
+// Checks every field of a group configuration (the rules ep.h states for ep_group_config_t).
+ep_result_t validate_config(const ep_group_config_t* cfg) {
+    if (!cfg || cfg->size != sizeof(ep_group_config_t)) return EP_ERR_INVALID_ARG;
+    const int R = cfg->num_ranks, E = cfg->num_experts, H = cfg->hidden, K = cfg->top_k;
+    if (R < 1 || cfg->my_rank < 0 || cfg->my_rank >= R) return EP_ERR_INVALID_ARG;
+    if (E < 1 || E > kMaxExperts || E % R != 0) return EP_ERR_INVALID_ARG;
+    if (H < 8 || (2 * (int64_t)H) % 16 != 0) return EP_ERR_INVALID_ARG;
+    if (K < 1 || K > kMaxTopK) return EP_ERR_INVALID_ARG;
+    if (cfg->max_tokens_per_rank < 1 || (int64_t)cfg->max_tokens_per_rank * K > (1 << 28)) return EP_ERR_INVALID_ARG;
+    if (cfg->dtype != EP_DTYPE_BF16) return EP_ERR_UNSUPPORTED;
+    if (cfg->mode != EP_MODE_LL && cfg->mode != EP_MODE_HT) return EP_ERR_INVALID_ARG;
+    if (cfg->dispatch_path != EP_PATH_DIRECT && cfg->dispatch_path != EP_PATH_RANK_DEDUP) return EP_ERR_INVALID_ARG;
+    if (cfg->slots_per_subregion < 0 || cfg->max_handles < 0) return EP_ERR_INVALID_ARG;
+    if (cfg->staged_buffers < 0 || cfg->staged_buffers > 2) return EP_ERR_INVALID_ARG;
+    if (cfg->ranks_per_node < 0) return EP_ERR_INVALID_ARG;
+    if (cfg->dispatch_order < EP_ORDER_TOKEN || cfg->dispatch_order > EP_ORDER_DESTINATION_RESIDENT) return EP_ERR_INVALID_ARG;
+    const int C = cfg->slots_per_subregion ? cfg->slots_per_subregion : cfg->max_tokens_per_rank;
+    if (cfg->mode == EP_MODE_LL && (int64_t)E * C > 0x7fffffffLL) return EP_ERR_INVALID_ARG;
+    return EP_SUCCESS;
+}
+
+int log2_exact(int v) {  // log2(v) when v is a power of two, else -1
+    for (int b = 0; b < 31; ++b)
+        if ((1 << b) == v) return b;
+    return -1;
+}
+
 ep_result_t sync_and_read_totals(ep_handle_s* h, int32_t* tot) {
     if (hipStreamSynchronize(h->last_stream) != hipSuccess) return EP_ERR_HIP;
     if (hipMemcpy(tot, h->slab.totals, sizeof(int32_t) * kTotalsWords, hipMemcpyDeviceToHost) != hipSuccess)
@@ -242,7 +269,14 @@ const char* ep_error_string(ep_result_t code) {
     return "unknown error code";
 }
 
-int32_t ep_version(void) { return 100; }
+int32_t ep_version(void) { return 200; }
+
+#ifndef EP_BUILD_ID_STRING
+#define EP_BUILD_ID_STRING "unknown"
+#endif
+// the marker lets build tooling read the id from the file without loading it
+static const char kBuildId[] = "EP_BUILD_ID=" EP_BUILD_ID_STRING;
+const char* ep_build_id(void) { return kBuildId + sizeof("EP_BUILD_ID=") - 1; }
 
 ep_result_t ep_layout_plan(int64_t num_entries, int32_t* passes, int32_t* wave_chunks) {
     if (!passes || !wave_chunks || num_entries < 0 || num_entries > (1 << 28)) return EP_ERR_INVALID_ARG;
@@ -278,35 +312,19 @@ ep_result_t ep_calibration_copy(void* dst, const void* src, size_t bytes, ep_str
 
 ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_stream_t stream,
                             ep_alloc_fn alloc_fn, ep_free_fn free_fn) {
-    if (!group || !cfg || cfg->size != sizeof(ep_group_config_t)) return EP_ERR_INVALID_ARG;
+    if (!group || !cfg) return EP_ERR_INVALID_ARG;
     if ((alloc_fn == nullptr) != (free_fn == nullptr)) return EP_ERR_INVALID_ARG;
+    if (ep_result_t v = validate_config(cfg); v != EP_SUCCESS) return v;
     const int R = cfg->num_ranks, E = cfg->num_experts, H = cfg->hidden, K = cfg->top_k;
-    if (R < 1 || cfg->my_rank < 0 || cfg->my_rank >= R) return EP_ERR_INVALID_ARG;
-    if (E < 1 || E > kMaxExperts || E % R != 0) return EP_ERR_INVALID_ARG;
-    if (H < 8 || (2 * (int64_t)H) % 16 != 0) return EP_ERR_INVALID_ARG;
-    if (K < 1 || K > kMaxTopK) return EP_ERR_INVALID_ARG;
-    if (cfg->max_tokens_per_rank < 1 || (int64_t)cfg->max_tokens_per_rank * K > (1 << 28)) return EP_ERR_INVALID_ARG;
-    if (cfg->dtype != EP_DTYPE_BF16) return EP_ERR_UNSUPPORTED;
-    if (cfg->mode != EP_MODE_LL && cfg->mode != EP_MODE_HT) return EP_ERR_INVALID_ARG;
-    if (cfg->dispatch_path != EP_PATH_DIRECT && cfg->dispatch_path != EP_PATH_RANK_DEDUP) return EP_ERR_INVALID_ARG;
-    if (cfg->slots_per_subregion < 0 || cfg->max_handles < 0) return EP_ERR_INVALID_ARG;
-    if (cfg->staged_buffers < 0 || cfg->staged_buffers > 2) return EP_ERR_INVALID_ARG;
-    if (cfg->ranks_per_node < 0) return EP_ERR_INVALID_ARG;
-    if (cfg->dispatch_order < EP_ORDER_TOKEN || cfg->dispatch_order > EP_ORDER_DESTINATION_RESIDENT) return EP_ERR_INVALID_ARG;
     const int C = cfg->slots_per_subregion ? cfg->slots_per_subregion : cfg->max_tokens_per_rank;
-    if (cfg->mode == EP_MODE_LL && (int64_t)E * C > 0x7fffffffLL) return EP_ERR_INVALID_ARG;
 
     ep_group_s* g = new (std::nothrow) ep_group_s();
     if (!g) return EP_ERR_NOMEM;
     g->cfg = *cfg;
     g->C = C;
     g->L = E / R;
-    g->L_shift = -1;
-    g->K_shift = -1;
-    for (int b = 0; b < 31; ++b) {
-        if ((1 << b) == g->L) g->L_shift = b;
-        if ((1 << b) == K) g->K_shift = b;
-    }
+    g->L_shift = log2_exact(g->L);
+    g->K_shift = log2_exact(K);
     g->W = E + 2 + R;
     g->bits_e = bits_for(E);
     g->bits_r = bits_for(R);

@@ -15,13 +15,14 @@ from paper_2603_13606_amd import binding as ep
 from paper_2603_13606_amd import workloads as wl
 
 def ensure_built() -> None:
-    """Build the HIP library if no built one is in the tree (harness convenience; the
-    binding itself never builds and never falls back)."""
-    import os
-    if not os.path.exists(ep.LIB_PATH):
-        from paper_2603_13606_amd import build
+    """Build the HIP library unless the one in the tree was built from the sources in the
+    tree (harness convenience; the binding itself never builds and never falls back).  Must
+    run before the library is first loaded: a loaded library cannot be replaced."""
+    from paper_2603_13606_amd import build
+    if not build.is_current():
         build.build()
     ep.load()
+    assert ep.ep_build_id() == build.source_id(), "the loaded library does not match the sources"
 
 
 DEV = "cuda:0"

@@ -17,9 +17,8 @@ def _declared():
 
 @pytest.fixture(scope="module")
 def ep():
-    from paper_2603_13606_amd import binding
-    if not os.path.exists(binding.LIB_PATH):
-        from paper_2603_13606_amd import build
+    from paper_2603_13606_amd import binding, build
+    if not build.is_current():
         build.build()
     binding.load()
     return binding
@@ -46,7 +45,9 @@ def test_struct_sizes_match_header(ep):
 
 
 def test_error_strings_and_version(ep):
-    assert ep.ep_version() >= 100
+    from paper_2603_13606_amd import build
+    assert ep.ep_version() >= 200
+    assert ep.ep_build_id() == build.source_id() == build.built_id()
     seen = {ep.error_string(c) for c in range(9)}
     assert len(seen) == 9 and "success" in seen
 
