@@ -300,6 +300,53 @@ EP_API ep_result_t ep_layout_prefetch(ep_handle_t *handle, ep_group_t group, con
                                const ep_tensor_t *expert_base, const ep_tensor_t *tokens,
                                ep_stream_t stream);
 
+/* Output arrays of ep_layout_static: DEVICE pointers to int32 arrays the caller owns.
+ * `size` must be sizeof(ep_layout_arrays_t).  Meanings as in ep_layout_info_t. */
+typedef struct {
+    uint32_t size;
+    uint32_t reserved;
+    int32_t *totals;           /* [16] required: rows_kept, rows_dropped, entries_masked,
+                                  entries_invalid, entries_sorted, rank_messages, status,
+                                  rows_end, then 8 unused words                            */
+    int32_t *expert_count;     /* [E]   required                                           */
+    int32_t *expert_kept;      /* [E]   required                                           */
+    int32_t *expert_offset;    /* [E+1] required                                           */
+    int32_t *rank_pair_count;  /* [R]   required                                           */
+    int32_t *rank_token_count; /* [R]   required                                           */
+    int32_t *rank_offset;      /* [R+1] required                                           */
+    int32_t *dst_row;          /* [T,K] required when T > 0                                */
+    int32_t *slot;             /* [T,K] optional (NULL = not wanted)                       */
+    int32_t *rank_row;         /* [T,K] optional                                           */
+    int32_t *entry_rank;       /* [T,K] optional                                           */
+    int32_t *sorted_token;     /* [T*K] optional; the three sorted arrays come together    */
+    int32_t *sorted_k;         /* [T*K]                                                    */
+    int32_t *sorted_row;       /* [T*K]                                                    */
+} ep_layout_arrays_t;
+
+/*
+ * ep_layout_static -- ep_layout for callers that cannot allocate: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  It creates no group and
+ * no handle and calls no allocating routine, on the host or on the device: the
+ * configuration comes in as the plain struct (validated like ep_group_create does; only
+ * num_ranks, num_experts, top_k, max_tokens_per_rank, mode and slots_per_subregion matter
+ * here), the results go to arrays the caller passes in `out`, and the kernels' own working
+ * memory -- the per-chunk histograms ep_layout keeps in its handle -- is a fixed array of
+ * 2.1 MB inside the library image, one copy per GPU, held until the process ends.  That array
+ * is sized for the limits of ep_group_create (1024 experts, hence histograms of at most
+ * 2050 bins, 256 chunks, 2^28 entries); a configuration beyond them is refused with
+ * EP_ERR_INVALID_ARG.
+ * Same kernels, same results as ep_layout, array for array (ep_handle_query of an ep_layout
+ * handle is what `out` is compared with).  All calls on one GPU share the one scratch
+ * array: calls that may overlap in time on one GPU (different streams, or different
+ * threads) race and must be serialised by the caller; calls on one stream are safe.  Every
+ * launch overwrites what it reads from the scratch, so nothing is kept between calls.
+ * topk_idx and expert_base as for ep_layout.  Errors: EP_ERR_INVALID_ARG,
+ * EP_ERR_UNSUPPORTED, EP_ERR_HIP.
+ */
+EP_API ep_result_t ep_layout_static(const ep_group_config_t *cfg, const ep_tensor_t *topk_idx,
+                                    const ep_tensor_t *expert_base, const ep_layout_arrays_t *out,
+                                    ep_stream_t stream);
+
 /* Synchronises the handle's last stream and fills `info`.  Returns
  * EP_ERR_INVALID_ROUTING if bad expert ids were seen and EP_ERR_OVERFLOW if a
  * dispatch ran out of output rows (info is filled in both cases); capacity drops

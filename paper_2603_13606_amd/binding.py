@@ -47,7 +47,7 @@ STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW, STATUS_TIMEOUT
 
 EXPORTS = [
     "ep_error_string", "ep_version", "ep_build_id", "ep_layout_plan", "ep_dispatch_plan", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
-    "ep_layout", "ep_layout_prefetch", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
+    "ep_layout", "ep_layout_prefetch", "ep_layout_static", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
     "ep_dispatch", "ep_combine", "ep_complete", "ep_group_reset_signals",
 ]
 
@@ -103,6 +103,14 @@ class ep_layout_info_t(ctypes.Structure):
         (n, ctypes.c_void_p) for n in _INFO_PTRS]
 
 
+_ARRAY_PTRS = ("totals", "expert_count", "expert_kept", "expert_offset", "rank_pair_count", "rank_token_count",
+               "rank_offset", "dst_row", "slot", "rank_row", "entry_rank", "sorted_token", "sorted_k", "sorted_row")
+
+
+class ep_layout_arrays_t(ctypes.Structure):
+    _fields_ = [("size", ctypes.c_uint32), ("reserved", ctypes.c_uint32)] + [(n, ctypes.c_void_p) for n in _ARRAY_PTRS]
+
+
 ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t)
 FREE_FN = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.c_void_p)
 
@@ -138,6 +146,8 @@ def load() -> ctypes.CDLL:
                                   ctypes.POINTER(ep_tensor_t), vp]
         lib.ep_layout_prefetch.argtypes = [ctypes.POINTER(vp), vp, ctypes.POINTER(ep_tensor_t),
                                            ctypes.POINTER(ep_tensor_t), ctypes.POINTER(ep_tensor_t), vp]
+        lib.ep_layout_static.argtypes = [ctypes.POINTER(ep_group_config_t), ctypes.POINTER(ep_tensor_t),
+                                         ctypes.POINTER(ep_tensor_t), ctypes.POINTER(ep_layout_arrays_t), vp]
         lib.ep_handle_query.argtypes = [vp, ctypes.POINTER(ep_layout_info_t)]
         lib.ep_handle_get_num_recv_tokens.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
         lib.ep_handle_destroy.argtypes = [vp]
@@ -276,6 +286,20 @@ def ep_layout_prefetch(group, topk_idx: torch.Tensor, tokens: torch.Tensor,
     _check(load().ep_layout_prefetch(ctypes.byref(h), group, ctypes.byref(td), bd, ctypes.byref(xd),
                                      _stream_ptr(stream)), "ep_layout_prefetch")
     return h
+
+
+def ep_layout_static(cfg: ep_group_config_t, topk_idx: torch.Tensor, arrays: dict,
+                     expert_base: Optional[torch.Tensor] = None, stream=None) -> None:
+    """ep_layout into int32 tensors of the caller (`arrays`: field name of ep_layout_arrays_t -> tensor)."""
+    out = ep_layout_arrays_t()
+    out.size = ctypes.sizeof(ep_layout_arrays_t)
+    for name, t in arrays.items():
+        assert name in _ARRAY_PTRS and t.dtype == torch.int32 and t.is_contiguous()
+        setattr(out, name, t.data_ptr())
+    td = tensor_desc(topk_idx, EP_TAG_TOPK_IDX)
+    bd = ctypes.byref(tensor_desc(expert_base, EP_TAG_EXPERT_BASE)) if expert_base is not None else None
+    _check(load().ep_layout_static(ctypes.byref(cfg), ctypes.byref(td), bd, ctypes.byref(out), _stream_ptr(stream)),
+           "ep_layout_static")
 
 
 def ep_handle_query(handle, ok: Sequence[int] = (EP_SUCCESS,)) -> ep_layout_info_t:

@@ -250,6 +250,35 @@ ep_result_t sync_and_read_totals(ep_handle_s* h, int32_t* tot) {
     return EP_SUCCESS;
 }
 
+
+// ---- scratch of ep_layout_static: one array per GPU, part of the library image, so the
+// entry point never allocates.  It holds what ep_layout keeps in the handle's slab beyond
+// the arrays a caller asks for: the chunk histograms and the per-expert positions in the
+// expert-sorted entry list.
+constexpr int64_t kStaticHistInts = (int64_t)kMaxWaveChunks * (2 * kMaxExperts + 2);
+constexpr int64_t kStaticScratchInts = kStaticHistInts + kMaxExperts + 1 + kSlabAlign;
+static __device__ __align__(256) int32_t scratch[kStaticScratchInts];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+int32_t* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU, once known
+
+// Device address of this GPU's copy of the scratch array (the array's name is only a
+// host-side stand-in for it).
+ep_result_t static_scratch(int32_t** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return EP_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return EP_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return EP_ERR_HIP;
+        g_scratch_ptr[dev] = (int32_t*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return EP_SUCCESS;
+}
+
 }  // namespace
 
 extern "C" {
@@ -766,6 +795,58 @@ ep_result_t ep_combine(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inp
     h->pending_combine.win.base = g->comb_stage[set];
     h->pending_combine.staged = 1;
     return EP_SUCCESS;
+}
+
+ep_result_t ep_layout_static(const ep_group_config_t* cfg, const ep_tensor_t* topk_idx, const ep_tensor_t* expert_base,
+                             const ep_layout_arrays_t* out, ep_stream_t stream) {
+    if (!topk_idx || !out || out->size != sizeof(ep_layout_arrays_t)) return EP_ERR_INVALID_ARG;
+    if (ep_result_t v = validate_config(cfg); v != EP_SUCCESS) return v;
+    const ep_group_config_t& c = *cfg;
+    if (topk_idx->tag != EP_TAG_TOPK_IDX || topk_idx->ndim != 2 || topk_idx->dtype != EP_DTYPE_I32)
+        return EP_ERR_INVALID_ARG;
+    const int64_t T = topk_idx->shape[0];
+    if (T < 0 || T > c.max_tokens_per_rank) return EP_ERR_INVALID_ARG;
+    if (!check_2d(topk_idx, EP_DTYPE_I32, T, c.top_k, true)) return EP_ERR_INVALID_ARG;
+    if (expert_base) {
+        if (c.mode != EP_MODE_HT) return EP_ERR_INVALID_ARG;
+        if (expert_base->tag != EP_TAG_EXPERT_BASE || !check_1d(expert_base, EP_DTYPE_I32, c.num_experts) ||
+            !expert_base->data)
+            return EP_ERR_INVALID_ARG;
+    }
+    if (!out->totals || !out->expert_count || !out->expert_kept || !out->expert_offset || !out->rank_pair_count ||
+        !out->rank_token_count || !out->rank_offset)
+        return EP_ERR_INVALID_ARG;
+    if (T > 0 && !out->dst_row) return EP_ERR_INVALID_ARG;
+    // the expert-sorted list is three arrays: all of them or none
+    const int nsorted = (out->sorted_token != nullptr) + (out->sorted_k != nullptr) + (out->sorted_row != nullptr);
+    if (nsorted != 0 && nsorted != 3) return EP_ERR_INVALID_ARG;
+    LayoutArgs a;
+    a.E = c.num_experts; a.R = c.num_ranks; a.K = c.top_k; a.T = (int)T;
+    a.W = a.E + 2 + a.R;
+    // the limit of the scratch array: at most kMaxWaveChunks histograms of W bins
+    if ((int64_t)kMaxWaveChunks * a.W > kStaticHistInts) return EP_ERR_INVALID_ARG;
+    int32_t* sc = nullptr;
+    if (ep_result_t r = static_scratch(&sc); r != EP_SUCCESS) return r;
+    a.topk = (const int32_t*)topk_idx->data;
+    a.topk_stride = topk_idx->stride[0];
+    a.expert_base = expert_base ? (const int32_t*)expert_base->data : nullptr;
+    a.L = a.E / a.R; a.L_shift = log2_exact(a.L); a.K_shift = log2_exact(a.K);
+    a.padded = c.mode == EP_MODE_LL;
+    a.C = c.slots_per_subregion ? c.slots_per_subregion : c.max_tokens_per_rank;
+    a.C_rank = c.max_tokens_per_rank;
+    a.n = (int)(T * c.top_k);
+    plan_layout(a.n, &a.passes, &a.nwc);
+    a.bits_e = bits_for(a.E); a.bits_r = bits_for(a.R);
+    a.hist = sc;  // every launch overwrites the rows it reads: nothing has to start at zero
+    a.own_prefix = sc + round_up(kStaticHistInts, kSlabAlign);
+    a.expert_count = out->expert_count; a.expert_kept = out->expert_kept; a.expert_offset = out->expert_offset;
+    a.rank_pair_count = out->rank_pair_count; a.rank_token_count = out->rank_token_count;
+    a.rank_offset = out->rank_offset; a.totals = out->totals;
+    a.slot = out->slot; a.dst_row = out->dst_row; a.rank_row = out->rank_row; a.entry_rank = out->entry_rank;
+    a.sorted_token = out->sorted_token; a.sorted_k = out->sorted_k; a.sorted_row = out->sorted_row;
+    a.run_start = nullptr;
+    a.warm_x = nullptr; a.warm_stride = 0; a.warm_rows = 0; a.warm_units = c.hidden / 8; a.nchunks = 1;
+    return launch_layout(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
 }
 
 }  // extern "C"
