@@ -330,16 +330,16 @@ typedef struct {
  * configuration comes in as the plain struct (validated like ep_group_create does; only
  * num_ranks, num_experts, top_k, max_tokens_per_rank, mode and slots_per_subregion matter
  * here), the results go to arrays the caller passes in `out`, and the kernels' own working
- * memory -- the per-chunk histograms ep_layout keeps in its handle -- is a fixed array of
+ * memory -- the per-chunk bin sums ep_layout keeps in its handle -- is a fixed array of
  * 2.1 MB inside the library image, one copy per GPU, held until the process ends.  That array
- * is sized for the limits of ep_group_create (1024 experts, hence histograms of at most
- * 2050 bins, 256 chunks, 2^28 entries); a configuration beyond them is refused with
+ * is sized for the limits of ep_group_create (1024 experts, hence at most 2050 bins,
+ * 256 chunks, 2^28 entries); a configuration beyond them is refused with
  * EP_ERR_INVALID_ARG.
  * Same kernels, same results as ep_layout, array for array (ep_handle_query of an ep_layout
  * handle is what `out` is compared with).  All calls on one GPU share the one scratch
  * array: calls that may overlap in time on one GPU (different streams, or different
- * threads) race and must be serialised by the caller; calls on one stream are safe.  Every
- * launch overwrites what it reads from the scratch, so nothing is kept between calls.
+ * threads) race and must be serialised by the caller; calls on one stream are safe.  The array
+ * is zero when the library is loaded and every launch leaves it ready for the next one.
  * topk_idx and expert_base as for ep_layout.  Errors: EP_ERR_INVALID_ARG,
  * EP_ERR_UNSUPPORTED, EP_ERR_HIP.
  */

@@ -19,7 +19,9 @@ struct Slab {
     int32_t* base = nullptr;
     // carved arrays
     int32_t *totals, *expert_count, *expert_kept, *expert_offset, *own_prefix;
-    int32_t *rank_pair_count, *rank_token_count, *rank_offset, *hist;
+    int32_t *rank_pair_count, *rank_token_count, *rank_offset;
+    uint32_t* pub;   // per-chunk bin sums of the layout kernel (kMaxChunks rows of W words)
+    uint32_t* ctl;   // its generation / arrival words; pub and ctl are zeroed when the slab is made
     int32_t *slot, *dst_row, *rank_row, *sorted_token, *sorted_k, *sorted_row, *entry_rank, *run_start;
     // receiving side of the once-per-rank path (only carved for EP_PATH_RANK_DEDUP)
     int32_t *recv_count, *recv_kept, *recv_dst_row;
@@ -124,7 +126,7 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
     const int64_t o_tot = carve(&cur, kTotalsWords), o_ec = carve(&cur, E), o_ek = carve(&cur, E);
     const int64_t o_eo = carve(&cur, E + 1), o_op = carve(&cur, E + 1), o_rp = carve(&cur, R);
     const int64_t o_rt = carve(&cur, R), o_ro = carve(&cur, R + 1);
-    const int64_t o_h = carve(&cur, (int64_t)kMaxWaveChunks * g->W);
+    const int64_t o_h = carve(&cur, (int64_t)kMaxChunks * g->W), o_ctl = carve(&cur, kLayoutCtlWords);
     const bool runs = g->cfg.dispatch_order != EP_ORDER_TOKEN && g->cfg.dispatch_path == EP_PATH_DIRECT;
     const int64_t o_rn = runs ? carve(&cur, (int64_t)(kMaxWaveChunks + 1) * E) : 0;
     const int64_t o_sl = carve(&cur, nB), o_dr = carve(&cur, nB), o_rr = carve(&cur, nB);
@@ -138,7 +140,7 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
         s->totals = base + o_tot; s->expert_count = base + o_ec; s->expert_kept = base + o_ek;
         s->expert_offset = base + o_eo; s->own_prefix = base + o_op; s->rank_pair_count = base + o_rp;
         s->rank_token_count = base + o_rt; s->rank_offset = base + o_ro;
-        s->hist = base + o_h; s->slot = base + o_sl; s->dst_row = base + o_dr; s->rank_row = base + o_rr;
+        s->pub = (uint32_t*)(base + o_h); s->ctl = (uint32_t*)(base + o_ctl); s->slot = base + o_sl; s->dst_row = base + o_dr; s->rank_row = base + o_rr;
         s->sorted_token = base + o_st; s->sorted_k = base + o_sk; s->sorted_row = base + o_sr;
         s->entry_rank = base + o_er; s->run_start = runs ? base + o_rn : nullptr;
         s->recv_count = dedup ? base + o_vc : nullptr; s->recv_kept = dedup ? base + o_vk : nullptr;
@@ -148,11 +150,18 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
     return cur;
 }
 
-ep_result_t new_slab(ep_group_s* g, Slab* s) {
+// A new slab; the words through which the layout workgroups talk to each other must start
+// out zero (pub and ctl are adjacent), which a small fill kernel on `stream` sees to.
+ep_result_t new_slab(ep_group_s* g, Slab* s, hipStream_t stream) {
     void* p = nullptr;
     ep_result_t r = dev_alloc(g, &p, sizeof(int32_t) * (size_t)g->slab_ints);
     if (r != EP_SUCCESS) return r;
     carve_slab(g, s, (int32_t*)p);
+    const int64_t ints = (int32_t*)(s->ctl + kLayoutCtlWords) - (int32_t*)s->pub;
+    if (launch_clear_counts((int32_t*)s->pub, (int)ints, stream) != hipSuccess) {
+        dev_free(g, p);
+        return EP_ERR_HIP;
+    }
     return EP_SUCCESS;
 }
 
@@ -253,10 +262,11 @@ ep_result_t sync_and_read_totals(ep_handle_s* h, int32_t* tot) {
 
 // ---- scratch of ep_layout_static: one array per GPU, part of the library image, so the
 // entry point never allocates.  It holds what ep_layout keeps in the handle's slab beyond
-// the arrays a caller asks for: the chunk histograms and the per-expert positions in the
+// the arrays a caller asks for: the per-chunk bin sums through which the layout workgroups
+// talk to each other, their generation words, and the per-expert positions in the
 // expert-sorted entry list.
-constexpr int64_t kStaticHistInts = (int64_t)kMaxWaveChunks * (2 * kMaxExperts + 2);
-constexpr int64_t kStaticScratchInts = kStaticHistInts + kMaxExperts + 1 + kSlabAlign;
+constexpr int64_t kStaticPubInts = (int64_t)kMaxChunks * (2 * kMaxExperts + 2);
+constexpr int64_t kStaticScratchInts = kStaticPubInts + kSlabAlign + kMaxExperts + 1 + kSlabAlign;
 static __device__ __align__(256) int32_t scratch[kStaticScratchInts];
 
 constexpr int kMaxDevices = 64;
@@ -401,10 +411,12 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     const int nslabs = cfg->max_handles ? cfg->max_handles : 2;
     for (int i = 0; i < nslabs; ++i) {
         Slab s;
-        ep_result_t r = new_slab(g, &s);
+        ep_result_t r = new_slab(g, &s, (hipStream_t)stream);
         if (r != EP_SUCCESS) return fail(r);
         g->free_slabs.push_back(s);
     }
+    // the slabs were zeroed on `stream`; layouts may come on any stream
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return fail(EP_ERR_HIP);
     *group = g;
     return EP_SUCCESS;
 }
@@ -485,7 +497,7 @@ ep_result_t ep_layout_prefetch(ep_handle_t* handle, ep_group_t g, const ep_tenso
             h->slab = g->free_slabs.back();
             g->free_slabs.pop_back();
         } else {
-            ep_result_t r = new_slab(g, &h->slab);
+            ep_result_t r = new_slab(g, &h->slab, (hipStream_t)stream);
             if (r != EP_SUCCESS) { delete h; return r; }
         }
         g->live_handles += 1;
@@ -505,7 +517,7 @@ ep_result_t ep_layout_prefetch(ep_handle_t* handle, ep_group_t g, const ep_tenso
     plan_layout(a.n, &a.passes, &a.nwc);
     a.W = g->W; a.bits_e = g->bits_e; a.bits_r = g->bits_r;
     const Slab& s = h->slab;
-    a.hist = s.hist; a.expert_count = s.expert_count; a.expert_kept = s.expert_kept;
+    a.pub = s.pub; a.ctl = s.ctl; a.expert_count = s.expert_count; a.expert_kept = s.expert_kept;
     a.expert_offset = s.expert_offset; a.own_prefix = s.own_prefix; a.rank_pair_count = s.rank_pair_count;
     a.rank_token_count = s.rank_token_count; a.rank_offset = s.rank_offset; a.totals = s.totals;
     a.slot = s.slot; a.dst_row = s.dst_row; a.rank_row = s.rank_row; a.sorted_token = s.sorted_token;
@@ -823,8 +835,8 @@ ep_result_t ep_layout_static(const ep_group_config_t* cfg, const ep_tensor_t* to
     LayoutArgs a;
     a.E = c.num_experts; a.R = c.num_ranks; a.K = c.top_k; a.T = (int)T;
     a.W = a.E + 2 + a.R;
-    // the limit of the scratch array: at most kMaxWaveChunks histograms of W bins
-    if ((int64_t)kMaxWaveChunks * a.W > kStaticHistInts) return EP_ERR_INVALID_ARG;
+    // the limit of the scratch array: at most kMaxChunks rows of W bin sums
+    if ((int64_t)kMaxChunks * a.W > kStaticPubInts) return EP_ERR_INVALID_ARG;
     int32_t* sc = nullptr;
     if (ep_result_t r = static_scratch(&sc); r != EP_SUCCESS) return r;
     a.topk = (const int32_t*)topk_idx->data;
@@ -837,8 +849,11 @@ ep_result_t ep_layout_static(const ep_group_config_t* cfg, const ep_tensor_t* to
     a.n = (int)(T * c.top_k);
     plan_layout(a.n, &a.passes, &a.nwc);
     a.bits_e = bits_for(a.E); a.bits_r = bits_for(a.R);
-    a.hist = sc;  // every launch overwrites the rows it reads: nothing has to start at zero
-    a.own_prefix = sc + round_up(kStaticHistInts, kSlabAlign);
+    // the array is zero when the library is loaded, and every launch leaves the words through
+    // which its workgroups talk to each other ready for the next one
+    a.pub = (uint32_t*)sc;
+    a.ctl = (uint32_t*)(sc + kStaticPubInts);
+    a.own_prefix = sc + kStaticPubInts + kSlabAlign;
     a.expert_count = out->expert_count; a.expert_kept = out->expert_kept; a.expert_offset = out->expert_offset;
     a.rank_pair_count = out->rank_pair_count; a.rank_token_count = out->rank_token_count;
     a.rank_offset = out->rank_offset; a.totals = out->totals;

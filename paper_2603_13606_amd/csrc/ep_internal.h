@@ -12,11 +12,12 @@ namespace ep {
 constexpr int kWave = 64;            // CDNA wavefront width
 constexpr int kMaxExperts = 1024;
 constexpr int kMaxTopK = 64;
-constexpr int kMaxWaveChunks = 256;        // wave-chunks per layout, and rows of the chunk histogram scratch
-constexpr int kLayoutWavesPerBlock = 16;   // wavefronts of the single workgroup that lays out a small input
-constexpr int kLayoutWavesPerChunk = 8;    // wavefronts per workgroup (chunk) for larger inputs
+constexpr int kMaxWaveChunks = 512;        // wave-chunks per layout
+constexpr int kMaxChunks = 256;            // workgroups (chunks) per layout, and rows of the published bin sums
+constexpr int kLayoutWavesPerBlock = 16;   // wavefronts per workgroup (chunk); fewer when the bin tables are large
 constexpr int kLayoutOneBlockEntries = 4096;  // inputs up to this size are laid out by one workgroup
 constexpr int kTotalsWords = 16;
+constexpr int kLayoutCtlWords = 4;
 
 // indices into the device totals block
 enum { TOT_KEPT = 0, TOT_DROPPED, TOT_MASKED, TOT_INVALID, TOT_SORTED, TOT_MSGS, TOT_STATUS,
@@ -40,7 +41,9 @@ struct LayoutArgs {
     int nwc;                  // number of wave-chunks
     int W;                    // histogram width: E experts + masked + invalid + R ranks
     int bits_e, bits_r;       // key widths for the in-wave match
-    int32_t* hist;            // [chunks, W] scratch, chunks <= kMaxWaveChunks
+    uint32_t* pub;            // [kMaxChunks, W] scratch: per-chunk bin sums, each tagged with its launch
+    uint32_t* ctl;            // [kLayoutCtlWords] scratch: generation and arrival count (see ep_layout.hip);
+                              // pub and ctl start out zero and are kept consistent by the kernel itself
     int32_t* expert_count;    // [E]
     int32_t* expert_kept;     // [E]
     int32_t* expert_offset;   // [E+1]

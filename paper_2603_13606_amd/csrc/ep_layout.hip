@@ -11,17 +11,27 @@
 //
 // Larger inputs: the flattened entry list is cut into chunks, one per workgroup of up
 // to 16 wavefronts, and every chunk into wave-chunks of 64*passes consecutive entries,
-// one per wavefront.
-//   count kernel  (only when there is more than one chunk) each workgroup
-//                 histograms its chunk -- bins: E experts, masked, invalid, R
-//                 destination ranks -- with LDS integer atomics;
-//   slot kernel   one thread per bin adds up the histograms of the chunks before
-//                 this one (its prefix) and of all chunks (the totals, hence the
-//                 expert offsets); the workgroup histograms its own wave-chunks
-//                 to split the prefix per wave; every wave builds the offset
-//                 tables for itself and then walks its entries 64 at a time:
-//                 slot = prefix of the bin + number of lower lanes holding the
-//                 same key, found with one ballot per key bit.
+// one per wavefront.  ONE launch (Sec. IV-C "Token Count": the count runs next to the
+// send, not as a phase of its own):
+//   histogram   every wave histograms its wave-chunk -- bins: E experts, masked,
+//               invalid, R destination ranks -- with LDS integer atomics;
+//   publish     one thread per bin sums the wave histograms of the chunk and stores
+//               the sum, tagged with the number of this launch, to global memory;
+//   in-chunk    meanwhile every wave ranks its entries inside the chunk: prefix of the
+//   ranks       bin over the earlier waves + number of lower lanes holding the same
+//               key, found with one ballot per key bit;
+//   look across one thread per bin reads that bin's sums of ALL chunks (it waits, a
+//               bounded number of polls, until each carries this launch's tag): entries
+//               in earlier chunks (the prefix) and in all chunks (the totals, hence
+//               the expert offsets).  Only sums of counts cross between workgroups,
+//               so the result does not depend on which chunk is published first;
+//   scan        one exclusive scan of the totals over all bins by the whole workgroup;
+//   emit        slot = prefix of earlier chunks + in-chunk rank, the destination row
+//               and the expert-sorted entry list.
+// The chunks wait for each other, so all of them must be resident at the same time:
+// there are at most 256 of them (32 with the usual bin counts), no more than the part
+// has compute units, they are the lowest workgroup ids of the launch, and every
+// wait gives up after a fixed number of polls (status bit, never a hang).
 // The work is latency bound (a chain of dependent LDS and global round trips per
 // wave), so every phase issues all of its global loads before it waits for any of
 // them and the workgroup barriers order LDS traffic only.
@@ -30,14 +40,16 @@
 namespace ep {
 namespace {
 
-constexpr int PU = 4;  // passes whose loads are issued together
+constexpr int PU = 2;  // passes whose loads are issued together and whose entries stay in registers
 
-// Workgroup barrier that orders LDS traffic only: global loads issued before it stay
-// in flight across it (a full __syncthreads() would wait for them).
+// Workgroup barrier that orders LDS traffic only: the LDS operations of this wave have
+// completed when it arrives (s_waitcnt lgkmcnt(0)), and the compiler moves no memory access
+// across it, but global loads and stores issued before it stay in flight (a
+// __syncthreads(), or a workgroup-scope fence, would wait for them: a round trip to
+// memory at every barrier of a latency-bound kernel).  Global memory written by one wave
+// is never read by another wave of the workgroup in these kernels.
 __device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 __device__ __forceinline__ void wave_lds_fence() {
@@ -47,6 +59,40 @@ __device__ __forceinline__ void wave_lds_fence() {
 
 __device__ __forceinline__ int lane_id() {
     return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+
+// Data-parallel-primitive controls of the cross-lane moves below (CDNA ISA, DPP_CTRL).
+constexpr int kDppRowShr = 0x110;      // + n: lane i reads lane i-n of its row of 16
+constexpr int kDppWaveShr1 = 0x138;    // lane i reads lane i-1 of the wavefront
+constexpr int kDppRowBcast15 = 0x142;  // lane 15 of each row to every lane of the next row
+constexpr int kDppRowBcast31 = 0x143;  // lane 31 to every lane of rows 2 and 3
+
+// The value of the lane below; lane 0 gets `fill`.
+__device__ __forceinline__ int lane_below(int v, int fill) {
+    return __builtin_amdgcn_update_dpp(fill, v, kDppWaveShr1, 0xf, 0xf, false);
+}
+
+// Inclusive prefix sum over the 64 lanes: within rows of 16 by shifted adds, then the
+// row sums are carried into the rows above.  A lane whose source lies outside its row
+// (or whose row is masked out) adds 0.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, kDppRowShr + 1, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, kDppRowShr + 2, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, kDppRowShr + 4, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, kDppRowShr + 8, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, kDppRowBcast15, 0xa, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, kDppRowBcast31, 0xc, 0xf, false);
+    return v;
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ int wave_max(int v) {
+    for (int off = kWave / 2; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off, kWave));
+    return v;
 }
 
 // Lanes (among those with valid == true) that hold the same key as this lane.
@@ -78,40 +124,48 @@ struct Entry {
     bool lead;     // first k of its token that names destination rank d
 };
 
-// LDS carve-up shared by the kernels.
+// LDS carve-up shared by the kernels.  wh .. flag are contiguous (zeroed in one sweep).
 struct Lds {
-    int32_t *wh;     // [nw][W] per-wave histograms, later per-wave prefixes
-    int32_t *tot;    // [W] totals over the whole input
-    int32_t *pre;    // [W] entries of each bin in earlier chunks
-    int32_t *eoff, *opre, *roff;  // [E+1], [E+1], [R+1]
+    int32_t *wh;      // [nw+1][W] per-wave histograms, later "entries of the bin in the earlier waves of the
+                      //     chunk"; row nw stands in for the rows a smaller workgroup does not have, so that
+                      //     sweeps over kLayoutWavesPerBlock rows need no branch: it reads as 0 and is never used
+    int32_t *tot;     // [W] totals over the whole input
+    int32_t *S;       // [W] exclusive scan of tot over all bins.  S[e], e <= E, is the first position of expert
+                      //     e in the expert-sorted list (S[E] = routed entries), and its first row in the
+                      //     concatenated layout unless the caller gave the first rows; the rank bins are the
+                      //     last R bins: for compact staging windows rank_offset[d] = S[E+2+d] - S[E+2]
+    int32_t *before;  // [W] entries of each bin in earlier chunks
+    int32_t *wsum;    // [kLayoutWavesPerBlock] per-wave sums of the scan (0 for waves the workgroup does not have)
+    int32_t *flag;    // [1] set when a thread of the workgroup gave up waiting for another chunk
 };
 
 __device__ __forceinline__ Lds carve_lds(int32_t* base, const LayoutArgs& a, int nw) {
     Lds l;
     l.wh = base;
-    l.tot = l.wh + nw * a.W;
-    l.pre = l.tot + a.W;
-    l.eoff = l.pre + a.W;
-    l.opre = l.eoff + a.E + 1;
-    l.roff = l.opre + a.E + 1;
+    l.tot = l.wh + (nw + 1) * a.W;
+    l.S = l.tot + a.W;
+    l.before = l.S + a.W;
+    l.wsum = l.before + a.W;
+    l.flag = l.wsum + kLayoutWavesPerBlock;
     return l;
 }
 
-size_t lds_bytes(const LayoutArgs& a, int nw) {
-    return sizeof(int32_t) * ((size_t)nw * a.W + 2 * a.W + 2 * (a.E + 1) + (a.R + 1));
-}
+constexpr int lds_ints(int W, int nw) { return (nw + 1) * W + 3 * W + kLayoutWavesPerBlock + 1; }
+
+size_t lds_bytes(const LayoutArgs& a, int nw) { return sizeof(int32_t) * (size_t)lds_ints(a.W, nw); }
 
 // Marks the entries that are the first of their token to name their destination
 // rank.  The entries of a token sit in consecutive lanes, so lane l compares its
-// rank with the ranks held by lanes l-1 .. l-k (one cross-lane read each); only
+// rank with the ranks held by lanes l-1 .. l-k (one shift of the wave per step); only
 // when a token began before lane 0 are its earlier entries read from memory.
 // Must be called by all 64 lanes.
 __device__ __forceinline__ void mark_leaders(const LayoutArgs& a, Entry& en, int lane) {
     const int dkey = en.ok ? en.d : -1;
     bool lead = en.ok;
+    int prev = dkey;
     for (int j = 1; j < a.K; ++j) {
-        const int prev = __shfl_up(dkey, j, kWave);
-        if (j <= en.k && j <= lane && prev == dkey) lead = false;
+        prev = lane_below(prev, -2);  // the key of lane l-j; -2 (no key) below lane 0
+        if (j <= en.k && prev == dkey) lead = false;
     }
     if (en.ok && en.k > lane) {  // entries of this token that precede lane 0 of this pass
         const int32_t* row = a.topk + (int64_t)en.t * a.topk_stride;
@@ -180,21 +234,36 @@ __device__ __forceinline__ void hist_group(const LayoutArgs& a, const Entry (&en
     }
 }
 
-// Writes what the layout records for one entry, given its slot among the entries of its
-// expert and (for a leader) its slot among the tokens of its destination rank.
+// First row of expert e in the receiver's tensor.
+__device__ __forceinline__ int first_row(const LayoutArgs& a, const Lds& l, int e) {
+    if (a.padded) return e * a.C;
+    return a.expert_base ? a.expert_base[e] : l.S[e];
+}
+
+// First staging slot of destination rank d (d == R: one past the last).
+__device__ __forceinline__ int first_slot(const LayoutArgs& a, const Lds& l, int d) {
+    if (a.padded) return d * a.C_rank;
+    const int end = d < a.R ? l.S[a.E + 2 + d] : l.S[a.W - 1] + l.tot[a.W - 1];
+    return end - l.S[a.E + 2];
+}
+
+// Writes what the layout records for one entry, given its rank inside the chunk among the
+// entries of its expert and (for a leader) among the tokens of its destination rank; the
+// entries of earlier chunks (l.before) turn the ranks into slots.
 __device__ __forceinline__ void emit_entry(const LayoutArgs& a, const Entry& x, int slot, int rslot, const Lds& l) {
     int row = -1, rrow = -1;
     if (x.ok) {
+        slot += l.before[x.e];
         if (a.padded) row = slot < a.C ? x.e * a.C + slot : -1;
-        else row = l.eoff[x.e] + slot;
+        else row = first_row(a, l, x.e) + slot;
         if (a.sorted_token) {
-            const int pos = l.opre[x.e] + slot;
+            const int pos = l.S[x.e] + slot;
             a.sorted_token[pos] = x.t;
             a.sorted_k[pos] = x.k;
             a.sorted_row[pos] = row;
         }
     }
-    if (x.lead) rrow = l.roff[x.d] + rslot;
+    if (x.lead) rrow = first_slot(a, l, x.d) + l.before[a.E + 2 + x.d] + rslot;
     if (x.i >= 0) {
         if (a.slot) a.slot[x.i] = slot;
         a.dst_row[x.i] = row;
@@ -203,203 +272,217 @@ __device__ __forceinline__ void emit_entry(const LayoutArgs& a, const Entry& x, 
     }
 }
 
-// Slot assignment for a loaded group: h holds, per bin, the number of entries of
-// that bin before the group; it is advanced as the group is walked.  LDS accesses
-// of one wavefront are performed in program order, and the wave barriers keep the
-// compiler from moving them across each other.  Must be called by all 64 lanes.
-__device__ __forceinline__ void slots_group(const LayoutArgs& a, const Entry (&en)[PU], int p0, int32_t* h,
-                                            const Lds& l, int lane) {
+// Where an entry stands among the entries of its wave that hold the same key, for the expert
+// key and (for a leader) the destination-rank key: entries below it and entries in all.
+struct InWave {
+    int below, all;      // among the lanes naming the same expert
+    int below_r, all_r;  // among the leader lanes naming the same destination rank
+};
+
+// The in-wave standing of a loaded group: ballots only, no memory.  Must be called by all
+// 64 lanes.
+__device__ __forceinline__ void rank_group(const LayoutArgs& a, const Entry (&en)[PU], int p0, int lane, InWave (&iw)[PU]) {
     const uint64_t lt = (1ull << lane) - 1ull;
 #pragma unroll
     for (int j = 0; j < PU; ++j) {
-        if (p0 + j >= a.passes) break;  // wave-uniform
+        iw[j] = InWave{0, 0, 0, 0};
+        if (p0 + j >= a.passes) continue;  // wave-uniform
+        const uint64_t peers = match_key(en[j].e, en[j].ok, a.bits_e);
+        const uint64_t peers_r = match_key(en[j].d, en[j].lead, a.bits_r);
+        iw[j] = InWave{(int)__popcll(peers & lt), (int)__popcll(peers), (int)__popcll(peers_r & lt), (int)__popcll(peers_r)};
+    }
+}
+
+// Ranks of a loaded group inside its chunk: h holds, per bin, the number of entries of that
+// bin in the earlier waves of the chunk and in the earlier groups of this wave; it is
+// advanced as the group is walked.  LDS accesses of one wavefront are performed in program
+// order, and the wave barriers keep the compiler from moving them across each other.
+// Must be called by all 64 lanes.
+__device__ __forceinline__ void place_group(const LayoutArgs& a, const Entry (&en)[PU], const InWave (&iw)[PU], int p0,
+                                            int32_t* h, int (&slot)[PU], int (&rslot)[PU]) {
+#pragma unroll
+    for (int j = 0; j < PU; ++j) {
+        slot[j] = -1;
+        rslot[j] = -1;
+        if (p0 + j >= a.passes) continue;  // wave-uniform
         const Entry& x = en[j];
-        const uint64_t peers = match_key(x.e, x.ok, a.bits_e);
-        const uint64_t peers_r = match_key(x.d, x.lead, a.bits_r);
-        const int rank = __popcll(peers & lt);
-        const int rank_r = __popcll(peers_r & lt);
-        const int slot = x.ok ? h[x.e] + rank : -1;
-        const int rslot = x.lead ? h[a.E + 2 + x.d] + rank_r : -1;
+        if (x.ok) slot[j] = h[x.e] + iw[j].below;
+        if (x.lead) rslot[j] = h[a.E + 2 + x.d] + iw[j].below_r;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
         __builtin_amdgcn_wave_barrier();
-        if (x.ok && rank == 0) h[x.e] += __popcll(peers);
-        if (x.lead && rank_r == 0) h[a.E + 2 + x.d] += __popcll(peers_r);
+        if (x.ok && iw[j].below == 0) h[x.e] += iw[j].all;
+        if (x.lead && iw[j].below_r == 0) h[a.E + 2 + x.d] += iw[j].all_r;
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
         __builtin_amdgcn_wave_barrier();
-        emit_entry(a, x, slot, rslot, l);
     }
 }
 
-__device__ __forceinline__ int wave_sum(int v) {
-    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
+__device__ __forceinline__ void emit_group(const LayoutArgs& a, const Entry (&en)[PU], int p0, const int (&slot)[PU],
+                                           const int (&rslot)[PU], const Lds& l) {
+#pragma unroll
+    for (int j = 0; j < PU; ++j)
+        if (p0 + j < a.passes) emit_entry(a, en[j], slot[j], rslot[j], l);  // wave-uniform condition
 }
 
-__device__ __forceinline__ int wave_max(int v) {
-    for (int off = kWave / 2; off > 0; off >>= 1) v = max(v, __shfl_xor(v, off, kWave));
-    return v;
-}
-
-// From the totals tot[0..W): the offset tables of the slot walk (eoff, opre, roff in
-// LDS).  Runs per WAVEFRONT without any workgroup barrier:
-// every wave computes the same values and stores them to the same LDS words, and
-// afterwards reads only words it has stored itself.  One exclusive scan S over all W
-// bins serves both prefix arrays: own_prefix[e] = S[e] and, for compact staging
-// windows, rank_offset[d] = S[E+2+d] - S[E+2].  Must be called by all 64 lanes,
-// after a barrier that makes tot[] final and pre[] free.
-__device__ void wave_offsets(const LayoutArgs& a, const Lds& l, int lane) {
-    const int32_t* tot = l.tot;
-    const int W = a.W, E = a.E, R = a.R;
-    const int ipt = (W + kWave - 1) / kWave;  // bins per lane, consecutive
-    const int start = lane * ipt;
-    constexpr int TV = 8;  // totals of up to TV own bins are kept in registers
-    int tv[TV];
+// Exclusive scan of the totals tot[0..W) over all bins into S, by the whole workgroup
+// (thread = bin; with more bins than threads, in rounds).  Starts with a barrier (tot and
+// whatever else was written to LDS before become visible) and ends with one (S is final).
+// Must be called by every thread of the workgroup.
+__device__ void block_scan_totals(const LayoutArgs& a, const Lds& l, int tid, int lane, int w, int nw) {
+    int carry = 0;
+    lds_barrier();
+    for (int c0 = 0; c0 < a.W; c0 += blockDim.x) {
+        const int c = c0 + tid;
+        const int v = c < a.W ? l.tot[c] : 0;
+        const int inc = wave_inclusive_scan(v);
+        if (lane == kWave - 1) l.wsum[w] = inc;
+        lds_barrier();
+        int below = 0, all = 0;
 #pragma unroll
-    for (int j = 0; j < TV; ++j) tv[j] = (j < ipt && start + j < W) ? tot[start + j] : 0;
-    int sum = 0;
-#pragma unroll
-    for (int j = 0; j < TV; ++j) sum += tv[j];
-    for (int j = TV; j < ipt; ++j)
-        if (start + j < W) sum += tot[start + j];
-    int inc = sum;
-    for (int off = 1; off < kWave; off <<= 1) {
-        const int v = __shfl_up(inc, off, kWave);
-        if (lane >= off) inc += v;
-    }
-    // S of the first rank bin is held by the lane that owns bin E+2
-    const int owner = (E + 2) / ipt, jb = (E + 2) - owner * ipt;
-    int my_rbase = inc - sum;
-#pragma unroll
-    for (int j = 0; j < TV; ++j)
-        if (j < jb) my_rbase += tv[j];
-    for (int j = TV; j < jb; ++j) my_rbase += tot[start + j];
-    const int rbase = __shfl(my_rbase, owner, kWave);
-    const int grand = __shfl(inc, kWave - 1, kWave);  // sum over all W bins
-    int run = inc - sum;
-    int32_t* S = l.pre;
-    auto emit = [&](int c, int v) {
-        S[c] = run;
-        if (c <= E) {  // bin E is "masked": S[E] = number of routed entries
-            l.opre[c] = run;
-            int eo;
-            if (a.padded) eo = c * a.C;
-            else if (a.expert_base) eo = c < E ? a.expert_base[c] : 0;  // eoff[E] is only reported
-            else eo = run;
-            l.eoff[c] = eo;
+        for (int r = 0; r < kLayoutWavesPerBlock; ++r) {  // waves the workgroup does not have left 0
+            const int s = l.wsum[r];
+            below += r < w ? s : 0;
+            all += s;
         }
-        if (c >= E + 2) l.roff[c - E - 2] = a.padded ? (c - E - 2) * a.C_rank : run - rbase;
-        run += v;
-    };
-#pragma unroll
-    for (int j = 0; j < TV; ++j)
-        if (j < ipt && start + j < W) emit(start + j, tv[j]);
-    for (int j = TV; j < ipt; ++j)
-        if (start + j < W) emit(start + j, tot[start + j]);
-    if (lane == 0) l.roff[R] = a.padded ? R * a.C_rank : grand - rbase;  // rank bins are the last R bins
-    wave_lds_fence();
+        if (c < a.W) l.S[c] = carry + below + inc - v;
+        carry += all;
+        lds_barrier();
+    }
 }
 
-// The per-expert / per-rank arrays and the totals block in global memory, from the
-// tables wave_offsets left in LDS.  One wavefront; must be called by all 64 lanes.
-__device__ void wave_write_tables(const LayoutArgs& a, const Lds& l, int lane) {
+// The per-expert / per-rank arrays and the totals block (all but the status word) in
+// global memory, from tot and S in LDS.  By every thread of one workgroup.
+__device__ void write_tables(const LayoutArgs& a, const Lds& l, int tid, int lane, int w) {
     const int32_t* tot = l.tot;
-    const int32_t* S = l.pre;
+    const int32_t* S = l.S;
     const int E = a.E, R = a.R;
-    const int total_e = S[E];
-    const int msgs = S[E + 1 + R] + tot[E + 1 + R] - S[E + 2];
+    for (int e = tid; e < E; e += blockDim.x) {
+        const int v = tot[e];
+        a.expert_count[e] = v;
+        a.expert_kept[e] = a.padded ? min(v, a.C) : v;
+        a.expert_offset[e] = first_row(a, l, e);
+        a.own_prefix[e] = S[e];
+        if (a.run_start) a.run_start[e] = S[e];  // row 0: nothing precedes the first wave-chunk
+    }
+    if (a.rank_pair_count) {
+        for (int d = tid; d <= R; d += blockDim.x) {
+            if (d < R) {
+                a.rank_pair_count[d] = S[(d + 1) * a.L] - S[d * a.L];
+                a.rank_token_count[d] = tot[E + 2 + d];
+            }
+            a.rank_offset[d] = first_slot(a, l, d);
+        }
+    }
+    if (w != 0) return;
+    // wave 0: the sums over all experts
     int kept = 0, dropped = 0, rend = 0;
     for (int e = lane; e < E; e += kWave) {
         const int v = tot[e];
         const int k = a.padded ? min(v, a.C) : v;
         kept += k;
         dropped += v - k;
-        if (!a.padded && a.expert_base && v > 0) rend = max(rend, l.eoff[e] + v);
-        a.expert_count[e] = v;
-        a.expert_kept[e] = k;
-        a.expert_offset[e] = l.eoff[e];
-        a.own_prefix[e] = l.opre[e];
-        if (a.run_start) a.run_start[e] = l.opre[e];  // row 0: nothing precedes the first wave-chunk
+        if (!a.padded && a.expert_base && v > 0) rend = max(rend, a.expert_base[e] + v);
     }
     kept = wave_sum(kept);
     dropped = wave_sum(dropped);
     rend = wave_max(rend);
-    const int rows_end = a.padded ? E * a.C : (a.expert_base ? rend : total_e);
-    if (a.rank_pair_count) {
-        for (int d = lane; d < R; d += kWave) {
-            a.rank_pair_count[d] = S[(d + 1) * a.L] - S[d * a.L];
-            a.rank_token_count[d] = tot[E + 2 + d];
-        }
-        for (int d = lane; d <= R; d += kWave) a.rank_offset[d] = l.roff[d];
-    }
     if (lane == 0) {
-        const int masked = tot[E], invalid = tot[E + 1];
+        const int total_e = S[E];
+        const int rows_end = a.padded ? E * a.C : (a.expert_base ? rend : total_e);
         a.expert_offset[E] = rows_end;
         a.own_prefix[E] = total_e;
         a.totals[TOT_KEPT] = kept;
         a.totals[TOT_DROPPED] = dropped;
-        a.totals[TOT_MASKED] = masked;
-        a.totals[TOT_INVALID] = invalid;
+        a.totals[TOT_MASKED] = tot[E];
+        a.totals[TOT_INVALID] = tot[E + 1];
         a.totals[TOT_SORTED] = total_e;
-        a.totals[TOT_MSGS] = msgs;
-        a.totals[TOT_STATUS] = (invalid ? STATUS_INVALID_IDS : 0) | (dropped ? STATUS_CAPACITY_DROP : 0);
+        a.totals[TOT_MSGS] = S[a.W - 1] + tot[a.W - 1] - S[E + 2];  // the rank bins are the last R bins
         a.totals[TOT_ROWS_END] = rows_end;
     }
 }
 
-// Extra workgroups of the slot kernel (blockIdx >= nchunks): read the token rows the caller
-// announced, with ordinary cached loads, while the layout workgroups -- a few dozen on a
-// part with 256 compute units -- do their latency-bound work.  wb of nwb.
-// Rows [r0, r1), 16 bytes per thread and step, the workgroups side by side.
-__device__ void warm_tokens(const LayoutArgs& a, int wb, int nwb, int r0, int r1) {
+// The status word of the totals block.  One wavefront; must be called by all 64 lanes.
+__device__ void write_status(const LayoutArgs& a, const Lds& l, int lane, int extra_status) {
+    int dropped = 0;
+    if (a.padded)
+        for (int e = lane; e < a.E; e += kWave) dropped |= l.tot[e] > a.C ? 1 : 0;
+    const bool any_dropped = __ballot(dropped != 0) != 0;
+    if (lane == 0)
+        a.totals[TOT_STATUS] = (l.tot[a.E + 1] ? STATUS_INVALID_IDS : 0) | (any_dropped ? STATUS_CAPACITY_DROP : 0) |
+                               extra_status;
+}
+
+// Extra workgroups of the layout kernel (blockIdx >= nchunks): read the token rows the
+// caller announced, with ordinary cached loads, while the layout workgroups -- a few dozen
+// on a part with 256 compute units -- do their latency-bound work.  wb of nwb.  Rows
+// [0, warm_rows), 16 bytes per load, four loads of a thread in flight.
+constexpr int kWarmUnroll = 4;
+__device__ void warm_tokens(const LayoutArgs& a, int wb, int nwb) {
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const int64_t total = (int64_t)(r1 - r0) * a.warm_units;
-    const int64_t stride = (int64_t)nwb * blockDim.x;
+    const uint32_t units = (uint32_t)a.warm_units;
+    const uint32_t total = (uint32_t)a.warm_rows * units;  // at most 64 MiB / 16
+    const uint32_t stride = (uint32_t)nwb * blockDim.x;
+    const bool dense = a.warm_stride == (int64_t)units * 8;  // rows back to back: no division
     uint32_t acc = 0;
-    for (int64_t i = (int64_t)wb * blockDim.x + threadIdx.x; i < total; i += stride) {
-        const int64_t t = r0 + i / a.warm_units;
-        const int col = (int)(i % a.warm_units);
-        const u32x4 v = *((const u32x4*)(a.warm_x + t * a.warm_stride) + col);
-        acc ^= v[0] ^ v[1] ^ v[2] ^ v[3];
-    }
-    if (acc == 0x9e3779b9u) a.totals[kTotalsWords - 1] = (int32_t)acc;  // keeps the loads; the word is unused
-}
-
-// Chunk b = wave-chunks [b*wpb, (b+1)*wpb).  Writes hist[b][0..W).
-__global__ __launch_bounds__(512) void layout_count_kernel(LayoutArgs a) {
-    extern __shared__ int32_t lds[];
-    const int wpb = blockDim.x >> 6;
-    const Lds l = carve_lds(lds, a, 1);
-    const int W = a.W;
-    const int tid = threadIdx.x;
-    const int lane = lane_id();
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wc = blockIdx.x * wpb + w;
-    const bool active = wc < a.nwc;
-    int raw[PU];
-    if (active) issue_group(a, wc, 0, lane, raw);  // in flight during the LDS set-up
-    for (int j = tid; j < W; j += blockDim.x) l.wh[j] = 0;
-    lds_barrier();
-    if (active) {
-        Entry en[PU];
-        for (int p0 = 0; p0 < a.passes; p0 += PU) {
-            if (p0 > 0) issue_group(a, wc, p0, lane, raw);
-            classify_group(a, wc, p0, lane, raw, en);
-            hist_group(a, en, l.wh);
+    for (uint32_t i0 = (uint32_t)wb * blockDim.x + threadIdx.x; i0 < total; i0 += kWarmUnroll * stride) {
+        u32x4 v[kWarmUnroll];
+#pragma unroll
+        for (int q = 0; q < kWarmUnroll; ++q) {
+            const uint32_t i = min(i0 + q * stride, total - 1);  // the tail repeats the last unit
+            if (dense) {
+                v[q] = *((const u32x4*)a.warm_x + i);
+            } else {
+                const uint32_t t = i / units;
+                v[q] = *((const u32x4*)(a.warm_x + (int64_t)t * a.warm_stride) + (i - t * units));
+            }
         }
+#pragma unroll
+        for (int q = 0; q < kWarmUnroll; ++q) acc ^= v[q][0] ^ v[q][1] ^ v[q][2] ^ v[q][3];
     }
-    lds_barrier();
-    int32_t* g = a.hist + (int64_t)blockIdx.x * W;
-    for (int j = tid; j < W; j += blockDim.x) g[j] = l.wh[j];
+    asm volatile("" ::"v"(acc));  // the loads are the point: keep them
 }
 
-// With one chunk (gridDim.x == 1) this kernel is the whole layout.  MAXT = largest
-// workgroup it is launched with; HB = chunk histograms whose words each thread loads
-// up front (thread = bin).
-template <int MAXT, int HB>
-__global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
+constexpr int kLookLimit = 1 << 19;  // rounds of polling after which a thread stops waiting (about a second)
+constexpr int HB = 32;               // chunks whose published words a thread loads in one batch (at most 32: bit masks)
+constexpr int kTagShift = 24;        // a published word is (tag << 24) | count: a chunk holds fewer than 2^24 entries
+constexpr uint32_t kCountMask = (1u << kTagShift) - 1u;
+constexpr uint32_t kTags = 255;      // tags 1 .. 255; 0 is what a cleared word holds
+
+// Loads the words chunks r0 .. r0+HB-1 have published for bin c.  Every lane loads from a
+// valid address (rows beyond the last chunk repeat it, their words are ignored later):
+// no branch, so all HB loads are in flight together.
+__device__ __forceinline__ void look_across(const LayoutArgs& a, int c, int r0, uint32_t (&v)[HB]) {
+    const int last = a.nchunks - 1;
+    const uint32_t* row = a.pub + (int64_t)min(r0, last) * a.W;  // wave-uniform: the row pointer steps in scalar registers
+#pragma unroll
+    for (int j = 0; j < HB; ++j) {
+        v[j] = __hip_atomic_load(row + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        row += r0 + j < last ? a.W : 0;
+    }
+}
+
+// Chunk b = wave-chunks [b*wpb, (b+1)*wpb); workgroups from nchunks on read tokens ahead.
+// With one chunk nothing is published or awaited.
+//
+// Cross-workgroup state (only with more than one chunk), all in a.pub / a.ctl:
+//   pub[r][c]  one word: (tag << 24) | entries of bin c in chunk r, tag = ctl[0] + 1 of the
+//              launch that wrote it; written once per launch with one atomic store, so a
+//              reader that sees the tag of its own launch also sees the count;
+//   ctl[0]     launches completed on this scratch since pub was last cleared (the
+//              generation, 0 .. 254); read at the start, advanced by the workgroup that is
+//              last to finish looking across, which clears pub when the tags run out;
+//   ctl[1]     workgroups of this launch that have finished looking across, in the low 16
+//              bits; a workgroup that gave up waiting also adds 1 << 16.  Back to 0 at the end.
+// Tags never repeat between two clearings of pub, and the scratch starts out all zero,
+// which no launch uses as a tag.
+//
+// MULTI: more than one chunk.  ONE_GROUP: a wave's entries fit one load group (at most PU
+// passes) and stay in registers from the histogram to the emit.
+template <bool MULTI, bool ONE_GROUP>
+__global__ __launch_bounds__(1024) void layout_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
     if ((int)blockIdx.x >= a.nchunks) {  // a whole workgroup: no barrier below is reached by part of one
-        warm_tokens(a, blockIdx.x - a.nchunks, gridDim.x - a.nchunks, 0, a.warm_rows);
+        warm_tokens(a, blockIdx.x - a.nchunks, gridDim.x - a.nchunks);
         return;
     }
     const int wpb = blockDim.x >> 6;
@@ -412,18 +495,14 @@ __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
     const int nchunks = a.nchunks;
     const int b = blockIdx.x;
     const bool active = wc < a.nwc;
-    const bool one_group = a.passes <= PU;
+    constexpr bool one_group = ONE_GROUP, multi = MULTI;
 
-    // (1) issue every global load this workgroup needs up front: its own ids and the
-    //     other chunks' histograms (consumed in (3)); they stay in flight across the
-    //     LDS-only barrier
+    // (1) the global loads this workgroup can issue at once: its own ids and the generation
+    //     (first needed in (3): nothing here waits for it)
     int raw[PU];
     if (active) issue_group(a, wc, 0, lane, raw);
-    int hv[HB];  // column tid of the first HB chunk histograms
-    const int nrows = nchunks > 1 ? nchunks : 0;
-#pragma unroll
-    for (int r = 0; r < HB; ++r) hv[r] = (r < nrows && tid < W) ? a.hist[(int64_t)r * W + tid] : 0;
-    for (int j = tid; j < wpb * W + 2 * W; j += blockDim.x) l.wh[j] = 0;  // wh, tot, pre are contiguous
+    uint32_t gen = __hip_atomic_load(&a.ctl[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int j = tid; j < lds_ints(W, wpb); j += blockDim.x) l.wh[j] = 0;
     lds_barrier();
 
     // (2) per-wave histograms of this chunk
@@ -435,45 +514,102 @@ __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
             hist_group(a, en, l.wh + w * W);
         }
     }
-    // (3) totals over all chunks and the prefix of this chunk, per bin (thread = column)
-    if (nrows > 0) {
+    lds_barrier();
+
+    // (3) per bin (thread = column): the sum of the chunk, which is published at once, and
+    //     the running sum down the waves -- row r becomes "entries of the bin in the waves
+    //     before r"; then the first look across, in flight while the in-wave ranks are
+    //     computed
+    asm volatile("" : "+v"(gen));  // the generation is first looked at here
+    const uint32_t tag = gen + 1u;
+    for (int c = tid; c < W; c += blockDim.x) {
+        int v[kLayoutWavesPerBlock];
+#pragma unroll
+        for (int r = 0; r < kLayoutWavesPerBlock; ++r) v[r] = l.wh[min(r, wpb) * W + c];  // rows beyond the last: 0
+        int run = 0;
+#pragma unroll
+        for (int r = 0; r < kLayoutWavesPerBlock; ++r) {
+            const int x = v[r];
+            v[r] = run;
+            run += x;
+        }
+        if (multi)
+            __hip_atomic_store(&a.pub[(int64_t)b * W + c], (tag << kTagShift) | (uint32_t)run, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        l.tot[c] = run;
+#pragma unroll
+        for (int r = 0; r < kLayoutWavesPerBlock; ++r) l.wh[min(r, wpb) * W + c] = v[r];
+    }
+    uint32_t hv[HB];
+    if (multi) look_across(a, min(tid, W - 1), 0, hv);
+    // (4) ranks inside the chunk; with one load group they are computed here, while the
+    //     other chunks' sums are on their way: first what needs no memory
+    InWave iw[PU];
+    if (active && one_group) rank_group(a, en, 0, lane, iw);
+    lds_barrier();
+    int sl[PU], rsl[PU];
+    if (active && one_group) place_group(a, en, iw, 0, l.wh + w * W, sl, rsl);
+
+    // (5) per bin: entries in earlier chunks and in all chunks.  A batch of words is polled
+    //     as a whole until every word of it carries this launch's tag (rows beyond the last
+    //     chunk repeat its words, and the chunk's own word is among them: no exceptions to
+    //     test for).  Which words of a batch count, and which belong to earlier chunks, are
+    //     wave-uniform bit masks.
+    if (multi) {
+        int rounds = 0;  // of this thread, over all its batches
+        bool gave_up = false;
+        bool have = true;  // hv holds the batch (tid, 0)
         for (int c = tid; c < W; c += blockDim.x) {
             int before = 0, total = 0;
-            if (c == tid) {
+            for (int r0 = 0; r0 < nchunks; r0 += HB) {
+                for (;;) {
+                    if (!have) look_across(a, c, r0, hv);
+                    have = false;
+                    bool all = true;
 #pragma unroll
-                for (int r = 0; r < HB; ++r) {
-                    total += hv[r];
-                    if (r < b) before += hv[r];
+                    for (int j = 0; j < HB; ++j) all = all && (hv[j] >> kTagShift) == tag;
+                    if (all) break;
+                    if (++rounds >= kLookLimit) {  // a chunk never published: flag it (the counts are then undefined)
+                        gave_up = true;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                const int nvalid = min(nchunks - r0, HB), nbefore = min(max(b - r0, 0), HB);
+                const uint32_t valid = nvalid >= 32 ? ~0u : (1u << nvalid) - 1u;
+                const uint32_t earlier = nbefore >= 32 ? ~0u : (1u << nbefore) - 1u;
+#pragma unroll
+                for (int j = 0; j < HB; ++j) {
+                    const uint32_t cnt = hv[j] & kCountMask & (0u - ((valid >> j) & 1u));
+                    total += (int)cnt;
+                    before += (int)(cnt & (0u - ((earlier >> j) & 1u)));
                 }
             }
-            for (int r = (c == tid ? HB : 0); r < nrows; ++r) {
-                const int v = a.hist[(int64_t)r * W + c];
-                total += v;
-                if (r < b) before += v;
-            }
-            l.tot[c] = total;
-            l.pre[c] = before;
+            l.tot[c] = total;  // the chunk's own sum is one of the words
+            l.before[c] = before;
         }
+        if (gave_up) atomicOr(l.flag, 1);
     }
-    lds_barrier();
-    // (4) running sum down the waves: row r becomes "entries of the bin before wave r"
-    for (int c = tid; c < W; c += blockDim.x) {
-        int run = l.pre[c];
-        for (int r = 0; r < wpb; ++r) {
-            const int v = l.wh[r * W + c];
-            l.wh[r * W + c] = run;
-            run += v;
-        }
-        if (nchunks == 1) l.tot[c] = run;
-    }
-    lds_barrier();
-    // (5) offset tables, per wave
-    wave_offsets(a, l, lane);
-    // (6) slots
+    // (6) the scan over the bins (its first barrier also makes tot, before and flag final)
+    block_scan_totals(a, l, tid, lane, w, wpb);
+    // thread 0 reports for the workgroup: the value it gets back tells wave 0 whether this
+    // workgroup is the last to have looked across (then every chunk is done with pub and ctl,
+    // and it may advance the generation) and whether any workgroup gave up waiting
+    const int any_gave_up = *l.flag;
+    uint32_t ticket = 0;
+    constexpr uint32_t kGaveUp = 1u << 16;  // low 16 bits count workgroups, the rest flags a time-out
+    const uint32_t mine = 1u + (any_gave_up ? kGaveUp : 0u);
+    if (multi && tid == 0) ticket = __hip_atomic_fetch_add(&a.ctl[1], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    // (7) slots
     if (active) {
         for (int p0 = 0; p0 < a.passes; p0 += PU) {
-            if (!one_group) load_group(a, wc, p0, lane, en);
-            slots_group(a, en, p0, l.wh + w * W, l, lane);
+            if (!one_group) {
+                load_group(a, wc, p0, lane, en);
+                rank_group(a, en, p0, lane, iw);
+                place_group(a, en, iw, p0, l.wh + w * W, sl, rsl);
+            }
+            emit_group(a, en, p0, sl, rsl, l);
         }
         // the walk has advanced the wave's prefixes past its own entries: they are now the
         // positions at which the next wave-chunk's entries start in the expert-sorted list
@@ -481,12 +617,31 @@ __global__ __launch_bounds__(MAXT) void layout_slot_kernel(LayoutArgs a) {
             wave_lds_fence();
             int32_t* rs = a.run_start + (int64_t)(wc + 1) * a.E;
             const int32_t* h = l.wh + w * W;
-            for (int e = lane; e < a.E; e += kWave) rs[e] = l.opre[e] + h[e];
+            for (int e = lane; e < a.E; e += kWave) rs[e] = l.S[e] + l.before[e] + h[e];
         }
     }
-    // (7) one wave publishes the per-expert / per-rank arrays and the totals; it does so
-    //     after its own slot walk so that the walk of the chunk is not held up
-    if (b == 0 && w == 0) wave_write_tables(a, l, lane);
+    // (8) the per-expert / per-rank arrays and the totals: by the first chunk, after its own
+    //     walk so that the walk is not held up.  The status word comes from one wavefront:
+    //     with several chunks wave 0 of the workgroup that finished looking across last,
+    //     which then also leaves the cross-workgroup words ready for the next launch
+    if (b == 0) write_tables(a, l, tid, lane, w);
+    if (w != 0) return;
+    if (!multi) {
+        write_status(a, l, lane, 0);
+        return;
+    }
+    const uint32_t seen = __builtin_amdgcn_readfirstlane(ticket) + mine;  // lane 0 holds the ticket
+    if ((int)(seen & (kGaveUp - 1u)) != nchunks) return;
+    write_status(a, l, lane, seen >= kGaveUp ? STATUS_TIMEOUT : 0);
+    uint32_t next = gen + 1u;
+    if (next >= kTags) {  // the tags have run out: clear every published word and start over
+        for (int64_t j = lane; j < (int64_t)kMaxChunks * W; j += kWave) a.pub[j] = 0u;
+        next = 0u;
+    }
+    if (lane == 0) {
+        __hip_atomic_store(&a.ctl[1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&a.ctl[0], next, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 // ---- inputs of at most 1024 entries: one workgroup, one entry per thread, bitmaps ----
@@ -500,7 +655,7 @@ constexpr int kBitmapWords = 16;   // words per bitmap: one per wavefront of a 1
 constexpr int kBitmapStride = 17;  // row stride in words: odd, so that the rows start in different LDS banks
 
 size_t bitmap_lds_bytes(const LayoutArgs& a) {
-    return 8 * (size_t)(a.E + a.R) * kBitmapStride + sizeof(int32_t) * (2 * (size_t)a.W + 2 * (a.E + 1) + (a.R + 1));
+    return 8 * (size_t)(a.E + a.R) * kBitmapStride + sizeof(int32_t) * (3 * (size_t)a.W + kLayoutWavesPerBlock);
 }
 
 // Set bits of a bitmap row below position (w, lane): all 16 words are read at once.
@@ -524,17 +679,17 @@ __global__ __launch_bounds__(1024) void layout_bitmap_kernel(LayoutArgs a) {
     Lds l;
     l.wh = nullptr;
     l.tot = lds + 2 * nbins * kBitmapStride;
-    l.pre = l.tot + a.W;
-    l.eoff = l.pre + a.W;
-    l.opre = l.eoff + a.E + 1;
-    l.roff = l.opre + a.E + 1;
+    l.S = l.tot + a.W;
+    l.before = l.S + a.W;  // stays zero: there is only this chunk
+    l.wsum = l.before + a.W;
+    l.flag = nullptr;
     const int tid = threadIdx.x;
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     int raw[PU];
     issue_group(a, w, 0, lane, raw);  // one pass: the entry of this thread
     for (int j = tid; j < nbins * kBitmapStride; j += blockDim.x) bm[j] = 0ull;
-    for (int j = tid; j < a.W; j += blockDim.x) l.tot[j] = 0;
+    for (int j = tid; j < 3 * a.W + kLayoutWavesPerBlock; j += blockDim.x) l.tot[j] = 0;  // tot, S, before, wsum
     lds_barrier();
     Entry en[PU];
     classify_group(a, w, 0, lane, raw, en);
@@ -552,27 +707,24 @@ __global__ __launch_bounds__(1024) void layout_bitmap_kernel(LayoutArgs a) {
         l.tot[c < a.E ? c : c + 2] = bits_below(bm + c * kBitmapStride, kBitmapWords, 0ull);
     const int slot = x.ok ? bits_below(bm + x.e * kBitmapStride, w, bit - 1) : -1;
     const int rslot = x.lead ? bits_below(bm + (a.E + x.d) * kBitmapStride, w, bit - 1) : -1;
-    lds_barrier();
-    wave_offsets(a, l, lane);
+    block_scan_totals(a, l, tid, lane, w, blockDim.x >> 6);
     emit_entry(a, x, slot, rslot, l);
-    if (w == 0) wave_write_tables(a, l, lane);
+    write_tables(a, l, tid, lane, w);
+    if (w == 0) write_status(a, l, lane, 0);
 }
 
 constexpr size_t kLdsLimit = 64 * 1024;
 
 }  // namespace
 
-// Wave-chunk plan for n entries.  Up to kLayoutOneBlockEntries: one workgroup of 16
-// waves, 64*passes entries each (one launch).  Beyond: at least two passes per wave so
-// that there are fewer, fuller chunks, and at most kMaxWaveChunks wave-chunks.
+// Wave-chunk plan for n entries: 64*passes consecutive entries per wavefront.  Up to
+// kLayoutOneBlockEntries: one workgroup of 16 waves (one launch, nothing crosses between
+// workgroups).  Beyond: as many wave-chunks as there are passes of 64 entries, up to
+// kMaxWaveChunks, so that every wave has as short a chain of dependent steps as possible.
 void plan_layout(int n, int* passes, int* nwc) {
     int p;
-    if (n <= kLayoutOneBlockEntries) {
-        p = (n + kWave * kLayoutWavesPerBlock - 1) / (kWave * kLayoutWavesPerBlock);
-    } else {
-        p = (n + kWave * kMaxWaveChunks - 1) / (kWave * kMaxWaveChunks);
-        if (p < 2) p = 2;
-    }
+    if (n <= kLayoutOneBlockEntries) p = (n + kWave * kLayoutWavesPerBlock - 1) / (kWave * kLayoutWavesPerBlock);
+    else p = (n + kWave * kMaxWaveChunks - 1) / (kWave * kMaxWaveChunks);
     if (p < 1) p = 1;
     *passes = p;
     *nwc = (n + kWave * p - 1) / (kWave * p);
@@ -584,13 +736,13 @@ static bool use_bitmap(const LayoutArgs& a) {
 
 bool layout_writes_runs(const LayoutArgs& a) { return a.run_start != nullptr && !use_bitmap(a); }
 
-// The read-ahead rides on the slot kernel of inputs that are laid out by several workgroups.
+// The read-ahead rides on the layout kernel of inputs that are laid out by several workgroups.
 bool layout_prefetches(const LayoutArgs& a) {
     return a.warm_x != nullptr && a.warm_rows > 0 && a.n >= kRunOrderMinEntries && !use_bitmap(a) &&
            a.nwc > kLayoutWavesPerBlock;
 }
 
-constexpr int kWarmBlocks = 2048;  // extra workgroups of the slot kernel that read tokens
+constexpr int kWarmBlocks = 512;  // extra workgroups of the layout kernel that read tokens
 
 hipError_t launch_layout(const LayoutArgs& a_in, hipStream_t s) {
     LayoutArgs a = a_in;
@@ -599,27 +751,23 @@ hipError_t launch_layout(const LayoutArgs& a_in, hipStream_t s) {
         hipLaunchKernelGGL(layout_bitmap_kernel, dim3(1), dim3(a.nwc * kWave), bitmap_lds_bytes(a), s, a);
         return hipGetLastError();
     }
-    // One workgroup of up to 16 waves when the plan has at most 16 wave-chunks and its
-    // LDS tables fit; otherwise chunks of at most 8 waves so that the walk is spread
-    // over many compute units while one thread per bin can add up the chunk histograms.
-    int wpb;
-    if (a.nwc <= kLayoutWavesPerBlock && lds_bytes(a, kLayoutWavesPerBlock) <= kLdsLimit) {
-        wpb = kLayoutWavesPerBlock;
-    } else {
-        wpb = kLayoutWavesPerChunk;
-        while (wpb > 1 && lds_bytes(a, wpb) > kLdsLimit) wpb >>= 1;
-        if (lds_bytes(a, wpb) > kLdsLimit) return hipErrorInvalidValue;
-    }
+    // Workgroups of 16 waves, fewer when the bin tables would not fit the LDS otherwise.
+    int wpb = kLayoutWavesPerBlock;
+    while (wpb > 1 && lds_bytes(a, wpb) > kLdsLimit) wpb >>= 1;
+    if (lds_bytes(a, wpb) > kLdsLimit) return hipErrorInvalidValue;
     int nblk = (a.nwc + wpb - 1) / wpb;
     if (nblk < 1) nblk = 1;
-    if (nblk > kMaxWaveChunks) return hipErrorInvalidValue;
-    const dim3 grid(nblk), block(wpb * kWave);
-    const size_t lds = lds_bytes(a, wpb);
+    if (nblk > kMaxChunks) return hipErrorInvalidValue;
+    if ((int64_t)wpb * kWave * a.passes > (int64_t)kCountMask) return hipErrorInvalidValue;  // a chunk's count must fit its word
     a.nchunks = nblk;
     const bool pf = layout_prefetches(a);
-    if (nblk > 1) hipLaunchKernelGGL(layout_count_kernel, grid, block, lds_bytes(a, 1), s, a);
-    if (nblk == 1) hipLaunchKernelGGL((layout_slot_kernel<1024, 1>), grid, block, lds, s, a);
-    else hipLaunchKernelGGL((layout_slot_kernel<512, 32>), dim3(nblk + (pf ? kWarmBlocks : 0)), block, lds, s, a);
+    const dim3 grid(nblk + (pf ? kWarmBlocks : 0)), block(wpb * kWave);
+    const size_t lds = lds_bytes(a, wpb);
+    const bool one_group = a.passes <= PU;
+    if (nblk > 1 && one_group) hipLaunchKernelGGL((layout_kernel<true, true>), grid, block, lds, s, a);
+    else if (nblk > 1) hipLaunchKernelGGL((layout_kernel<true, false>), grid, block, lds, s, a);
+    else if (one_group) hipLaunchKernelGGL((layout_kernel<false, true>), grid, block, lds, s, a);
+    else hipLaunchKernelGGL((layout_kernel<false, false>), grid, block, lds, s, a);
     return hipGetLastError();
 }
 

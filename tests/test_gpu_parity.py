@@ -206,6 +206,35 @@ def test_layout_expert_base(ep, hx, oracle_mod):
         ep.ep_group_destroy(g)
 
 
+def test_layout_many_launches_on_one_slab(ep, hx, oracle_mod):
+    """The workgroups of a layout launch tell each other's published counts from stale ones by a
+    tag that counts the launches on the handle's slab and starts over after 255 of them (the
+    published words are cleared at that point): more than two such cycles on one slab, every
+    result equal to the oracle's."""
+    spec = wl.SPECS["skew"]
+    T = 1200  # 9600 entries: several workgroups
+    g = _group(ep, spec, T, ep.EP_MODE_HT, max_handles=1)
+    try:
+        want = {}
+        tops = []
+        for v in range(3):
+            topk, _, _ = wl.make_routing(spec, T=T, seed_offset=v)
+            tops.append((torch.from_numpy(topk).to(hx.DEV), oracle_mod.layout(topk, E=spec.E, R=spec.R, C_rank=T)))
+        n = T * spec.K
+        for it in range(600):
+            d_topk, lay = tops[it % 3]
+            h = ep.ep_layout(g, d_topk)
+            info = ep.ep_handle_query(h)
+            got = ep.read_device_i32(info.dst_row, n).numpy().reshape(T, spec.K)
+            assert np.array_equal(got, lay.dst_row), f"launch {it}"
+            assert int(info.status) == 0 and int(info.rows_kept) == lay.kept
+            if it % 85 == 0 or it in (254, 255, 256, 509, 510, 511):
+                hx.assert_layout_equal(hx.fetch_layout(h, T, spec.K, spec.E, spec.R), lay)
+            ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
 def test_layout_is_deterministic(ep, hx):
     spec = wl.SPECS["stress_hot"]
     topk, _, _ = wl.make_routing(spec)
