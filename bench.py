@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the dispatch/combine hot path on one MI355X.
 
-One step = ep_layout + ep_dispatch + ep_combine (+ handle destroy) over one batch
-of synthetic routing.  Inputs (tokens, top-k ids, gate weights, expert outputs)
-are resident in HBM before the timed region.  Prints ONE JSON line.
+One step = layout + dispatch + combine (+ handle destroy) over one batch of synthetic
+routing.  Inputs (tokens, top-k ids, gate weights, expert outputs) are resident in HBM
+before the timed region.  Prints ONE JSON line.
 
-By default the group is configured with EP_ORDER_DESTINATION and the layout call is
-ep_layout_prefetch (the tokens are announced to it); --dispatch-order 0 times the
-token-ordered dispatch with plain ep_layout.
+Headline: the high-throughput prefill shape.  By default the group is configured with
+EP_ORDER_DESTINATION and the layout call is ep_layout_prefetch (the tokens are announced
+to it); --dispatch-order 0 times the token-ordered dispatch with plain ep_layout.  The
+same line carries every other workload shape (`all_configs`), the once-per-rank dispatch
+and the CPU oracle's rate on the host cores.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload ht_prefill]
 """
@@ -25,21 +27,28 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
         sys.path.insert(0, p)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+ORDER_NAMES = ["EP_ORDER_TOKEN", "EP_ORDER_DESTINATION + ep_layout_prefetch", "EP_ORDER_DESTINATION_RESIDENT"]
 
 
-def _traffic(workload: str, kernel: str):
-    """HBM bytes per launch measured with rocprofv3 counters (FETCH_SIZE + WRITE_SIZE scaled
-    by the calibration copy), read from the committed summary; None if there is none."""
+def _profiled(workload: str, kernel: str):
+    """What the committed rocprofv3 summaries say about one kernel of one workload: HBM bytes per
+    launch (FETCH_SIZE + WRITE_SIZE scaled by the calibration copy) and its average duration,
+    with the commit and date of the profiled run.  None when there is no such line."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    meta, found = {}, None
     try:
         with open(path) as f:
             for line in f:
                 parts = line.split()
-                if len(parts) == 3 and parts[0] == workload and parts[1] == kernel:
-                    return int(parts[2])
+                if line.startswith("#") and len(parts) >= 3 and parts[1] in ("commit", "date", "command"):
+                    meta[parts[1]] = " ".join(parts[2:])
+                elif len(parts) >= 3 and parts[0] == workload and parts[1] == kernel:
+                    found = {"traffic": int(parts[2]), "kernel_us": float(parts[3]) if len(parts) > 3 else None}
     except (OSError, ValueError):
-        pass
-    return None
+        return None
+    if found:
+        found.update(meta)
+    return found
 
 
 def cpu_baseline(w, steps_budget_s: float = 12.0):
@@ -124,6 +133,141 @@ def cpu_baseline_all_cores(w, threads: int, budget_s: float = 4.0):
             "ms_per_step": round(t_total / reps * 1e3, 2)}
 
 
+class StepBench:
+    """One workload prepared for timing: `nsets` rotated input/window sets resident in HBM, the
+    expert outputs that combine reads computed once, the call descriptors built once.  A step is
+    then three or four foreign-function calls:
+        inputs of at most 1024 routed entries:  ep_layout_dispatch, ep_combine, ep_handle_destroy
+        larger ones:  ep_layout[_prefetch], ep_dispatch, ep_combine, ep_handle_destroy"""
+
+    def __init__(self, ep, hx, wl, torch, np, workload: str, mode: str = "ht", slots: int = 0, order: int = 1,
+                 nsets: int = 3):
+        self.ep, self.torch, self.np, self.wl = ep, torch, np, wl
+        self.w = wl.make_workload(workload)
+        spec = self.spec = self.w.spec
+        T, K, H, E = spec.T, spec.K, spec.H, spec.E
+        self.ll = mode == "ll"
+        self.C = (slots or max(1, 2 * T * K // E)) if self.ll else 0
+        self.order = order
+        self.nsets = nsets
+        self.fused = T * K <= 1024
+        cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_LL if self.ll else ep.EP_MODE_HT,
+                             slots_per_subregion=self.C, max_handles=nsets + 2,  # no allocation later
+                             dispatch_order=order)
+        self.group = ep.ep_group_create(cfg)
+        self.sets = []
+        scale = wl.expert_scale_table(spec)
+        for s in range(nsets):
+            ws = self.w if s == 0 else wl.make_workload(workload, seed_offset=10 * s)
+            x = hx.bits_to_dev(ws.x_bits)
+            topk = torch.from_numpy(ws.topk_idx).to(hx.DEV)
+            gate = torch.from_numpy(ws.topk_w).to(hx.DEV)
+            recv = torch.zeros((E, self.C, H) if self.ll else (T * K, H), dtype=torch.bfloat16, device=hx.DEV)
+            out = torch.zeros((T, H), dtype=torch.bfloat16, device=hx.DEV)
+            # expert outputs for combine: stand-in experts applied once to the dispatched rows
+            h = ep.ep_layout(self.group, topk)
+            ep.ep_dispatch(h, x, recv)
+            info = ep.ep_handle_query(h)
+            counts = ep.read_device_i32(info.expert_count, E).numpy()
+            row_e = torch.from_numpy(np.repeat(np.arange(E), self.C if self.ll else counts)).to(hx.DEV)
+            y = torch.empty_like(recv)
+            flat_in, flat_out = recv.view(-1, H), y.view(-1, H)
+            for r0 in range(0, flat_in.shape[0], 8192):
+                flat_out[r0:r0 + 8192] = hx.expert_standin(flat_in[r0:r0 + 8192], row_e[r0:r0 + 8192], scale)
+            if s == 0:
+                self.rows, self.dropped = int(info.rows_kept), int(info.rows_dropped)
+            ep.ep_handle_destroy(h)
+            self.sets.append((x, topk, gate, recv, y, out))
+        torch.cuda.synchronize()
+        self.stream_ptr = torch.cuda.current_stream().cuda_stream
+        self._destroy = ep.load().ep_handle_destroy
+        self.prefetch = order == 1 and not self.fused
+        if self.fused:
+            self.prepared = [(ep.PreparedLayoutDispatch(self.group, topk, x, recv, topk_weights=gate), None,
+                              ep.prepare_combine(y, out, topk_weights=gate)) for (x, topk, gate, recv, y, out) in self.sets]
+        else:
+            self.prepared = [(ep.PreparedLayout(self.group, topk, tokens=x if self.prefetch else None),
+                              ep.prepare_dispatch(x, recv, topk_weights=gate), ep.prepare_combine(y, out, topk_weights=gate))
+                             for (x, topk, gate, recv, y, out) in self.sets]
+        ab = wl.algorithmic_bytes(spec, self.rows)
+        self.bytes = ab
+        self.step_bytes = ab["layout"] + ab["dispatch"] + ab["combine"]
+        self.calls = ("ep_layout_dispatch (layout and dispatch in one launch) + ep_combine" if self.fused else
+                      ("ep_layout_prefetch" if self.prefetch else "ep_layout") + " + ep_dispatch + ep_combine")
+
+    def step(self, i: int, ev=None) -> None:
+        a, b, c = self.prepared[i % self.nsets]
+        sp = self.stream_ptr
+        if ev:
+            ev[0].record()
+        h = a(sp)
+        if ev:
+            ev[1].record()
+        if b is not None:
+            b(h, sp)
+        if ev:
+            ev[2].record()
+        c(h, sp)
+        if ev:
+            ev[3].record()
+        self._destroy(h)
+
+    def timed(self, steps: int, first: int = 0) -> float:
+        """Seconds for exactly `steps` steps, bracketed by synchronisation on both sides."""
+        torch = self.torch
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            self.step(first + i)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def per_op(self, steps: int):
+        """Microseconds per call from HIP events around every call of `steps` steps (they include
+        the gap between two dependent launches, and recording them slows the step itself, so
+        this is a pass of its own): arrays layout, dispatch, combine.  In the one-launch case
+        `layout` is the layout+dispatch call and `dispatch` is empty."""
+        torch, np = self.torch, self.np
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        for i in range(steps):
+            self.step(i, events[i])
+        torch.cuda.synchronize()
+        f = lambda a, b: np.array([e[a].elapsed_time(e[b]) for e in events]) * 1e3
+        return f(0, 1), f(1, 2), f(2, 3)
+
+    def summary(self, steps: int, warmup: int, repeats: int = 10) -> dict:
+        """Median / min / max over `repeats` timed regions of `steps` steps, per-op medians, rates."""
+        np = self.np
+        for i in range(warmup):
+            self.step(i)
+        per_step = np.array([self.timed(steps, first=r * steps) / steps * 1e6 for r in range(repeats)])
+        lay, dis, com = self.per_op(max(12, min(steps, 40)))
+        spec = self.spec
+        med = float(np.median(per_step))
+        res = {"workload": f"{spec.name}: R={spec.R} T={spec.T} H={spec.H} E={spec.E} K={spec.K} bf16, "
+                           f"{'padded layout [E, C=%d, H]' % self.C if self.ll else 'concatenated layout'}"
+                           f"{', ' + ORDER_NAMES[self.order] if not self.fused else ''}",
+               "calls": self.calls, "rows": self.rows, "rows_dropped": self.dropped,
+               "step_us": round(med, 2), "step_us_min": round(float(per_step.min()), 2),
+               "step_us_max": round(float(per_step.max()), 2), "repeats": repeats, "steps_per_repeat": steps,
+               "gbps": round(self.step_bytes / (med * 1e-6) / 1e9, 1),
+               "pct_of_hbm_peak": round(100.0 * self.step_bytes / (med * 1e-6) / 1e9 / HBM_PEAK_GBS, 2),
+               "algorithmic_bytes": self.bytes}
+        if self.fused:
+            res["layout_dispatch_us"] = round(float(np.median(lay)), 2)
+        else:
+            res["layout_us"] = round(float(np.median(lay)), 2)
+            res["dispatch_us"] = round(float(np.median(dis)), 2)
+            res["layout_plus_dispatch_us"] = round(float(np.median(lay + dis)), 2)
+        res["combine_us"] = round(float(np.median(com)), 2)
+        return res
+
+    def close(self) -> None:
+        self.ep.ep_group_destroy(self.group)
+        self.sets, self.prepared = [], []
+        self.torch.cuda.empty_cache()
+
+
 def _timed_us(torch, np, fn, iters: int = 20) -> float:
     for _ in range(3):
         fn()
@@ -136,7 +280,7 @@ def _timed_us(torch, np, fn, iters: int = 20) -> float:
     return float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(iters)])) * 1e3
 
 
-def once_per_rank(ep, torch, np, spec, sets, stream_ptr):
+def once_per_rank(ep, torch, np, spec, sets, rows, stream_ptr):
     """The dispatch variant that sends a token once per destination rank and fans out on arrival
     (send + receiver ranking + fan-out), timed over the rotated input sets; HIP events."""
     T, K, H, E = spec.T, spec.K, spec.H, spec.E
@@ -147,7 +291,6 @@ def once_per_rank(ep, torch, np, spec, sets, stream_ptr):
     calls = [ep.prepare_dispatch(s[0], s[3], topk_weights=s[2], topk_idx=s[1]) for s in sets]
     info = ep.ep_handle_query(hs[0])
     ginfo = ep.ep_group_query(g2)
-    rows = sets[0][6]
     it = [0]
 
     def one():
@@ -171,71 +314,12 @@ def once_per_rank(ep, torch, np, spec, sets, stream_ptr):
     return res
 
 
-def decode_shape(ep, hx, wl, torch, np, stream_ptr, steps: int = 200):
-    """The low-latency decode shape (R=32, T=128, H=7168, E=256, K=8) in the padded [E, C, H] window
-    layout: microseconds per call (HIP events on every 4th step) and per whole step (wall clock)."""
-    w = wl.make_workload("ll_decode")
-    spec = w.spec
-    T, K, H, E = spec.T, spec.K, spec.H, spec.E
-    C = T
-    g = ep.ep_group_create(ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_LL, slots_per_subregion=C, max_handles=4))
-    x = hx.bits_to_dev(w.x_bits)
-    topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
-    gate = torch.from_numpy(w.topk_w).to(hx.DEV)
-    recv = torch.zeros((E, C, H), dtype=torch.bfloat16, device=hx.DEV)
-    out = torch.zeros((T, H), dtype=torch.bfloat16, device=hx.DEV)
-    lay, dis, com = ep.PreparedLayout(g, topk), ep.prepare_dispatch(x, recv, topk_weights=gate), \
-        ep.prepare_combine(recv, out, topk_weights=gate)
-    destroy = ep.load().ep_handle_destroy
-
-    def step(ev=None):
-        if ev:
-            ev[0].record()
-        h = lay(stream_ptr)
-        if ev:
-            ev[1].record()
-        dis(h, stream_ptr)
-        if ev:
-            ev[2].record()
-        com(h, stream_ptr)
-        if ev:
-            ev[3].record()
-        destroy(h)
-
-    for _ in range(20):
-        step()
-    torch.cuda.synchronize()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps // 4)]
-    t0 = time.perf_counter()
-    for i in range(steps):
-        step(events[i // 4] if i % 4 == 0 else None)
-    torch.cuda.synchronize()
-    el = time.perf_counter() - t0
-    us = lambda a, b: round(float(np.mean([e[a].elapsed_time(e[b]) for e in events])) * 1e3, 2)
-    ab = wl.algorithmic_bytes(spec, T * K)
-    res = {"workload": f"ll_decode: R={spec.R} T={T} H={H} E={E} K={K} bf16, padded layout [E, C={C}, H], token order",
-           "step_us": round(el / steps * 1e6, 2), "layout_us": us(0, 1), "dispatch_us": us(1, 2), "combine_us": us(2, 3),
-           "algorithmic_bytes": ab, "note": "launch and latency bound: 16.5 MB per call is 2 us at the HBM peak"}
-    ep.ep_group_destroy(g)
-    return res
-
-
-def extras(ep, hx, wl, torch, np, group, spec, first_set, stream_ptr, iters: int = 20):
+def extras(ep, hx, wl, torch, np, group, spec, first_set, rows, stream_ptr, iters: int = 20):
     """Timings of the dispatch variants outside the headline step (HIP events, mean of iters)."""
-    x, topk, gate, recv, y, out, rows = first_set
+    x, topk, gate, recv, y, out = first_set
     T, K, H, E = spec.T, spec.K, spec.H, spec.E
     res = {}
-
-    def timed(fn):
-        for _ in range(3):
-            fn()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
-        for i in range(iters):
-            ev[i].record()
-            fn()
-        ev[iters].record()
-        torch.cuda.synchronize()
-        return float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(iters)])) * 1e3
+    timed = lambda fn: _timed_us(torch, np, fn, iters)
 
     h = ep.ep_layout(group, topk)
     if H % 128 == 0:
@@ -296,6 +380,18 @@ def extras(ep, hx, wl, torch, np, group, spec, first_set, stream_ptr, iters: int
     return res
 
 
+# every other shape of the workload list, in the configuration the headline uses
+ALL_CONFIGS = [
+    ("tiny", "tiny", "ht", 0),
+    ("ll_decode", "ll_decode", "ll", 128),
+    ("skew", "skew", "ht", 0),
+    ("skew_padded_C512", "skew", "ll", 512),
+    ("skew_rank0", "skew_rank0", "ht", 0),
+    ("stress", "stress", "ht", 0),
+    ("stress_hot", "stress_hot", "ht", 0),
+]
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -312,16 +408,20 @@ def main() -> int:
                     help="C of the padded layout (default: twice the mean rows per expert, 2*T*K/E)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--step-only", action="store_true",
-                    help="leave out the add-on measurements (decode_shape, once_per_rank, CPU baselines): only the "
-                         "kernels of the headline step run, which is what the rocprofv3 summaries are taken with")
-    ap.add_argument("--event-every", type=int, default=4,
-                    help="record the per-op HIP events on every n-th timed step only (four event "
-                         "records cost about 12 us of a step, so they are sampled)")
+                    help="leave out the add-on measurements (all_configs, once_per_rank, per-op events, CPU "
+                         "baselines): only the kernels of the step run, which is what the rocprofv3 summaries are "
+                         "taken with")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="the headline step with its per-op times and roofline, without all_configs, once_per_rank "
+                         "and the CPU baselines")
+    ap.add_argument("--repeats", type=int, default=10,
+                    help="timed regions of --steps steps per workload; medians over them are reported next to "
+                         "the one region the headline value is taken from")
     ap.add_argument("--graph", action="store_true",
                     help="also replay the step from captured HIP graphs (reported in a 'graph' object)")
     ap.add_argument("--extras", action="store_true",
-                    help="also time the FP8 quantising dispatch and the once-per-rank dispatch (reported "
-                         "in an 'extras' object; the headline numbers are unaffected)")
+                    help="also time the FP8 quantising dispatch, the staged calls and the two-level combine "
+                         "(reported in an 'extras' object; the headline numbers are unaffected)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one rank's share on ONE GPU; this build has no multi-GPU path "
@@ -335,110 +435,19 @@ def main() -> int:
     from paper_2603_13606_amd import binding as ep
     from paper_2603_13606_amd import workloads as wl
 
-    hx.ensure_built()  # builds only if no library is in the tree; there is no fallback path
+    hx.ensure_built()  # rebuilds a library that does not match the sources; there is no fallback path
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    w = wl.make_workload(args.workload)
-    spec = w.spec
+    nsets = max(1, args.sets)
+    sb = StepBench(ep, hx, wl, torch, np, args.workload, args.mode, args.slots, args.dispatch_order, nsets)
+    spec, ab, rows = sb.spec, sb.bytes, sb.rows
     T, K, H, E = spec.T, spec.K, spec.H, spec.E
-    nsets = max(1, args.sets)
-    ll = args.mode == "ll"
-    C = (args.slots or max(1, 2 * T * K // E)) if ll else 0
-    cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_LL if ll else ep.EP_MODE_HT, slots_per_subregion=C,
-                         max_handles=nsets + 2,  # no allocation later
-                         dispatch_order=args.dispatch_order)
-    group = ep.ep_group_create(cfg)
-
-    nsets = max(1, args.sets)
-    sets = []
-    scale = wl.expert_scale_table(spec)
-    for s in range(nsets):
-        ws = w if s == 0 else wl.make_workload(args.workload, seed_offset=10 * s)
-        x = hx.bits_to_dev(ws.x_bits)
-        topk = torch.from_numpy(ws.topk_idx).to(hx.DEV)
-        gate = torch.from_numpy(ws.topk_w).to(hx.DEV)
-        recv = torch.zeros((E, C, H) if ll else (T * K, H), dtype=torch.bfloat16, device=hx.DEV)
-        out = torch.zeros((T, H), dtype=torch.bfloat16, device=hx.DEV)
-        # expert outputs for combine: stand-in experts applied once to the dispatched rows
-        h = ep.ep_layout(group, topk)
-        ep.ep_dispatch(h, x, recv)
-        info = ep.ep_handle_query(h)
-        counts = ep.read_device_i32(info.expert_count, E).numpy()
-        row_e = torch.from_numpy(np.repeat(np.arange(E), C if ll else counts)).to(hx.DEV)
-        y = torch.empty_like(recv)
-        flat_in, flat_out = recv.view(-1, H), y.view(-1, H)
-        step_rows = 8192
-        for r0 in range(0, flat_in.shape[0], step_rows):
-            flat_out[r0:r0 + step_rows] = hx.expert_standin(flat_in[r0:r0 + step_rows], row_e[r0:r0 + step_rows], scale)
-        rows = int(info.rows_kept)
-        ep.ep_handle_destroy(h)
-        sets.append((x, topk, gate, recv, y, out, rows))
-    torch.cuda.synchronize()
-
-    # descriptors are built once per input set; a step is then four foreign-function calls
-    stream_ptr = torch.cuda.current_stream().cuda_stream
-    destroy = ep.load().ep_handle_destroy
-    prepared = [(ep.PreparedLayout(group, topk, tokens=x if args.dispatch_order == 1 else None), ep.prepare_dispatch(x, recv, topk_weights=gate),
-                 ep.prepare_combine(y, out, topk_weights=gate)) for (x, topk, gate, recv, y, out, _) in sets]
-
-    def step(i, ev=None):
-        lay, dis, com = prepared[i % nsets]
-        if ev:
-            ev[0].record()
-        h = lay(stream_ptr)
-        if ev:
-            ev[1].record()
-        dis(h, stream_ptr)
-        if ev:
-            ev[2].record()
-        com(h, stream_ptr)
-        if ev:
-            ev[3].record()
-        destroy(h)
 
     for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-
-    # reference point: what a plain streaming copy of 512 MiB reaches on this GPU
-    cal_src = torch.empty(512 << 20, dtype=torch.uint8, device=hx.DEV).fill_(1)
-    cal_dst = torch.empty_like(cal_src)
-    cal_ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
-    ep.ep_calibration_copy(cal_dst, cal_src)
-    for j in range(6):
-        cal_ev[j].record()
-        ep.ep_calibration_copy(cal_dst, cal_src)
-    cal_ev[6].record()
-    torch.cuda.synchronize()
-    cal_us = min(cal_ev[j].elapsed_time(cal_ev[j + 1]) for j in range(6)) * 1e3
-    copy_gbps = 2 * cal_src.numel() / (cal_us * 1e-6) / 1e9
-    del cal_src, cal_dst
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, events[i] if i % args.event_every == 0 else None)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    events = [e for i, e in enumerate(events) if i % args.event_every == 0]
-
-    lay_us = np.array([e[0].elapsed_time(e[1]) for e in events]) * 1e3
-    dis_us = np.array([e[1].elapsed_time(e[2]) for e in events]) * 1e3
-    com_us = np.array([e[2].elapsed_time(e[3]) for e in events]) * 1e3
-    rows = sets[0][6]
-    ab = wl.algorithmic_bytes(spec, rows)
-    step_bytes = ab["layout"] + ab["dispatch"] + ab["combine"]
-    value = step_bytes * args.steps / elapsed / 1e9
-    dom = "dispatch" if dis_us.mean() >= com_us.mean() else "combine"
-    dom_us = dis_us.mean() if dom == "dispatch" else com_us.mean()
-    kernel_name = {"dispatch": "dispatch_runs_kernel" if args.dispatch_order else "dispatch_direct_kernel",
-                   "combine": "combine_kernel"}[dom]
-    traffic_key = spec.name + ["_token_order", "", "_destination_order_resident"][args.dispatch_order]
-    achieved = ab[dom] / (dom_us * 1e-6) / 1e9
-
-    def stats(a):
-        return {"mean": round(float(a.mean()), 2), "p10": round(float(np.percentile(a, 10)), 2),
-                "p50": round(float(np.percentile(a, 50)), 2), "p90": round(float(np.percentile(a, 90)), 2)}
+        sb.step(i)
+    # THE timed region: exactly --steps steps between two synchronisations
+    elapsed = sb.timed(args.steps, first=args.warmup)
+    value = sb.step_bytes * args.steps / elapsed / 1e9
 
     line = {
         "metric": "dispatch+combine µs and effective HBM GB/s (% of peak), 1 MI355X",
@@ -448,38 +457,94 @@ def main() -> int:
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{spec.name}: R={spec.R} T={T} H={H} E={E} K={K} bf16, "
-                               f"{'padded layout [E, C=%d, H]' % C if ll else 'concatenated layout'}, "
-                               f"direct dispatch {['EP_ORDER_TOKEN', 'EP_ORDER_DESTINATION + ep_layout_prefetch', 'EP_ORDER_DESTINATION_RESIDENT'][args.dispatch_order]}, "
+                               f"{'padded layout [E, C=%d, H]' % sb.C if sb.ll else 'concatenated layout'}, "
+                               f"direct dispatch {ORDER_NAMES[args.dispatch_order]}, "
                                f"gate logits N(0,1) prior={spec.prior}",
-                   "rows": rows, "input_sets_rotated": nsets},
+                   "rows": rows, "input_sets_rotated": nsets, "calls": sb.calls},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
-        "us": {"layout": stats(lay_us), "dispatch": stats(dis_us), "combine": stats(com_us),
-               "dispatch_plus_combine_mean": round(float(dis_us.mean() + com_us.mean()), 2)},
-        "gbps": {"dispatch": round(ab["dispatch"] / (dis_us.mean() * 1e-6) / 1e9, 1),
-                 "combine": round(ab["combine"] / (com_us.mean() * 1e-6) / 1e9, 1),
-                 "dispatch_plus_combine": round((ab["dispatch"] + ab["combine"]) /
-                                                ((dis_us.mean() + com_us.mean()) * 1e-6) / 1e9, 1)},
         "algorithmic_bytes": ab,
-        "hbm_copy_reference": {"gbps": round(copy_gbps, 1), "what": "plain 16-byte-per-lane copy of 512 MiB "
-                               "(read + write bytes / best of 6 launches)"},
-        "roofline": {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": _traffic(traffic_key, kernel_name),
-                     "timing": f"HIP events on the launch stream around the kernel, mean over every "
-                               f"{args.event_every}-th step of the timed region ({len(events)} samples)"},
+        "build_id": ep.ep_build_id(),
     }
+    if not args.step_only:
+        # more regions of the same length: how much one region moves
+        per_step = np.array([sb.timed(args.steps, first=r * args.steps) / args.steps * 1e6 for r in range(args.repeats)])
+        line["step_us_over_repeats"] = {"median": round(float(np.median(per_step)), 2), "min": round(float(per_step.min()), 2),
+                                        "max": round(float(per_step.max()), 2), "regions": args.repeats}
+        # per call, from HIP events around every call (a pass of its own: recording slows the step)
+        lay_us, dis_us, com_us = sb.per_op(max(30, min(args.steps, 100)))
+
+        def stats(a):
+            return {"mean": round(float(a.mean()), 2), "p10": round(float(np.percentile(a, 10)), 2),
+                    "p50": round(float(np.percentile(a, 50)), 2), "p90": round(float(np.percentile(a, 90)), 2)}
+
+        lpd = lay_us + dis_us
+        line["us"] = {"layout": stats(lay_us), "dispatch": stats(dis_us), "combine": stats(com_us),
+                      "layout_plus_dispatch": stats(lpd),
+                      "dispatch_plus_combine_mean": round(float(dis_us.mean() + com_us.mean()), 2),
+                      "samples": int(lay_us.size),
+                      "note": "HIP events on the launch stream around each call; they include the gap between two "
+                              "dependent launches, so they read a few us above the kernel durations of rocprofv3"}
+        row = spec.row_bytes
+        gb = lambda nbytes, us: round(nbytes / (us * 1e-6) / 1e9, 1)
+        line["gbps"] = {"layout_plus_dispatch": gb(ab["layout"] + ab["dispatch"], lpd.mean()),
+                        "combine": gb(ab["combine"], com_us.mean()),
+                        "step": round(value, 1)}
+        if sb.prefetch:
+            line["gbps"]["note"] = ("the tokens are read in the layout launch (ep_layout_prefetch) and found in the "
+                                    "memory-side cache by the dispatch: the dispatch call alone is not credited with "
+                                    "that read, layout + dispatch are rated together")
+            dispatch_bytes = ab["dispatch"] - T * row  # what the copy launch itself moves through HBM
+        else:
+            line["gbps"]["dispatch"] = gb(ab["dispatch"], dis_us.mean())
+            dispatch_bytes = ab["dispatch"]
+        # roofline of the dominant kernel (the longer of the two row kernels)
+        dom = "dispatch" if dis_us.mean() >= com_us.mean() else "combine"
+        dom_us = dis_us.mean() if dom == "dispatch" else com_us.mean()
+        dom_bytes = dispatch_bytes if dom == "dispatch" else ab["combine"]
+        run_order = args.dispatch_order != 0 and T * K >= 8192
+        kernel_name = {"dispatch": "dispatch_runs_kernel" if run_order else "dispatch_direct_kernel",
+                       "combine": "combine_kernel"}[dom]
+        traffic_key = spec.name + ("_padded" if sb.ll else "") + ["_token_order", "", "_destination_order_resident"][args.dispatch_order]
+        prof = _profiled(traffic_key, kernel_name) or {}
+        achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+        line["roofline"] = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
+                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                            "traffic": prof.get("traffic"),
+                            "algorithmic_bytes_per_launch": int(dom_bytes),
+                            "kernel_us_events": round(float(dom_us), 2),
+                            "kernel_us_profiled": prof.get("kernel_us"),
+                            "profile": {k: prof.get(k) for k in ("commit", "date", "command")} if prof else None,
+                            "timing": f"HIP events on the launch stream around the kernel, mean of {int(lay_us.size)} "
+                                      "consecutive steps (launch gap included); traffic and kernel_us_profiled are "
+                                      "rocprofv3 figures of the committed run named in 'profile'"}
+        # reference point: what a plain streaming copy of 512 MiB reaches on this GPU
+        cal_src = torch.empty(512 << 20, dtype=torch.uint8, device=hx.DEV).fill_(1)
+        cal_dst = torch.empty_like(cal_src)
+        cal_ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
+        ep.ep_calibration_copy(cal_dst, cal_src)
+        for j in range(6):
+            cal_ev[j].record()
+            ep.ep_calibration_copy(cal_dst, cal_src)
+        cal_ev[6].record()
+        torch.cuda.synchronize()
+        cal_us = min(cal_ev[j].elapsed_time(cal_ev[j + 1]) for j in range(6)) * 1e3
+        line["hbm_copy_reference"] = {"gbps": round(2 * cal_src.numel() / (cal_us * 1e-6) / 1e9, 1),
+                                      "what": "plain 16-byte-per-lane copy of 512 MiB (read + write bytes / best of 6 launches)"}
+        del cal_src, cal_dst
     if args.graph:
         # one graph per input set: layout + dispatch + combine captured on a side stream
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         sp = side.cuda_stream
+        destroy = ep.load().ep_handle_destroy
         graphs, live = [], []
-        for lay, dis, com in prepared:
+        for a, b, c in sb.prepared:
             gr = torch.cuda.CUDAGraph()
             with torch.cuda.graph(gr, stream=side):
-                hh = lay(sp)
-                dis(hh, sp)
-                com(hh, sp)
+                hh = a(sp)
+                if b is not None:
+                    b(hh, sp)
+                c(hh, sp)
             graphs.append(gr)
             live.append(hh)
         for i in range(args.warmup):
@@ -491,19 +556,29 @@ def main() -> int:
         torch.cuda.synchronize()
         el = time.perf_counter() - tg
         line["graph"] = {"ms_per_step": round(el / args.steps * 1e3, 4),
-                         "value": round(step_bytes * args.steps / el / 1e9, 2), "unit": "GB/s",
+                         "value": round(sb.step_bytes * args.steps / el / 1e9, 2), "unit": "GB/s",
                          "what": "the same step replayed from a captured HIP graph (one graph per input set)"}
         del graphs
         for hh in live:
             destroy(hh)
-    if spec.name == "ht_prefill" and not args.step_only:
-        line["decode_shape"] = decode_shape(ep, hx, wl, torch, np, stream_ptr)
-    if spec.T * spec.K >= 1024 and not ll and not args.step_only:
-        line["once_per_rank"] = once_per_rank(ep, torch, np, spec, sets, stream_ptr)
-    if args.extras and not ll:
-        line["extras"] = extras(ep, hx, wl, torch, np, group, spec, sets[0], stream_ptr)
-    ep.ep_group_destroy(group)
-    if not args.no_cpu_baseline and not args.step_only:
+    addons = not args.step_only and not args.headline_only
+    if T * K >= 1024 and not sb.ll and addons:
+        line["once_per_rank"] = once_per_rank(ep, torch, np, spec, sb.sets, rows, sb.stream_ptr)
+    if args.extras and not sb.ll:
+        line["extras"] = extras(ep, hx, wl, torch, np, sb.group, spec, sb.sets[0], rows, sb.stream_ptr)
+    w = sb.w
+    sb.close()
+    if spec.name == "ht_prefill" and addons:
+        # the other workload shapes, each in the configuration of the headline (their own groups and inputs)
+        allc = {}
+        for key, name, mode, slots in ALL_CONFIGS:
+            b2 = StepBench(ep, hx, wl, torch, np, name, mode, slots, args.dispatch_order, nsets)
+            allc[key] = b2.summary(args.steps, args.warmup, args.repeats)
+            b2.close()
+            del b2
+        line["all_configs"] = allc
+        line["decode_shape"] = allc["ll_decode"]
+    if not args.no_cpu_baseline and addons:
         line["cpu_baseline"] = cpu_baseline(w)
         # box share of one GPU: 16 cores, whatever os.cpu_count() shows
         line["cpu_baseline_all_cores"] = cpu_baseline_all_cores(w, threads=min(16, os.cpu_count() or 1))

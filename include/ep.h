@@ -421,6 +421,22 @@ EP_API ep_result_t ep_combine(ep_handle_t handle, const ep_tensor_t *inputs, int
                        const ep_tensor_t *outputs, int32_t num_outputs, int32_t send_only,
                        ep_stream_t stream);
 
+/*
+ * ep_layout_dispatch -- ep_layout (Table II "ncclEpCreateHandle") and ep_dispatch of the
+ * tokens it was made for, in one call.  In the paper's low-latency kernels the token count
+ * runs next to the send (Sec. IV-C); here an input of at most 1024 routed entries on the
+ * direct path with bf16 rows is laid out and dispatched by ONE kernel launch: every
+ * workgroup derives the layout from the few KB of ids in its own LDS and copies its share
+ * of the rows, one workgroup also writes the handle's arrays.  Any other input runs the two
+ * calls one after the other (the layout with the tokens announced, as ep_layout_prefetch
+ * does).  Arguments, outputs, results and errors are those of ep_layout and ep_dispatch
+ * (send_only = 0); on an error no handle is returned.
+ */
+EP_API ep_result_t ep_layout_dispatch(ep_handle_t *handle, ep_group_t group, const ep_tensor_t *topk_idx,
+                                      const ep_tensor_t *expert_base, const ep_tensor_t *inputs,
+                                      int32_t num_inputs, const ep_tensor_t *outputs, int32_t num_outputs,
+                                      ep_stream_t stream);
+
 /* Options of ep_complete.  `size` must be sizeof(ep_complete_config_t). */
 typedef struct {
     uint32_t size;

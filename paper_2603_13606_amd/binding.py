@@ -47,7 +47,7 @@ STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW, STATUS_TIMEOUT
 
 EXPORTS = [
     "ep_error_string", "ep_version", "ep_build_id", "ep_layout_plan", "ep_dispatch_plan", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
-    "ep_layout", "ep_layout_prefetch", "ep_layout_static", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
+    "ep_layout", "ep_layout_prefetch", "ep_layout_static", "ep_layout_dispatch", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
     "ep_dispatch", "ep_combine", "ep_complete", "ep_group_reset_signals",
 ]
 
@@ -148,6 +148,8 @@ def load() -> ctypes.CDLL:
                                            ctypes.POINTER(ep_tensor_t), ctypes.POINTER(ep_tensor_t), vp]
         lib.ep_layout_static.argtypes = [ctypes.POINTER(ep_group_config_t), ctypes.POINTER(ep_tensor_t),
                                          ctypes.POINTER(ep_tensor_t), ctypes.POINTER(ep_layout_arrays_t), vp]
+        lib.ep_layout_dispatch.argtypes = [ctypes.POINTER(vp), vp, ctypes.POINTER(ep_tensor_t), ctypes.POINTER(ep_tensor_t),
+                                           ctypes.POINTER(ep_tensor_t), i32, ctypes.POINTER(ep_tensor_t), i32, vp]
         lib.ep_handle_query.argtypes = [vp, ctypes.POINTER(ep_layout_info_t)]
         lib.ep_handle_get_num_recv_tokens.argtypes = [vp, ctypes.POINTER(ctypes.c_int64)]
         lib.ep_handle_destroy.argtypes = [vp]
@@ -336,10 +338,9 @@ def _descs(pairs) -> "ctypes.Array":
     return arr
 
 
-def ep_dispatch(handle, x: torch.Tensor, recv_x: torch.Tensor, topk_weights: Optional[torch.Tensor] = None,
-                recv_w: Optional[torch.Tensor] = None, recv_src: Optional[torch.Tensor] = None,
-                recv_count: Optional[torch.Tensor] = None, send_only: int = 0, stream=None,
-                topk_idx: Optional[torch.Tensor] = None, recv_scales: Optional[torch.Tensor] = None) -> None:
+def _dispatch_tensors(x, recv_x, topk_weights=None, recv_w=None, recv_src=None, recv_count=None, topk_idx=None,
+                      recv_scales=None):
+    """(inputs, outputs) of a dispatch call as lists of (tensor, tag)."""
     ins = [(x, EP_TAG_TOKENS)]
     if topk_weights is not None:
         ins.append((topk_weights, EP_TAG_TOPK_WEIGHTS))
@@ -354,6 +355,30 @@ def ep_dispatch(handle, x: torch.Tensor, recv_x: torch.Tensor, topk_weights: Opt
         outs.append((recv_count, EP_TAG_RECV_EXPERT_COUNTER_DEVICE))
     if recv_scales is not None:
         outs.append((recv_scales, EP_TAG_SCALES))
+    return ins, outs
+
+
+def ep_layout_dispatch(group, topk_idx: torch.Tensor, x: torch.Tensor, recv_x: torch.Tensor,
+                       topk_weights: Optional[torch.Tensor] = None, recv_w: Optional[torch.Tensor] = None,
+                       recv_src: Optional[torch.Tensor] = None, recv_count: Optional[torch.Tensor] = None,
+                       expert_base: Optional[torch.Tensor] = None, recv_scales: Optional[torch.Tensor] = None,
+                       pass_topk_idx: bool = False, stream=None) -> ctypes.c_void_p:
+    """ep_layout + ep_dispatch in one call; returns the handle."""
+    h = ctypes.c_void_p()
+    td = tensor_desc(topk_idx, EP_TAG_TOPK_IDX)
+    bd = ctypes.byref(tensor_desc(expert_base, EP_TAG_EXPERT_BASE)) if expert_base is not None else None
+    ins, outs = _dispatch_tensors(x, recv_x, topk_weights, recv_w, recv_src, recv_count,
+                                  topk_idx if pass_topk_idx else None, recv_scales)
+    _check(load().ep_layout_dispatch(ctypes.byref(h), group, ctypes.byref(td), bd, _descs(ins), len(ins), _descs(outs),
+                                     len(outs), _stream_ptr(stream)), "ep_layout_dispatch")
+    return h
+
+
+def ep_dispatch(handle, x: torch.Tensor, recv_x: torch.Tensor, topk_weights: Optional[torch.Tensor] = None,
+                recv_w: Optional[torch.Tensor] = None, recv_src: Optional[torch.Tensor] = None,
+                recv_count: Optional[torch.Tensor] = None, send_only: int = 0, stream=None,
+                topk_idx: Optional[torch.Tensor] = None, recv_scales: Optional[torch.Tensor] = None) -> None:
+    ins, outs = _dispatch_tensors(x, recv_x, topk_weights, recv_w, recv_src, recv_count, topk_idx, recv_scales)
     _check(load().ep_dispatch(handle, _descs(ins), len(ins), _descs(outs), len(outs), send_only,
                               _stream_ptr(stream)), "ep_dispatch")
 
@@ -389,21 +414,32 @@ class PreparedCall:
 
 def prepare_dispatch(x, recv_x, topk_weights=None, recv_w=None, recv_src=None, recv_count=None,
                      topk_idx=None, recv_scales=None) -> PreparedCall:
-    ins = [(x, EP_TAG_TOKENS)]
-    if topk_weights is not None:
-        ins.append((topk_weights, EP_TAG_TOPK_WEIGHTS))
-    if topk_idx is not None:
-        ins.append((topk_idx, EP_TAG_TOPK_IDX))
-    outs = [(recv_x, EP_TAG_TOKENS)]
-    if recv_w is not None:
-        outs.append((recv_w, EP_TAG_TOPK_WEIGHTS))
-    if recv_src is not None:
-        outs.append((recv_src, EP_TAG_RECV_SRC_TOKEN))
-    if recv_count is not None:
-        outs.append((recv_count, EP_TAG_RECV_EXPERT_COUNTER_DEVICE))
-    if recv_scales is not None:
-        outs.append((recv_scales, EP_TAG_SCALES))
+    ins, outs = _dispatch_tensors(x, recv_x, topk_weights, recv_w, recv_src, recv_count, topk_idx, recv_scales)
     return PreparedCall("ep_dispatch", ins, outs)
+
+
+class PreparedLayoutDispatch:
+    """ep_layout_dispatch with its descriptors built once; calling it returns the handle."""
+
+    def __init__(self, group, topk_idx, x, recv_x, topk_weights=None, recv_w=None, recv_src=None, recv_count=None,
+                 expert_base=None):
+        self._fn = load().ep_layout_dispatch
+        self._group = group
+        ins, outs = _dispatch_tensors(x, recv_x, topk_weights, recv_w, recv_src, recv_count)
+        self._keep = [topk_idx, expert_base] + [t for t, _ in ins] + [t for t, _ in outs]
+        self._td = tensor_desc(topk_idx, EP_TAG_TOPK_IDX)
+        self._bd = tensor_desc(expert_base, EP_TAG_EXPERT_BASE) if expert_base is not None else None
+        self._ins, self._n_in = _descs(ins), len(ins)
+        self._outs, self._n_out = _descs(outs), len(outs)
+
+    def __call__(self, stream_ptr: int = 0) -> ctypes.c_void_p:
+        h = ctypes.c_void_p()
+        code = self._fn(ctypes.byref(h), self._group, ctypes.byref(self._td),
+                        ctypes.byref(self._bd) if self._bd is not None else None, self._ins, self._n_in,
+                        self._outs, self._n_out, stream_ptr)
+        if code != EP_SUCCESS:
+            raise EpError(code, "ep_layout_dispatch")
+        return h
 
 
 def prepare_combine(y, out, topk_weights=None) -> PreparedCall:

@@ -469,8 +469,11 @@ ep_result_t ep_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk
     return ep_layout_prefetch(handle, g, topk_idx, expert_base, nullptr, stream);
 }
 
-ep_result_t ep_layout_prefetch(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk_idx,
-                               const ep_tensor_t* expert_base, const ep_tensor_t* tokens, ep_stream_t stream) {
+// Validates a layout call, takes a slab for the new handle and fills the kernel arguments;
+// launches nothing.  On success *handle is live (ep_handle_destroy releases it).
+static ep_result_t prepare_layout(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk_idx,
+                                  const ep_tensor_t* expert_base, const ep_tensor_t* tokens, ep_stream_t stream,
+                                  LayoutArgs* args) {
     if (!handle || !g || !topk_idx) return EP_ERR_INVALID_ARG;
     const ep_group_config_t& c = g->cfg;
     if (topk_idx->tag != EP_TAG_TOPK_IDX || topk_idx->ndim != 2 || topk_idx->dtype != EP_DTYPE_I32)
@@ -526,6 +529,7 @@ ep_result_t ep_layout_prefetch(ep_handle_t* handle, ep_group_t g, const ep_tenso
     // the table of run starts is only wanted by the destination-ordered dispatch
     a.run_start = (c.dispatch_order != EP_ORDER_TOKEN && c.dispatch_path == EP_PATH_DIRECT) ? s.run_start : nullptr;
     a.warm_x = nullptr; a.warm_stride = 0; a.warm_rows = 0; a.warm_units = c.hidden / 8; a.nchunks = 1;
+    a.rows_cap = -1; a.recv_count = nullptr;
     if (tokens && a.run_start && c.dispatch_order == EP_ORDER_DESTINATION) {
         a.warm_x = (const uint16_t*)tokens->data;
         a.warm_stride = tokens->stride[0];
@@ -539,6 +543,16 @@ ep_result_t ep_layout_prefetch(ep_handle_t* handle, ep_group_t g, const ep_tenso
     h->has_runs = layout_writes_runs(a);
     h->nwc = a.nwc;
     h->chunk_entries = a.passes * kWave;
+    *args = a;
+    *handle = h;
+    return EP_SUCCESS;
+}
+
+ep_result_t ep_layout_prefetch(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk_idx,
+                               const ep_tensor_t* expert_base, const ep_tensor_t* tokens, ep_stream_t stream) {
+    LayoutArgs a;
+    ep_handle_t h = nullptr;
+    if (ep_result_t r = prepare_layout(&h, g, topk_idx, expert_base, tokens, stream, &a); r != EP_SUCCESS) return r;
     if (launch_layout(a, (hipStream_t)stream) != hipSuccess) {
         ep_handle_destroy(h);
         return EP_ERR_HIP;
@@ -591,15 +605,19 @@ ep_result_t ep_handle_destroy(ep_handle_t h) {
     return EP_SUCCESS;
 }
 
-ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inputs,
-                        const ep_tensor_t* outputs, int32_t num_outputs, int32_t send_only,
-                        ep_stream_t stream) {
-    if (!h || !inputs || !outputs || num_inputs < 1 || num_outputs < 1) return EP_ERR_INVALID_ARG;
-    if (send_only != 0 && send_only != 1) return EP_ERR_INVALID_ARG;
+// The tensors of a dispatch call, checked against the group and turned into kernel arguments
+// (everything but what depends on the handle's bookkeeping).
+struct DispatchCall {
+    DispatchArgs a;
+    bool fp8;
+    float* scales;
+    const ep_tensor_t* x;
+};
+
+static ep_result_t parse_dispatch(ep_group_s* g, int T, const Slab& slab, const ep_tensor_t* inputs, int32_t num_inputs,
+                                  const ep_tensor_t* outputs, int32_t num_outputs, DispatchCall* call) {
+    if (!inputs || !outputs || num_inputs < 1 || num_outputs < 1) return EP_ERR_INVALID_ARG;
     if (has_scales(inputs, num_inputs)) return EP_ERR_UNSUPPORTED;  // inputs are bf16 tokens
-    ep_group_s* g = h->group;
-    if (send_only && g->nsets == 0) return EP_ERR_UNSUPPORTED;
-    if (send_only && h->pending != PENDING_NONE) return EP_ERR_BUSY;
     const ep_group_config_t& c = g->cfg;
     const ep_tensor_t* x = find_tag(inputs, num_inputs, EP_TAG_TOKENS);
     const ep_tensor_t* w = find_tag(inputs, num_inputs, EP_TAG_TOPK_WEIGHTS);
@@ -609,14 +627,14 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     const ep_tensor_t* rq = find_tag(outputs, num_outputs, EP_TAG_SCALES);
     const ep_tensor_t* rc = find_tag(outputs, num_outputs, EP_TAG_RECV_EXPERT_COUNTER_DEVICE,
                                      EP_TAG_RECV_EXPERT_COUNTER_HOST, EP_TAG_TOKENS_PER_EXPERTS);
-    if (!check_2d(x, EP_DTYPE_BF16, h->T, c.hidden, true) || x->stride[0] % 8 || !aligned16(x->data))
+    if (!check_2d(x, EP_DTYPE_BF16, T, c.hidden, true) || x->stride[0] % 8 || !aligned16(x->data))
         return EP_ERR_INVALID_ARG;
-    if (w && !check_2d(w, EP_DTYPE_F32, h->T, c.top_k, true)) return EP_ERR_INVALID_ARG;
+    if (w && !check_2d(w, EP_DTYPE_F32, T, c.top_k, true)) return EP_ERR_INVALID_ARG;
     // An FP8 output selects the quantising dispatch (Sec. III-E: the tags tell the library
     // which tensors to expect -- FP8 tokens come with a SCALES tensor).
     const bool fp8 = rx && rx->dtype == EP_DTYPE_FP8_E4M3;
     if (fp8 != (rq != nullptr)) return EP_ERR_INVALID_ARG;
-    DispatchArgs a;
+    DispatchArgs& a = call->a;
     if (!window_from_tensor(g, rx, &a.win, fp8 ? EP_DTYPE_FP8_E4M3 : EP_DTYPE_BF16)) return EP_ERR_INVALID_ARG;
     if (fp8) {
         if (c.hidden % 128 != 0) return EP_ERR_INVALID_ARG;
@@ -631,18 +649,39 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     a.x_stride = x->stride[0];
     a.w = w ? (const float*)w->data : nullptr;
     a.w_stride = w ? w->stride[0] : 0;
-    a.dst_row = h->slab.dst_row;
+    a.dst_row = slab.dst_row;
     a.recv_w = rw ? (float*)rw->data : nullptr;
     a.recv_src = rs ? (int32_t*)rs->data : nullptr;
     a.recv_count = rc ? (int32_t*)rc->data : nullptr;
-    a.expert_kept = h->slab.expert_kept;
-    a.totals = h->slab.totals;
-    a.T = h->T; a.K = c.top_k; a.H = c.hidden; a.E = c.num_experts;
-    a.sorted_token = h->slab.sorted_token; a.sorted_k = h->slab.sorted_k; a.sorted_row = h->slab.sorted_row;
-    a.own_prefix = h->slab.own_prefix;
+    a.expert_kept = slab.expert_kept;
+    a.totals = slab.totals;
+    a.T = T; a.K = c.top_k; a.H = c.hidden; a.E = c.num_experts;
+    a.sorted_token = slab.sorted_token; a.sorted_k = slab.sorted_k; a.sorted_row = slab.sorted_row;
+    a.own_prefix = slab.own_prefix;
+    a.run_start = nullptr; a.nwc = 0; a.chunk_entries = 0; a.order = c.dispatch_order; a.prefetched_rows = 0;
+    call->fp8 = fp8;
+    call->scales = rq ? (float*)rq->data : nullptr;
+    call->x = x;
+    return EP_SUCCESS;
+}
+
+ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inputs,
+                        const ep_tensor_t* outputs, int32_t num_outputs, int32_t send_only,
+                        ep_stream_t stream) {
+    if (!h) return EP_ERR_INVALID_ARG;
+    if (send_only != 0 && send_only != 1) return EP_ERR_INVALID_ARG;
+    ep_group_s* g = h->group;
+    if (send_only && g->nsets == 0) return EP_ERR_UNSUPPORTED;
+    if (send_only && h->pending != PENDING_NONE) return EP_ERR_BUSY;
+    const ep_group_config_t& c = g->cfg;
+    DispatchCall call;
+    if (ep_result_t r = parse_dispatch(g, h->T, h->slab, inputs, num_inputs, outputs, num_outputs, &call); r != EP_SUCCESS)
+        return r;
+    DispatchArgs& a = call.a;
+    const bool fp8 = call.fp8;
+    const ep_tensor_t* x = call.x;
     a.run_start = h->has_runs ? h->slab.run_start : nullptr;
     a.nwc = h->nwc; a.chunk_entries = h->chunk_entries;
-    a.order = c.dispatch_order;
     // the read-ahead of the layout call is good for the dispatch that follows it, once
     a.prefetched_rows = (h->warm_x == x->data && h->warm_stride == x->stride[0]) ? h->warm_rows : 0;
     h->warm_x = nullptr;
@@ -659,7 +698,7 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
         // per-expert counts are delivered by ep_complete from the coordination counters
         int32_t* recv_count = a.recv_count;
         if (send_only) a.recv_count = nullptr;
-        hipError_t e = fp8 ? launch_dispatch_fp8(a, (float*)rq->data, (hipStream_t)stream)
+        hipError_t e = fp8 ? launch_dispatch_fp8(a, call.scales, (hipStream_t)stream)
                            : launch_dispatch(a, (hipStream_t)stream);
         if (e != hipSuccess) return EP_ERR_HIP;
         if (send_only) {
@@ -722,6 +761,35 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     }
     if (launch_dedup_rank(ra, (hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
     return launch_dedup_fanout(fa, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+}
+
+ep_result_t ep_layout_dispatch(ep_handle_t* handle, ep_group_t g, const ep_tensor_t* topk_idx,
+                               const ep_tensor_t* expert_base, const ep_tensor_t* inputs, int32_t num_inputs,
+                               const ep_tensor_t* outputs, int32_t num_outputs, ep_stream_t stream) {
+    if (!handle || !g || !inputs || num_inputs < 1) return EP_ERR_INVALID_ARG;
+    LayoutArgs la;
+    ep_handle_t h = nullptr;
+    // the tokens are announced to the layout, as ep_layout_prefetch would
+    const ep_tensor_t* x = find_tag(inputs, num_inputs, EP_TAG_TOKENS);
+    if (ep_result_t r = prepare_layout(&h, g, topk_idx, expert_base, x, stream, &la); r != EP_SUCCESS) return r;
+    DispatchCall call;
+    ep_result_t r = parse_dispatch(g, h->T, h->slab, inputs, num_inputs, outputs, num_outputs, &call);
+    if (r == EP_SUCCESS) {
+        if (!call.fp8 && g->cfg.dispatch_path == EP_PATH_DIRECT && layout_dispatch_fusable(la, call.a)) {
+            h->warm_x = nullptr;
+            h->warm_rows = 0;
+            if (launch_layout_dispatch(la, call.a, (hipStream_t)stream) != hipSuccess) r = EP_ERR_HIP;
+        } else {
+            if (launch_layout(la, (hipStream_t)stream) != hipSuccess) r = EP_ERR_HIP;
+            else r = ep_dispatch(h, inputs, num_inputs, outputs, num_outputs, 0, stream);
+        }
+    }
+    if (r != EP_SUCCESS) {
+        ep_handle_destroy(h);
+        return r;
+    }
+    *handle = h;
+    return EP_SUCCESS;
 }
 
 ep_result_t ep_complete(ep_handle_t h, const ep_complete_config_t* cfg, ep_stream_t stream) {
@@ -861,6 +929,7 @@ ep_result_t ep_layout_static(const ep_group_config_t* cfg, const ep_tensor_t* to
     a.sorted_token = out->sorted_token; a.sorted_k = out->sorted_k; a.sorted_row = out->sorted_row;
     a.run_start = nullptr;
     a.warm_x = nullptr; a.warm_stride = 0; a.warm_rows = 0; a.warm_units = c.hidden / 8; a.nchunks = 1;
+    a.rows_cap = -1; a.recv_count = nullptr;
     return launch_layout(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
 }
 

@@ -18,15 +18,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KB = 8;  // rows gathered per batch of loads
 
-__device__ __forceinline__ int64_t window_offset(const WindowDesc& w, int row) {
-    if (w.padded) {
-        const int e = row / w.C;
-        const int s = row - e * w.C;
-        return (int64_t)e * w.stride0 + (int64_t)s * w.stride1;
-    }
-    return (int64_t)row * w.stride0;
-}
-
 __device__ __forceinline__ float bf16_lo(uint32_t p) { return __uint_as_float(p << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
 

@@ -28,15 +28,6 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ int64_t window_offset(const WindowDesc& w, int row) {
-    if (w.padded) {
-        const int e = row / w.C;
-        const int s = row - e * w.C;
-        return (int64_t)e * w.stride0 + (int64_t)s * w.stride1;
-    }
-    return (int64_t)row * w.stride0;
-}
-
 __global__ __launch_bounds__(256) void dedup_send_kernel(DedupSendArgs a, int nseg, int units) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

@@ -64,6 +64,8 @@ struct LayoutArgs {
     int64_t warm_stride;
     int warm_rows, warm_units;  // rows to read, 16-byte units per row
     int nchunks;              // workgroups of the slot kernel that lay out (set by launch_layout)
+    int64_t rows_cap;         // a launch that also dispatches: rows its output takes (more are flagged); else -1
+    int32_t* recv_count;      // such a launch: where the caller wants the rows placed per expert [E]; else nullptr
     int32_t* run_start;       // [nwc+1, E] or nullptr: first sorted position of expert e among the entries
                               // of wave-chunks >= c (row c); only the histogram kernels fill it
 };
@@ -79,6 +81,16 @@ struct WindowDesc {
     int padded;
     int C;
 };
+
+// Element offset of logical row `row` of a window (see WindowDesc).
+__device__ __forceinline__ int64_t window_offset(const WindowDesc& w, int row) {
+    if (w.padded) {
+        const int e = row / w.C;
+        const int s = row - e * w.C;
+        return (int64_t)e * w.stride0 + (int64_t)s * w.stride1;
+    }
+    return (int64_t)row * w.stride0;
+}
 
 struct DispatchArgs {
     const uint16_t* x;
@@ -173,6 +185,10 @@ struct DedupRankArgs {
 };
 
 hipError_t launch_layout(const LayoutArgs& a, hipStream_t s);
+// Layout and direct dispatch of a small input in one launch (see ep_layout.hip); `fusable` says
+// whether the pair qualifies.
+bool layout_dispatch_fusable(const LayoutArgs& a, const DispatchArgs& d);
+hipError_t launch_layout_dispatch(const LayoutArgs& a, const DispatchArgs& d, hipStream_t s);
 hipError_t launch_dedup_rank(const DedupRankArgs& a, hipStream_t s);
 hipError_t launch_dedup_send(const DedupSendArgs& a, hipStream_t s);
 hipError_t launch_dedup_fanout(const DedupFanoutArgs& a, hipStream_t s);

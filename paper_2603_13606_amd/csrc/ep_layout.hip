@@ -6,10 +6,7 @@
 // expert: a stable counting sort.  No atomic decides an order anywhere (atomics
 // only add counts or set bits), so the output is a pure function of the input.
 //
-// Up to 1024 entries (the decode regime): one workgroup, one entry per thread, one
-// bitmap per bin; slot = popcount of the bits below the entry (layout_bitmap_kernel).
-//
-// Larger inputs: the flattened entry list is cut into chunks, one per workgroup of up
+// The flattened entry list is cut into chunks, one per workgroup of up
 // to 16 wavefronts, and every chunk into wave-chunks of 64*passes consecutive entries,
 // one per wavefront.  ONE launch (Sec. IV-C "Token Count": the count runs next to the
 // send, not as a phase of its own):
@@ -36,6 +33,8 @@
 // wave), so every phase issues all of its global loads before it waits for any of
 // them and the workgroup barriers order LDS traffic only.
 #include "ep_internal.h"
+
+#include <algorithm>
 
 namespace ep {
 namespace {
@@ -351,8 +350,9 @@ __device__ void block_scan_totals(const LayoutArgs& a, const Lds& l, int tid, in
 }
 
 // The per-expert / per-rank arrays and the totals block (all but the status word) in
-// global memory, from tot and S in LDS.  By every thread of one workgroup.
-__device__ void write_tables(const LayoutArgs& a, const Lds& l, int tid, int lane, int w) {
+// global memory, from tot and S in LDS.  By every thread of one workgroup.  Returns one past
+// the highest destination row (in wave 0; other waves get 0).
+__device__ int write_tables(const LayoutArgs& a, const Lds& l, int tid, int lane, int w) {
     const int32_t* tot = l.tot;
     const int32_t* S = l.S;
     const int E = a.E, R = a.R;
@@ -360,6 +360,7 @@ __device__ void write_tables(const LayoutArgs& a, const Lds& l, int tid, int lan
         const int v = tot[e];
         a.expert_count[e] = v;
         a.expert_kept[e] = a.padded ? min(v, a.C) : v;
+        if (a.recv_count) a.recv_count[e] = a.padded ? min(v, a.C) : v;
         a.expert_offset[e] = first_row(a, l, e);
         a.own_prefix[e] = S[e];
         if (a.run_start) a.run_start[e] = S[e];  // row 0: nothing precedes the first wave-chunk
@@ -373,7 +374,7 @@ __device__ void write_tables(const LayoutArgs& a, const Lds& l, int tid, int lan
             a.rank_offset[d] = first_slot(a, l, d);
         }
     }
-    if (w != 0) return;
+    if (w != 0) return 0;
     // wave 0: the sums over all experts
     int kept = 0, dropped = 0, rend = 0;
     for (int e = lane; e < E; e += kWave) {
@@ -386,9 +387,9 @@ __device__ void write_tables(const LayoutArgs& a, const Lds& l, int tid, int lan
     kept = wave_sum(kept);
     dropped = wave_sum(dropped);
     rend = wave_max(rend);
+    const int total_e = S[E];
+    const int rows_end = a.padded ? E * a.C : (a.expert_base ? rend : total_e);
     if (lane == 0) {
-        const int total_e = S[E];
-        const int rows_end = a.padded ? E * a.C : (a.expert_base ? rend : total_e);
         a.expert_offset[E] = rows_end;
         a.own_prefix[E] = total_e;
         a.totals[TOT_KEPT] = kept;
@@ -399,6 +400,7 @@ __device__ void write_tables(const LayoutArgs& a, const Lds& l, int tid, int lan
         a.totals[TOT_MSGS] = S[a.W - 1] + tot[a.W - 1] - S[E + 2];  // the rank bins are the last R bins
         a.totals[TOT_ROWS_END] = rows_end;
     }
+    return rows_end;
 }
 
 // The status word of the totals block.  One wavefront; must be called by all 64 lanes.
@@ -479,21 +481,15 @@ __device__ __forceinline__ void look_across(const LayoutArgs& a, int c, int r0, 
 // MULTI: more than one chunk.  ONE_GROUP: a wave's entries fit one load group (at most PU
 // passes) and stay in registers from the histogram to the emit.
 template <bool MULTI, bool ONE_GROUP>
-__global__ __launch_bounds__(1024) void layout_kernel(LayoutArgs a) {
-    extern __shared__ int32_t lds[];
-    if ((int)blockIdx.x >= a.nchunks) {  // a whole workgroup: no barrier below is reached by part of one
-        warm_tokens(a, blockIdx.x - a.nchunks, gridDim.x - a.nchunks);
-        return;
-    }
+__device__ __forceinline__ void layout_chunk(const LayoutArgs& a, int32_t* lds, const int b) {
     const int wpb = blockDim.x >> 6;
     const Lds l = carve_lds(lds, a, wpb);
     const int W = a.W;
     const int tid = threadIdx.x;
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wc = blockIdx.x * wpb + w;
+    const int wc = b * wpb + w;
     const int nchunks = a.nchunks;
-    const int b = blockIdx.x;
     const bool active = wc < a.nwc;
     constexpr bool one_group = ONE_GROUP, multi = MULTI;
 
@@ -624,10 +620,11 @@ __global__ __launch_bounds__(1024) void layout_kernel(LayoutArgs a) {
     //     walk so that the walk is not held up.  The status word comes from one wavefront:
     //     with several chunks wave 0 of the workgroup that finished looking across last,
     //     which then also leaves the cross-workgroup words ready for the next launch
-    if (b == 0) write_tables(a, l, tid, lane, w);
+    int rows_end = 0;
+    if (b == 0) rows_end = write_tables(a, l, tid, lane, w);
     if (w != 0) return;
-    if (!multi) {
-        write_status(a, l, lane, 0);
+    if (!multi) {  // the caller of a fused launch says how many rows its output takes
+        write_status(a, l, lane, (!a.padded && a.rows_cap >= 0 && rows_end > a.rows_cap) ? STATUS_OUTPUT_OVERFLOW : 0);
         return;
     }
     const uint32_t seen = __builtin_amdgcn_readfirstlane(ticket) + mine;  // lane 0 holds the ticket
@@ -644,73 +641,102 @@ __global__ __launch_bounds__(1024) void layout_kernel(LayoutArgs a) {
     }
 }
 
-// ---- inputs of at most 1024 entries: one workgroup, one entry per thread, bitmaps ----
-//
-// Every bin keeps one bit per entry (a 64-bit word per wavefront).  An entry sets its bit;
-// its slot is the number of set bits below its own position in the bitmap of its bin --
-// a handful of independent LDS reads and popcounts instead of a histogram, a scan across
-// waves and a ballot walk.  Bits are set with atomic ORs, whose result does not depend on
-// their order.
-constexpr int kBitmapWords = 16;   // words per bitmap: one per wavefront of a 1024-thread workgroup
-constexpr int kBitmapStride = 17;  // row stride in words: odd, so that the rows start in different LDS banks
-
-size_t bitmap_lds_bytes(const LayoutArgs& a) {
-    return 8 * (size_t)(a.E + a.R) * kBitmapStride + sizeof(int32_t) * (3 * (size_t)a.W + kLayoutWavesPerBlock);
-}
-
-// Set bits of a bitmap row below position (w, lane): all 16 words are read at once.
-__device__ __forceinline__ int bits_below(const uint64_t* row, int w, uint64_t below_in_word) {
-    uint64_t v[kBitmapWords];
-#pragma unroll
-    for (int j = 0; j < kBitmapWords; ++j) v[j] = row[j];
-    int n = 0;
-#pragma unroll
-    for (int j = 0; j < kBitmapWords; ++j) {
-        const uint64_t m = j < w ? ~0ull : (j == w ? below_in_word : 0ull);
-        n += __popcll(v[j] & m);
-    }
-    return n;
-}
-
-__global__ __launch_bounds__(1024) void layout_bitmap_kernel(LayoutArgs a) {
+template <bool MULTI, bool ONE_GROUP>
+__global__ __launch_bounds__(1024) void layout_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
-    const int nbins = a.E + a.R;  // expert bitmaps, then destination-rank bitmaps
-    uint64_t* bm = (uint64_t*)lds;
-    Lds l;
-    l.wh = nullptr;
-    l.tot = lds + 2 * nbins * kBitmapStride;
-    l.S = l.tot + a.W;
-    l.before = l.S + a.W;  // stays zero: there is only this chunk
-    l.wsum = l.before + a.W;
-    l.flag = nullptr;
+    if ((int)blockIdx.x >= a.nchunks) {  // a whole workgroup: no barrier is reached by part of one
+        warm_tokens(a, blockIdx.x - a.nchunks, gridDim.x - a.nchunks);
+        return;
+    }
+    layout_chunk<MULTI, ONE_GROUP>(a, lds, blockIdx.x);
+}
+
+// ---- layout and direct dispatch of a small input in ONE launch (Sec. IV-C: in the
+// low-latency kernels the count runs next to the send) ----
+//
+// For an input of at most 1024 entries (one per thread of a workgroup).  Workgroup 0 is the
+// layout above, single chunk, and writes the handle's arrays, which combine and the queries
+// read later.  Every other workgroup copies a share of one token row -- work unit = one
+// wavefront x one 1 KiB segment, `spp` segments per workgroup, `parts` workgroups per token
+// -- and needs only the destination rows of that token's K entries, which it counts out of
+// the ids directly: row of entry (t, k) naming expert e = first row of e + number of entries
+// before (t, k) that name e, the first row being the number of entries that name a lower
+// expert (or e * C, or the caller's).  Counting = one ballot per wavefront and target over
+// the ids its lanes hold, summed over the wavefronts through LDS.  Same ids, same
+// arithmetic as the layout: the rows are those workgroup 0 records.  No workgroup waits
+// for another.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(1024) void layout_dispatch_kernel(LayoutArgs a, DispatchArgs d, int nseg, int units, int parts,
+                                                               int spp) {
+    extern __shared__ int32_t lds[];
+    if (blockIdx.x == 0) {
+        layout_chunk<false, true>(a, lds, 0);
+        return;
+    }
     const int tid = threadIdx.x;
     const int lane = lane_id();
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    int raw[PU];
-    issue_group(a, w, 0, lane, raw);  // one pass: the entry of this thread
-    for (int j = tid; j < nbins * kBitmapStride; j += blockDim.x) bm[j] = 0ull;
-    for (int j = tid; j < 3 * a.W + kLayoutWavesPerBlock; j += blockDim.x) l.tot[j] = 0;  // tot, S, before, wsum
-    lds_barrier();
-    Entry en[PU];
-    classify_group(a, w, 0, lane, raw, en);
-    const Entry& x = en[0];
-    const uint64_t bit = 1ull << lane;
-    if (x.ok) atomicOr((unsigned long long*)&bm[x.e * kBitmapStride + w], (unsigned long long)bit);
-    if (x.lead) atomicOr((unsigned long long*)&bm[(a.E + x.d) * kBitmapStride + w], (unsigned long long)bit);
-    const uint64_t bmask = __ballot(x.masked), binv = __ballot(x.invalid);
-    if (lane == 0) {
-        if (bmask) atomicAdd(&l.tot[a.E], __popcll(bmask));
-        if (binv) atomicAdd(&l.tot[a.E + 1], __popcll(binv));
+    const int nw = blockDim.x >> 6;
+    const int wg = blockIdx.x - 1;
+    const int t = wg / parts;
+    const int seg = (wg - t * parts) * spp + w;
+    const bool copies = w < spp && seg < nseg;
+    const int unit = seg * kWave + lane;
+    const bool active = copies && unit < units;
+    // the loads this wave needs, all issued before any is waited for: its piece of the
+    // token, the id of the entry this thread stands for, the token's K ids and gate weights
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (active) v = __builtin_nontemporal_load((const u32x4*)(d.x + (int64_t)t * d.x_stride) + unit);
+    int id = -1;
+    if (tid < a.n) {
+        const int ti = token_of(a, tid);
+        id = a.topk[(int64_t)ti * a.topk_stride + (tid - ti * a.K)];
     }
+    const int my_e = lane < a.K ? a.topk[(int64_t)t * a.topk_stride + lane] : -1;
+    float my_w = 1.0f;
+    if (copies && seg == 0 && d.w && lane < a.K) my_w = d.w[(int64_t)t * d.w_stride + lane];
+    int my_base = 0;
+    if (!a.padded && a.expert_base && lane < a.K && (unsigned)my_e < (unsigned)a.E) my_base = a.expert_base[my_e];
+    // per target k (lane k keeps its counts): entries of this wave that name the same expert
+    // and come before (t, k), and entries of this wave that name a lower expert
+    int same_before = 0, lower = 0;
+    const int first = t * a.K;
+    for (int k = 0; k < a.K; ++k) {
+        const int e = __builtin_amdgcn_readlane(my_e, k);
+        const uint64_t m_same = __ballot(id == e && tid < first + k);
+        const uint64_t m_lower = __ballot((unsigned)id < (unsigned)e);  // ids that are not routed compare high
+        if (lane == k) {
+            same_before = __popcll(m_same);
+            lower = __popcll(m_lower);
+        }
+    }
+    int32_t* part_same = lds;                    // [nw][64]
+    int32_t* part_lower = lds + nw * kWave;      // [nw][64]
+    part_same[w * kWave + lane] = same_before;
+    part_lower[w * kWave + lane] = lower;
     lds_barrier();
-    for (int c = tid; c < nbins; c += blockDim.x)  // totals per bin
-        l.tot[c < a.E ? c : c + 2] = bits_below(bm + c * kBitmapStride, kBitmapWords, 0ull);
-    const int slot = x.ok ? bits_below(bm + x.e * kBitmapStride, w, bit - 1) : -1;
-    const int rslot = x.lead ? bits_below(bm + (a.E + x.d) * kBitmapStride, w, bit - 1) : -1;
-    block_scan_totals(a, l, tid, lane, w, blockDim.x >> 6);
-    emit_entry(a, x, slot, rslot, l);
-    write_tables(a, l, tid, lane, w);
-    if (w == 0) write_status(a, l, lane, 0);
+    if (!copies) return;
+    int slot = 0, start = 0;
+    for (int r = 0; r < nw; ++r) {
+        slot += part_same[r * kWave + lane];
+        start += part_lower[r * kWave + lane];
+    }
+    int my_row = -1;
+    if (lane < a.K && (unsigned)my_e < (unsigned)a.E) {
+        if (a.padded) my_row = slot < a.C ? my_e * a.C + slot : -1;
+        else my_row = (a.expert_base ? my_base : start) + slot;
+    }
+    for (int k = 0; k < a.K; ++k) {
+        const int row = __builtin_amdgcn_readlane(my_row, k);
+        if (row < 0 || row >= d.win.rows_cap) continue;  // rows beyond the output are flagged by workgroup 0
+        uint16_t* dst = d.win.base + window_offset(d.win, row);
+        if (active) __builtin_nontemporal_store(v, (u32x4*)dst + unit);
+        if (seg == 0 && lane == 0) {
+            if (d.recv_w) d.recv_w[row] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), k));
+            if (d.recv_src) d.recv_src[row] = t;
+        }
+    }
 }
 
 constexpr size_t kLdsLimit = 64 * 1024;
@@ -730,16 +756,42 @@ void plan_layout(int n, int* passes, int* nwc) {
     *nwc = (n + kWave * p - 1) / (kWave * p);
 }
 
-static bool use_bitmap(const LayoutArgs& a) {
-    return a.passes == 1 && a.nwc >= 1 && a.nwc <= kLayoutWavesPerBlock && bitmap_lds_bytes(a) <= kLdsLimit;
-}
-
-bool layout_writes_runs(const LayoutArgs& a) { return a.run_start != nullptr && !use_bitmap(a); }
+bool layout_writes_runs(const LayoutArgs& a) { return a.run_start != nullptr; }
 
 // The read-ahead rides on the layout kernel of inputs that are laid out by several workgroups.
 bool layout_prefetches(const LayoutArgs& a) {
-    return a.warm_x != nullptr && a.warm_rows > 0 && a.n >= kRunOrderMinEntries && !use_bitmap(a) &&
-           a.nwc > kLayoutWavesPerBlock;
+    return a.warm_x != nullptr && a.warm_rows > 0 && a.n >= kRunOrderMinEntries && a.nwc > kLayoutWavesPerBlock;
+}
+
+constexpr int kFusedMaxEntries = kLayoutWavesPerBlock * kWave;  // one entry per thread of a workgroup
+
+// The one-launch path takes inputs of at most 1024 entries, copied by the plain token-ordered
+// walk (bf16 rows, the K entries of a token held by the lanes of one wave).
+bool layout_dispatch_fusable(const LayoutArgs& a, const DispatchArgs& d) {
+    return a.n >= 1 && a.n <= kFusedMaxEntries && a.passes == 1 && a.K <= kWave && d.H >= 8 &&
+           lds_bytes(a, kLayoutWavesPerBlock) <= kLdsLimit;
+}
+
+hipError_t launch_layout_dispatch(const LayoutArgs& a_in, const DispatchArgs& d, hipStream_t s) {
+    LayoutArgs a = a_in;
+    a.nchunks = 1;
+    if (!layout_dispatch_fusable(a, d)) return hipErrorInvalidValue;
+    a.rows_cap = d.win.rows_cap;
+    a.recv_count = d.recv_count;
+    const int units = d.H / 8;
+    const int nseg = (units + kWave - 1) / kWave;
+    // workgroups per token: enough of them to put every compute unit to work, at most 16 segments each
+    int parts = (nseg + kLayoutWavesPerBlock - 1) / kLayoutWavesPerBlock;
+    while (parts < nseg && (int64_t)a.T * parts < 256) ++parts;
+    const int spp = (nseg + parts - 1) / parts;
+    parts = (nseg + spp - 1) / spp;
+    const int64_t nblk = 1 + (int64_t)a.T * parts;
+    if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    // a thread per entry, a wave per segment, and the 16 waves the layout workgroup is laid out for
+    const size_t lds = std::max(lds_bytes(a, kLayoutWavesPerBlock), sizeof(int32_t) * 2 * kLayoutWavesPerBlock * kWave);
+    hipLaunchKernelGGL(layout_dispatch_kernel, dim3((unsigned)nblk), dim3(kLayoutWavesPerBlock * kWave), lds, s, a, d, nseg,
+                       units, parts, spp);
+    return hipGetLastError();
 }
 
 constexpr int kWarmBlocks = 512;  // extra workgroups of the layout kernel that read tokens
@@ -747,10 +799,6 @@ constexpr int kWarmBlocks = 512;  // extra workgroups of the layout kernel that 
 hipError_t launch_layout(const LayoutArgs& a_in, hipStream_t s) {
     LayoutArgs a = a_in;
     a.nchunks = 1;
-    if (use_bitmap(a)) {
-        hipLaunchKernelGGL(layout_bitmap_kernel, dim3(1), dim3(a.nwc * kWave), bitmap_lds_bytes(a), s, a);
-        return hipGetLastError();
-    }
     // Workgroups of 16 waves, fewer when the bin tables would not fit the LDS otherwise.
     int wpb = kLayoutWavesPerBlock;
     while (wpb > 1 && lds_bytes(a, wpb) > kLdsLimit) wpb >>= 1;

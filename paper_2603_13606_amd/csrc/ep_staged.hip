@@ -60,15 +60,6 @@ __global__ __launch_bounds__(256) void clear_counts_kernel(int32_t* sig, int n) 
         __hip_atomic_store(&sig[i], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ __forceinline__ int64_t window_offset(const WindowDesc& w, int row) {
-    if (w.padded) {
-        const int e = row / w.C;
-        const int s = row - e * w.C;
-        return (int64_t)e * w.stride0 + (int64_t)s * w.stride1;
-    }
-    return (int64_t)row * w.stride0;
-}
-
 // Send phase of a staged combine (Sec. IV-D): the expert side packs its outputs into
 // the source's staging at slot t*K + k -- no wasted slots, O(B*K*P).  Work unit = one
 // wavefront x one 1 KiB segment of one (t, k) entry.

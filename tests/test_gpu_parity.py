@@ -272,7 +272,7 @@ PATH_CASES = [
 ]
 
 
-def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True, order=0, prefetch=False):
+def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True, order=0, prefetch=False, fused=False):
     w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
     spec = w.spec
     T = spec.T
@@ -292,18 +292,23 @@ def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True
     try:
         x = hx.bits_to_dev(w.x_bits)
         d_w = torch.from_numpy(w.topk_w).to(hx.DEV)
-        if prefetch:
-            h = ep.ep_layout_prefetch(g, torch.from_numpy(topk).to(hx.DEV), x)
-            hx.assert_layout_equal(hx.fetch_layout(h, T, spec.K, spec.E, spec.R, ok=(ep.EP_SUCCESS, ep.EP_ERR_INVALID_ROUTING)), lay)
-        else:
-            h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
         store = hx.poison_bf16((rows + guard, spec.H))
         recv = store[:rows].view(spec.E, Cc, spec.H) if ll else store[:rows]
         r_w = torch.full((rows + guard,), -3.5, dtype=torch.float32, device=hx.DEV)
         r_src = torch.full((rows + guard,), -9, dtype=torch.int32, device=hx.DEV)
         r_cnt = torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)
-        ep.ep_dispatch(h, x, recv, topk_weights=d_w if weights else None, recv_w=r_w[:rows] if rows else r_w[:0],
-                       recv_src=r_src[:rows], recv_count=r_cnt)
+        outs = dict(topk_weights=d_w if weights else None, recv_w=r_w[:rows] if rows else r_w[:0],
+                    recv_src=r_src[:rows], recv_count=r_cnt)
+        if fused:  # layout and dispatch in one call (one launch for small inputs)
+            h = ep.ep_layout_dispatch(g, torch.from_numpy(topk).to(hx.DEV), x, recv, **outs)
+            hx.assert_layout_equal(hx.fetch_layout(h, T, spec.K, spec.E, spec.R, ok=(ep.EP_SUCCESS, ep.EP_ERR_INVALID_ROUTING)), lay)
+        else:
+            if prefetch:
+                h = ep.ep_layout_prefetch(g, torch.from_numpy(topk).to(hx.DEV), x)
+                hx.assert_layout_equal(hx.fetch_layout(h, T, spec.K, spec.E, spec.R, ok=(ep.EP_SUCCESS, ep.EP_ERR_INVALID_ROUTING)), lay)
+            else:
+                h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+            ep.ep_dispatch(h, x, recv, **outs)
         torch.cuda.synchronize()
         got = hx.dev_to_bits(store)
         assert np.array_equal(got, o_recv), "dispatched rows differ"
@@ -349,6 +354,122 @@ def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True
 def test_dispatch_combine_parity(ep, hx, oracle_mod, name, T, H, mode, C):
     _say(f"path case {name} T={T} H={H} mode={mode} C={C}")
     _run_path(ep, hx, oracle_mod, name, T, H, mode, C)
+
+
+FUSED_CASES = [
+    # inputs of at most 1024 routed entries: ep_layout_dispatch lays out and dispatches in one launch
+    ("ll_decode", None, None, "ll", 0, 0),     # the decode shape, padded windows
+    ("ll_decode", None, None, "ht", 0, 0),     # concatenated windows
+    ("ll_decode", 127, None, "ll", 16, 0),     # capacity drops, ragged last wave
+    ("ll_decode", 50, 1000, "ht", 0, 1),       # ragged last 1 KiB segment; group set to the destination order
+    ("ll_decode", 50, 8, "ll", 9, 0),          # smallest row: one 16-byte unit
+    ("tiny", None, None, "ht", 0, 0),
+    ("tiny", None, None, "ll", 6, 0),
+    ("tiny", 1, None, "ht", 0, 0),             # one token
+    ("skew", 100, None, "ll", 7, 0),           # 800 entries on 128 experts, most of them dropped
+    ("skew", 128, 4096, "ht", 0, 0),           # exactly 1024 entries
+    ("ll_decode", 129, 512, "ht", 0, 0),       # 1032 entries: falls back to two launches
+    ("ht_prefill", 1500, 256, "ht", 0, 1),     # large input: two launches, destination order with read-ahead
+]
+
+
+@pytest.mark.parametrize("weights", [True, False])
+@pytest.mark.parametrize("name,T,H,mode,C,order", FUSED_CASES)
+def test_layout_dispatch_one_call_parity(ep, hx, oracle_mod, name, T, H, mode, C, order, weights):
+    """ep_layout_dispatch = ep_layout + ep_dispatch: every array of the layout, the dispatched rows,
+    side arrays and counts equal the oracle's, untouched rows stay untouched, and combine on the
+    handle it returns is unchanged."""
+    _say(f"one-call case {name} T={T} H={H} mode={mode} C={C} order={order} weights={weights}")
+    _run_path(ep, hx, oracle_mod, name, T, H, mode, C, order=order, weights=weights, fused=True)
+
+
+def test_layout_dispatch_one_call_random_shapes(ep, hx, oracle_mod):
+    """Thirty seeded random small configurations (odd expert counts per rank, K up to 64, strided
+    top-k rows, invalid and masked ids, expert_base) through ep_layout_dispatch."""
+    rng = np.random.default_rng(31337)
+    for case in range(30):
+        R = int(rng.choice([1, 2, 3, 4, 8, 16, 32]))
+        L = int(rng.choice([1, 2, 3, 4, 8, 13]))
+        E = R * L
+        K = int(rng.choice([1, 2, 3, 5, 8, 17, 33, 64]))
+        K = min(K, E)
+        T = int(rng.integers(1, 1024 // K + 1))
+        H = int(rng.choice([8, 64, 200, 512, 520, 1024, 7168]))
+        ll = bool(rng.integers(0, 2))
+        C = int(rng.integers(1, max(2, (3 * T * K) // (2 * E) + 2))) if ll else 0
+        use_base = (not ll) and bool(rng.integers(0, 2))
+        spec = wl.WorkloadSpec(f"randsmall{case}", 240 + case, R=R, T=T, H=H, E=E, K=K)
+        w = wl.make_workload(spec)
+        topk = _mess_up(w.topk_idx, E, seed=case, frac_masked=float(rng.choice([0.0, 0.05, 0.5])),
+                        n_invalid=int(rng.integers(0, 3)))
+        base = None
+        if use_base:  # rows of lower-ranked sources precede this source's rows in every expert region
+            cnt = np.bincount(topk[(topk >= 0) & (topk < E)], minlength=E)
+            other = rng.integers(0, 5, size=E)
+            base = (np.concatenate([[0], np.cumsum(cnt + other)[:-1]]) + other // 2).astype(np.int32)
+        _say(f"one-call random case {case}: E={E} R={R} K={K} T={T} H={H} ll={ll} C={C} base={use_base}")
+        lay = oracle_mod.layout(topk, E=E, R=R, layout=int(ll), C=C if ll else 0, C_rank=T, expert_base=base)
+        rows = E * C if ll else int(lay.expert_offset[-1])
+        o_recv = np.full((rows + 1, H), hx.POISON, np.uint16)
+        o_w = np.full(rows + 1, np.float32(-3.5), np.float32)
+        o_src = np.full(rows + 1, -9, np.int32)
+        oracle_mod.dispatch(w.x_bits, w.topk_w, lay, o_recv, o_w, o_src)
+        g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C)
+        try:
+            wide = torch.full((T, K + 3), -1, dtype=torch.int32, device=hx.DEV)  # strided top-k rows
+            wide[:, :K] = torch.from_numpy(topk).to(hx.DEV)
+            store = hx.poison_bf16((rows + 1, H))
+            recv = store[:rows].view(E, C, H) if ll else store[:rows]
+            r_w = torch.full((rows + 1,), -3.5, dtype=torch.float32, device=hx.DEV)
+            r_src = torch.full((rows + 1,), -9, dtype=torch.int32, device=hx.DEV)
+            r_cnt = torch.full((E,), -1, dtype=torch.int32, device=hx.DEV)
+            gate = torch.from_numpy(w.topk_w).to(hx.DEV)
+            h = ep.ep_layout_dispatch(g, wide[:, :K], hx.bits_to_dev(w.x_bits), recv, topk_weights=gate,
+                                      recv_w=r_w[:rows], recv_src=r_src[:rows], recv_count=r_cnt,
+                                      expert_base=torch.from_numpy(base).to(hx.DEV) if use_base else None)
+            got = hx.fetch_layout(h, T, K, E, R, ok=(ep.EP_SUCCESS, ep.EP_ERR_INVALID_ROUTING))
+            hx.assert_layout_equal(got, lay)
+            out = hx.poison_bf16((T, H))
+            ep.ep_combine(h, recv, out, topk_weights=gate)
+            torch.cuda.synchronize()
+            assert np.array_equal(hx.dev_to_bits(store), o_recv), f"case {case}: rows differ"
+            assert np.array_equal(r_w.cpu().numpy(), o_w) and np.array_equal(r_src.cpu().numpy(), o_src)
+            assert np.array_equal(r_cnt.cpu().numpy(), lay.expert_kept)
+            ref = oracle_mod.combine(o_recv[:rows], w.topk_w, lay, H, acc="f32")
+            assert np.array_equal(hx.dev_to_bits(out), ref), f"case {case}: combine differs"
+            ep.ep_handle_destroy(h)
+        finally:
+            ep.ep_group_destroy(g)
+
+
+def test_layout_dispatch_one_call_errors_and_overflow(ep, hx, oracle_mod):
+    """A bad dispatch argument returns no handle and leaves none alive; an output with too few
+    rows is flagged (status bit 2) and not overrun, in the one-launch path as in ep_dispatch."""
+    w = wl.make_workload("ll_decode", T=100, H=256)
+    spec = w.spec
+    g = _group(ep, spec, 100, ep.EP_MODE_HT)
+    try:
+        topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
+        x = hx.bits_to_dev(w.x_bits)
+        lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=100)
+        rows = lay.kept
+        with pytest.raises(ep.EpError) as e:
+            ep.ep_layout_dispatch(g, topk, x[:50], hx.poison_bf16((rows, spec.H)))  # tokens of the wrong length
+        assert e.value.code == ep.EP_ERR_INVALID_ARG
+        assert ep.ep_group_query(g).live_handles == 0
+        short = rows - 37
+        store = hx.poison_bf16((rows, spec.H))
+        h = ep.ep_layout_dispatch(g, topk, x, store[:short])
+        info = ep.ep_handle_query(h, ok=(ep.EP_ERR_OVERFLOW,))
+        assert info.status & ep.STATUS_OUTPUT_OVERFLOW
+        torch.cuda.synchronize()
+        o_recv = np.full((rows, spec.H), hx.POISON, np.uint16)
+        oracle_mod.dispatch(w.x_bits, None, lay, o_recv)
+        o_recv[short:] = hx.POISON
+        assert np.array_equal(hx.dev_to_bits(store), o_recv)
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
 
 
 ORDER_CASES = [
