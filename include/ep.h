@@ -392,6 +392,7 @@ EP_API ep_result_t ep_handle_destroy(ep_handle_t handle);
  * H % 128 == 0 and EP_PATH_DIRECT.  Per token and group of 128 channels:
  * amax = max|x|; scales[row, g] = amax / 448; q = e4m3(f32(x) * (448 / amax)), float32
  * operations, round to nearest even, magnitudes above 448 saturate; amax == 0 gives scale 1.
+ * The quantising dispatch walks the tokens whatever the group's dispatch_order.
  * EP_PATH_RANK_DEDUP runs three steps on the stream -- send to the group's staging
  * windows, receiver-side ranking of the header entries, fan-out -- and produces the
  * same outputs; dispatches of one group must then not overlap (they share the

@@ -16,6 +16,49 @@ namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// One wavefront copies one 1 KiB segment (16-byte unit `seg * 64 + lane` of every lane) of
+// token t to the token's destination rows, in two halves so that a caller can put other
+// work between the loads and the stores.  Both must be called by all 64 lanes.
+struct TokenSegment {
+    u32x4 v;     // the 16 bytes of this lane
+    int my_row;  // lane k: destination row of the token's k-th entry
+};
+
+__device__ __forceinline__ TokenSegment load_token_segment(const DispatchArgs& a, int t, int seg, int units, int lane) {
+    TokenSegment s;
+    const int unit = seg * kWave + lane;
+    s.v = (u32x4){0u, 0u, 0u, 0u};
+    if (unit < units) s.v = __builtin_nontemporal_load((const u32x4*)(a.x + (int64_t)t * a.x_stride) + unit);
+    // lane k fetches the k-th destination row of the token: one load for all K entries
+    s.my_row = lane < a.K ? a.dst_row[(int64_t)t * a.K + lane] : -1;
+    return s;
+}
+
+__device__ __forceinline__ void store_token_segment(const DispatchArgs& a, const TokenSegment& s, int t, int seg, int units,
+                                                    int lane) {
+    const int unit = seg * kWave + lane;
+    const bool active = unit < units;
+    for (int k = 0; k < a.K; ++k) {
+        const int row = __builtin_amdgcn_readlane(s.my_row, k);
+        if (row < 0) continue;
+        if (row >= a.win.rows_cap) {
+            if (seg == 0 && lane == 0) atomicOr(&a.totals[TOT_STATUS], STATUS_OUTPUT_OVERFLOW);
+            continue;
+        }
+        uint16_t* dst = a.win.base + window_offset(a.win, row);
+        if (active) __builtin_nontemporal_store(s.v, (u32x4*)dst + unit);
+        if (seg == 0 && lane == 0) {
+            if (a.recv_w) a.recv_w[row] = a.w ? a.w[(int64_t)t * a.w_stride + k] : 1.0f;
+            if (a.recv_src) a.recv_src[row] = t;
+        }
+    }
+}
+
+__device__ __forceinline__ void copy_token_segment(const DispatchArgs& a, int t, int seg, int units, int lane) {
+    const TokenSegment s = load_token_segment(a, t, seg, units, lane);
+    store_token_segment(a, s, t, seg, units, lane);
+}
+
 __global__ __launch_bounds__(256) void dispatch_direct_kernel(DispatchArgs a, int nseg, int units) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -25,27 +68,7 @@ __global__ __launch_bounds__(256) void dispatch_direct_kernel(DispatchArgs a, in
     }
     if (u >= (int64_t)a.T * nseg) return;
     const int t = (int)(u / nseg);
-    const int seg = (int)(u - (int64_t)t * nseg);
-    const int unit = seg * kWave + lane;
-    const bool active = unit < units;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (active) v = __builtin_nontemporal_load((const u32x4*)(a.x + (int64_t)t * a.x_stride) + unit);
-    // lane k fetches the k-th destination row of the token: one load for all K entries
-    const int my_row = lane < a.K ? a.dst_row[(int64_t)t * a.K + lane] : -1;
-    for (int k = 0; k < a.K; ++k) {
-        const int row = __builtin_amdgcn_readlane(my_row, k);
-        if (row < 0) continue;
-        if (row >= a.win.rows_cap) {
-            if (seg == 0 && lane == 0) atomicOr(&a.totals[TOT_STATUS], STATUS_OUTPUT_OVERFLOW);
-            continue;
-        }
-        uint16_t* dst = a.win.base + window_offset(a.win, row);
-        if (active) __builtin_nontemporal_store(v, (u32x4*)dst + unit);
-        if (seg == 0 && lane == 0) {
-            if (a.recv_w) a.recv_w[row] = a.w ? a.w[(int64_t)t * a.w_stride + k] : 1.0f;
-            if (a.recv_src) a.recv_src[row] = t;
-        }
-    }
+    copy_token_segment(a, t, (int)(u - (int64_t)t * nseg), units, lane);
 }
 
 // ---- run-ordered variant for large inputs
@@ -82,6 +105,34 @@ template <int TPR_SHIFT, bool PADDED>
 __global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunPlan p) {
     if (blockIdx.x == 0 && blockIdx.y == 0 && p.first_block == 0 && a.recv_count) {
         for (int e = threadIdx.x; e < a.E; e += blockDim.x) a.recv_count[e] = a.expert_kept[e];
+    }
+    if (PADDED) {
+        // With most entries cut by the capacity, the rows that remain come from the first tokens
+        // of every hot expert: a few long runs in the first blocks and next to nothing after
+        // them, which this walk balances badly.  The launch then walks the tokens instead (the
+        // plain token order over whatever workgroups the grid has); the layout has left the
+        // counts that decide it in the handle.  The first token segment of the wave is loaded
+        // before the counts are known, so that the decision costs no round trip of its own.
+        const int units = p.units, nseg = (units + kWave - 1) / kWave;
+        const int lane = threadIdx.x & (kWave - 1);
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int64_t nwaves = (int64_t)gridDim.x * gridDim.y * 4, total = (int64_t)a.T * nseg;
+        int64_t u = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave;
+        const bool first = p.first_block == 0 && u < total;
+        const int t0 = first ? (int)(u / nseg) : 0, seg0 = first ? (int)(u - (int64_t)t0 * nseg) : 0;
+        TokenSegment s0;
+        if (first) s0 = load_token_segment(a, t0, seg0, units, lane);
+        const int kept = __builtin_amdgcn_readfirstlane(a.totals[TOT_KEPT]);
+        const int dropped = __builtin_amdgcn_readfirstlane(a.totals[TOT_DROPPED]);
+        if (2 * dropped > kept) {
+            if (!first) return;  // one launch does all of it
+            store_token_segment(a, s0, t0, seg0, units, lane);
+            for (u += nwaves; u < total; u += nwaves) {
+                const int t = (int)(u / nseg);
+                copy_token_segment(a, t, (int)(u - (int64_t)t * nseg), units, lane);
+            }
+            return;
+        }
     }
     constexpr int tpr = 1 << TPR_SHIFT, nsub = 256 >> TPR_SHIFT;
     // grid = (kSlices * splits * E, blocks): x runs fastest, so workgroups are handed out
@@ -181,19 +232,63 @@ void launch_runs(const DispatchArgs& a, const RunPlan& p, int nblocks, hipStream
 // a lane owns 16 consecutive channels (32 bytes in, 16 bytes out), a group is 8 lanes.
 // The row is quantised once and stored K times.
 
-// float32 -> E4M3 code: round to nearest even, saturate above 448, NaN -> 0x7F.
-__device__ __forceinline__ uint32_t f32_to_e4m3(float f) {
-    const uint32_t u = __float_as_uint(f);
-    const uint32_t sign = (u >> 24) & 0x80u;
-    uint32_t a = u & 0x7fffffffu;
-    if (a > 0x7f800000u) return 0x7fu;
-    if (a > 0x43e00000u) return sign | 0x7eu;  // above 448
-    if (a < 0x3c800000u) {                      // below 2^-6: multiples of 2^-9
-        const int m = __float2int_rn(__uint_as_float(a) * 512.0f);
-        return sign | (uint32_t)m;
+// Four float32 -> four E4M3 codes, packed low to high.  The conversion instruction of this
+// part rounds to nearest even exactly as the rule above asks for magnitudes up to 448 and
+// turns anything beyond 464 into NaN, so the value is clamped first (a product can exceed 448
+// only through an overflowing 448 / amax); a NaN product stays NaN and gets the one NaN code
+// this library writes, 0x7F.
+__device__ __forceinline__ float clamp_e4m3(float p) {
+    const float c = fminf(fmaxf(p, -448.0f), 448.0f);
+    return p != p ? p : c;
+}
+
+__device__ __forceinline__ uint32_t pack4_e4m3(float f0, float f1, float f2, float f3) {
+    int r = __builtin_amdgcn_cvt_pk_fp8_f32(clamp_e4m3(f0), clamp_e4m3(f1), 0, false);
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(clamp_e4m3(f2), clamp_e4m3(f3), r, true);
+    const uint32_t u = (uint32_t)r;
+    const uint32_t nan = ((u & 0x7f7f7f7fu) + 0x01010101u) & 0x80808080u;  // bit 7 of every byte that is +-NaN
+    return u & ~nan;
+}
+
+// 16 consecutive bf16 channels (two 16-byte units) of a lane, as float32.
+__device__ __forceinline__ void unpack16(const u32x4& in0, const u32x4& in1, float (&f)[16]) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        f[2 * c] = __uint_as_float(in0[c] << 16);
+        f[2 * c + 1] = __uint_as_float(in0[c] & 0xffff0000u);
+        f[8 + 2 * c] = __uint_as_float(in1[c] << 16);
+        f[8 + 2 * c + 1] = __uint_as_float(in1[c] & 0xffff0000u);
     }
-    a += 0x0007ffffu + ((a >> 20) & 1u);        // keep 3 mantissa bits, ties to even
-    return sign | ((a >> 20) - (120u << 3));    // rebias the exponent from 127 to 7
+}
+
+// Quantises the 16 channels of this lane; the 8 lanes lane & ~7 .. | 7 hold one group of 128
+// channels and must all be active.  Returns the 16 codes, and the scale of the group.
+__device__ __forceinline__ u32x4 quantize16(const u32x4& in0, const u32x4& in1, float* scale_out) {
+    float f[16];
+    unpack16(in0, in1, f);
+    float amax = 0.0f;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const float v = fabsf(f[c]);
+        amax = v > amax ? v : amax;
+    }
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) {  // the 8 lanes of a 128-channel group
+        const float o = __shfl_xor(amax, off, kWave);
+        amax = o > amax ? o : amax;
+    }
+    float scale = 1.0f, inv = 1.0f;
+    if (amax != 0.0f) {
+        scale = __fdiv_rn(amax, 448.0f);
+        inv = __fdiv_rn(448.0f, amax);
+    }
+    u32x4 q;
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        q[c] = pack4_e4m3(__fmul_rn(f[4 * c], inv), __fmul_rn(f[4 * c + 1], inv), __fmul_rn(f[4 * c + 2], inv),
+                          __fmul_rn(f[4 * c + 3], inv));
+    *scale_out = scale;
+    return q;
 }
 
 __global__ __launch_bounds__(256) void dispatch_fp8_kernel(DispatchArgs a, float* recv_scales, int nseg) {
@@ -214,36 +309,8 @@ __global__ __launch_bounds__(256) void dispatch_fp8_kernel(DispatchArgs a, float
         in0 = __builtin_nontemporal_load(src);
         in1 = __builtin_nontemporal_load(src + 1);
     }
-    float f[16];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        f[2 * c] = __uint_as_float(in0[c] << 16);
-        f[2 * c + 1] = __uint_as_float(in0[c] & 0xffff0000u);
-        f[8 + 2 * c] = __uint_as_float(in1[c] << 16);
-        f[8 + 2 * c + 1] = __uint_as_float(in1[c] & 0xffff0000u);
-    }
-    float amax = 0.0f;
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        const float v = fabsf(f[c]);
-        amax = v > amax ? v : amax;
-    }
-#pragma unroll
-    for (int off = 1; off < 8; off <<= 1) {  // the 8 lanes of a 128-channel group
-        const float o = __shfl_xor(amax, off, kWave);
-        amax = o > amax ? o : amax;
-    }
-    float scale = 1.0f, inv = 1.0f;
-    if (amax != 0.0f) {
-        scale = __fdiv_rn(amax, 448.0f);
-        inv = __fdiv_rn(448.0f, amax);
-    }
-    u32x4 q;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        q[c] = f32_to_e4m3(__fmul_rn(f[4 * c], inv)) | (f32_to_e4m3(__fmul_rn(f[4 * c + 1], inv)) << 8) |
-               (f32_to_e4m3(__fmul_rn(f[4 * c + 2], inv)) << 16) | (f32_to_e4m3(__fmul_rn(f[4 * c + 3], inv)) << 24);
-    }
+    float scale;
+    const u32x4 q = quantize16(in0, in1, &scale);
     const int groups = a.H >> 7;
     const int my_row = lane < a.K ? a.dst_row[(int64_t)t * a.K + lane] : -1;
     uint8_t* base = (uint8_t*)a.win.base;  // window strides are in one-byte elements here
@@ -282,16 +349,6 @@ hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hip
     if (nblk > 256 * 64) nblk = 256 * 64;
     hipLaunchKernelGGL(calibration_copy_kernel, dim3((unsigned)nblk), dim3(256), 0, s, (u32x4*)dst,
                        (const u32x4*)src, n16);
-    return hipGetLastError();
-}
-
-hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStream_t s) {
-    const int nseg = (a.H + 1023) / 1024;
-    const int64_t nwaves = (int64_t)a.T * nseg;
-    int64_t nblk = (nwaves + 3) / 4;
-    if (nblk < 1) nblk = 1;
-    if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(dispatch_fp8_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, recv_scales, nseg);
     return hipGetLastError();
 }
 
@@ -343,6 +400,23 @@ bool plan_dispatch(int T, int K, int H, int E, int order, bool have_runs, int pr
     return true;
 }
 
+// The copy launches of the run order (with their read passes): `launch(plan, blocks)` starts
+// the copy of `blocks` blocks from plan.first_block on.
+template <typename Launch>
+static void launch_run_order(const DispatchArgs& a, const DispatchPlan& d, RunPlan p, hipStream_t s, Launch launch) {
+    const int units = a.H / 8;
+    for (int b0 = 0; b0 < d.blocks; b0 += d.blocks_per_launch) {
+        const int nb = std::min(d.blocks_per_launch, d.blocks - b0);
+        const int t0 = (int)std::min<int64_t>(a.T, (int64_t)b0 * d.block_entries / a.K);
+        const int t1 = (int)std::min<int64_t>(a.T, ((int64_t)(b0 + nb) * d.block_entries + a.K - 1) / a.K);
+        // a read pass, unless the layout launch has read these rows already
+        if (a.order == EP_ORDER_DESTINATION && t1 > a.prefetched_rows)
+            hipLaunchKernelGGL(dispatch_warm_kernel, dim3(2048), dim3(256), 0, s, a, units, t0, t1, b0 == 0 ? 1 : 0);
+        p.first_block = b0;
+        launch(p, nb);
+    }
+}
+
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s) {
     const int units = a.H / 8;  // 16-byte units per row
     DispatchPlan d;
@@ -350,22 +424,15 @@ hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s) {
         RunPlan p;
         p.group = d.group; p.nblocks = d.blocks; p.units = units; p.piece = d.piece; p.tpr_shift = d.tpr_shift;
         p.splits = d.splits;
-        for (int b0 = 0; b0 < d.blocks; b0 += d.blocks_per_launch) {
-            const int nb = std::min(d.blocks_per_launch, d.blocks - b0);
-            const int t0 = (int)std::min<int64_t>(a.T, (int64_t)b0 * d.block_entries / a.K);
-            const int t1 = (int)std::min<int64_t>(a.T, ((int64_t)(b0 + nb) * d.block_entries + a.K - 1) / a.K);
-            // a read pass, unless the layout launch has read these rows already
-            if (a.order == EP_ORDER_DESTINATION && t1 > a.prefetched_rows)
-                hipLaunchKernelGGL(dispatch_warm_kernel, dim3(2048), dim3(256), 0, s, a, units, t0, t1, b0 == 0 ? 1 : 0);
-            p.first_block = b0;
-            switch (p.tpr_shift) {
-                case 4: launch_runs<4>(a, p, nb, s); break;
-                case 5: launch_runs<5>(a, p, nb, s); break;
-                case 6: launch_runs<6>(a, p, nb, s); break;
-                case 7: launch_runs<7>(a, p, nb, s); break;
-                default: launch_runs<8>(a, p, nb, s); break;
+        launch_run_order(a, d, p, s, [&](const RunPlan& q, int nb) {
+            switch (q.tpr_shift) {
+                case 4: launch_runs<4>(a, q, nb, s); break;
+                case 5: launch_runs<5>(a, q, nb, s); break;
+                case 6: launch_runs<6>(a, q, nb, s); break;
+                case 7: launch_runs<7>(a, q, nb, s); break;
+                default: launch_runs<8>(a, q, nb, s); break;
             }
-        }
+        });
         return hipGetLastError();
     }
     const int nseg = (units + kWave - 1) / kWave;
@@ -374,6 +441,21 @@ hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s) {
     if (nblk < 1) nblk = 1;  // block 0 also copies the per-expert counts
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(dispatch_direct_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);
+    return hipGetLastError();
+}
+
+// The quantising dispatch walks the tokens whatever the group's dispatch order: a row is
+// quantised once for all its destinations.  (Measured at the prefill shape, 66 us this way:
+// quantising a row piece again for every destination row in the run-ordered walk is bound by
+// arithmetic, 129 us; quantising once into a staging copy and copying that in run order, 90 us,
+// the run-ordered copy being bound by its per-workgroup cost once the rows are half as long.)
+hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStream_t s) {
+    const int nseg = (a.H + 1023) / 1024;
+    const int64_t nwaves = (int64_t)a.T * nseg;
+    int64_t nblk = (nwaves + 3) / 4;
+    if (nblk < 1) nblk = 1;
+    if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dispatch_fp8_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, recv_scales, nseg);
     return hipGetLastError();
 }
 

@@ -810,31 +810,44 @@ def test_once_per_rank_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, 
 # ------------------------------------------------------------------------------ quantising dispatch (FP8 + scales)
 
 FP8_CASES = [
-    # name, T, H, mode, C, wide dynamic range
-    ("tiny", None, None, "ht", 0, False),
-    ("tiny", None, 384, "ll", 6, True),
-    ("ll_decode", None, None, "ll", 0, False),
-    ("ll_decode", 90, 1152, "ht", 0, True),     # ragged last 1024-channel segment
-    ("skew", 500, None, "ht", 0, True),
-    ("ht_prefill", None, None, "ht", 0, False),  # full benchmark shape
+    # name, T, H, mode, C, wide dynamic range, dispatch order of the group
+    ("tiny", None, None, "ht", 0, False, 0),
+    ("tiny", None, 384, "ll", 6, True, 0),
+    ("ll_decode", None, None, "ll", 0, False, 0),
+    ("ll_decode", 90, 1152, "ht", 0, True, 0),     # ragged last 1024-channel segment
+    ("skew", 500, None, "ht", 0, True, 0),
+    ("ht_prefill", None, None, "ht", 0, False, 0),  # full benchmark shape
+    # groups set to the order of the destination rows (the quantising dispatch walks the tokens all the same)
+    ("ht_prefill", 4095, None, "ht", 0, True, 2),   # ragged, wide range and special values
+    ("skew", None, None, "ht", 0, True, 1),         # hot experts
+    ("ll_decode", 1100, 1024, "ht", 0, True, 2),
+    ("skew", None, None, "ll", 512, True, 1),       # padded windows, capacity drops
 ]
 
 
-@pytest.mark.parametrize("name,T,H,mode,C,wide", FP8_CASES)
-def test_fp8_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, wide):
-    """E4M3 codes and float scales bit-exact with the oracle; untouched rows keep their fill."""
+@pytest.mark.parametrize("name,T,H,mode,C,wide,order", FP8_CASES)
+def test_fp8_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, wide, order):
+    """E4M3 codes and float scales bit-exact with the oracle (special values included: NaN, infinities,
+    subnormal groups whose 448 / amax overflows); untouched rows keep their fill."""
     w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
     spec = w.spec
     T = spec.T
-    _say(f"fp8 case {name} T={T} H={spec.H} mode={mode} C={C} wide={wide}")
+    _say(f"fp8 case {name} T={T} H={spec.H} mode={mode} C={C} wide={wide} order={order}")
     x_bits = w.x_bits.copy()
-    if wide:  # spread magnitudes over 2^-24 .. 2^12, plus zero groups and signed zeros
+    if wide:  # spread magnitudes over 2^-24 .. 2^12, plus zero groups, signed zeros and special values
         rng = np.random.default_rng(T)
         xf = wl.bf16_bits_to_f32(x_bits) * np.exp2(rng.integers(-24, 13, x_bits.shape)).astype(np.float32)
         x_bits = wl.f32_to_bf16_bits(xf)
         x_bits[0, :128] = 0
         x_bits[1 % T, 128:256] = 0x8000
         x_bits[2 % T, 5] = 0x7F7F  # largest finite bf16
+        if T > 8 and spec.H >= 384:
+            x_bits[3, 130] = 0x7FC0       # NaN in a group of ordinary values
+            x_bits[4, 131] = 0xFFC1       # a negative NaN
+            x_bits[5, 7] = 0x7F80         # +infinity: the scale is infinite, every other code of the group 0
+            x_bits[6, 300] = 0xFF80       # -infinity
+            x_bits[7, 256:384] = rng.integers(0, 4, 128).astype(np.uint16) | (rng.integers(0, 2, 128).astype(np.uint16) << 15)
+            x_bits[7, 257] = 0x0003       # a group of bf16 subnormals: 448 / amax overflows
     topk = _mess_up(w.topk_idx, spec.E, seed=T + 3, frac_masked=0.01)
     ll = mode == "ll"
     Cc = (C if C else T) if ll else 0
@@ -844,7 +857,7 @@ def test_fp8_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, wide):
     o_q = np.full((rows + 1, spec.H), 0xAB, np.uint8)
     o_s = np.full((rows + 1, G), np.float32(-2.0), np.float32)
     oracle_mod.dispatch_fp8(x_bits, lay, o_q, o_s)
-    g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C)
+    g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C, dispatch_order=order)
     try:
         h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
         store = torch.full((rows + 1, spec.H), 0xAB, dtype=torch.uint8, device=hx.DEV)
