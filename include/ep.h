@@ -377,7 +377,8 @@ EP_API ep_result_t ep_handle_destroy(ep_handle_t handle);
  *                   RECV_EXPERT_COUNTER_DEVICE / _HOST / TOKENS_PER_EXPERTS [E] int32
  *                     (optional): rows placed per expert.
  * For every (t,k) with dst_row >= 0: recv_x[dst_row] = x[t] (byte copy),
- * recv_w[dst_row] = w[t,k], recv_src[dst_row] = t.  Rows not named by the layout are
+ * recv_w[dst_row] = w[t,k] (1.0 when no TOPK_WEIGHTS input is given: absent weights mean a
+ * plain sum, Sec. III-B), recv_src[dst_row] = t.  Rows not named by the layout are
  * left untouched.  A row index >= rows_cap is skipped and flagged (status bit 2).
  * send_only = 1 (staged execution, Sec. III-B; needs staged_buffers > 0, else
  * EP_ERR_UNSUPPORTED; a handle can have one staged call pending, else EP_ERR_BUSY): only

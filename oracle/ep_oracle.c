@@ -222,7 +222,9 @@ static int64_t row_offset(int64_t row, int layout, int C, int64_t stride0, int64
 /* For every routed entry copy the token's row to its destination row
  * (Sec. IV-C "Send Tokens"; the row is pure token data, the source index and
  * the gate weight travel in side arrays).  Rows not named by dst_row are left
- * untouched.  recv_w / recv_src / w may be NULL. */
+ * untouched.  recv_w / recv_src / w may be NULL; without gate weights every
+ * forwarded weight is 1 (Sec. III-B: absent weights mean a plain sum), which is
+ * also what the once-per-rank messages carry in that case. */
 void ep_oracle_dispatch(const uint16_t *x, int64_t x_stride, const float *w, const int32_t *dst_row,
                         int T, int K, int H, int layout, int C, int64_t stride0, int64_t stride1,
                         uint16_t *recv_x, float *recv_w, int32_t *recv_src) {
@@ -232,7 +234,7 @@ void ep_oracle_dispatch(const uint16_t *x, int64_t x_stride, const float *w, con
             if (row < 0) continue;
             uint16_t *dst = recv_x + row_offset(row, layout, C, stride0, stride1);
             for (int h = 0; h < H; ++h) dst[h] = x[(int64_t)t * x_stride + h];
-            if (recv_w && w) recv_w[row] = w[t * K + k];
+            if (recv_w) recv_w[row] = w ? w[t * K + k] : 1.0f;
             if (recv_src) recv_src[row] = t;
         }
     }

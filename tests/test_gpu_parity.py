@@ -312,8 +312,7 @@ def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True
         torch.cuda.synchronize()
         got = hx.dev_to_bits(store)
         assert np.array_equal(got, o_recv), "dispatched rows differ"
-        if weights:
-            assert np.array_equal(r_w.cpu().numpy(), o_w)
+        assert np.array_equal(r_w.cpu().numpy(), o_w)  # without gate weights: 1.0 at every placed row
         assert np.array_equal(r_src.cpu().numpy(), o_src)
         assert np.array_equal(r_cnt.cpu().numpy(), lay.expert_kept)
         # ---- experts (harness), then combine

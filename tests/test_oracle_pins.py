@@ -274,6 +274,32 @@ def test_dispatch_is_index_select(oracle_mod, name, T):
         assert np.array_equal(seg, want_tok)
 
 
+def test_dispatch_without_weights_forwards_unit_weights(oracle_mod):
+    """No gate weights given: every placed row gets the weight 1 (absent weights mean a plain sum,
+    Sec. III-B), rows without an entry keep their fill; the once-per-rank path, whose message
+    headers then carry 1.0, ends with the same side array."""
+    w = wl.make_workload("ll_decode", T=40)
+    spec = w.spec
+    topk = w.topk_idx.copy()
+    topk[::7, 1] = -1
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R)
+    rows = int(lay.expert_offset[-1])
+    recv = np.zeros((rows + 2, spec.H), np.uint16)
+    recv_w = np.full(rows + 2, np.float32(-77.0), np.float32)
+    oracle_mod.dispatch(w.x_bits, None, lay, recv, recv_w)
+    assert np.all(recv_w[:rows] == 1.0) and np.all(recv_w[rows:] == -77.0)
+    combined = oracle_mod.combine(recv[:rows], recv_w_to_topk(recv_w, lay), lay, spec.H, acc="f32")
+    assert np.array_equal(combined, oracle_mod.combine(recv[:rows], None, lay, spec.H, acc="f32"))
+
+
+def recv_w_to_topk(recv_w, lay):
+    """The forwarded per-row weights seen from the token side: w[t, k] = recv_w[dst_row[t, k]]."""
+    out = np.zeros(lay.dst_row.shape, np.float32)
+    ok = lay.dst_row >= 0
+    out[ok] = recv_w[lay.dst_row[ok]]
+    return out
+
+
 def test_dispatch_padded_strided_and_poison(oracle_mod):
     """3-D [E, C, H] windows embedded in a receiver tensor [E, R*C, H]: only this
     source's sub-region of each expert may change (Sec. III-E LL layout)."""
