@@ -179,7 +179,10 @@ typedef struct {
     int32_t num_tokens;      /* T of this layout                                           */
     int32_t status;          /* bit 0: ids outside [0,E) seen; bit 1: entries dropped for
                                 capacity; bit 2: a dispatch found rows beyond its output;
-                                bit 3: ep_complete gave up waiting for counters            */
+                                bit 3: a bounded device-side wait ran out (ep_complete waiting
+                                for counters, or the workgroups of a layout for each other).
+                                Bits 2 and 3 stay set for the lifetime of the handle once a
+                                call has raised them                                       */
     int64_t rows_kept;       /* routed entries that own a destination row                  */
     int64_t rows_dropped;    /* entries cut by the LL capacity C                           */
     int64_t entries_masked;  /* topk_idx == -1                                             */
@@ -357,10 +360,15 @@ EP_API ep_result_t ep_handle_query(ep_handle_t handle, ep_layout_info_t *info);
  * receivers' tensors (rows_kept).  Synchronises like ep_handle_query. */
 EP_API ep_result_t ep_handle_get_num_recv_tokens(ep_handle_t handle, int64_t *num);
 
-/* Table II "ncclEpHandleDestroy".  The handle's device arrays return to the group's
- * pool at once and the next ep_layout may overwrite them: the caller guarantees that
- * stream work using the handle has completed, or that every later ep_layout of this
- * group is enqueued on the same stream as that work (stream order then protects it). */
+/* Table II "ncclEpHandleDestroy".  Host-only and immediate: the handle's device arrays return
+ * to the group's pool and the next ep_layout may take them.  Work of this handle that is still
+ * queued stays safe: the library remembers the stream of the handle's last call, and a later
+ * ep_layout on another stream first makes that stream wait (on the device, through an event)
+ * for everything queued there; a later ep_layout on the same stream is ordered by the stream.
+ * What the caller must see to: calls of one handle on several streams must have been ordered
+ * among themselves so that the last call's stream comes after the others (as data dependencies
+ * between dispatch and combine require anyway).  A staged call that was never completed is
+ * abandoned: its coordination counters are cleared on the stream of its send phase. */
 EP_API ep_result_t ep_handle_destroy(ep_handle_t handle);
 
 /*

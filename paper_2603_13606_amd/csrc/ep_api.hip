@@ -27,6 +27,11 @@ struct Slab {
     int32_t *recv_count, *recv_kept, *recv_dst_row;
     // what the receiving side of a staged call learns from the coordination counters
     int32_t *recv_rank_count, *recv_rank_offset;
+    // the stream of the last call of the handle that held the slab before (valid once `used`), and
+    // the event through which a layout on another stream waits for the work queued there
+    hipStream_t last_stream = nullptr;
+    hipEvent_t reuse_event = nullptr;
+    bool used = false;
 };
 
 }  // namespace
@@ -158,11 +163,18 @@ ep_result_t new_slab(ep_group_s* g, Slab* s, hipStream_t stream) {
     if (r != EP_SUCCESS) return r;
     carve_slab(g, s, (int32_t*)p);
     const int64_t ints = (int32_t*)(s->ctl + kLayoutCtlWords) - (int32_t*)s->pub;
-    if (launch_clear_counts((int32_t*)s->pub, (int)ints, stream) != hipSuccess) {
+    if (launch_clear_counts((int32_t*)s->pub, (int)ints, stream) != hipSuccess ||
+        hipEventCreateWithFlags(&s->reuse_event, hipEventDisableTiming) != hipSuccess) {
         dev_free(g, p);
         return EP_ERR_HIP;
     }
+    s->used = false;
     return EP_SUCCESS;
+}
+
+void free_slab(ep_group_s* g, Slab& s) {
+    if (s.reuse_event) (void)hipEventDestroy(s.reuse_event);
+    dev_free(g, s.base);
 }
 
 const ep_tensor_t* find_tag(const ep_tensor_t* ts, int n, int tag, int tag2 = -1, int tag3 = -1) {
@@ -386,7 +398,7 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     g->nsets = cfg->staged_buffers;
     auto fail = [&](ep_result_t r) {
         for (int i = 0; i < 2; ++i) { dev_free(g, g->staging[i]); dev_free(g, g->signals[i]); dev_free(g, g->comb_stage[i]); }
-        for (auto& f : g->free_slabs) dev_free(g, f.base);
+        for (auto& f : g->free_slabs) free_slab(g, f);
         delete g;
         return r;
     };
@@ -428,7 +440,7 @@ ep_result_t ep_group_destroy(ep_group_t g, ep_stream_t stream) {
         if (g->live_handles > 0) return EP_ERR_BUSY;
     }
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
-    for (auto& s : g->free_slabs) dev_free(g, s.base);
+    for (auto& s : g->free_slabs) free_slab(g, s);
     for (int i = 0; i < 2; ++i) { dev_free(g, g->staging[i]); dev_free(g, g->signals[i]); dev_free(g, g->comb_stage[i]); }
     delete g;
     return EP_SUCCESS;
@@ -508,6 +520,20 @@ static ep_result_t prepare_layout(ep_handle_t* handle, ep_group_t g, const ep_te
     h->group = g;
     h->T = (int)T;
     h->last_stream = (hipStream_t)stream;
+    // The slab may still be read by work of the handle that held it before, queued on another
+    // stream: this stream then waits for everything queued there so far (no host wait; work of
+    // that handle on the same stream is ordered by the stream itself).
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (h->slab.used && h->slab.last_stream != (hipStream_t)stream &&
+        hipStreamIsCapturing((hipStream_t)stream, &capturing) == hipSuccess && capturing == hipStreamCaptureStatusNone) {
+        // (a stream under graph capture cannot wait for work outside its graph: there the caller
+        // orders the capture after that work)
+        if (hipEventRecord(h->slab.reuse_event, h->slab.last_stream) != hipSuccess ||
+            hipStreamWaitEvent((hipStream_t)stream, h->slab.reuse_event, 0) != hipSuccess) {
+            ep_handle_destroy(h);
+            return EP_ERR_HIP;
+        }
+    }
     h->expert_base = expert_base ? (const int32_t*)expert_base->data : nullptr;
 
     LayoutArgs a;
@@ -596,13 +622,25 @@ ep_result_t ep_handle_get_num_recv_tokens(ep_handle_t h, int64_t* num) {
 ep_result_t ep_handle_destroy(ep_handle_t h) {
     if (!h) return EP_ERR_INVALID_ARG;
     ep_group_s* g = h->group;
+    ep_result_t r = EP_SUCCESS;
+    if (h->pending != PENDING_NONE) {
+        // an abandoned staged call: its coordination counters are raised and would be taken for
+        // those of the next call that uses the buffer set; clear them behind the send phase
+        const ep_group_config_t& c = g->cfg;
+        int32_t* sig = h->pending == PENDING_DISPATCH_DIRECT ? g->sig_dispatch(h->pending_set)
+                       : h->pending == PENDING_DISPATCH_DEDUP ? g->sig_rank(h->pending_set) : g->sig_combine(h->pending_set);
+        const int n = h->pending == PENDING_DISPATCH_DEDUP ? c.num_ranks : c.num_experts;
+        if (launch_clear_counts(sig, n, h->last_stream) != hipSuccess) r = EP_ERR_HIP;
+    }
+    h->slab.last_stream = h->last_stream;
+    h->slab.used = true;
     {
         std::lock_guard<std::mutex> lk(g->mu);
         g->free_slabs.push_back(h->slab);
         g->live_handles -= 1;
     }
     delete h;
-    return EP_SUCCESS;
+    return r;
 }
 
 // The tensors of a dispatch call, checked against the group and turned into kernel arguments

@@ -212,7 +212,7 @@ __global__ __launch_bounds__(256) void dispatch_warm_kernel(DispatchArgs a, int 
         for (int64_t i = gid; i < n; i += stride) acc ^= (uint32_t)(a.sorted_token[i] ^ a.sorted_row[i]);
         for (int64_t i = gid; i < table; i += stride) acc ^= (uint32_t)a.run_start[i];
     }
-    if (acc == 0x9e3779b9u) a.totals[kTotalsWords - 1] = (int32_t)acc;  // keeps the loads; the word is unused
+    asm volatile("" ::"v"(acc));  // the loads are the point: keep them
 }
 
 template <int TPR_SHIFT>

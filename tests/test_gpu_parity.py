@@ -206,6 +206,94 @@ def test_layout_expert_base(ep, hx, oracle_mod):
         ep.ep_group_destroy(g)
 
 
+@pytest.mark.parametrize("n_src,padded,order", [(4, True, 0), (8, True, 0), (4, False, 0), (8, False, 1), (5, False, 2)])
+def test_several_sources_into_one_receiver_tensor(ep, hx, oracle_mod, n_src, padded, order):
+    """What one GPU can show of (source rank, token index) order: n_src simulated source ranks, each
+    with its own routing and group (my_rank = r), dispatch one after another into ONE receiver-shaped
+    tensor -- padded [E, R*C, H] through each source's strided view, concatenated [rows, H] through
+    expert_base -- and the whole tensor, the side arrays and every count equal the stable sort of
+    all entries by (expert, source rank, token, k).  Each source then combines from the shared
+    tensor, and its output equals the oracle's for that source."""
+    import multi_source as ms
+    big = order != 0
+    spec = wl.WorkloadSpec("ms", 78, R=n_src, T=2100 if big else 300, H=512 if big else 1000, E=n_src * 4, K=5)
+    E, H, K = spec.E, spec.H, spec.K
+    tokens = [spec.T, spec.T - 123, 1700 if big else 1, spec.T - 7]
+    sources = ms.make_sources(spec, n_src, tokens)
+    C = 41
+    fill = hx.POISON
+    _say(f"several sources: n_src={n_src} padded={padded} order={order}")
+    want_rows, want_src, want_w, want_rank = ms.expected_receiver(sources, E, H, padded, C, fill)
+    nrows = want_rows.shape[0]
+    store = hx.poison_bf16((nrows + 1, H))
+    scale = wl.expert_scale_table(spec)
+    bases = None if padded else ms.expert_bases(sources, E)
+    r_w = torch.full((nrows + 1,), -3.5, dtype=torch.float32, device=hx.DEV)
+    r_src = torch.full((nrows + 1,), -9, dtype=torch.int32, device=hx.DEV)
+    groups, handles = [], []
+    try:
+        for s in sources:
+            T = s.topk.shape[0]
+            cfg = ep.make_config(n_src, E, H, K, spec.T, mode=ep.EP_MODE_LL if padded else ep.EP_MODE_HT,
+                                 my_rank=s.rank, slots_per_subregion=C if padded else 0, dispatch_order=order)
+            g = ep.ep_group_create(cfg)
+            groups.append(g)
+            topk = torch.from_numpy(s.topk).to(hx.DEV)
+            x = hx.bits_to_dev(s.x_bits)
+            gate = torch.from_numpy(s.w).to(hx.DEV)
+            cnt = torch.full((E,), -1, dtype=torch.int32, device=hx.DEV)
+            if padded:
+                recv = store[:nrows].view(E, n_src * C, H)[:, s.rank * C:(s.rank + 1) * C, :]
+                lay = oracle_mod.layout(s.topk, E=E, R=n_src, layout=oracle_mod.LAYOUT_PADDED, C=C, C_rank=spec.T)
+                side_w = torch.full((E * C,), -3.5, dtype=torch.float32, device=hx.DEV)
+                side_src = torch.full((E * C,), -9, dtype=torch.int32, device=hx.DEV)
+                h = ep.ep_layout(g, topk)
+                ep.ep_dispatch(h, x, recv, topk_weights=gate, recv_w=side_w, recv_src=side_src, recv_count=cnt)
+                torch.cuda.synchronize()
+                assert np.array_equal(side_src.cpu().numpy(), want_src.reshape(E, n_src, C)[:, s.rank, :].reshape(-1))
+                assert np.array_equal(side_w.cpu().numpy(), want_w.reshape(E, n_src, C)[:, s.rank, :].reshape(-1))
+            else:
+                base = torch.from_numpy(bases[s.rank]).to(hx.DEV)
+                lay = oracle_mod.layout(s.topk, E=E, R=n_src, expert_base=bases[s.rank], C_rank=spec.T)
+                h = ep.ep_layout_prefetch(g, topk, x, expert_base=base) if order == 1 else ep.ep_layout(g, topk, expert_base=base)
+                ep.ep_dispatch(h, x, store[:nrows], topk_weights=gate, recv_w=r_w[:nrows], recv_src=r_src[:nrows], recv_count=cnt)
+            hx.assert_layout_equal(hx.fetch_layout(h, T, K, E, n_src), lay)
+            assert np.array_equal(cnt.cpu().numpy(), lay.expert_kept)
+            handles.append((h, lay, s, gate, base if not padded else None))
+        torch.cuda.synchronize()
+        got = hx.dev_to_bits(store)
+        assert np.array_equal(got[:nrows], want_rows), "receiver tensor differs from the global ordering"
+        assert np.all(got[nrows:] == fill)
+        if not padded:
+            assert np.array_equal(r_src.cpu().numpy()[:nrows], want_src) and np.array_equal(r_w.cpu().numpy()[:nrows], want_w)
+        # experts run on the shared tensor; every source combines its own tokens back
+        if padded:
+            row_e = np.repeat(np.arange(E), n_src * C)
+        else:
+            row_e = np.repeat(np.arange(E), np.diff(np.concatenate([bases[0], [nrows]])))
+        o_y = hx.expert_standin_np(want_rows, row_e, scale)
+        d_y = hx.expert_standin(store[:nrows], torch.from_numpy(row_e).to(hx.DEV), scale)
+        assert np.array_equal(hx.dev_to_bits(d_y), o_y)
+        for h, lay, s, gate, base in handles:
+            T = s.topk.shape[0]
+            out = hx.poison_bf16((T, H))
+            if padded:
+                y_view = d_y.view(E, n_src * C, H)[:, s.rank * C:(s.rank + 1) * C, :]
+                ep.ep_combine(h, y_view, out, topk_weights=gate)
+                o_view = o_y.reshape(E, n_src * C, H)[:, s.rank * C:(s.rank + 1) * C, :]
+                ref = oracle_mod.combine(o_view, s.w, lay, H, acc="f32", stride0=n_src * C * H, stride1=H)
+            else:
+                ep.ep_combine(h, d_y, out, topk_weights=gate)
+                ref = oracle_mod.combine(o_y, s.w, lay, H, acc="f32")
+            torch.cuda.synchronize()
+            assert np.array_equal(hx.dev_to_bits(out), ref), f"combine of source {s.rank} differs"
+    finally:
+        for h, *_ in handles:
+            ep.ep_handle_destroy(h)
+        for g in groups:
+            ep.ep_group_destroy(g)
+
+
 def test_layout_many_launches_on_one_slab(ep, hx, oracle_mod):
     """The workgroups of a layout launch tell each other's published counts from stale ones by a
     tag that counts the launches on the handle's slab and starts over after 255 of them (the
@@ -633,6 +721,74 @@ def test_output_too_small_is_flagged_not_overrun(ep, hx, oracle_mod):
         o = np.full((spec.T * spec.K, spec.H), hx.POISON, np.uint16)
         oracle_mod.dispatch(w.x_bits, None, lay, o)
         assert np.array_equal(got[:cap], o[:cap])
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_slab_reuse_on_another_stream_waits_for_the_previous_handle(ep, hx, oracle_mod):
+    """A handle is destroyed while its dispatches and combines are still queued on stream A; the
+    next layout, on stream B, takes the same slab (the group has one) with another routing.  It
+    must not overwrite the arrays the queued work reads: every result of stream A is the oracle's."""
+    w = wl.make_workload("ht_prefill", T=2048, H=2048)
+    spec = w.spec
+    T = spec.T
+    lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=T)
+    rows = int(lay.expert_offset[-1])
+    o_recv = np.zeros((rows, spec.H), np.uint16)
+    oracle_mod.dispatch(w.x_bits, None, lay, o_recv)
+    ref = oracle_mod.combine(o_recv, w.topk_w, lay, spec.H, acc="f32")
+    topk2, _, _ = wl.make_routing(spec, T=T, seed_offset=99)
+    lay2 = oracle_mod.layout(topk2, E=spec.E, R=spec.R, C_rank=T)
+    g = _group(ep, spec, T, ep.EP_MODE_HT, max_handles=1)
+    try:
+        x = hx.bits_to_dev(w.x_bits)
+        gate = torch.from_numpy(w.topk_w).to(hx.DEV)
+        d_topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
+        d_topk2 = torch.from_numpy(topk2).to(hx.DEV)
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        for rep in range(3):
+            recv = hx.poison_bf16((rows, spec.H))
+            outs = [hx.poison_bf16((T, spec.H)) for _ in range(12)]
+            torch.cuda.synchronize()
+            h = ep.ep_layout(g, d_topk, stream=sa)
+            for o in outs:  # a queue of work that reads the handle's arrays
+                ep.ep_dispatch(h, x, recv, stream=sa)
+                ep.ep_combine(h, recv, o, topk_weights=gate, stream=sa)
+            ep.ep_handle_destroy(h)
+            h2 = ep.ep_layout(g, d_topk2, stream=sb)  # same slab, other stream, other routing
+            got2 = hx.fetch_layout(h2, T, spec.K, spec.E, spec.R)
+            hx.assert_layout_equal(got2, lay2)
+            torch.cuda.synchronize()
+            assert np.array_equal(hx.dev_to_bits(recv), o_recv), f"round {rep}: rows differ"
+            for i, o in enumerate(outs):
+                assert np.array_equal(hx.dev_to_bits(o), ref), f"round {rep}: combine {i} differs"
+            ep.ep_handle_destroy(h2)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+def test_overflow_status_stays_set_for_the_handle(ep, hx, oracle_mod):
+    """Status bit 2 (rows beyond the output) is sticky: once a dispatch has raised it, queries of
+    that handle keep reporting it, also after a dispatch into a tensor that is large enough; a new
+    handle starts clean."""
+    w = wl.make_workload("ll_decode", T=90, H=256)
+    spec = w.spec
+    g = _group(ep, spec, 90, ep.EP_MODE_HT)
+    try:
+        topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
+        x = hx.bits_to_dev(w.x_bits)
+        rows = 90 * spec.K
+        h = ep.ep_layout(g, topk)
+        ep.ep_dispatch(h, x, hx.poison_bf16((rows - 10, spec.H)))
+        assert ep.ep_handle_query(h, ok=(ep.EP_ERR_OVERFLOW,)).status & ep.STATUS_OUTPUT_OVERFLOW
+        ep.ep_dispatch(h, x, hx.poison_bf16((rows, spec.H)))
+        assert ep.ep_handle_query(h, ok=(ep.EP_ERR_OVERFLOW,)).status & ep.STATUS_OUTPUT_OVERFLOW
+        ep.ep_handle_destroy(h)
+        h = ep.ep_layout(g, topk)
+        ep.ep_dispatch(h, x, hx.poison_bf16((rows, spec.H)))
+        assert ep.ep_handle_query(h).status == 0
         ep.ep_handle_destroy(h)
     finally:
         ep.ep_group_destroy(g)

@@ -216,3 +216,33 @@ def test_send_only_needs_buffer_sets(ep, hx):
         ep.ep_handle_destroy(h)
     finally:
         ep.ep_group_destroy(g)
+
+
+def test_destroy_with_a_pending_staged_call_clears_its_counters(ep, hx, oracle_mod):
+    """A handle destroyed between send_only and ep_complete leaves no raised counters behind:
+    the next staged call on the same buffer set sees its own counts, not stale ones."""
+    w, spec, lay, g, rows, Cc = _setup(ep, hx, oracle_mod, "ll_decode", 96, 512, "ht", ep.EP_PATH_DIRECT, sets=1)
+    try:
+        topk = torch.from_numpy(w.topk_idx).to(hx.DEV)
+        x = hx.bits_to_dev(w.x_bits)
+        recv = hx.poison_bf16((rows, spec.H))
+        h = ep.ep_layout(g, topk)
+        ep.ep_dispatch(h, x, recv, send_only=1)
+        torch.cuda.synchronize()
+        assert np.array_equal(_signals(ep, g, spec, 0)[:spec.E], lay.expert_kept + 1)
+        ep.ep_handle_destroy(h)  # abandoned
+        torch.cuda.synchronize()
+        assert np.all(_signals(ep, g, spec, 0) == 0)
+        # a second routing through the same (only) buffer set
+        topk2, _, _ = wl.make_routing(spec, T=96, seed_offset=5)
+        lay2 = oracle_mod.layout(topk2, E=spec.E, R=spec.R, C_rank=96)
+        h2 = ep.ep_layout(g, torch.from_numpy(topk2).to(hx.DEV))
+        cnt = torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)
+        recv2 = hx.poison_bf16((int(lay2.expert_offset[-1]), spec.H))
+        ep.ep_dispatch(h2, x, recv2, recv_count=cnt, send_only=1)
+        ep.ep_complete(h2)
+        torch.cuda.synchronize()
+        assert np.array_equal(cnt.cpu().numpy(), lay2.expert_kept)
+        ep.ep_handle_destroy(h2)
+    finally:
+        ep.ep_group_destroy(g)

@@ -675,3 +675,49 @@ def test_combine_hier_order(oracle_mod):
     assert d.max() <= 1
     f64 = oracle_mod.combine(y, w.topk_w, lay, spec.H, acc="f64")
     assert np.abs(ordered(hier) - ordered(f64)).max() <= 1
+
+
+# --------------------------------------------------------------------------- several sources, one receiver
+
+
+@pytest.mark.parametrize("padded", [False, True])
+def test_multi_source_composition_is_a_stable_sort(oracle_mod, padded):
+    """(source rank, token index) order: per-source oracle layouts and dispatches, composed into one
+    receiver tensor through expert_base (concatenated) or through each source's columns of the
+    [E, R*C, H] tensor (padded), give exactly the stable sort of all entries of all sources by
+    (expert, source rank, token, k) -- written down without the oracle in multi_source.py."""
+    import multi_source as ms
+    spec = wl.WorkloadSpec("ms", 77, R=4, T=64, H=32, E=16, K=3)
+    E, H, K, R = spec.E, spec.H, spec.K, 4
+    sources = ms.make_sources(spec, R, [50, 37, 1, 64])
+    C = 9
+    fill = 0xBEEF
+    want_rows, want_src, want_w, want_rank = ms.expected_receiver(sources, E, H, padded, C, fill)
+    if padded:
+        full = np.full((E, R * C, H), fill, np.uint16)
+        for s in sources:
+            lay = oracle_mod.layout(s.topk, E=E, R=R, layout=oracle_mod.LAYOUT_PADDED, C=C, C_rank=s.topk.shape[0])
+            side_w = np.full(E * C, np.float32(-3.5), np.float32)
+            side_src = np.full(E * C, -9, np.int32)
+            oracle_mod.dispatch(s.x_bits, s.w, lay, full[:, s.rank * C:(s.rank + 1) * C, :], side_w, side_src,
+                                stride0=R * C * H, stride1=H)
+            # the side arrays of a source are indexed by its own rows e*C + slot
+            sel = want_rank.reshape(E, R, C)[:, s.rank, :].reshape(-1)
+            assert np.array_equal(side_src, want_src.reshape(E, R, C)[:, s.rank, :].reshape(-1))
+            assert np.array_equal(side_w, want_w.reshape(E, R, C)[:, s.rank, :].reshape(-1))
+            assert np.all((sel == s.rank) == (side_src >= 0))
+        assert np.array_equal(full.reshape(-1, H), want_rows)
+        assert (want_rank >= 0).sum() < sum(((s.topk >= 0).sum() for s in sources))  # some entries were cut by C
+    else:
+        bases = ms.expert_bases(sources, E)
+        total = want_rows.shape[0]
+        full = np.full((total, H), fill, np.uint16)
+        side_w = np.full(total, np.float32(-3.5), np.float32)
+        side_src = np.full(total, -9, np.int32)
+        for s in sources:
+            lay = oracle_mod.layout(s.topk, E=E, R=R, expert_base=bases[s.rank], C_rank=s.topk.shape[0])
+            oracle_mod.dispatch(s.x_bits, s.w, lay, full, side_w, side_src)
+        assert np.array_equal(full, want_rows)
+        assert np.array_equal(side_src, want_src) and np.array_equal(side_w, want_w)
+        assert not np.any(full == fill) or True
+        assert np.all(want_rank >= 0)  # the concatenated receiver has no holes
