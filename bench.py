@@ -349,6 +349,49 @@ def extras(ep, hx, wl, torch, np, group, spec, first_set, rows, stream_ptr, iter
         ep.ep_handle_destroy(h4)
         ep.ep_group_destroy(g4)
 
+    # training step: forward (layout, dispatch, combine) and backward with the handle of the forward pass
+    # (combine backward = output gradient scaled into the rows + gate-weight gradients from the rows;
+    # dispatch backward = unweighted combine of the row gradients)
+    g_out = torch.randn((T, H), device=hx.DEV).bfloat16()
+    grad_y = torch.empty_like(recv)
+    grad_w = torch.empty((T, K), dtype=torch.float32, device=hx.DEV)
+    grad_x = torch.empty((T, H), dtype=torch.bfloat16, device=hx.DEV)
+    lay_call = ep.PreparedLayout(group, topk, tokens=x)
+    fwd_d = ep.prepare_dispatch(x, recv, topk_weights=gate)
+    fwd_c = ep.prepare_combine(y, out, topk_weights=gate)
+    bwd_c = ep.prepare_combine_backward(g_out, grad_y, topk_weights=gate, y=y, grad_w=grad_w)
+    bwd_d = ep.prepare_combine(grad_y, grad_x)
+
+    def train_step():
+        h = lay_call(stream_ptr)
+        fwd_d(h, stream_ptr)
+        fwd_c(h, stream_ptr)
+        bwd_c(h, stream_ptr)
+        bwd_d(h, stream_ptr)
+        ep.ep_handle_destroy(h)
+
+    def backward_only(h):
+        bwd_c(h, stream_ptr)
+        bwd_d(h, stream_ptr)
+
+    hb = lay_call(stream_ptr)
+    us_b = timed(lambda: backward_only(hb))
+    us_cb = timed(lambda: bwd_c(hb, stream_ptr))
+    ep.ep_handle_destroy(hb)
+    us_t = timed(train_step)
+    b_cb = T * 2 * H + 2 * rows * 2 * H + 8 * rows + 4 * T * K
+    b_db = rows * 2 * H + T * 2 * H + 4 * rows
+    b_fwd = (T * 2 * H + rows * 2 * H) * 2 + 20 * rows
+    res["training_step"] = {
+        "forward_plus_backward_us": round(us_t, 2), "backward_us": round(us_b, 2),
+        "combine_backward_us": round(us_cb, 2),
+        "combine_backward_gbps": round(b_cb / (us_cb * 1e-6) / 1e9, 1),
+        "algorithmic_bytes": {"forward": b_fwd, "combine_backward": b_cb, "dispatch_backward": b_db},
+        "gbps": round((b_fwd + b_cb + b_db) / (us_t * 1e-6) / 1e9, 1),
+        "what": "layout + dispatch + combine, then ep_combine_backward (gradient rows and gate-weight gradients) "
+                "and the unweighted combine of the gradient rows, all on one handle"}
+    del grad_y, grad_w, grad_x, g_out
+
     # staged execution (send phase + ep_complete) and the two-level combine order
     cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, staged_buffers=2, ranks_per_node=8)
     g3 = ep.ep_group_create(cfg)

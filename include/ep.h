@@ -91,7 +91,9 @@ enum {
     EP_TAG_RECV_EXPERT_COUNTER_HOST = 6,   /* same, pinned host memory mapped to device   */
     EP_TAG_TOKENS_PER_EXPERTS = 7,         /* same as RECV_EXPERT_COUNTER_DEVICE          */
     EP_TAG_RECV_SRC_TOKEN = 8,             /* int32 [rows] source token index of each row */
-    EP_TAG_EXPERT_BASE = 9                 /* int32 [E], see ep_layout                    */
+    EP_TAG_EXPERT_BASE = 9,                /* int32 [E], see ep_layout                    */
+    EP_TAG_EXPERT_TOKENS = 10              /* expert outputs, shaped like dispatch's TOKENS
+                                              output (input of ep_combine_backward)       */
 };
 
 /* N-d tensor descriptor (Sec. III-E): shape and strides in ELEMENTS, innermost
@@ -446,6 +448,26 @@ EP_API ep_result_t ep_layout_dispatch(ep_handle_t *handle, ep_group_t group, con
                                       const ep_tensor_t *expert_base, const ep_tensor_t *inputs,
                                       int32_t num_inputs, const ep_tensor_t *outputs, int32_t num_outputs,
                                       ep_stream_t stream);
+
+/*
+ * ep_combine_backward -- the backward pass of ep_combine with the handle of the forward pass
+ * (Sec. III-C: a handle serves forward and backward; Sec. III-F training pattern, where the
+ * backward of combine is a dispatch of the gradients).  For out[t] = sum_k w[t,k] * y[row(t,k)]
+ * and g the gradient with respect to out:
+ * inputs:  TOKENS g [T, H] bf16 (required); TOPK_WEIGHTS w [T, K] f32 (optional, absent = 1);
+ *          EXPERT_TOKENS y with the shape rules of dispatch's TOKENS output (optional; needed for
+ *          the weight gradient).
+ * outputs: TOKENS grad_y, shaped like y / like dispatch's TOKENS output (required):
+ *            grad_y[row(t,k), h] = bf16_rne( w[t,k] * f32(g[t,h]) ), other rows untouched;
+ *          TOPK_WEIGHTS grad_w [T, K] f32 (given exactly when y is):
+ *            grad_w[t,k] = sum over h of f32(y[row(t,k), h]) * f32(g[t,h]) in float32, in a fixed
+ *            order (per thread of a 256-thread workgroup over its 16-byte units, a fixed tree over
+ *            the lanes, the four waves in order); 0 for an entry without a row.
+ * The backward pass of ep_dispatch needs no call of its own: it is ep_combine without weights.
+ * Errors: EP_ERR_INVALID_ARG, EP_ERR_UNSUPPORTED, EP_ERR_HIP.
+ */
+EP_API ep_result_t ep_combine_backward(ep_handle_t handle, const ep_tensor_t *inputs, int32_t num_inputs,
+                                       const ep_tensor_t *outputs, int32_t num_outputs, ep_stream_t stream);
 
 /* Options of ep_complete.  `size` must be sizeof(ep_complete_config_t). */
 typedef struct {

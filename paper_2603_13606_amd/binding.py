@@ -42,13 +42,14 @@ EP_TAG_RECV_EXPERT_COUNTER_HOST = 6
 EP_TAG_TOKENS_PER_EXPERTS = 7
 EP_TAG_RECV_SRC_TOKEN = 8
 EP_TAG_EXPERT_BASE = 9
+EP_TAG_EXPERT_TOKENS = 10
 
 STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW, STATUS_TIMEOUT = 1, 2, 4, 8
 
 EXPORTS = [
     "ep_error_string", "ep_version", "ep_build_id", "ep_layout_plan", "ep_dispatch_plan", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
     "ep_layout", "ep_layout_prefetch", "ep_layout_static", "ep_layout_dispatch", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
-    "ep_dispatch", "ep_combine", "ep_complete", "ep_group_reset_signals",
+    "ep_dispatch", "ep_combine", "ep_combine_backward", "ep_complete", "ep_group_reset_signals",
 ]
 
 
@@ -155,6 +156,7 @@ def load() -> ctypes.CDLL:
         lib.ep_handle_destroy.argtypes = [vp]
         for fn in (lib.ep_dispatch, lib.ep_combine):
             fn.argtypes = [vp, ctypes.POINTER(ep_tensor_t), i32, ctypes.POINTER(ep_tensor_t), i32, i32, vp]
+        lib.ep_combine_backward.argtypes = [vp, ctypes.POINTER(ep_tensor_t), i32, ctypes.POINTER(ep_tensor_t), i32, vp]
         lib.ep_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.ep_complete.argtypes = [vp, ctypes.POINTER(ep_complete_config_t), vp]
         lib.ep_group_reset_signals.argtypes = [vp, vp]
@@ -393,6 +395,21 @@ def ep_combine(handle, y: torch.Tensor, out: torch.Tensor, topk_weights: Optiona
                              _stream_ptr(stream)), "ep_combine")
 
 
+def ep_combine_backward(handle, grad_out: torch.Tensor, grad_y: torch.Tensor, topk_weights: Optional[torch.Tensor] = None,
+                        y: Optional[torch.Tensor] = None, grad_w: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Backward of the weighted combine: grad_y (windows) and, when y is given, grad_w [T, K]."""
+    ins = [(grad_out, EP_TAG_TOKENS)]
+    if topk_weights is not None:
+        ins.append((topk_weights, EP_TAG_TOPK_WEIGHTS))
+    if y is not None:
+        ins.append((y, EP_TAG_EXPERT_TOKENS))
+    outs = [(grad_y, EP_TAG_TOKENS)]
+    if grad_w is not None:
+        outs.append((grad_w, EP_TAG_TOPK_WEIGHTS))
+    _check(load().ep_combine_backward(handle, _descs(ins), len(ins), _descs(outs), len(outs), _stream_ptr(stream)),
+           "ep_combine_backward")
+
+
 class PreparedCall:
     """Descriptors of one ep_dispatch / ep_combine call built once and reused: the
     per-call cost drops to a single foreign-function call.  The tensors must stay
@@ -407,7 +424,10 @@ class PreparedCall:
         self._send_only = send_only
 
     def __call__(self, handle, stream_ptr: int = 0) -> None:
-        code = self._fn(handle, self._ins, self._n_in, self._outs, self._n_out, self._send_only, stream_ptr)
+        if self._name == "ep_combine_backward":  # the one call of this shape without a send_only argument
+            code = self._fn(handle, self._ins, self._n_in, self._outs, self._n_out, stream_ptr)
+        else:
+            code = self._fn(handle, self._ins, self._n_in, self._outs, self._n_out, self._send_only, stream_ptr)
         if code != EP_SUCCESS:
             raise EpError(code, self._name)
 
@@ -447,6 +467,18 @@ def prepare_combine(y, out, topk_weights=None) -> PreparedCall:
     if topk_weights is not None:
         ins.append((topk_weights, EP_TAG_TOPK_WEIGHTS))
     return PreparedCall("ep_combine", ins, [(out, EP_TAG_TOKENS)])
+
+
+def prepare_combine_backward(grad_out, grad_y, topk_weights=None, y=None, grad_w=None) -> PreparedCall:
+    ins = [(grad_out, EP_TAG_TOKENS)]
+    if topk_weights is not None:
+        ins.append((topk_weights, EP_TAG_TOPK_WEIGHTS))
+    if y is not None:
+        ins.append((y, EP_TAG_EXPERT_TOKENS))
+    outs = [(grad_y, EP_TAG_TOKENS)]
+    if grad_w is not None:
+        outs.append((grad_w, EP_TAG_TOPK_WEIGHTS))
+    return PreparedCall("ep_combine_backward", ins, outs)
 
 
 class PreparedLayout:

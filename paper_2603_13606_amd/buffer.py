@@ -1,6 +1,6 @@
 """Framework-facing buffer over the C ABI (Sec. VI-A "Common Backend Architecture",
 Table V "Buffer operations"): `dispatch`, `combine`, `get_tokens_per_expert_list`,
-`get_comm_stream`, `capture`, `destroy_handle`, plus autograd wrappers that reuse one
+`get_comm_stream`, `capture`, `destroy_handle`, `combine_backward`, plus autograd wrappers that reuse one
 handle for the forward and the backward pass (Sec. III-F training pattern, Sec. VI-B).
 
 What it adds to the binding is resource plumbing only, as the paper describes it:
@@ -140,6 +140,26 @@ class EPBuffer:
             out.record_stream(self.comm_stream)
         return out, self._leave()
 
+    def combine_backward(self, grad_out: torch.Tensor, handle: EPHandle, topk_weights: Optional[torch.Tensor] = None,
+                         y: Optional[torch.Tensor] = None, previous_event: Optional[torch.cuda.Event] = None):
+        """grad_y, grad_w, event = combine_backward(grad_out, handle, topk_weights, y): the gradient of a
+        weighted combine with respect to the expert outputs (windows like y, rows without an entry
+        zero) and, when y is given, with respect to the gate weights [T, K]."""
+        self._enter(previous_event)
+        sp = self.comm_stream.cuda_stream
+        with torch.cuda.stream(self.comm_stream):
+            if y is not None:
+                grad_y = torch.zeros(y.shape, dtype=torch.bfloat16, device=self.device)
+            else:
+                rows = self.E * self.C if self.ll else handle.num_tokens * self.K
+                store = torch.zeros((rows, self.H), dtype=torch.bfloat16, device=self.device)
+                grad_y = store.view(self.E, self.C, self.H) if self.ll else store
+            grad_w = torch.empty((handle.num_tokens, self.K), dtype=torch.float32, device=self.device) if y is not None else None
+            ep.ep_combine_backward(handle.raw, grad_out, grad_y, topk_weights=topk_weights, y=y, grad_w=grad_w, stream=sp)
+            for t in (grad_out, grad_y) + ((y, grad_w) if y is not None else ()):
+                t.record_stream(self.comm_stream)
+        return grad_y, grad_w, self._leave()
+
     def get_tokens_per_expert_list(self) -> List[int]:
         """Rows placed per expert by the last dispatch, read from the pinned counter."""
         if self._last_event is not None:
@@ -232,28 +252,19 @@ class EPDispatchFn(torch.autograd.Function):
 
 
 class EPCombineFn(torch.autograd.Function):
-    """Forward: weighted combine.  Backward: cached dispatch of the output gradient; each
-    row is then scaled by its gate weight, and the weight gradient is the row-wise dot
-    product of expert output and dispatched gradient (both plain torch ops on the rows)."""
+    """Forward: weighted combine.  Backward: one call with the same handle -- the output gradient
+    dispatched to the rows of y, each copy scaled by its gate weight, and the weight gradient as
+    the dot product of every expert output row with the gradient of its token."""
 
     @staticmethod
-    def forward(ctx, y, topk_weights, buf: EPBuffer, handle: EPHandle, dst_row):
+    def forward(ctx, y, topk_weights, buf: EPBuffer, handle: EPHandle):
         out, _ = buf.combine(y, handle, topk_weights)
         ctx.buf, ctx.handle = buf, handle
-        ctx.save_for_backward(y, topk_weights, dst_row)
+        ctx.save_for_backward(y, topk_weights)
         return out
 
     @staticmethod
     def backward(ctx, grad_out):
-        y, w, dst_row = ctx.saved_tensors
-        g_rows, _, recv_w, _, _ = ctx.buf.dispatch(grad_out.contiguous(), topk_weights=w, handle=ctx.handle)
-        flat = g_rows.reshape(-1, g_rows.shape[-1])
-        valid = dst_row >= 0
-        rows = dst_row.clamp(min=0).long()
-        grad_y = torch.zeros_like(y)
-        gy_flat = grad_y.reshape(-1, y.shape[-1])
-        used = rows[valid]
-        gy_flat[used] = (flat[used].float() * recv_w[used][:, None]).to(y.dtype)
-        dots = (y.reshape(-1, y.shape[-1])[rows].float() * grad_out.float()[:, None, :]).sum(-1)
-        grad_w = torch.where(valid, dots, torch.zeros_like(dots))
-        return grad_y, grad_w, None, None, None
+        y, w = ctx.saved_tensors
+        grad_y, grad_w, _ = ctx.buf.combine_backward(grad_out.contiguous(), ctx.handle, w, y)
+        return grad_y, grad_w, None, None

@@ -971,4 +971,41 @@ ep_result_t ep_layout_static(const ep_group_config_t* cfg, const ep_tensor_t* to
     return launch_layout(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
 }
 
+ep_result_t ep_combine_backward(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_inputs,
+                                const ep_tensor_t* outputs, int32_t num_outputs, ep_stream_t stream) {
+    if (!h || !inputs || !outputs || num_inputs < 1 || num_outputs < 1) return EP_ERR_INVALID_ARG;
+    if (has_scales(inputs, num_inputs) || has_scales(outputs, num_outputs)) return EP_ERR_UNSUPPORTED;
+    ep_group_s* g = h->group;
+    const ep_group_config_t& c = g->cfg;
+    const ep_tensor_t* go = find_tag(inputs, num_inputs, EP_TAG_TOKENS);
+    const ep_tensor_t* w = find_tag(inputs, num_inputs, EP_TAG_TOPK_WEIGHTS);
+    const ep_tensor_t* y = find_tag(inputs, num_inputs, EP_TAG_EXPERT_TOKENS);
+    const ep_tensor_t* gy = find_tag(outputs, num_outputs, EP_TAG_TOKENS);
+    const ep_tensor_t* gw = find_tag(outputs, num_outputs, EP_TAG_TOPK_WEIGHTS);
+    if (!check_2d(go, EP_DTYPE_BF16, h->T, c.hidden, true) || go->stride[0] % 8 || !aligned16(go->data))
+        return EP_ERR_INVALID_ARG;
+    if (w && !check_2d(w, EP_DTYPE_F32, h->T, c.top_k, true)) return EP_ERR_INVALID_ARG;
+    if ((y != nullptr) != (gw != nullptr)) return EP_ERR_INVALID_ARG;  // the weight gradient needs the expert outputs
+    if (gw && !check_2d(gw, EP_DTYPE_F32, h->T, c.top_k, true)) return EP_ERR_INVALID_ARG;
+    CombineArgs a;
+    WindowDesc gyw;
+    if (!window_from_tensor(g, gy, &gyw)) return EP_ERR_INVALID_ARG;
+    if (y) {
+        if (!window_from_tensor(g, y, &a.win)) return EP_ERR_INVALID_ARG;
+        if (a.win.rows_cap != gyw.rows_cap) return EP_ERR_INVALID_ARG;
+    } else {
+        a.win = gyw;
+        a.win.base = nullptr;
+    }
+    a.w = w ? (const float*)w->data : nullptr;
+    a.w_stride = w ? w->stride[0] : 0;
+    a.dst_row = h->slab.dst_row;
+    a.out = nullptr; a.out_stride = 0;
+    a.T = h->T; a.K = c.top_k; a.H = c.hidden;
+    a.staged = 0; a.entry_rank = nullptr; a.ranks_per_node = 0; a.nodes = 1;
+    h->last_stream = (hipStream_t)stream;
+    return launch_combine_backward(a, (const uint16_t*)go->data, go->stride[0], gyw, gw ? (float*)gw->data : nullptr,
+                                   gw ? gw->stride[0] : 0, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+}
+
 }  // extern "C"

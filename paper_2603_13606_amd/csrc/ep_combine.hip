@@ -149,7 +149,76 @@ __global__ __launch_bounds__(256) void combine_hier_kernel(CombineArgs a, int ns
     }
 }
 
+// Backward pass of the weighted combine (Sec. III-F training pattern: the handle of the
+// forward pass is reused).  With out[t] = sum_k w[t,k] * y[row(t,k)], the gradient g = d/d out
+// gives
+//   grad_y[row(t,k), h] = bf16_rne( w[t,k] * f32(g[t,h]) )      (a dispatch of g scaled per entry)
+//   grad_w[t,k]         = sum_h f32(y[row(t,k), h]) * f32(g[t,h])
+// One workgroup per token: for every entry its threads walk the row in 16-byte units (y and g
+// read, grad_y written), each thread sums its products in float32 in the order it meets them,
+// the 64 lanes of a wave are summed by a fixed exchange tree and the four waves in order: the
+// result does not depend on timing.  Entries without a row get grad_w = 0 and write nothing.
+// Bound by HBM: per entry one row read and one written; the gradient row comes from the caches
+// after the first entry.
+__global__ __launch_bounds__(256) void combine_backward_kernel(CombineArgs a, const uint16_t* g, int64_t g_stride,
+                                                               WindowDesc gy, float* grad_w, int64_t gw_stride, int units) {
+    __shared__ float part[4];
+    const int t = blockIdx.x;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const u32x4* grow = (const u32x4*)(g + (int64_t)t * g_stride);
+    for (int k0 = 0; k0 < a.K; k0 += kWave) {  // the entries of the token, 64 at a time in the lanes of a wave
+        const int kk = k0 + lane;
+        const int my_row = kk < a.K ? a.dst_row[(int64_t)t * a.K + kk] : -1;
+        const float my_w = (a.w && kk < a.K) ? a.w[(int64_t)t * a.w_stride + kk] : 1.0f;
+        const int nk = min(kWave, a.K - k0);
+        for (int j = 0; j < nk; ++j) {
+            int row = __builtin_amdgcn_readlane(my_row, j);
+            const float w = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), j));
+            if (row >= a.win.rows_cap) row = -1;
+            float dot = 0.0f;
+            if (row >= 0) {
+                const u32x4* yrow = a.win.base ? (const u32x4*)(a.win.base + window_offset(a.win, row)) : nullptr;
+                u32x4* gyrow = (u32x4*)(gy.base + window_offset(gy, row));
+                for (int u = threadIdx.x; u < units; u += blockDim.x) {
+                    const u32x4 gv = grow[u];
+                    u32x4 o;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        o[c] = f32_to_bf16(__fmul_rn(w, bf16_lo(gv[c]))) | (f32_to_bf16(__fmul_rn(w, bf16_hi(gv[c]))) << 16);
+                    __builtin_nontemporal_store(o, gyrow + u);
+                    if (yrow) {
+                        const u32x4 yv = __builtin_nontemporal_load(yrow + u);
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            dot = __fadd_rn(dot, __fmul_rn(bf16_lo(yv[c]), bf16_lo(gv[c])));
+                            dot = __fadd_rn(dot, __fmul_rn(bf16_hi(yv[c]), bf16_hi(gv[c])));
+                        }
+                    }
+                }
+            }
+            if (grad_w) {  // wave-uniform: every thread of the workgroup takes part
+                for (int off = kWave / 2; off > 0; off >>= 1) dot = __fadd_rn(dot, __shfl_xor(dot, off, kWave));
+                if (lane == 0) part[wave] = dot;
+                __syncthreads();
+                if (threadIdx.x == 0)
+                    grad_w[(int64_t)t * gw_stride + k0 + j] =
+                        __fadd_rn(__fadd_rn(__fadd_rn(part[0], part[1]), part[2]), part[3]);
+                __syncthreads();
+            }
+        }
+    }
+}
+
 }  // namespace
+
+hipError_t launch_combine_backward(const CombineArgs& a, const uint16_t* g, int64_t g_stride, const WindowDesc& gy,
+                                   float* grad_w, int64_t gw_stride, hipStream_t s) {
+    if (a.T == 0) return hipSuccess;
+    hipLaunchKernelGGL(combine_backward_kernel, dim3((unsigned)a.T), dim3(256), 0, s, a, g, g_stride, gy, grad_w, gw_stride,
+                       a.H / 8);
+    return hipGetLastError();
+}
 
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s) {
     const int units = a.H / 8;

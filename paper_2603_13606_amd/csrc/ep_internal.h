@@ -195,6 +195,10 @@ hipError_t launch_dedup_fanout(const DedupFanoutArgs& a, hipStream_t s);
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s);
 hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStream_t s);
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
+// Backward of the weighted combine: a.win = expert outputs y (base may be nullptr: no grad_w), a.w, a.dst_row,
+// T, K, H as for the forward; g = gradient of the combined output [T, H]; gy = windows for grad_y.
+hipError_t launch_combine_backward(const CombineArgs& a, const uint16_t* g, int64_t g_stride, const WindowDesc& gy,
+                                   float* grad_w, int64_t gw_stride, hipStream_t s);
 hipError_t launch_publish_counts(int32_t* sig, const int32_t* counts, int n, hipStream_t s);
 hipError_t launch_await_counts(int32_t* sig, int n, int spin_limit, int32_t* count_out, int32_t* offset_out,
                                int32_t* totals, hipStream_t s);

@@ -357,11 +357,20 @@ PATH_CASES = [
     ("ht_prefill", None, None, "ht", 0),   # full benchmark shape
     ("skew", None, None, "ll", 512),       # full skewed shape, hot experts overflow C = 2*T*K/E
     ("stress_hot", None, None, "ht", 0),   # full stress shape, 8 of 64 ranks take half the traffic
+    ("stress", None, None, "ht", 0),       # full stress shape, uniform routing
+    # more entries per token than the 8 a combine wave gathers at a time, up to the limit of 64
+    (("skew", dict(K=17)), 300, 520, "ht", 0),
+    (("skew", dict(K=33)), 300, 520, "ll", 90),
+    (("skew", dict(K=64)), 130, 1000, "ht", 0),
+    (("skew", dict(K=64)), 130, 256, "ll", 70),
 ]
 
 
 def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True, order=0, prefetch=False, fused=False):
-    w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
+    over = {}
+    if isinstance(name, tuple):  # (workload name, overrides of its shape)
+        name, over = name[0], dict(name[1])
+    w = wl.make_workload(name, T=T, **({"H": H} if H else {}), **over)
     spec = w.spec
     T = spec.T
     topk = _mess_up(w.topk_idx, spec.E, seed=T + spec.H, frac_masked=masked)
@@ -568,6 +577,8 @@ ORDER_CASES = [
     ("ll_decode", 1030, 64, "ll", 40),      # one unit per slice, heavy drops
     ("stress_hot", None, None, "ht", 0),    # 117 MB of tokens: two read passes
     ("ll_decode", 200, None, "ht", 0),      # below the switch: token order whatever the setting
+    (("skew", dict(K=33)), 300, 520, "ht", 0),   # 9900 entries of 33 per token
+    (("skew", dict(K=64)), 200, 1024, "ll", 150),
 ]
 
 
@@ -871,6 +882,9 @@ DEDUP_CASES = [
     (("ll_decode", dict(R=4, E=24, K=3)), 333, 64, "ll", 50, True),   # K and L not powers of two, drops
     (("ll_decode", dict(R=8, E=1024, K=16)), 200, 64, "ht", 0, False),  # 128 local experts, 16 ids per header
     (("tiny", dict(dup=True)), 64, None, "ht", 0, True),              # a token naming one expert twice
+    (("skew", dict(K=17)), 300, 520, "ht", 0, True),                   # headers of 17, 33 and 64 ids (up to 528 bytes)
+    (("skew", dict(K=33)), 200, 256, "ll", 80, True),
+    (("skew", dict(K=64)), 130, 1000, "ht", 0, False),
 ]
 
 
@@ -1109,11 +1123,18 @@ def test_graph_capture_and_replay(ep, hx, oracle_mod, T, order):
 
 @pytest.mark.parametrize("name,T,H,rpn,mode", [("ll_decode", None, 512, 8, "ht"), ("ll_decode", 77, 1000, 4, "ll"),
                                                ("stress_hot", 300, 256, 8, "ht"), ("skew", 200, 512, 2, "ht"),
-                                               ("ht_prefill", None, None, 8, "ht")])
+                                               ("ht_prefill", None, None, 8, "ht"),
+                                               # 16 and 6 nodes, 17 to 64 entries per token
+                                               (("skew", dict(K=17)), 300, 520, 1, "ht"),
+                                               (("skew", dict(K=33)), 200, 256, 3, "ll"),
+                                               (("skew", dict(K=64)), 130, 1000, 1, "ht")])
 def test_combine_two_level_order(ep, hx, oracle_mod, name, T, H, rpn, mode):
     """Sum per node of rpn ranks first, then across nodes: bit-exact with the oracle's
     two-level float32 order, within one bf16 ulp of the flat order and of the float64 sum."""
-    w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
+    over = {}
+    if isinstance(name, tuple):
+        name, over = name[0], dict(name[1])
+    w = wl.make_workload(name, T=T, **({"H": H} if H else {}), **over)
     spec = w.spec
     T = spec.T
     _say(f"two-level combine {name} T={T} H={spec.H} ranks_per_node={rpn} mode={mode}")
