@@ -314,6 +314,23 @@ def once_per_rank(ep, torch, np, spec, sets, rows, stream_ptr):
     return res
 
 
+def hbm_copy_reference(ep, hx, torch):
+    """A plain streaming copy of 512 MiB: the reference point for bandwidth, and the kernel of known
+    size that scales the rocprofv3 byte counters."""
+    cal_src = torch.empty(512 << 20, dtype=torch.uint8, device=hx.DEV).fill_(1)
+    cal_dst = torch.empty_like(cal_src)
+    cal_ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
+    ep.ep_calibration_copy(cal_dst, cal_src)
+    for j in range(6):
+        cal_ev[j].record()
+        ep.ep_calibration_copy(cal_dst, cal_src)
+    cal_ev[6].record()
+    torch.cuda.synchronize()
+    cal_us = min(cal_ev[j].elapsed_time(cal_ev[j + 1]) for j in range(6)) * 1e3
+    return {"gbps": round(2 * cal_src.numel() / (cal_us * 1e-6) / 1e9, 1),
+            "what": "plain 16-byte-per-lane copy of 512 MiB (read + write bytes / best of 6 launches)"}
+
+
 def extras(ep, hx, wl, torch, np, group, spec, first_set, rows, stream_ptr, iters: int = 20):
     """Timings of the dispatch variants outside the headline step (HIP events, mean of iters)."""
     x, topk, gate, recv, y, out = first_set
@@ -456,6 +473,9 @@ def main() -> int:
                     help="leave out the add-on measurements (all_configs, once_per_rank, per-op events, CPU "
                          "baselines): only the kernels of the step run, which is what the rocprofv3 summaries are "
                          "taken with")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="with --step-only: also run the 512 MiB calibration copy (the kernel of known size the "
+                         "rocprofv3 byte counters are scaled by)")
     ap.add_argument("--headline-only", action="store_true",
                     help="the headline step with its per-op times and roofline, without all_configs, once_per_rank "
                          "and the CPU baselines")
@@ -562,20 +582,8 @@ def main() -> int:
                             "timing": f"HIP events on the launch stream around the kernel, mean of {int(lay_us.size)} "
                                       "consecutive steps (launch gap included); traffic and kernel_us_profiled are "
                                       "rocprofv3 figures of the committed run named in 'profile'"}
-        # reference point: what a plain streaming copy of 512 MiB reaches on this GPU
-        cal_src = torch.empty(512 << 20, dtype=torch.uint8, device=hx.DEV).fill_(1)
-        cal_dst = torch.empty_like(cal_src)
-        cal_ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
-        ep.ep_calibration_copy(cal_dst, cal_src)
-        for j in range(6):
-            cal_ev[j].record()
-            ep.ep_calibration_copy(cal_dst, cal_src)
-        cal_ev[6].record()
-        torch.cuda.synchronize()
-        cal_us = min(cal_ev[j].elapsed_time(cal_ev[j + 1]) for j in range(6)) * 1e3
-        line["hbm_copy_reference"] = {"gbps": round(2 * cal_src.numel() / (cal_us * 1e-6) / 1e9, 1),
-                                      "what": "plain 16-byte-per-lane copy of 512 MiB (read + write bytes / best of 6 launches)"}
-        del cal_src, cal_dst
+    if not args.step_only or args.calibrate:
+        line["hbm_copy_reference"] = hbm_copy_reference(ep, hx, torch)
     if args.graph:
         # one graph per input set: layout + dispatch + combine captured on a side stream
         side = torch.cuda.Stream()
