@@ -173,6 +173,15 @@ typedef struct {
      * written. */
     int64_t msg_stride;
     int64_t msg_lead;
+    /* Padded windows with EP_ORDER_DESTINATION*: rows kept and rows cut by the capacity in the
+     * most recent layout of the group that has FINISHED on the device (0, 0 before the first,
+     * and for every other kind of group).  The layout kernel leaves the pair in host memory
+     * and ep_dispatch reads it as a hint, without waiting for anything: when more than a
+     * third of the routed entries were cut, it walks the tokens instead of the destination
+     * rows (the rows that survive then sit in a few long runs, which the token walk copies
+     * faster).  Both walks write the same bytes; the hint changes time only. */
+    int32_t hint_rows_kept;
+    int32_t hint_rows_dropped;
 } ep_group_info_t;
 
 /* Result of a layout, host-side copy of the totals plus borrowed DEVICE pointers

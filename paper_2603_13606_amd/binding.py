@@ -83,7 +83,8 @@ class ep_group_info_t(ctypes.Structure):
         ("footprint_optimised_bytes", ctypes.c_int64), ("live_handles", ctypes.c_int32),
         ("staged_buffers", ctypes.c_int32), ("staging_sets", ctypes.c_void_p * 2),
         ("signals", ctypes.c_void_p * 2), ("combine_staging", ctypes.c_void_p * 2),
-        ("msg_stride", ctypes.c_int64), ("msg_lead", ctypes.c_int64)]
+        ("msg_stride", ctypes.c_int64), ("msg_lead", ctypes.c_int64),
+        ("hint_rows_kept", ctypes.c_int32), ("hint_rows_dropped", ctypes.c_int32)]
 
 
 _INFO_PTRS = ("expert_count", "expert_kept", "expert_offset", "rank_pair_count", "rank_token_count",

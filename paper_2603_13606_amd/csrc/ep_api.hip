@@ -57,6 +57,13 @@ struct ep_group_s {
     int nsets = 0, next_set = 0;
     int32_t* signals[2] = {nullptr, nullptr};
     uint16_t* comb_stage[2] = {nullptr, nullptr};
+    // Padded windows, destination-ordered dispatch: what the capacity kept and cut in the most
+    // recent layout that has finished, low word kept, high word dropped, written by the layout
+    // kernel into mapped host memory (one 8-byte store).  ep_dispatch reads it as a hint: when
+    // most entries were cut, the rows that remain sit in a few long runs and the token walk
+    // copies them faster.  Either walk writes the same bytes; a stale hint costs time only.
+    int64_t* drop_hint = nullptr;      // host address
+    int64_t* drop_hint_dev = nullptr;  // the same word as the kernels address it
     int sig_ints() const { return 2 * cfg.num_experts + cfg.num_ranks; }
     int32_t* sig_dispatch(int set) const { return signals[set]; }
     int32_t* sig_rank(int set) const { return signals[set] + cfg.num_experts; }
@@ -399,9 +406,18 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     auto fail = [&](ep_result_t r) {
         for (int i = 0; i < 2; ++i) { dev_free(g, g->staging[i]); dev_free(g, g->signals[i]); dev_free(g, g->comb_stage[i]); }
         for (auto& f : g->free_slabs) free_slab(g, f);
+        if (g->drop_hint) (void)hipHostFree(g->drop_hint);
         delete g;
         return r;
     };
+    if (cfg->mode == EP_MODE_LL && cfg->dispatch_order != EP_ORDER_TOKEN && cfg->dispatch_path == EP_PATH_DIRECT) {
+        void *hp = nullptr, *dp = nullptr;
+        if (hipHostMalloc(&hp, 64, hipHostMallocMapped) != hipSuccess) return fail(EP_ERR_NOMEM);
+        g->drop_hint = (int64_t*)hp;
+        *g->drop_hint = 0;
+        if (hipHostGetDevicePointer(&dp, hp, 0) != hipSuccess) return fail(EP_ERR_HIP);
+        g->drop_hint_dev = (int64_t*)dp;
+    }
     const int nstaging = g->staging_slots > 0 ? (g->nsets > 1 ? g->nsets : 1) : 0;
     for (int i = 0; i < nstaging; ++i) {
         void* p = nullptr;
@@ -442,6 +458,7 @@ ep_result_t ep_group_destroy(ep_group_t g, ep_stream_t stream) {
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
     for (auto& s : g->free_slabs) free_slab(g, s);
     for (int i = 0; i < 2; ++i) { dev_free(g, g->staging[i]); dev_free(g, g->signals[i]); dev_free(g, g->comb_stage[i]); }
+    if (g->drop_hint) (void)hipHostFree(g->drop_hint);
     delete g;
     return EP_SUCCESS;
 }
@@ -458,6 +475,9 @@ ep_result_t ep_group_query(ep_group_t g, ep_group_info_t* info) {
     info->msg_bytes = g->msg_bytes;
     info->msg_stride = g->msg_stride;
     info->msg_lead = g->msg_lead;
+    const int64_t hint = g->drop_hint ? __atomic_load_n(g->drop_hint, __ATOMIC_RELAXED) : 0;
+    info->hint_rows_kept = (int32_t)(hint & 0xffffffffLL);
+    info->hint_rows_dropped = (int32_t)(hint >> 32);
     info->staging_slots = g->staging_slots;
     info->staging = g->staging[0];
     info->staged_buffers = g->nsets;
@@ -556,6 +576,7 @@ static ep_result_t prepare_layout(ep_handle_t* handle, ep_group_t g, const ep_te
     a.run_start = (c.dispatch_order != EP_ORDER_TOKEN && c.dispatch_path == EP_PATH_DIRECT) ? s.run_start : nullptr;
     a.warm_x = nullptr; a.warm_stride = 0; a.warm_rows = 0; a.warm_units = c.hidden / 8; a.nchunks = 1;
     a.rows_cap = -1; a.recv_count = nullptr;
+    a.drop_hint = (a.padded && a.run_start) ? g->drop_hint_dev : nullptr;
     if (tokens && a.run_start && c.dispatch_order == EP_ORDER_DESTINATION) {
         a.warm_x = (const uint16_t*)tokens->data;
         a.warm_stride = tokens->stride[0];
@@ -719,6 +740,11 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
     const bool fp8 = call.fp8;
     const ep_tensor_t* x = call.x;
     a.run_start = h->has_runs ? h->slab.run_start : nullptr;
+    if (a.run_start && a.win.padded && g->drop_hint) {  // capacity cut most entries last time: walk the tokens
+        const int64_t v = __atomic_load_n(g->drop_hint, __ATOMIC_RELAXED);
+        const int64_t kept = v & 0xffffffffLL, dropped = v >> 32;
+        if (2 * dropped > kept) a.run_start = nullptr;
+    }
     a.nwc = h->nwc; a.chunk_entries = h->chunk_entries;
     // the read-ahead of the layout call is good for the dispatch that follows it, once
     a.prefetched_rows = (h->warm_x == x->data && h->warm_stride == x->stride[0]) ? h->warm_rows : 0;
@@ -965,7 +991,7 @@ ep_result_t ep_layout_static(const ep_group_config_t* cfg, const ep_tensor_t* to
     a.rank_offset = out->rank_offset; a.totals = out->totals;
     a.slot = out->slot; a.dst_row = out->dst_row; a.rank_row = out->rank_row; a.entry_rank = out->entry_rank;
     a.sorted_token = out->sorted_token; a.sorted_k = out->sorted_k; a.sorted_row = out->sorted_row;
-    a.run_start = nullptr;
+    a.run_start = nullptr; a.drop_hint = nullptr;
     a.warm_x = nullptr; a.warm_stride = 0; a.warm_rows = 0; a.warm_units = c.hidden / 8; a.nchunks = 1;
     a.rows_cap = -1; a.recv_count = nullptr;
     return launch_layout(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;

@@ -106,34 +106,6 @@ __global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunP
     if (blockIdx.x == 0 && blockIdx.y == 0 && p.first_block == 0 && a.recv_count) {
         for (int e = threadIdx.x; e < a.E; e += blockDim.x) a.recv_count[e] = a.expert_kept[e];
     }
-    if (PADDED) {
-        // With most entries cut by the capacity, the rows that remain come from the first tokens
-        // of every hot expert: a few long runs in the first blocks and next to nothing after
-        // them, which this walk balances badly.  The launch then walks the tokens instead (the
-        // plain token order over whatever workgroups the grid has); the layout has left the
-        // counts that decide it in the handle.  The first token segment of the wave is loaded
-        // before the counts are known, so that the decision costs no round trip of its own.
-        const int units = p.units, nseg = (units + kWave - 1) / kWave;
-        const int lane = threadIdx.x & (kWave - 1);
-        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const int64_t nwaves = (int64_t)gridDim.x * gridDim.y * 4, total = (int64_t)a.T * nseg;
-        int64_t u = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 4 + wave;
-        const bool first = p.first_block == 0 && u < total;
-        const int t0 = first ? (int)(u / nseg) : 0, seg0 = first ? (int)(u - (int64_t)t0 * nseg) : 0;
-        TokenSegment s0;
-        if (first) s0 = load_token_segment(a, t0, seg0, units, lane);
-        const int kept = __builtin_amdgcn_readfirstlane(a.totals[TOT_KEPT]);
-        const int dropped = __builtin_amdgcn_readfirstlane(a.totals[TOT_DROPPED]);
-        if (2 * dropped > kept) {
-            if (!first) return;  // one launch does all of it
-            store_token_segment(a, s0, t0, seg0, units, lane);
-            for (u += nwaves; u < total; u += nwaves) {
-                const int t = (int)(u / nseg);
-                copy_token_segment(a, t, (int)(u - (int64_t)t * nseg), units, lane);
-            }
-            return;
-        }
-    }
     constexpr int tpr = 1 << TPR_SHIFT, nsub = 256 >> TPR_SHIFT;
     // grid = (kSlices * splits * E, blocks): x runs fastest, so workgroups are handed out
     // slice by slice, then share by share of a run, expert by expert, block by block

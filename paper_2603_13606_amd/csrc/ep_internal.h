@@ -66,6 +66,7 @@ struct LayoutArgs {
     int nchunks;              // workgroups of the slot kernel that lay out (set by launch_layout)
     int64_t rows_cap;         // a launch that also dispatches: rows its output takes (more are flagged); else -1
     int32_t* recv_count;      // such a launch: where the caller wants the rows placed per expert [E]; else nullptr
+    int64_t* drop_hint;       // mapped host word or nullptr: gets kept | dropped << 32 (rows of padded windows)
     int32_t* run_start;       // [nwc+1, E] or nullptr: first sorted position of expert e among the entries
                               // of wave-chunks >= c (row c); only the histogram kernels fill it
 };

@@ -399,6 +399,7 @@ __device__ int write_tables(const LayoutArgs& a, const Lds& l, int tid, int lane
         a.totals[TOT_SORTED] = total_e;
         a.totals[TOT_MSGS] = S[a.W - 1] + tot[a.W - 1] - S[E + 2];  // the rank bins are the last R bins
         a.totals[TOT_ROWS_END] = rows_end;
+        if (a.drop_hint) *a.drop_hint = (int64_t)kept | ((int64_t)dropped << 32);
     }
     return rows_end;
 }

@@ -40,7 +40,7 @@ def test_struct_sizes_match_header(ep):
     assert ctypes.sizeof(ep.ep_group_config_t) == 60
     assert ctypes.sizeof(ep.ep_tensor_t) == 8 + 16 + 64
     assert ctypes.sizeof(ep.ep_layout_info_t) == 8 + 7 * 8 + 13 * 8
-    assert ctypes.sizeof(ep.ep_group_info_t) == 40 + 7 * 8 + 8 + 6 * 8 + 2 * 8
+    assert ctypes.sizeof(ep.ep_group_info_t) == 40 + 7 * 8 + 8 + 6 * 8 + 2 * 8 + 8
     assert ctypes.sizeof(ep.ep_complete_config_t) == 8
 
 

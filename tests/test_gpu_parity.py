@@ -593,6 +593,55 @@ def test_dispatch_destination_order_parity(ep, hx, oracle_mod, name, T, H, mode,
     _run_path(ep, hx, oracle_mod, name, T, H, mode, C, order=int(str(order)[0]), prefetch=prefetch)
 
 
+def test_padded_destination_order_follows_the_drop_hint(ep, hx, oracle_mod):
+    """Padded windows in a destination-ordered group: the layout leaves the kept / dropped row
+    counts where the host can see them, and a later dispatch walks the tokens when the capacity
+    cut most entries.  The hint is what the oracle counts; every dispatch -- before the hint is
+    there (run order), with a hint that says "mostly dropped" (token walk), and after routing
+    without drops has turned it back -- writes the oracle's bytes."""
+    w = wl.make_workload("skew", T=1100, H=512)          # 8800 entries: above the run-order switch
+    spec = w.spec
+    T, C = spec.T, 80   # the skewed routing loses 6324 of 8800 entries to it, the even one 20
+    rng = np.random.default_rng(5)
+    flat = np.stack([rng.permutation(spec.E)[: spec.K] for _ in range(T)]).astype(np.int32)  # even routing
+    g = _group(ep, spec, T, ep.EP_MODE_LL, C=C, dispatch_order=ep.EP_ORDER_DESTINATION)
+    try:
+        x = hx.bits_to_dev(w.x_bits)
+        d_w = torch.from_numpy(w.topk_w).to(hx.DEV)
+        rows = spec.E * C
+        assert (ep.ep_group_query(g).hint_rows_kept, ep.ep_group_query(g).hint_rows_dropped) == (0, 0)
+        seen = []
+        for step, topk in enumerate([w.topk_idx, w.topk_idx, flat, flat, w.topk_idx]):
+            _say(f"drop hint step {step}")
+            lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, layout=1, C=C, C_rank=T)
+            o_recv = np.full((rows, spec.H), hx.POISON, np.uint16)
+            o_w = np.full(rows, np.float32(-3.5), np.float32)
+            o_src = np.full(rows, -9, np.int32)
+            oracle_mod.dispatch(w.x_bits, w.topk_w, lay, o_recv, o_w, o_src)
+            store = hx.poison_bf16((rows, spec.H))
+            r_w = torch.full((rows,), -3.5, dtype=torch.float32, device=hx.DEV)
+            r_src = torch.full((rows,), -9, dtype=torch.int32, device=hx.DEV)
+            h = ep.ep_layout_prefetch(g, torch.from_numpy(topk).to(hx.DEV), x)
+            ep.ep_dispatch(h, x, store.view(spec.E, C, spec.H), topk_weights=d_w, recv_w=r_w, recv_src=r_src)
+            torch.cuda.synchronize()
+            assert np.array_equal(hx.dev_to_bits(store), o_recv)
+            assert np.array_equal(r_w.cpu().numpy(), o_w) and np.array_equal(r_src.cpu().numpy(), o_src)
+            info = ep.ep_group_query(g)
+            assert (info.hint_rows_kept, info.hint_rows_dropped) == (int(lay.kept), int(lay.dropped))
+            seen.append(2 * int(lay.dropped) > int(lay.kept))
+            ep.ep_handle_destroy(h)
+        assert seen == [True, True, False, False, True], "the two routings should sit on either side of the switch"
+    finally:
+        ep.ep_group_destroy(g)
+    # a group that walks the tokens anyway keeps no hint
+    g0 = _group(ep, spec, T, ep.EP_MODE_LL, C=C, dispatch_order=ep.EP_ORDER_TOKEN)
+    h = ep.ep_layout(g0, torch.from_numpy(w.topk_idx).to(hx.DEV))
+    torch.cuda.synchronize()
+    assert ep.ep_group_query(g0).hint_rows_dropped == 0
+    ep.ep_handle_destroy(h)
+    ep.ep_group_destroy(g0)
+
+
 def test_destination_order_output_too_small_is_flagged_not_overrun(ep, hx, oracle_mod):
     w = wl.make_workload("ll_decode", T=1100, H=256)
     spec = w.spec
