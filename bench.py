@@ -350,6 +350,29 @@ def extras(ep, hx, wl, torch, np, group, spec, first_set, rows, stream_ptr, iter
             res[key] = {"us": round(us, 2), "algorithmic_bytes": nbytes, "gbps": round(nbytes / (us * 1e-6) / 1e9, 1)}
             ep.ep_handle_destroy(h)
             ep.ep_group_destroy(g5)
+        # the same with the quantisation moved into the layout launch (group option quantize_ahead): layout and
+        # dispatch are rated together, once for the token walk (plain layout + quantising dispatch) and once for
+        # the staged rows copied in destination order
+        pair = {}
+        for key, order, ahead in (("token_walk", ep.EP_ORDER_TOKEN, 0), ("quantize_ahead", ep.EP_ORDER_DESTINATION, 1)):
+            g6 = ep.ep_group_create(ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_HT, dispatch_order=order,
+                                                   quantize_ahead=ahead))
+            lay6 = ep.PreparedLayout(g6, topk, tokens=x if ahead else None)
+            call = ep.prepare_dispatch(x, q, topk_weights=gate, recv_scales=sc)
+
+            def both():
+                h6 = lay6(stream_ptr)
+                call(h6, stream_ptr)
+                ep.ep_handle_destroy(h6)
+
+            def lay_only():
+                ep.ep_handle_destroy(lay6(stream_ptr))
+
+            us, us_l = timed(both), timed(lay_only)
+            pair[key] = {"layout_plus_dispatch_us": round(us, 2), "layout_us": round(us_l, 2),
+                         "gbps": round((nbytes + 4 * T * K) / (us * 1e-6) / 1e9, 1)}
+            ep.ep_group_destroy(g6)
+        res["fp8_layout_plus_dispatch"] = pair
         del q, sc
     # destination-ordered dispatch: with its read pass, and without it for cache-resident tokens
     for order, key in ((ep.EP_ORDER_DESTINATION, "dispatch_destination_order"),

@@ -137,6 +137,19 @@ typedef struct {
                                     "hierarchical" reduction of Sec. III-D / V-A)          */
     int32_t dispatch_order;      /* EP_ORDER_TOKEN / EP_ORDER_DESTINATION /
                                     EP_ORDER_DESTINATION_RESIDENT (EP_PATH_DIRECT only)     */
+    int32_t quantize_ahead;      /* 0, or 1 (needs EP_ORDER_DESTINATION, EP_PATH_DIRECT and
+                                    H % 128 == 0): ep_layout_prefetch does not only read the
+                                    announced tokens, it also quantises them to FP8 -- the
+                                    format of the quantising ep_dispatch -- into a staging
+                                    copy kept with the handle (max_tokens_per_rank *
+                                    (H + H/32) bytes per handle), on the compute units the
+                                    layout leaves idle.  The first quantising ep_dispatch of
+                                    that tensor then copies the staged rows in destination
+                                    order instead of quantising in token order: same codes,
+                                    same scales.  The tokens must not change between the two
+                                    calls.  Inputs too small for the destination order are
+                                    quantised by the dispatch as usual.  (Sec. I: dispatch
+                                    may quantise; Sec. IV-C: work next to the send.)       */
 } ep_group_config_t;
 
 /* Allocator callbacks (Sec. III-C): when given, every device allocation of the
@@ -412,7 +425,8 @@ EP_API ep_result_t ep_handle_destroy(ep_handle_t handle);
  * H % 128 == 0 and EP_PATH_DIRECT.  Per token and group of 128 channels:
  * amax = max|x|; scales[row, g] = amax / 448; q = e4m3(f32(x) * (448 / amax)), float32
  * operations, round to nearest even, magnitudes above 448 saturate; amax == 0 gives scale 1.
- * The quantising dispatch walks the tokens whatever the group's dispatch_order.
+ * The quantising dispatch walks the tokens whatever the group's dispatch_order, except in a
+ * group with quantize_ahead, after an ep_layout_prefetch that announced the same tokens.
  * EP_PATH_RANK_DEDUP runs three steps on the stream -- send to the group's staging
  * windows, receiver-side ranking of the header entries, fan-out -- and produces the
  * same outputs; dispatches of one group must then not overlap (they share the

@@ -66,7 +66,7 @@ class ep_group_config_t(ctypes.Structure):
                 ("mode", ctypes.c_int32), ("slots_per_subregion", ctypes.c_int32),
                 ("dispatch_path", ctypes.c_int32), ("max_handles", ctypes.c_int32),
                 ("staged_buffers", ctypes.c_int32), ("ranks_per_node", ctypes.c_int32),
-                ("dispatch_order", ctypes.c_int32)]
+                ("dispatch_order", ctypes.c_int32), ("quantize_ahead", ctypes.c_int32)]
 
 
 class ep_complete_config_t(ctypes.Structure):
@@ -242,7 +242,7 @@ def make_config(num_ranks: int, num_experts: int, hidden: int, top_k: int, max_t
                 mode: int = EP_MODE_HT, my_rank: int = 0, slots_per_subregion: int = 0,
                 dispatch_path: int = EP_PATH_DIRECT, max_handles: int = 0,
                 dtype: int = EP_DTYPE_BF16, staged_buffers: int = 0, ranks_per_node: int = 0,
-                dispatch_order: int = 0) -> ep_group_config_t:
+                dispatch_order: int = 0, quantize_ahead: int = 0) -> ep_group_config_t:
     c = ep_group_config_t()
     c.size = ctypes.sizeof(ep_group_config_t)
     c.num_ranks, c.my_rank, c.num_experts, c.hidden, c.top_k = num_ranks, my_rank, num_experts, hidden, top_k
@@ -251,6 +251,7 @@ def make_config(num_ranks: int, num_experts: int, hidden: int, top_k: int, max_t
     c.staged_buffers = staged_buffers
     c.ranks_per_node = ranks_per_node
     c.dispatch_order = dispatch_order
+    c.quantize_ahead = quantize_ahead
     return c
 
 

@@ -21,7 +21,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hi
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-HEADERS = [os.path.join(CSRC, "ep_internal.h"), os.path.join(ROOT, "include", "ep.h")]
+HEADERS = [os.path.join(CSRC, "ep_internal.h"), os.path.join(CSRC, "ep_fp8.h"), os.path.join(ROOT, "include", "ep.h")]
 _ID_MARK = b"EP_BUILD_ID="
 
 

@@ -23,6 +23,7 @@ struct Slab {
     uint32_t* pub;   // per-chunk bin sums of the layout kernel (kMaxChunks rows of W words)
     uint32_t* ctl;   // its generation / arrival words; pub and ctl are zeroed when the slab is made
     int32_t *slot, *dst_row, *rank_row, *sorted_token, *sorted_k, *sorted_row, *entry_rank, *run_start;
+    uint8_t* quant;  // FP8 staging copy of the tokens (groups that quantise ahead), or nullptr
     // receiving side of the once-per-rank path (only carved for EP_PATH_RANK_DEDUP)
     int32_t *recv_count, *recv_kept, *recv_dst_row;
     // what the receiving side of a staged call learns from the coordination counters
@@ -84,6 +85,8 @@ struct ep_handle_s {
     const void* warm_x = nullptr;  // tokens the layout launch has read into cache (ep_layout_prefetch)
     int64_t warm_stride = 0;
     int warm_rows = 0;
+    const void* quant_x = nullptr;  // tokens the layout launch has quantised into slab.quant (all T rows)
+    int64_t quant_stride = 0;
     // receive phase of a staged (send_only) call, run by ep_complete
     int pending = PENDING_NONE;
     int pending_set = 0;
@@ -147,6 +150,8 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
     const int64_t o_vc = dedup ? carve(&cur, E) : 0, o_vk = dedup ? carve(&cur, E) : 0;
     const int64_t o_vr = dedup ? carve(&cur, g->staging_slots * g->cfg.top_k) : 0;
     const int64_t o_rc = carve(&cur, R), o_rf = carve(&cur, R + 1);
+    const bool ahead = g->cfg.quantize_ahead != 0;
+    const int64_t o_q = ahead ? carve(&cur, (int64_t)g->cfg.max_tokens_per_rank * quant_row_pitch(g->cfg.hidden) / 4) : 0;
     if (base && s) {
         s->base = base;
         s->totals = base + o_tot; s->expert_count = base + o_ec; s->expert_kept = base + o_ek;
@@ -158,6 +163,7 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
         s->recv_count = dedup ? base + o_vc : nullptr; s->recv_kept = dedup ? base + o_vk : nullptr;
         s->recv_dst_row = dedup ? base + o_vr : nullptr;
         s->recv_rank_count = base + o_rc; s->recv_rank_offset = base + o_rf;
+        s->quant = ahead ? (uint8_t*)(base + o_q) : nullptr;
     }
     return cur;
 }
@@ -260,6 +266,9 @@ ep_result_t validate_config(const ep_group_config_t* cfg) {
     if (cfg->staged_buffers < 0 || cfg->staged_buffers > 2) return EP_ERR_INVALID_ARG;
     if (cfg->ranks_per_node < 0) return EP_ERR_INVALID_ARG;
     if (cfg->dispatch_order < EP_ORDER_TOKEN || cfg->dispatch_order > EP_ORDER_DESTINATION_RESIDENT) return EP_ERR_INVALID_ARG;
+    if (cfg->quantize_ahead != 0 && cfg->quantize_ahead != 1) return EP_ERR_INVALID_ARG;
+    if (cfg->quantize_ahead && (cfg->dispatch_order != EP_ORDER_DESTINATION || cfg->dispatch_path != EP_PATH_DIRECT || H % 128 != 0))
+        return EP_ERR_INVALID_ARG;
     const int C = cfg->slots_per_subregion ? cfg->slots_per_subregion : cfg->max_tokens_per_rank;
     if (cfg->mode == EP_MODE_LL && (int64_t)E * C > 0x7fffffffLL) return EP_ERR_INVALID_ARG;
     return EP_SUCCESS;
@@ -577,12 +586,19 @@ static ep_result_t prepare_layout(ep_handle_t* handle, ep_group_t g, const ep_te
     a.warm_x = nullptr; a.warm_stride = 0; a.warm_rows = 0; a.warm_units = c.hidden / 8; a.nchunks = 1;
     a.rows_cap = -1; a.recv_count = nullptr;
     a.drop_hint = (a.padded && a.run_start) ? g->drop_hint_dev : nullptr;
+    a.quant_out = nullptr; a.quant_pitch = 0;
+    h->quant_x = nullptr;
     if (tokens && a.run_start && c.dispatch_order == EP_ORDER_DESTINATION) {
         a.warm_x = (const uint16_t*)tokens->data;
         a.warm_stride = tokens->stride[0];
-        a.warm_rows = (int)std::min<int64_t>(T, kWarmBytes / (2 * (int64_t)c.hidden));
+        const int cached_rows = (int)std::min<int64_t>(T, kWarmBytes / (2 * (int64_t)c.hidden));
+        a.warm_rows = c.quantize_ahead ? (int)T : cached_rows;  // a staging copy needs every row
         if (layout_prefetches(a)) {
-            h->warm_x = tokens->data; h->warm_stride = a.warm_stride; h->warm_rows = a.warm_rows;
+            h->warm_x = tokens->data; h->warm_stride = a.warm_stride; h->warm_rows = cached_rows;
+            if (c.quantize_ahead) {
+                a.quant_out = s.quant; a.quant_pitch = quant_row_pitch(c.hidden);
+                h->quant_x = tokens->data; h->quant_stride = a.warm_stride;
+            }
         } else {
             a.warm_x = nullptr;
         }
@@ -762,8 +778,12 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
         // per-expert counts are delivered by ep_complete from the coordination counters
         int32_t* recv_count = a.recv_count;
         if (send_only) a.recv_count = nullptr;
-        hipError_t e = fp8 ? launch_dispatch_fp8(a, call.scales, (hipStream_t)stream)
-                           : launch_dispatch(a, (hipStream_t)stream);
+        // rows the layout call quantised ahead are copied in destination order, once
+        const bool staged = fp8 && h->quant_x == x->data && h->quant_stride == x->stride[0] && dispatch_fp8_staged_possible(a);
+        if (fp8) h->quant_x = nullptr;
+        hipError_t e = staged ? launch_dispatch_fp8_staged(a, call.scales, h->slab.quant, quant_row_pitch(c.hidden), (hipStream_t)stream)
+                       : fp8  ? launch_dispatch_fp8(a, call.scales, (hipStream_t)stream)
+                              : launch_dispatch(a, (hipStream_t)stream);
         if (e != hipSuccess) return EP_ERR_HIP;
         if (send_only) {
             if (launch_publish_counts(g->sig_dispatch(set), h->slab.expert_kept, c.num_experts, (hipStream_t)stream) != hipSuccess)
@@ -991,7 +1011,7 @@ ep_result_t ep_layout_static(const ep_group_config_t* cfg, const ep_tensor_t* to
     a.rank_offset = out->rank_offset; a.totals = out->totals;
     a.slot = out->slot; a.dst_row = out->dst_row; a.rank_row = out->rank_row; a.entry_rank = out->entry_rank;
     a.sorted_token = out->sorted_token; a.sorted_k = out->sorted_k; a.sorted_row = out->sorted_row;
-    a.run_start = nullptr; a.drop_hint = nullptr;
+    a.run_start = nullptr; a.drop_hint = nullptr; a.quant_out = nullptr; a.quant_pitch = 0;
     a.warm_x = nullptr; a.warm_stride = 0; a.warm_rows = 0; a.warm_units = c.hidden / 8; a.nchunks = 1;
     a.rows_cap = -1; a.recv_count = nullptr;
     return launch_layout(a, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;

@@ -8,13 +8,12 @@
 // them K times, so all global accesses are full 64-lane x 16-byte bursts.  The
 // routing entries of the token are wave-uniform and come through scalar loads.
 #include "ep_internal.h"
+#include "ep_fp8.h"
 
 #include <algorithm>
 
 namespace ep {
 namespace {
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // One wavefront copies one 1 KiB segment (16-byte unit `seg * 64 + lane` of every lane) of
 // token t to the token's destination rows, in two halves so that a caller can put other
@@ -100,17 +99,44 @@ struct RunPlan {
     int splits;       // workgroups that share one run
 };
 
-// TPR_SHIFT = log2(threads that share one row piece); PADDED = window addressing mode.
-template <int TPR_SHIFT, bool PADDED>
-__global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunPlan p) {
+// What the walk copies when the rows were quantised ahead of the dispatch (FP8 codes and scales
+// in a staging copy, row t at staged + t * pitch: H bytes of codes, then H/128 floats): unit col
+// of a staged row goes to the code row of the output window while col < code_units and to the
+// row of the scales array after that.  A staged row is half as long as a token row, so it is cut
+// into 4 slices instead of 8 (two dies share a slice): the bytes per workgroup stay what they are
+// for bf16 rows.  Window strides are in one-byte elements then.
+constexpr int kFp8Slices = 4;
+
+struct StagedRows {
+    const uint8_t* staged;
+    int64_t pitch;
+    float* recv_scales;  // [rows, groups]
+    int code_units;      // H / 16
+    int groups;          // H / 128
+};
+
+// TPR_SHIFT = log2(threads that share one row piece); PADDED = window addressing mode; FP8 =
+// rows come from a staging copy of quantised rows instead of the bf16 tokens.
+//
+// The vector-memory counter of this part counts loads and stores alike, in order, and the
+// compiler waits for it to reach zero wherever control flow stands between an access and the
+// use of its result -- which, between two row stores, means waiting for the first store to
+// reach memory before the second is issued.  So the rows of a step are copied by straight-line
+// code (loads, then stores, nothing conditional in between) whenever every lane of the wave has
+// all its rows, with the general code kept for the ragged end of a run, and the side arrays
+// are read before the rows and written after them.
+template <int TPR_SHIFT, bool PADDED, bool FP8>
+__global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunPlan p, StagedRows f) {
     if (blockIdx.x == 0 && blockIdx.y == 0 && p.first_block == 0 && a.recv_count) {
         for (int e = threadIdx.x; e < a.E; e += blockDim.x) a.recv_count[e] = a.expert_kept[e];
     }
     constexpr int tpr = 1 << TPR_SHIFT, nsub = 256 >> TPR_SHIFT;
-    // grid = (kSlices * splits * E, blocks): x runs fastest, so workgroups are handed out
+    constexpr int slices = FP8 ? kFp8Slices : kSlices;
+    constexpr int elem_bytes = FP8 ? 1 : 2;  // size of the elements the window strides count
+    // grid = (slices * splits * E, blocks): x runs fastest, so workgroups are handed out
     // slice by slice, then share by share of a run, expert by expert, block by block
-    const int xs = blockIdx.x & (kSlices - 1);
-    const int es = blockIdx.x / kSlices;
+    const int xs = blockIdx.x & (slices - 1);
+    const int es = blockIdx.x / slices;
     const int e = es / p.splits, sp = es - e * p.splits;
     const int blk = p.first_block + blockIdx.y;
     const int c0 = blk * p.group, c1 = min(c0 + p.group, a.nwc);
@@ -122,7 +148,11 @@ __global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunP
     if (lo >= hi) return;
     const int sub = threadIdx.x >> TPR_SHIFT, u = threadIdx.x & (tpr - 1);
     const int u0 = xs * p.piece, u1 = min(p.units, u0 + p.piece);
+    const int cend = FP8 ? min(u1, f.code_units) : u1;  // units of the row proper end here
     const bool side = xs == 0 && u == 0;  // one lane per row fills the side arrays
+    const uint8_t* src_base = FP8 ? f.staged : (const uint8_t*)a.x;
+    const int64_t src_pitch = FP8 ? f.pitch : a.x_stride * 2;
+    uint8_t* dst_base = (uint8_t*)a.win.base;
     for (int pos0 = lo + sp * (nsub * kRunUnroll) + sub; pos0 < hi; pos0 += p.splits * nsub * kRunUnroll) {
         int t[kRunUnroll], row[kRunUnroll];
 #pragma unroll
@@ -139,16 +169,56 @@ __global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunP
                 }
             }
         }
-        for (int col = u0 + u; col < u1; col += tpr) {
-            u32x4 v[kRunUnroll];
-#pragma unroll
-            for (int q = 0; q < kRunUnroll; ++q)
-                if (row[q] >= 0) v[q] = *((const u32x4*)(a.x + (int64_t)t[q] * a.x_stride) + col);
+        float wq[kRunUnroll];
+        if (side && a.recv_w) {
 #pragma unroll
             for (int q = 0; q < kRunUnroll; ++q) {
-                if (row[q] < 0) continue;
-                const int64_t off = PADDED ? window_offset(a.win, row[q]) : (int64_t)row[q] * a.win.stride0;
-                __builtin_nontemporal_store(v[q], (u32x4*)(a.win.base + off) + col);
+                wq[q] = 1.0f;
+                if (row[q] >= 0 && a.w) wq[q] = a.w[(int64_t)t[q] * a.w_stride + a.sorted_k[pos0 + q * nsub]];
+            }
+        }
+        const uint8_t* src[kRunUnroll];
+        uint8_t* dst[kRunUnroll];
+        bool have_all = true;
+#pragma unroll
+        for (int q = 0; q < kRunUnroll; ++q) {
+            const int r = max(row[q], 0);
+            const int64_t off = PADDED ? window_offset(a.win, r) : (int64_t)r * a.win.stride0;
+            src[q] = src_base + (int64_t)t[q] * src_pitch;
+            dst[q] = dst_base + off * elem_bytes;
+            have_all = have_all && row[q] >= 0;
+        }
+        if (FP8 && u1 > f.code_units) {  // the slice that holds the scales (workgroup-uniform), a few lanes of it
+            for (int col = max(u0, f.code_units) + u; col < u1; col += tpr) {
+                const int j = (col - f.code_units) * 4;  // up to four scales; the last unit may be part padding
+#pragma unroll
+                for (int q = 0; q < kRunUnroll; ++q) {
+                    if (row[q] < 0) continue;
+                    const u32x4 v = *((const u32x4*)src[q] + col);
+                    float* sdst = f.recv_scales + (int64_t)row[q] * f.groups + j;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c)
+                        if (j + c < f.groups) sdst[c] = __uint_as_float(v[c]);
+                }
+            }
+        }
+        if (__builtin_amdgcn_ballot_w64(!have_all) == 0) {
+            for (int col = u0 + u; col < cend; col += tpr) {
+                u32x4 v[kRunUnroll];
+#pragma unroll
+                for (int q = 0; q < kRunUnroll; ++q) v[q] = *((const u32x4*)src[q] + col);
+#pragma unroll
+                for (int q = 0; q < kRunUnroll; ++q) __builtin_nontemporal_store(v[q], (u32x4*)dst[q] + col);
+            }
+        } else {
+            for (int col = u0 + u; col < cend; col += tpr) {
+                u32x4 v[kRunUnroll];
+#pragma unroll
+                for (int q = 0; q < kRunUnroll; ++q)
+                    if (row[q] >= 0) v[q] = *((const u32x4*)src[q] + col);
+#pragma unroll
+                for (int q = 0; q < kRunUnroll; ++q)
+                    if (row[q] >= 0) __builtin_nontemporal_store(v[q], (u32x4*)dst[q] + col);
             }
         }
         if (side) {
@@ -156,10 +226,7 @@ __global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunP
             for (int q = 0; q < kRunUnroll; ++q) {
                 if (row[q] < 0) continue;
                 if (a.recv_src) a.recv_src[row[q]] = t[q];
-                if (a.recv_w) {
-                    const int k = a.sorted_k[pos0 + q * nsub];
-                    a.recv_w[row[q]] = a.w ? a.w[(int64_t)t[q] * a.w_stride + k] : 1.0f;
-                }
+                if (a.recv_w) a.recv_w[row[q]] = wq[q];
             }
         }
     }
@@ -190,8 +257,9 @@ __global__ __launch_bounds__(256) void dispatch_warm_kernel(DispatchArgs a, int 
 template <int TPR_SHIFT>
 void launch_runs(const DispatchArgs& a, const RunPlan& p, int nblocks, hipStream_t s) {
     const dim3 grid((unsigned)(kSlices * a.E * p.splits), (unsigned)nblocks);
-    if (a.win.padded) hipLaunchKernelGGL((dispatch_runs_kernel<TPR_SHIFT, true>), grid, dim3(256), 0, s, a, p);
-    else hipLaunchKernelGGL((dispatch_runs_kernel<TPR_SHIFT, false>), grid, dim3(256), 0, s, a, p);
+    const StagedRows none = {nullptr, 0, nullptr, 0, 0};
+    if (a.win.padded) hipLaunchKernelGGL((dispatch_runs_kernel<TPR_SHIFT, true, false>), grid, dim3(256), 0, s, a, p, none);
+    else hipLaunchKernelGGL((dispatch_runs_kernel<TPR_SHIFT, false, false>), grid, dim3(256), 0, s, a, p, none);
 }
 
 // ---- quantising dispatch: FP8 (OCP E4M3) rows with one float scale per 128 channels
@@ -203,65 +271,6 @@ void launch_runs(const DispatchArgs& a, const RunPlan& p, int nblocks, hipStream
 // amax == 0 gives scale 1.  Work unit = one wavefront x 1024 channels of one token:
 // a lane owns 16 consecutive channels (32 bytes in, 16 bytes out), a group is 8 lanes.
 // The row is quantised once and stored K times.
-
-// Four float32 -> four E4M3 codes, packed low to high.  The conversion instruction of this
-// part rounds to nearest even exactly as the rule above asks for magnitudes up to 448 and
-// turns anything beyond 464 into NaN, so the value is clamped first (a product can exceed 448
-// only through an overflowing 448 / amax); a NaN product stays NaN and gets the one NaN code
-// this library writes, 0x7F.
-__device__ __forceinline__ float clamp_e4m3(float p) {
-    const float c = fminf(fmaxf(p, -448.0f), 448.0f);
-    return p != p ? p : c;
-}
-
-__device__ __forceinline__ uint32_t pack4_e4m3(float f0, float f1, float f2, float f3) {
-    int r = __builtin_amdgcn_cvt_pk_fp8_f32(clamp_e4m3(f0), clamp_e4m3(f1), 0, false);
-    r = __builtin_amdgcn_cvt_pk_fp8_f32(clamp_e4m3(f2), clamp_e4m3(f3), r, true);
-    const uint32_t u = (uint32_t)r;
-    const uint32_t nan = ((u & 0x7f7f7f7fu) + 0x01010101u) & 0x80808080u;  // bit 7 of every byte that is +-NaN
-    return u & ~nan;
-}
-
-// 16 consecutive bf16 channels (two 16-byte units) of a lane, as float32.
-__device__ __forceinline__ void unpack16(const u32x4& in0, const u32x4& in1, float (&f)[16]) {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        f[2 * c] = __uint_as_float(in0[c] << 16);
-        f[2 * c + 1] = __uint_as_float(in0[c] & 0xffff0000u);
-        f[8 + 2 * c] = __uint_as_float(in1[c] << 16);
-        f[8 + 2 * c + 1] = __uint_as_float(in1[c] & 0xffff0000u);
-    }
-}
-
-// Quantises the 16 channels of this lane; the 8 lanes lane & ~7 .. | 7 hold one group of 128
-// channels and must all be active.  Returns the 16 codes, and the scale of the group.
-__device__ __forceinline__ u32x4 quantize16(const u32x4& in0, const u32x4& in1, float* scale_out) {
-    float f[16];
-    unpack16(in0, in1, f);
-    float amax = 0.0f;
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {
-        const float v = fabsf(f[c]);
-        amax = v > amax ? v : amax;
-    }
-#pragma unroll
-    for (int off = 1; off < 8; off <<= 1) {  // the 8 lanes of a 128-channel group
-        const float o = __shfl_xor(amax, off, kWave);
-        amax = o > amax ? o : amax;
-    }
-    float scale = 1.0f, inv = 1.0f;
-    if (amax != 0.0f) {
-        scale = __fdiv_rn(amax, 448.0f);
-        inv = __fdiv_rn(448.0f, amax);
-    }
-    u32x4 q;
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-        q[c] = pack4_e4m3(__fmul_rn(f[4 * c], inv), __fmul_rn(f[4 * c + 1], inv), __fmul_rn(f[4 * c + 2], inv),
-                          __fmul_rn(f[4 * c + 3], inv));
-    *scale_out = scale;
-    return q;
-}
 
 __global__ __launch_bounds__(256) void dispatch_fp8_kernel(DispatchArgs a, float* recv_scales, int nseg) {
     const int lane = threadIdx.x & (kWave - 1);
@@ -336,20 +345,23 @@ hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hip
 // hot run then loop while the others idle; 8 to 16 rows are within 1 % of the best on every
 // shape measured.  A workgroup copies nsub * kRunUnroll rows at a time, so a run of average
 // length is shared by `splits` workgroups, one step each.
-bool plan_dispatch(int T, int K, int H, int E, int order, bool have_runs, int prefetched_rows, DispatchPlan* out) {
+// `units` 16-byte units per copied row, cut into `slices` slices; H = channels of a token row
+// (what a read pass reads).
+static bool plan_rows(int T, int K, int H, int units, int slices, int E, int order, bool have_runs, int prefetched_rows,
+                      DispatchPlan* out) {
     DispatchPlan d = {};
-    const int units = H / 8;  // 16-byte units per row
     const int64_t n = (int64_t)T * K;
-    d.run_order = order != EP_ORDER_TOKEN && have_runs && n >= kRunOrderMinEntries && units >= kSlices;
+    d.run_order = order != EP_ORDER_TOKEN && have_runs && n >= kRunOrderMinEntries && units >= slices;
     if (!d.run_order) { *out = d; return false; }
     int passes = 0, nwc = 0;
     plan_layout((int)n, &passes, &nwc);
     const int chunk_entries = passes * kWave;
-    const int64_t l2_tokens = (2ll << 20) / std::max(2 * H / kSlices, 1);
+    const int64_t l2_tokens = (2ll << 20) / std::max(16 * units / slices, 1);
     const int want = (int)std::max<int64_t>(768, std::min<int64_t>(12ll * E, l2_tokens * K));
     d.group = std::max(1, want / chunk_entries);
     d.blocks = (nwc + d.group - 1) / d.group;
-    d.piece = (units + kSlices - 1) / kSlices;
+    d.piece = (units + slices - 1) / slices;
+    if (d.piece >= 8) d.piece = (d.piece + 7) / 8 * 8;  // whole 128-byte lines per slice (the last slices get less)
     d.tpr_shift = 4;
     while ((1 << d.tpr_shift) < d.piece && d.tpr_shift < 8) ++d.tpr_shift;
     const int rows_per_step = (256 >> d.tpr_shift) * kRunUnroll;
@@ -370,6 +382,10 @@ bool plan_dispatch(int T, int K, int H, int E, int order, bool have_runs, int pr
     }
     *out = d;
     return true;
+}
+
+bool plan_dispatch(int T, int K, int H, int E, int order, bool have_runs, int prefetched_rows, DispatchPlan* out) {
+    return plan_rows(T, K, H, H / 8, kSlices, E, order, have_runs, prefetched_rows, out);
 }
 
 // The copy launches of the run order (with their read passes): `launch(plan, blocks)` starts
@@ -416,11 +432,13 @@ hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
-// The quantising dispatch walks the tokens whatever the group's dispatch order: a row is
-// quantised once for all its destinations.  (Measured at the prefill shape, 66 us this way:
-// quantising a row piece again for every destination row in the run-ordered walk is bound by
-// arithmetic, 129 us; quantising once into a staging copy and copying that in run order, 90 us,
-// the run-ordered copy being bound by its per-workgroup cost once the rows are half as long.)
+// The quantising dispatch in token order: a row is quantised once for all its destinations.
+// (Measured at the prefill shape, 61 us this way.  In the order of the destination rows:
+// quantising a row piece again for every destination row is bound by arithmetic, 129 us;
+// quantising once into a staging copy by a kernel of its own and copying that in run order,
+// 90 us for the two.  Only when the staging copy is made while the layout runs -- see
+// launch_dispatch_fp8_staged -- does the copy, 56 us, come out ahead, and the layout launch
+// then takes 7 us longer.)
 hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStream_t s) {
     const int nseg = (a.H + 1023) / 1024;
     const int64_t nwaves = (int64_t)a.T * nseg;
@@ -428,6 +446,44 @@ hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStr
     if (nblk < 1) nblk = 1;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(dispatch_fp8_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, recv_scales, nseg);
+    return hipGetLastError();
+}
+
+// Units of a staged FP8 row: H/16 of codes, then the scales rounded up to whole units.
+static int fp8_code_units(int H) { return H / 16; }
+static int fp8_row_units(int H) { return H / 16 + (H / 32 + 15) / 16; }
+
+bool dispatch_fp8_staged_possible(const DispatchArgs& a) {
+    DispatchPlan d;
+    return a.H % 128 == 0 && plan_rows(a.T, a.K, a.H, fp8_row_units(a.H), kFp8Slices, a.E, EP_ORDER_DESTINATION_RESIDENT,
+                                       a.run_start != nullptr, 0, &d);
+}
+
+template <int TPR_SHIFT>
+static void launch_runs_fp8(const DispatchArgs& a, const RunPlan& p, int nblocks, const uint8_t* staged, int64_t pitch,
+                            float* recv_scales, hipStream_t s) {
+    const dim3 grid((unsigned)(kFp8Slices * a.E * p.splits), (unsigned)nblocks);
+    const StagedRows f = {staged, pitch, recv_scales, fp8_code_units(a.H), a.H / 128};
+    if (a.win.padded) hipLaunchKernelGGL((dispatch_runs_kernel<TPR_SHIFT, true, true>), grid, dim3(256), 0, s, a, p, f);
+    else hipLaunchKernelGGL((dispatch_runs_kernel<TPR_SHIFT, false, true>), grid, dim3(256), 0, s, a, p, f);
+}
+
+hipError_t launch_dispatch_fp8_staged(const DispatchArgs& a, float* recv_scales, const uint8_t* staged, int64_t pitch,
+                                      hipStream_t s) {
+    DispatchPlan d;
+    if (a.H % 128 != 0 || !plan_rows(a.T, a.K, a.H, fp8_row_units(a.H), kFp8Slices, a.E, EP_ORDER_DESTINATION_RESIDENT,
+                                     a.run_start != nullptr, 0, &d))
+        return hipErrorInvalidValue;
+    RunPlan p;
+    p.group = d.group; p.nblocks = d.blocks; p.units = fp8_row_units(a.H); p.piece = d.piece; p.tpr_shift = d.tpr_shift;
+    p.splits = d.splits; p.first_block = 0;
+    switch (p.tpr_shift) {  // every block in one launch: the staged rows were written just before, nothing to read ahead
+        case 4: launch_runs_fp8<4>(a, p, d.blocks, staged, pitch, recv_scales, s); break;
+        case 5: launch_runs_fp8<5>(a, p, d.blocks, staged, pitch, recv_scales, s); break;
+        case 6: launch_runs_fp8<6>(a, p, d.blocks, staged, pitch, recv_scales, s); break;
+        case 7: launch_runs_fp8<7>(a, p, d.blocks, staged, pitch, recv_scales, s); break;
+        default: launch_runs_fp8<8>(a, p, d.blocks, staged, pitch, recv_scales, s); break;
+    }
     return hipGetLastError();
 }
 

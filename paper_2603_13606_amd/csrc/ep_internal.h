@@ -63,6 +63,8 @@ struct LayoutArgs {
     const uint16_t* warm_x;   // [warm_rows, H] bf16, row stride warm_stride elements, or nullptr
     int64_t warm_stride;
     int warm_rows, warm_units;  // rows to read, 16-byte units per row
+    uint8_t* quant_out;       // or nullptr: rows [0, warm_rows) are also quantised to FP8 into this staging copy,
+    int64_t quant_pitch;      // row t at quant_out + t * quant_pitch: H codes, then H/128 float scales
     int nchunks;              // workgroups of the slot kernel that lay out (set by launch_layout)
     int64_t rows_cap;         // a launch that also dispatches: rows its output takes (more are flagged); else -1
     int32_t* recv_count;      // such a launch: where the caller wants the rows placed per expert [E]; else nullptr
@@ -195,6 +197,13 @@ hipError_t launch_dedup_send(const DedupSendArgs& a, hipStream_t s);
 hipError_t launch_dedup_fanout(const DedupFanoutArgs& a, hipStream_t s);
 hipError_t launch_dispatch(const DispatchArgs& a, hipStream_t s);
 hipError_t launch_dispatch_fp8(const DispatchArgs& a, float* recv_scales, hipStream_t s);
+// The quantising dispatch from rows already quantised into a staging copy (LayoutArgs::quant_out),
+// in destination order.  False when this input is not walked in destination order.
+bool dispatch_fp8_staged_possible(const DispatchArgs& a);
+hipError_t launch_dispatch_fp8_staged(const DispatchArgs& a, float* recv_scales, const uint8_t* staged, int64_t pitch,
+                                      hipStream_t s);
+// Bytes between two rows of the staging copy for hidden size H (a multiple of 128).
+constexpr int64_t quant_row_pitch(int H) { return (int64_t)H + (((int64_t)H / 32 + 15) / 16) * 16; }
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
 // Backward of the weighted combine: a.win = expert outputs y (base may be nullptr: no grad_w), a.w, a.dst_row,
 // T, K, H as for the forward; g = gradient of the combined output [T, H]; gy = windows for grad_y.

@@ -33,6 +33,7 @@
 // wave), so every phase issues all of its global loads before it waits for any of
 // them and the workgroup barriers order LDS traffic only.
 #include "ep_internal.h"
+#include "ep_fp8.h"
 
 #include <algorithm>
 
@@ -421,7 +422,6 @@ __device__ void write_status(const LayoutArgs& a, const Lds& l, int lane, int ex
 // [0, warm_rows), 16 bytes per load, four loads of a thread in flight.
 constexpr int kWarmUnroll = 4;
 __device__ void warm_tokens(const LayoutArgs& a, int wb, int nwb) {
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const uint32_t units = (uint32_t)a.warm_units;
     const uint32_t total = (uint32_t)a.warm_rows * units;  // at most 64 MiB / 16
     const uint32_t stride = (uint32_t)nwb * blockDim.x;
@@ -481,6 +481,31 @@ __device__ __forceinline__ void look_across(const LayoutArgs& a, int c, int r0, 
 //
 // MULTI: more than one chunk.  ONE_GROUP: a wave's entries fit one load group (at most PU
 // passes) and stay in registers from the histogram to the emit.
+// The same workgroups, for a group that quantises ahead: instead of only reading the token
+// rows they quantise them (the FP8 dispatch's format, see ep_fp8.h) into a staging copy, row t
+// at quant_out + t * quant_pitch: H bytes of codes, then H/128 float scales.  The quantising
+// dispatch that follows copies staged rows in destination order and finds them, like the
+// tokens, in the caches.  A lane owns 16 consecutive channels, 8 neighbouring lanes one
+// 128-channel group; H is a multiple of 128, so a group never straddles rows and the 8 lanes
+// of a group are in or out of range together.  Ordinary cached loads and stores: both the
+// tokens and the staged rows are wanted in the cache afterwards.
+__device__ void quantize_tokens(const LayoutArgs& a, int wb, int nwb) {
+    const uint32_t per_row = (uint32_t)a.warm_units >> 1;   // 32-byte lane items per row (H / 16)
+    const uint32_t total = (uint32_t)a.warm_rows * per_row;
+    const uint32_t stride = (uint32_t)nwb * blockDim.x;
+    const uint32_t H = (uint32_t)a.warm_units * 8;
+    for (uint32_t i = (uint32_t)wb * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const uint32_t t = i / per_row, u = i - t * per_row;
+        const u32x4* src = (const u32x4*)(a.warm_x + (int64_t)t * a.warm_stride) + 2 * u;
+        const u32x4 in0 = src[0], in1 = src[1];
+        float scale;
+        const u32x4 q = quantize16(in0, in1, &scale);
+        uint8_t* row = a.quant_out + (int64_t)t * a.quant_pitch;
+        *((u32x4*)row + u) = q;
+        if ((u & 7u) == 0) *(float*)(row + H + 4 * (u >> 3)) = scale;
+    }
+}
+
 template <bool MULTI, bool ONE_GROUP>
 __device__ __forceinline__ void layout_chunk(const LayoutArgs& a, int32_t* lds, const int b) {
     const int wpb = blockDim.x >> 6;
@@ -646,7 +671,8 @@ template <bool MULTI, bool ONE_GROUP>
 __global__ __launch_bounds__(1024) void layout_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
     if ((int)blockIdx.x >= a.nchunks) {  // a whole workgroup: no barrier is reached by part of one
-        warm_tokens(a, blockIdx.x - a.nchunks, gridDim.x - a.nchunks);
+        if (a.quant_out) quantize_tokens(a, blockIdx.x - a.nchunks, gridDim.x - a.nchunks);
+        else warm_tokens(a, blockIdx.x - a.nchunks, gridDim.x - a.nchunks);
         return;
     }
     layout_chunk<MULTI, ONE_GROUP>(a, lds, blockIdx.x);
@@ -666,8 +692,6 @@ __global__ __launch_bounds__(1024) void layout_kernel(LayoutArgs a) {
 // the ids its lanes hold, summed over the wavefronts through LDS.  Same ids, same
 // arithmetic as the layout: the rows are those workgroup 0 records.  No workgroup waits
 // for another.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
 __global__ __launch_bounds__(1024) void layout_dispatch_kernel(LayoutArgs a, DispatchArgs d, int nseg, int units, int parts,
                                                                int spp) {
     extern __shared__ int32_t lds[];

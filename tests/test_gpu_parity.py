@@ -1040,6 +1040,16 @@ FP8_CASES = [
     ("skew", None, None, "ht", 0, True, 1),         # hot experts
     ("ll_decode", 1100, 1024, "ht", 0, True, 2),
     ("skew", None, None, "ll", 512, True, 1),       # padded windows, capacity drops
+    # groups that quantise ahead: the layout call quantises the announced tokens into a staging copy
+    # and the dispatch copies staged rows in destination order
+    ("ht_prefill", None, None, "ht", 0, True, "ahead"),    # full benchmark shape
+    ("ht_prefill", 4095, None, "ht", 0, True, "ahead"),    # ragged
+    ("skew", None, None, "ll", 512, True, "ahead"),        # padded windows, capacity drops
+    ("ll_decode", 1100, 1152, "ht", 0, True, "ahead"),     # 36 bytes of scales per row: a part-filled last unit
+    ("ll_decode", 1100, 128, "ll", 60, True, "ahead"),     # one group per row
+    ("ll_decode", 90, 1152, "ht", 0, True, "ahead"),       # too small for the destination order: token walk
+    ("stress_hot", None, None, "ht", 0, False, "ahead"),   # 117 MB of tokens, more than one read-ahead covers
+    (("skew", dict(K=33)), 300, 512, "ht", 0, True, "ahead"),
 ]
 
 
@@ -1047,10 +1057,14 @@ FP8_CASES = [
 def test_fp8_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, wide, order):
     """E4M3 codes and float scales bit-exact with the oracle (special values included: NaN, infinities,
     subnormal groups whose 448 / amax overflows); untouched rows keep their fill."""
-    w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
+    over = {}
+    if isinstance(name, tuple):
+        name, over = name[0], dict(name[1])
+    w = wl.make_workload(name, T=T, **({"H": H} if H else {}), **over)
     spec = w.spec
     T = spec.T
     _say(f"fp8 case {name} T={T} H={spec.H} mode={mode} C={C} wide={wide} order={order}")
+    ahead = order == "ahead"
     x_bits = w.x_bits.copy()
     if wide:  # spread magnitudes over 2^-24 .. 2^12, plus zero groups, signed zeros and special values
         rng = np.random.default_rng(T)
@@ -1075,22 +1089,38 @@ def test_fp8_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, wide, orde
     o_q = np.full((rows + 1, spec.H), 0xAB, np.uint8)
     o_s = np.full((rows + 1, G), np.float32(-2.0), np.float32)
     oracle_mod.dispatch_fp8(x_bits, lay, o_q, o_s)
-    g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C, dispatch_order=order)
+    g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C, dispatch_order=1 if ahead else order,
+               quantize_ahead=int(ahead))
     try:
-        h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+        d_x = hx.bits_to_dev(x_bits)
+        d_topk = torch.from_numpy(topk).to(hx.DEV)
+        h = ep.ep_layout_prefetch(g, d_topk, d_x) if ahead else ep.ep_layout(g, d_topk)
         store = torch.full((rows + 1, spec.H), 0xAB, dtype=torch.uint8, device=hx.DEV)
         recv = store[:rows].view(torch.float8_e4m3fn)
         recv = recv.view(spec.E, Cc, spec.H) if ll else recv
         scales = torch.full((rows + 1, G), -2.0, dtype=torch.float32, device=hx.DEV)
         r_src = torch.full((rows + 1,), -9, dtype=torch.int32, device=hx.DEV)
         r_cnt = torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)
-        ep.ep_dispatch(h, hx.bits_to_dev(x_bits), recv, recv_scales=scales[:rows], recv_src=r_src[:rows], recv_count=r_cnt)
-        torch.cuda.synchronize()
-        got_q = store.cpu().numpy()
-        got_s = scales.cpu().numpy()
-        assert np.array_equal(got_s.view(np.uint32), o_s.view(np.uint32)), "scales differ"
-        assert np.array_equal(got_q, o_q), "E4M3 codes differ"
-        assert np.array_equal(r_cnt.cpu().numpy(), lay.expert_kept)
+        r_w = torch.full((rows + 1,), -3.5, dtype=torch.float32, device=hx.DEV)
+        d_w = torch.from_numpy(w.topk_w).to(hx.DEV)
+        # twice on the same handle: a staging copy made by the layout call serves the first dispatch only
+        for again in range(2 if ahead else 1):
+            if again:
+                store.fill_(0xAB); scales.fill_(-2.0); r_src.fill_(-9); r_cnt.fill_(-1); r_w.fill_(-3.5)
+            ep.ep_dispatch(h, d_x, recv, topk_weights=d_w, recv_w=r_w[:rows], recv_scales=scales[:rows],
+                           recv_src=r_src[:rows], recv_count=r_cnt)
+            torch.cuda.synchronize()
+            got_q = store.cpu().numpy()
+            got_s = scales.cpu().numpy()
+            assert np.array_equal(got_s.view(np.uint32), o_s.view(np.uint32)), "scales differ"
+            assert np.array_equal(got_q, o_q), "E4M3 codes differ"
+            assert np.array_equal(r_cnt.cpu().numpy(), lay.expert_kept)
+            valid = lay.dst_row >= 0
+            want_w = np.full(rows + 1, np.float32(-3.5), np.float32)
+            want_w[lay.dst_row[valid]] = w.topk_w[valid]
+            want_src = np.full(rows + 1, -9, np.int32)
+            want_src[lay.dst_row[valid]] = np.nonzero(valid)[0]
+            assert np.array_equal(r_w.cpu().numpy(), want_w) and np.array_equal(r_src.cpu().numpy(), want_src)
         src = r_src.cpu().numpy()
         for t in range(0, T, max(1, T // 16)):
             for k in range(spec.K):
@@ -1098,7 +1128,7 @@ def test_fp8_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, wide, orde
                     assert src[lay.dst_row[t, k]] == t
         # FP8 output without scales (or the reverse) is refused
         with pytest.raises(ep.EpError) as e:
-            ep.ep_dispatch(h, hx.bits_to_dev(x_bits), recv)
+            ep.ep_dispatch(h, d_x, recv)
         assert e.value.code == ep.EP_ERR_INVALID_ARG
         ep.ep_handle_destroy(h)
     finally:
