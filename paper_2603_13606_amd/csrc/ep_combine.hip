@@ -21,12 +21,18 @@ constexpr int KB = 8;  // rows gathered per batch of loads
 __device__ __forceinline__ float bf16_lo(uint32_t p) { return __uint_as_float(p << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t p) { return __uint_as_float(p & 0xffff0000u); }
 
-// float32 -> bfloat16 bits, round to nearest even; every NaN becomes 0x7FC0.
-__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
+// Two float32 -> two bfloat16 packed low, high: round to nearest even, every NaN becomes 0x7FC0.
+// The conversion instruction of this part rounds exactly as the integer rule
+// (u + 0x7FFF + bit 16) >> 16 does -- compared over all 2^32 inputs -- and leaves only the
+// NaN payload to be made canonical here.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    uint32_t u = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    if (lo != lo) u = (u & 0xffff0000u) | 0x7fc0u;
+    if (hi != hi) u = (u & 0x0000ffffu) | 0x7fc00000u;
+    return u;
 }
 
 __device__ __forceinline__ void accumulate(float (&acc)[8], const u32x4& v, float w) {
@@ -82,7 +88,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nseg, i
     if (active) {
         u32x4 o;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) o[c] = f32_to_bf16(acc[2 * c]) | (f32_to_bf16(acc[2 * c + 1]) << 16);
+        for (int c = 0; c < 4; ++c) o[c] = pack_bf16(acc[2 * c], acc[2 * c + 1]);
         __builtin_nontemporal_store(o, (u32x4*)(a.out + (int64_t)t * a.out_stride) + unit);
     }
 }
@@ -144,7 +150,7 @@ __global__ __launch_bounds__(256) void combine_hier_kernel(CombineArgs a, int ns
     if (active) {
         u32x4 o;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) o[c] = f32_to_bf16(total[2 * c]) | (f32_to_bf16(total[2 * c + 1]) << 16);
+        for (int c = 0; c < 4; ++c) o[c] = pack_bf16(total[2 * c], total[2 * c + 1]);
         __builtin_nontemporal_store(o, (u32x4*)(a.out + (int64_t)t * a.out_stride) + unit);
     }
 }
@@ -154,56 +160,95 @@ __global__ __launch_bounds__(256) void combine_hier_kernel(CombineArgs a, int ns
 // gives
 //   grad_y[row(t,k), h] = bf16_rne( w[t,k] * f32(g[t,h]) )      (a dispatch of g scaled per entry)
 //   grad_w[t,k]         = sum_h f32(y[row(t,k), h]) * f32(g[t,h])
-// One workgroup per token: for every entry its threads walk the row in 16-byte units (y and g
-// read, grad_y written), each thread sums its products in float32 in the order it meets them,
-// the 64 lanes of a wave are summed by a fixed exchange tree and the four waves in order: the
-// result does not depend on timing.  Entries without a row get grad_w = 0 and write nothing.
-// Bound by HBM: per entry one row read and one written; the gradient row comes from the caches
-// after the first entry.
+// One workgroup per token.  Its threads walk the row 256 16-byte units at a time; a thread
+// loads its unit of g once and then, for up to 8 entries together, issues the loads of the
+// entries' y rows before it uses any of them (8 independent 16-byte loads in flight per
+// lane, as in the forward kernel), stores the scaled gradient to the entries' rows and adds
+// its products to one float32 sum per entry.  The sums of an entry batch are reduced once:
+// the 64 lanes of a wave by a fixed exchange tree, the four waves in order through LDS -- a
+// fixed order, so the result does not depend on timing.  Entries without a row get
+// grad_w = 0 and write nothing.  Bound by HBM: per entry one row read and one written.
+constexpr int KBB = 8;  // entries handled together
+
 __global__ __launch_bounds__(256) void combine_backward_kernel(CombineArgs a, const uint16_t* g, int64_t g_stride,
                                                                WindowDesc gy, float* grad_w, int64_t gw_stride, int units) {
-    __shared__ float part[4];
+    __shared__ float part[4][KBB];
     const int t = blockIdx.x;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const u32x4* grow = (const u32x4*)(g + (int64_t)t * g_stride);
     for (int k0 = 0; k0 < a.K; k0 += kWave) {  // the entries of the token, 64 at a time in the lanes of a wave
         const int kk = k0 + lane;
-        const int my_row = kk < a.K ? a.dst_row[(int64_t)t * a.K + kk] : -1;
+        int my_row = kk < a.K ? a.dst_row[(int64_t)t * a.K + kk] : -1;
+        if (my_row >= a.win.rows_cap) my_row = -1;
         const float my_w = (a.w && kk < a.K) ? a.w[(int64_t)t * a.w_stride + kk] : 1.0f;
         const int nk = min(kWave, a.K - k0);
-        for (int j = 0; j < nk; ++j) {
-            int row = __builtin_amdgcn_readlane(my_row, j);
-            const float w = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), j));
-            if (row >= a.win.rows_cap) row = -1;
-            float dot = 0.0f;
-            if (row >= 0) {
-                const u32x4* yrow = a.win.base ? (const u32x4*)(a.win.base + window_offset(a.win, row)) : nullptr;
-                u32x4* gyrow = (u32x4*)(gy.base + window_offset(gy, row));
-                for (int u = threadIdx.x; u < units; u += blockDim.x) {
-                    const u32x4 gv = grow[u];
+        for (int j0 = 0; j0 < nk; j0 += KBB) {
+            // wave-uniform per entry of the batch: row, weight, the row's addresses
+            int row[KBB];
+            float w[KBB];
+            const u32x4* yrow[KBB];
+            u32x4* gyrow[KBB];
+            float dot[KBB];
+#pragma unroll
+            for (int b = 0; b < KBB; ++b) {
+                const int j = j0 + b;  // lanes >= nk hold no row
+                row[b] = __builtin_amdgcn_readlane(my_row, j & (kWave - 1));
+                if (j >= nk) row[b] = -1;
+                w[b] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), j & (kWave - 1)));
+                const int r = max(row[b], 0);
+                yrow[b] = a.win.base ? (const u32x4*)(a.win.base + window_offset(a.win, r)) : nullptr;
+                gyrow[b] = (u32x4*)(gy.base + window_offset(gy, r));
+                dot[b] = 0.0f;
+            }
+            for (int u = threadIdx.x; u < units; u += blockDim.x) {
+                const u32x4 gv = grow[u];
+                u32x4 yv[KBB];
+                if (a.win.base) {
+#pragma unroll
+                    for (int b = 0; b < KBB; ++b)
+                        if (row[b] >= 0) yv[b] = __builtin_nontemporal_load(yrow[b] + u);
+                }
+                float gf[8];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    gf[2 * c] = bf16_lo(gv[c]);
+                    gf[2 * c + 1] = bf16_hi(gv[c]);
+                }
+#pragma unroll
+                for (int b = 0; b < KBB; ++b) {
+                    if (row[b] < 0) continue;  // wave-uniform
                     u32x4 o;
 #pragma unroll
                     for (int c = 0; c < 4; ++c)
-                        o[c] = f32_to_bf16(__fmul_rn(w, bf16_lo(gv[c]))) | (f32_to_bf16(__fmul_rn(w, bf16_hi(gv[c]))) << 16);
-                    __builtin_nontemporal_store(o, gyrow + u);
-                    if (yrow) {
-                        const u32x4 yv = __builtin_nontemporal_load(yrow + u);
+                        o[c] = pack_bf16(__fmul_rn(w[b], gf[2 * c]), __fmul_rn(w[b], gf[2 * c + 1]));
+                    __builtin_nontemporal_store(o, gyrow[b] + u);
+                }
+                if (a.win.base) {
+#pragma unroll
+                    for (int b = 0; b < KBB; ++b) {
+                        if (row[b] < 0) continue;
 #pragma unroll
                         for (int c = 0; c < 4; ++c) {
-                            dot = __fadd_rn(dot, __fmul_rn(bf16_lo(yv[c]), bf16_lo(gv[c])));
-                            dot = __fadd_rn(dot, __fmul_rn(bf16_hi(yv[c]), bf16_hi(gv[c])));
+                            dot[b] = __fadd_rn(dot[b], __fmul_rn(bf16_lo(yv[b][c]), gf[2 * c]));
+                            dot[b] = __fadd_rn(dot[b], __fmul_rn(bf16_hi(yv[b][c]), gf[2 * c + 1]));
                         }
                     }
                 }
             }
-            if (grad_w) {  // wave-uniform: every thread of the workgroup takes part
-                for (int off = kWave / 2; off > 0; off >>= 1) dot = __fadd_rn(dot, __shfl_xor(dot, off, kWave));
-                if (lane == 0) part[wave] = dot;
+            if (grad_w) {  // uniform over the workgroup: every thread takes part
+#pragma unroll
+                for (int b = 0; b < KBB; ++b) {
+                    float d = dot[b];
+                    for (int off = kWave / 2; off > 0; off >>= 1) d = __fadd_rn(d, __shfl_xor(d, off, kWave));
+                    if (lane == 0) part[wave][b] = d;
+                }
                 __syncthreads();
-                if (threadIdx.x == 0)
-                    grad_w[(int64_t)t * gw_stride + k0 + j] =
-                        __fadd_rn(__fadd_rn(__fadd_rn(part[0], part[1]), part[2]), part[3]);
+                if (threadIdx.x < KBB && j0 + (int)threadIdx.x < nk) {
+                    const int b = threadIdx.x;
+                    grad_w[(int64_t)t * gw_stride + k0 + j0 + b] =
+                        __fadd_rn(__fadd_rn(__fadd_rn(part[0][b], part[1][b]), part[2][b]), part[3][b]);
+                }
                 __syncthreads();
             }
         }

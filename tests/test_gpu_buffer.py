@@ -63,10 +63,18 @@ def _f64_to_bf16_bits(v: np.ndarray) -> np.ndarray:
     return (r.view(np.uint32) >> 16).astype(np.uint16)
 
 
-@pytest.mark.parametrize("name,T,H,mode,C", [("tiny", None, None, "ht", 0), ("tiny", None, None, "ll", 6),
-                                             ("ll_decode", 100, 1000, "ht", 0), ("skew", 700, 512, "ll", 30),
-                                             ("ht_prefill", 1500, 7168, "ht", 0)])
-def test_backward_calls_match_the_oracle_composition(hx, oracle_mod, name, T, H, mode, C):
+@pytest.mark.parametrize("name,T,H,mode,C,order", [
+    ("tiny", None, None, "ht", 0, 0), ("tiny", None, None, "ll", 6, 0),
+    ("ll_decode", 100, 1000, "ht", 0, 0), ("skew", 700, 512, "ll", 30, 0),
+    ("ht_prefill", 1500, 7168, "ht", 0, 0),
+    # groups in destination order, inputs of 8192 entries and more: the backward kernel walks the rows as they lie
+    ("ht_prefill", 1500, 7168, "ht", 0, 1),
+    ("skew", 1100, 520, "ll", 30, 1),          # padded windows, most entries cut by the capacity, 65 units per row
+    ("skew", 1100, 512, "ll", 1100, 2),        # padded, nothing cut
+    ("ll_decode", 1030, 64, "ht", 0, 1),       # rows of 8 units: one wave, most lanes idle
+    ("ll_decode", 300, 256, "ht", 0, 1),       # too small for the row order: token walk
+])
+def test_backward_calls_match_the_oracle_composition(hx, oracle_mod, name, T, H, mode, C, order):
     """The backward pass with the handle of the forward pass, piece by piece against oracle calls:
     grad_x (backward of dispatch) = unweighted oracle.combine of the row gradients, bit-exact;
     grad_y (backward of combine) = oracle.dispatch, entry by entry, of the output gradient scaled by
@@ -84,7 +92,7 @@ def test_backward_calls_match_the_oracle_composition(hx, oracle_mod, name, T, H,
     topk[::11, 0] = -1
     lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, layout=int(ll), C=Cc, C_rank=T)
     rows = spec.E * Cc if ll else T * K
-    buf = EPBuffer(spec.R, spec.E, Hh, K, max_tokens_per_rank=T, mode=mode, slots_per_subregion=C)
+    buf = EPBuffer(spec.R, spec.E, Hh, K, max_tokens_per_rank=T, mode=mode, slots_per_subregion=C, dispatch_order=order)
     try:
         rng = np.random.default_rng(T + Hh)
         d_topk = torch.from_numpy(topk).to(hx.DEV)
