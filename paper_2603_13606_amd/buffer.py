@@ -38,7 +38,7 @@ class EPBuffer:
     def __init__(self, num_ranks: int, num_experts: int, hidden: int, top_k: int,
                  max_tokens_per_rank: int, mode: str = "ht", my_rank: int = 0,
                  slots_per_subregion: int = 0, dispatch_path: str = "direct", max_handles: int = 4,
-                 device: str = "cuda:0", dispatch_order: int = ep.EP_ORDER_TOKEN):
+                 device: str = "cuda:0", dispatch_order: int = ep.EP_ORDER_TOKEN, quantize_ahead: bool = False):
         ep.load()
         self.device = torch.device(device)
         self.R, self.E, self.H, self.K, self.B = num_ranks, num_experts, hidden, top_k, max_tokens_per_rank
@@ -60,7 +60,7 @@ class EPBuffer:
                              mode=ep.EP_MODE_LL if self.ll else ep.EP_MODE_HT, my_rank=my_rank,
                              slots_per_subregion=slots_per_subregion,
                              dispatch_path=ep.EP_PATH_RANK_DEDUP if dispatch_path == "once_per_rank" else ep.EP_PATH_DIRECT,
-                             max_handles=max_handles, dispatch_order=dispatch_order)
+                             max_handles=max_handles, dispatch_order=dispatch_order, quantize_ahead=int(quantize_ahead))
         self._dedup = dispatch_path == "once_per_rank"
         with torch.cuda.device(self.device):
             self.group = ep.ep_group_create(cfg, alloc_fn=self._alloc_cb, free_fn=self._free_cb)

@@ -593,6 +593,43 @@ def test_dispatch_destination_order_parity(ep, hx, oracle_mod, name, T, H, mode,
     _run_path(ep, hx, oracle_mod, name, T, H, mode, C, order=int(str(order)[0]), prefetch=prefetch)
 
 
+def test_layout_dispatch_one_call_quantises_ahead(ep, hx, oracle_mod):
+    """ep_layout_dispatch on a large input with FP8 outputs in a group that quantises ahead: the
+    layout part quantises the tokens it is given, the dispatch part copies the staged rows; codes,
+    scales and the layout equal the oracle's.  The same call on a group without the option
+    quantises in the dispatch."""
+    w = wl.make_workload("skew", T=1200, H=1024)
+    spec = w.spec
+    T, G = spec.T, spec.H // 128
+    topk = _mess_up(w.topk_idx, spec.E, seed=11, frac_masked=0.01)
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, C_rank=T)
+    rows = int(lay.expert_offset[-1])
+    o_q = np.full((rows + 1, spec.H), 0xAB, np.uint8)
+    o_s = np.full((rows + 1, G), np.float32(-2.0), np.float32)
+    oracle_mod.dispatch_fp8(w.x_bits, lay, o_q, o_s)
+    for ahead in (1, 0):
+        _say(f"one call, fp8, quantize_ahead={ahead}")
+        g = _group(ep, spec, T, ep.EP_MODE_HT, dispatch_order=1, quantize_ahead=ahead)
+        try:
+            store = torch.full((rows + 1, spec.H), 0xAB, dtype=torch.uint8, device=hx.DEV)
+            scales = torch.full((rows + 1, G), -2.0, dtype=torch.float32, device=hx.DEV)
+            h = ep.ep_layout_dispatch(g, torch.from_numpy(topk).to(hx.DEV), hx.bits_to_dev(w.x_bits),
+                                      store[:rows].view(torch.float8_e4m3fn), recv_scales=scales[:rows])
+            torch.cuda.synchronize()
+            hx.assert_layout_equal(hx.fetch_layout(h, T, spec.K, spec.E, spec.R), lay)
+            assert np.array_equal(store.cpu().numpy(), o_q) and np.array_equal(scales.cpu().numpy(), o_s)
+            ep.ep_handle_destroy(h)
+        finally:
+            ep.ep_group_destroy(g)
+    # the option needs the destination order, the direct path and whole 128-channel groups
+    for bad in (dict(dispatch_order=0), dict(dispatch_order=2), dict(dispatch_path=ep.EP_PATH_RANK_DEDUP, dispatch_order=1)):
+        with pytest.raises(ep.EpError) as e:
+            _group(ep, spec, T, ep.EP_MODE_HT, quantize_ahead=1, **bad)
+        assert e.value.code == ep.EP_ERR_INVALID_ARG
+    with pytest.raises(ep.EpError):
+        ep.ep_group_create(ep.make_config(spec.R, spec.E, 1000, spec.K, T, dispatch_order=1, quantize_ahead=1))
+
+
 def test_padded_destination_order_follows_the_drop_hint(ep, hx, oracle_mod):
     """Padded windows in a destination-ordered group: the layout leaves the kept / dropped row
     counts where the host can see them, and a later dispatch walks the tokens when the capacity
