@@ -287,7 +287,8 @@ EP_API ep_result_t ep_group_create(ep_group_t *group, const ep_group_config_t *c
                             ep_alloc_fn alloc_fn, ep_free_fn free_fn);
 
 /* Table II "ncclEpGroupDestroy".  Fails with EP_ERR_BUSY while handles are alive.
- * Synchronises `stream` before freeing. */
+ * Before freeing it waits (on the host) for `stream` and for the streams the last calls of
+ * the group's destroyed handles were given. */
 EP_API ep_result_t ep_group_destroy(ep_group_t group, ep_stream_t stream);
 
 /* Geometry and footprints of a group (host struct filled synchronously). */

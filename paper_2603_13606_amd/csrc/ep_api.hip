@@ -465,6 +465,14 @@ ep_result_t ep_group_destroy(ep_group_t g, ep_stream_t stream) {
         if (g->live_handles > 0) return EP_ERR_BUSY;
     }
     if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return EP_ERR_HIP;
+    // work of destroyed handles may still be running on other streams: wait for it, slab by slab (a stream
+    // the caller has destroyed in the meantime had to finish its work then; its error is ignored)
+    for (auto& s : g->free_slabs) {
+        if (s.used && s.last_stream != (hipStream_t)stream && s.reuse_event &&
+            hipEventRecord(s.reuse_event, s.last_stream) == hipSuccess)
+            (void)hipEventSynchronize(s.reuse_event);
+    }
+    (void)hipGetLastError();
     for (auto& s : g->free_slabs) free_slab(g, s);
     for (int i = 0; i < 2; ++i) { dev_free(g, g->staging[i]); dev_free(g, g->signals[i]); dev_free(g, g->comb_stage[i]); }
     if (g->drop_hint) (void)hipHostFree(g->drop_hint);
