@@ -1403,3 +1403,63 @@ def test_random_large_shapes_destination_order(ep, hx, oracle_mod):
         finally:
             ep.ep_group_destroy(g)
         done += 1
+
+
+def test_random_large_shapes_quantise_ahead(ep, hx, oracle_mod):
+    """Sixteen seeded random configurations of at least 8192 routed entries in groups that quantise
+    ahead: FP8 codes, scales, side arrays and counts of the staged, destination-ordered dispatch
+    against the oracle (row sizes from one 128-channel group up, scale rows that end inside a
+    16-byte unit, padded windows with and without drops); the handle's second quantising dispatch
+    (token walk) must give the same."""
+    rng = np.random.default_rng(4242)
+    done = 0
+    case = 0
+    while done < 16:
+        case += 1
+        R = int(rng.choice([1, 2, 4, 8, 16, 32]))
+        L = int(rng.choice([1, 2, 3, 4, 8]))
+        E = R * L
+        K = int(rng.integers(1, min(E, 9) + 1))
+        T = int(rng.choice([8192 // K + 1, 9001 // K + 3, 16000 // K, 3000, 4099]))
+        if T * K < 8192 or T * K > 40000:
+            continue
+        H = int(rng.choice([128, 256, 384, 640, 1024, 1152, 2048]))
+        ll = bool(rng.integers(0, 2))
+        C = int(rng.integers(max(1, (T * K) // (2 * E)), (3 * T * K) // (2 * E) + 2)) if ll else 0
+        spec = wl.WorkloadSpec(f"randq{case}", 340 + case, R=R, T=T, H=H, E=E, K=K,
+                               prior=str(rng.choice(["uniform", "zipf"])))
+        w = wl.make_workload(spec)
+        topk = _mess_up(w.topk_idx, E, seed=case, frac_masked=float(rng.choice([0.0, 0.03])))
+        _say(f"random quantise-ahead case {case}: E={E} R={R} K={K} T={T} H={H} ll={ll} C={C}")
+        lay = oracle_mod.layout(topk, E=E, R=R, layout=int(ll), C=C if ll else 0, C_rank=T)
+        rows = E * C if ll else int(lay.expert_offset[-1])
+        G = H // 128
+        o_q = np.full((rows + 1, H), 0xAB, np.uint8)
+        o_s = np.full((rows + 1, G), np.float32(-2.0), np.float32)
+        oracle_mod.dispatch_fp8(w.x_bits, lay, o_q, o_s)
+        valid = lay.dst_row >= 0
+        want_src = np.full(rows + 1, -9, np.int32)
+        want_src[lay.dst_row[valid]] = np.nonzero(valid)[0]
+        g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C, dispatch_order=1, quantize_ahead=1)
+        try:
+            x = hx.bits_to_dev(w.x_bits)
+            h = ep.ep_layout_prefetch(g, torch.from_numpy(topk).to(hx.DEV), x)
+            store = torch.full((rows + 1, H), 0xAB, dtype=torch.uint8, device=hx.DEV)
+            recv = store[:rows].view(torch.float8_e4m3fn)
+            recv = recv.view(E, C, H) if ll else recv
+            scales = torch.full((rows + 1, G), -2.0, dtype=torch.float32, device=hx.DEV)
+            r_src = torch.full((rows + 1,), -9, dtype=torch.int32, device=hx.DEV)
+            r_cnt = torch.full((E,), -1, dtype=torch.int32, device=hx.DEV)
+            for again in range(2):
+                if again:
+                    store.fill_(0xAB); scales.fill_(-2.0); r_src.fill_(-9); r_cnt.fill_(-1)
+                ep.ep_dispatch(h, x, recv, recv_scales=scales[:rows], recv_src=r_src[:rows], recv_count=r_cnt)
+                torch.cuda.synchronize()
+                assert np.array_equal(store.cpu().numpy(), o_q), f"case {case}: codes differ (dispatch {again})"
+                assert np.array_equal(scales.cpu().numpy().view(np.uint32), o_s.view(np.uint32)), f"case {case}: scales differ"
+                assert np.array_equal(r_src.cpu().numpy(), want_src)
+                assert np.array_equal(r_cnt.cpu().numpy(), lay.expert_kept)
+            ep.ep_handle_destroy(h)
+        finally:
+            ep.ep_group_destroy(g)
+        done += 1
