@@ -1175,13 +1175,16 @@ def test_fp8_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, wide, orde
 # ------------------------------------------------------------------------------ HIP graph capture
 
 
-@pytest.mark.parametrize("T,order", [(96, 0), (1100, 1)])
+@pytest.mark.parametrize("T,order", [(96, 0), (1100, 1), (96, "one call")])
 def test_graph_capture_and_replay(ep, hx, oracle_mod, T, order):
     """layout + dispatch + combine captured once into a HIP graph and replayed with new
     token data each time; every replay must equal the eager result and the oracle.  The
     library records no memset nodes (it never calls one) and allocates nothing while a
     slab is free in the group's pool, so the three calls are capturable as they are.  The
-    second case captures the read-ahead layout call and the destination-ordered dispatch."""
+    second case captures the read-ahead layout call and the destination-ordered dispatch, the
+    third the one-launch layout + dispatch of a small input."""
+    fused = order == "one call"
+    order = 0 if fused else order
     w = wl.make_workload("ll_decode", T=T, H=1024)
     spec = w.spec
     lay = oracle_mod.layout(w.topk_idx, E=spec.E, R=spec.R, C_rank=spec.T)
@@ -1203,8 +1206,11 @@ def test_graph_capture_and_replay(ep, hx, oracle_mod, T, order):
         ep.ep_handle_destroy(h0)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            h = ep.ep_layout_prefetch(g, topk, x) if order else ep.ep_layout(g, topk)
-            ep.ep_dispatch(h, x, recv, topk_weights=gate)
+            if fused:
+                h = ep.ep_layout_dispatch(g, topk, x, recv, topk_weights=gate)
+            else:
+                h = ep.ep_layout_prefetch(g, topk, x) if order else ep.ep_layout(g, topk)
+                ep.ep_dispatch(h, x, recv, topk_weights=gate)
             ep.ep_combine(h, recv, out, topk_weights=gate)
         for it in range(4):
             xb = wl.make_tokens(spec, seed_offset=50 + it)
