@@ -566,12 +566,19 @@ def main() -> int:
                     "p50": round(float(np.percentile(a, 50)), 2), "p90": round(float(np.percentile(a, 90)), 2)}
 
         lpd = lay_us + dis_us
-        line["us"] = {"layout": stats(lay_us), "dispatch": stats(dis_us), "combine": stats(com_us),
-                      "layout_plus_dispatch": stats(lpd),
-                      "dispatch_plus_combine_mean": round(float(dis_us.mean() + com_us.mean()), 2),
-                      "samples": int(lay_us.size),
+        if sb.fused:  # one launch lays out and dispatches: there is no dispatch call of its own
+            lpd = lay_us
+            line["us"] = {"layout_plus_dispatch": stats(lay_us), "combine": stats(com_us),
+                          "samples": int(lay_us.size)}
+            dis_us = lay_us
+        else:
+            line["us"] = {"layout": stats(lay_us), "dispatch": stats(dis_us), "combine": stats(com_us),
+                          "layout_plus_dispatch": stats(lpd),
+                          "dispatch_plus_combine_mean": round(float(dis_us.mean() + com_us.mean()), 2),
+                          "samples": int(lay_us.size)}
+        line["us"].update({
                       "note": "HIP events on the launch stream around each call; they include the gap between two "
-                              "dependent launches, so they read a few us above the kernel durations of rocprofv3"}
+                              "dependent launches, so they read a few us above the kernel durations of rocprofv3"})
         row = spec.row_bytes
         gb = lambda nbytes, us: round(nbytes / (us * 1e-6) / 1e9, 1)
         line["gbps"] = {"layout_plus_dispatch": gb(ab["layout"] + ab["dispatch"], lpd.mean()),
@@ -590,7 +597,8 @@ def main() -> int:
         dom_us = dis_us.mean() if dom == "dispatch" else com_us.mean()
         dom_bytes = dispatch_bytes if dom == "dispatch" else ab["combine"]
         run_order = args.dispatch_order != 0 and T * K >= 8192
-        kernel_name = {"dispatch": "dispatch_runs_kernel" if run_order else "dispatch_direct_kernel",
+        kernel_name = {"dispatch": "layout_dispatch_kernel" if sb.fused else
+                                   "dispatch_runs_kernel" if run_order else "dispatch_direct_kernel",
                        "combine": "combine_kernel"}[dom]
         traffic_key = spec.name + ("_padded" if sb.ll else "") + ["_token_order", "", "_destination_order_resident"][args.dispatch_order]
         prof = _profiled(traffic_key, kernel_name) or {}
