@@ -143,11 +143,12 @@ typedef struct {
                                     format of the quantising ep_dispatch -- into a staging
                                     copy kept with the handle (max_tokens_per_rank *
                                     (H + H/32) bytes per handle), on the compute units the
-                                    layout leaves idle.  The first quantising ep_dispatch of
-                                    that tensor then copies the staged rows in destination
-                                    order instead of quantising in token order: same codes,
-                                    same scales.  The tokens must not change between the two
-                                    calls.  Inputs too small for the destination order are
+                                    layout leaves idle.  The handle's first ep_dispatch, when
+                                    it is a quantising one of that tensor (same address and
+                                    row stride), copies the staged rows in destination order
+                                    instead of quantising in token order: same codes, same
+                                    scales.  The tokens must not change between the two
+                                    calls; every later dispatch quantises for itself.  Inputs too small for the destination order are
                                     quantised by the dispatch as usual.  (Sec. I: dispatch
                                     may quantise; Sec. IV-C: work next to the send.)       */
 } ep_group_config_t;

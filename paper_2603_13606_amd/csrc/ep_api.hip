@@ -786,9 +786,9 @@ ep_result_t ep_dispatch(ep_handle_t h, const ep_tensor_t* inputs, int32_t num_in
         // per-expert counts are delivered by ep_complete from the coordination counters
         int32_t* recv_count = a.recv_count;
         if (send_only) a.recv_count = nullptr;
-        // rows the layout call quantised ahead are copied in destination order, once
+        // rows the layout call quantised ahead are copied in destination order, by the handle's first dispatch only
         const bool staged = fp8 && h->quant_x == x->data && h->quant_stride == x->stride[0] && dispatch_fp8_staged_possible(a);
-        if (fp8) h->quant_x = nullptr;
+        h->quant_x = nullptr;  // whatever this dispatch is, a later one may be given other data at the same address
         hipError_t e = staged ? launch_dispatch_fp8_staged(a, call.scales, h->slab.quant, quant_row_pitch(c.hidden), (hipStream_t)stream)
                        : fp8  ? launch_dispatch_fp8(a, call.scales, (hipStream_t)stream)
                               : launch_dispatch(a, (hipStream_t)stream);
