@@ -464,7 +464,8 @@ __device__ __forceinline__ void look_across(const LayoutArgs& a, int c, int r0, 
     }
 }
 
-// Chunk b = wave-chunks [b*wpb, (b+1)*wpb); workgroups from nchunks on read tokens ahead.
+// Chunk b = wave-chunks [b*wpb, (b+1)*wpb); with several chunks workgroup nchunks writes the
+// tables; the workgroups after those read tokens ahead.
 // With one chunk nothing is published or awaited.
 //
 // Cross-workgroup state (only with more than one chunk), all in a.pub / a.ctl:
@@ -554,7 +555,7 @@ __device__ __forceinline__ void layout_chunk(const LayoutArgs& a, int32_t* lds, 
             v[r] = run;
             run += x;
         }
-        if (multi)
+        if (multi && b < nchunks)  // the workgroup after the last chunk has no entries: it only writes the tables
             __hip_atomic_store(&a.pub[(int64_t)b * W + c], (tag << kTagShift) | (uint32_t)run, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         l.tot[c] = run;
@@ -643,19 +644,21 @@ __device__ __forceinline__ void layout_chunk(const LayoutArgs& a, int32_t* lds, 
             for (int e = lane; e < a.E; e += kWave) rs[e] = l.S[e] + l.before[e] + h[e];
         }
     }
-    // (8) the per-expert / per-rank arrays and the totals: by the first chunk, after its own
-    //     walk so that the walk is not held up.  The status word comes from one wavefront:
-    //     with several chunks wave 0 of the workgroup that finished looking across last,
-    //     which then also leaves the cross-workgroup words ready for the next launch
+    // (8) the per-expert / per-rank arrays and the totals.  With several chunks they come from a
+    //     workgroup of their own, number nchunks, which has no entries: it looks across, scans
+    //     and writes the tables while the chunks are still walking theirs (written by a chunk
+    //     after its walk they were the last thing the launch waited for).  The status word comes
+    //     from one wavefront: with several chunks wave 0 of the workgroup that finished looking
+    //     across last, which then also leaves the cross-workgroup words ready for the next launch
     int rows_end = 0;
-    if (b == 0) rows_end = write_tables(a, l, tid, lane, w);
+    if (b == (multi ? nchunks : 0)) rows_end = write_tables(a, l, tid, lane, w);
     if (w != 0) return;
     if (!multi) {  // the caller of a fused launch says how many rows its output takes
         write_status(a, l, lane, (!a.padded && a.rows_cap >= 0 && rows_end > a.rows_cap) ? STATUS_OUTPUT_OVERFLOW : 0);
         return;
     }
     const uint32_t seen = __builtin_amdgcn_readfirstlane(ticket) + mine;  // lane 0 holds the ticket
-    if ((int)(seen & (kGaveUp - 1u)) != nchunks) return;
+    if ((int)(seen & (kGaveUp - 1u)) != nchunks + 1) return;  // the chunks and the workgroup of the tables
     write_status(a, l, lane, seen >= kGaveUp ? STATUS_TIMEOUT : 0);
     uint32_t next = gen + 1u;
     if (next >= kTags) {  // the tags have run out: clear every published word and start over
@@ -671,9 +674,10 @@ __device__ __forceinline__ void layout_chunk(const LayoutArgs& a, int32_t* lds, 
 template <bool MULTI, bool ONE_GROUP>
 __global__ __launch_bounds__(1024) void layout_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
-    if ((int)blockIdx.x >= a.nchunks) {  // a whole workgroup: no barrier is reached by part of one
-        if (a.quant_out) quantize_tokens(a, blockIdx.x - a.nchunks, gridDim.x - a.nchunks);
-        else warm_tokens(a, blockIdx.x - a.nchunks, gridDim.x - a.nchunks);
+    const int nlay = a.nchunks + (MULTI ? 1 : 0);  // workgroups that lay out: the chunks and, with several, the one of the tables
+    if ((int)blockIdx.x >= nlay) {  // a whole workgroup: no barrier is reached by part of one
+        if (a.quant_out) quantize_tokens(a, blockIdx.x - nlay, gridDim.x - nlay);
+        else warm_tokens(a, blockIdx.x - nlay, gridDim.x - nlay);
         return;
     }
     layout_chunk<MULTI, ONE_GROUP>(a, lds, blockIdx.x);
@@ -835,7 +839,7 @@ hipError_t launch_layout(const LayoutArgs& a_in, hipStream_t s) {
     if ((int64_t)wpb * kWave * a.passes > (int64_t)kCountMask) return hipErrorInvalidValue;  // a chunk's count must fit its word
     a.nchunks = nblk;
     const bool pf = layout_prefetches(a);
-    const dim3 grid(nblk + (pf ? kWarmBlocks : 0)), block(wpb * kWave);
+    const dim3 grid(nblk + (nblk > 1 ? 1 : 0) + (pf ? kWarmBlocks : 0)), block(wpb * kWave);
     const size_t lds = lds_bytes(a, wpb);
     const bool one_group = a.passes <= PU;
     if (nblk > 1 && one_group) hipLaunchKernelGGL((layout_kernel<true, true>), grid, block, lds, s, a);
