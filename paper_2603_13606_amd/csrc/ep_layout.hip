@@ -676,6 +676,9 @@ __global__ __launch_bounds__(1024) void layout_kernel(LayoutArgs a) {
     extern __shared__ int32_t lds[];
     const int nlay = a.nchunks + (MULTI ? 1 : 0);  // workgroups that lay out: the chunks and, with several, the one of the tables
     if ((int)blockIdx.x >= nlay) {  // a whole workgroup: no barrier is reached by part of one
+        // a short pause first (about 0.4 us): the chunks' loads of their ids then go ahead of the flood of
+        // token reads instead of queueing behind it (1.2 us of the kernel at the prefill shape)
+        __builtin_amdgcn_s_sleep(16);
         if (a.quant_out) quantize_tokens(a, blockIdx.x - nlay, gridDim.x - nlay);
         else warm_tokens(a, blockIdx.x - nlay, gridDim.x - nlay);
         return;
