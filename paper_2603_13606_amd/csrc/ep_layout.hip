@@ -827,7 +827,12 @@ hipError_t launch_layout_dispatch(const LayoutArgs& a_in, const DispatchArgs& d,
     return hipGetLastError();
 }
 
-constexpr int kWarmBlocks = 512;  // extra workgroups of the layout kernel that read tokens
+// Extra workgroups of the layout kernel that read tokens.  All of them should be running from the
+// start: a compute unit of this part holds two workgroups of 1024 threads, the part has 256 units,
+// and the layout workgroups take their places first; workgroups that find no place start when the
+// others are done and then read their share alone, as a tail.
+constexpr int kWarmBlocks = 448;
+constexpr int kResidentBlocks = 2 * 256;
 
 hipError_t launch_layout(const LayoutArgs& a_in, hipStream_t s) {
     LayoutArgs a = a_in;
@@ -842,7 +847,9 @@ hipError_t launch_layout(const LayoutArgs& a_in, hipStream_t s) {
     if ((int64_t)wpb * kWave * a.passes > (int64_t)kCountMask) return hipErrorInvalidValue;  // a chunk's count must fit its word
     a.nchunks = nblk;
     const bool pf = layout_prefetches(a);
-    const dim3 grid(nblk + (nblk > 1 ? 1 : 0) + (pf ? kWarmBlocks : 0)), block(wpb * kWave);
+    const int nlay = nblk + (nblk > 1 ? 1 : 0);
+    const int nwarm = pf ? std::max(64, std::min(kWarmBlocks, kResidentBlocks - nlay - 16)) : 0;
+    const dim3 grid(nlay + nwarm), block(wpb * kWave);
     const size_t lds = lds_bytes(a, wpb);
     const bool one_group = a.passes <= PU;
     if (nblk > 1 && one_group) hipLaunchKernelGGL((layout_kernel<true, true>), grid, block, lds, s, a);
