@@ -43,6 +43,64 @@ __device__ __forceinline__ void accumulate(float (&acc)[8], const u32x4& v, floa
     }
 }
 
+// Byte offset of entry (t, k)'s row in the window, or -1 when the entry has no row: computed once
+// per entry by the lane that holds it (the division of the padded addressing included), so that
+// the loop over the entries only moves it into scalar registers.
+__device__ __forceinline__ int64_t entry_row_offset(const CombineArgs& a, int t, int k, int row) {
+    if (row < 0 || row >= a.win.rows_cap) return -1;
+    const int64_t elems = a.staged ? (int64_t)(t * a.K + k) * a.H : window_offset(a.win, row);  // (t,k)-indexed staging (Sec. IV-D)
+    return elems * 2;
+}
+
+__device__ __forceinline__ int64_t readlane64(int64_t v, int lane) {
+    const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)v, lane);
+    const uint32_t hi = __builtin_amdgcn_readlane((uint32_t)((uint64_t)v >> 32), lane);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// The next N entries that have rows (the set bits of `mask`, lowest first: ascending k), gathered
+// and added to the sums.  Straight-line code for a count known at compile time: all N loads are
+// in flight before the first is waited for -- behind a branch the compiler may wait for the earlier
+// loads before it issues the next -- and an entry without a row costs nothing, not even a test.
+template <int N, bool DENSE>
+__device__ __forceinline__ void gather_rows(uint64_t& mask, int& first, int64_t my_off, float my_w, const uint8_t* base,
+                                            float (&acc)[8]) {
+    u32x4 v[N];
+    float wk[N];
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        int src;  // wave-uniform: the lane that holds the entry
+        if (DENSE) {  // every entry has a row: the lanes in turn
+            src = first + j;
+        } else {
+            src = __builtin_ctzll(mask);
+            mask &= mask - 1;
+        }
+        wk[j] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), src));
+        v[j] = __builtin_nontemporal_load((const u32x4*)(base + readlane64(my_off, src)));
+    }
+    first += N;
+#pragma unroll
+    for (int j = 0; j < N; ++j) accumulate(acc, v[j], wk[j]);
+}
+
+template <bool DENSE>
+__device__ __forceinline__ void gather_all(uint64_t mask, int left, int64_t my_off, float my_w, const uint8_t* base,
+                                           float (&acc)[8]) {
+    int first = 0;
+    for (; left >= KB; left -= KB) gather_rows<KB, DENSE>(mask, first, my_off, my_w, base, acc);
+    switch (left) {
+        case 1: gather_rows<1, DENSE>(mask, first, my_off, my_w, base, acc); break;
+        case 2: gather_rows<2, DENSE>(mask, first, my_off, my_w, base, acc); break;
+        case 3: gather_rows<3, DENSE>(mask, first, my_off, my_w, base, acc); break;
+        case 4: gather_rows<4, DENSE>(mask, first, my_off, my_w, base, acc); break;
+        case 5: gather_rows<5, DENSE>(mask, first, my_off, my_w, base, acc); break;
+        case 6: gather_rows<6, DENSE>(mask, first, my_off, my_w, base, acc); break;
+        case 7: gather_rows<7, DENSE>(mask, first, my_off, my_w, base, acc); break;
+        default: break;
+    }
+}
+
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nseg, int units) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -51,41 +109,24 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nseg, i
     const int t = (int)(u / nseg);
     const int seg = (int)(u - (int64_t)t * nseg);
     const int unit = seg * kWave + lane;
-    const bool active = unit < units;
-    // lane k fetches the k-th row index and weight of the token: one load each for all K
-    const int my_row = lane < a.K ? a.dst_row[(int64_t)t * a.K + lane] : -1;
-    const float my_w = (a.w && lane < a.K) ? a.w[(int64_t)t * a.w_stride + lane] : 1.0f;
+    // lanes beyond the end of the row read its last unit (and store nothing)
+    const uint8_t* base = (const uint8_t*)a.win.base + (int64_t)min(unit, units - 1) * 16;
     float acc[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) acc[c] = 0.0f;
-    for (int k0 = 0; k0 < a.K; k0 += KB) {
-        u32x4 v[KB];
-        int row[KB];
-        float wk[KB];
-#pragma unroll
-        for (int j = 0; j < KB; ++j) {
-            const int k = k0 + j;
-            int r = -1;
-            float w = 1.0f;
-            if (k < a.K) {
-                r = __builtin_amdgcn_readlane(my_row, k);
-                w = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), k));
-            }
-            if (r >= a.win.rows_cap) r = -1;
-            if (a.staged && r >= 0) r = t * a.K + k;  // (t,k)-indexed staging (Sec. IV-D)
-            row[j] = r;
-            wk[j] = w;
-            v[j] = (u32x4){0u, 0u, 0u, 0u};
-            if (r >= 0 && active) {
-                const int64_t off = a.staged ? (int64_t)r * a.H : window_offset(a.win, r);
-                v[j] = __builtin_nontemporal_load((const u32x4*)(a.win.base + off) + unit);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < KB; ++j)
-            if (row[j] >= 0) accumulate(acc, v[j], wk[j]);
+    for (int k0 = 0; k0 < a.K; k0 += kWave) {  // the entries of the token, 64 at a time in the lanes of the wave
+        // lane j fetches row index and weight of entry k0 + j (one load each for up to 64 entries) and works
+        // out where the row lies
+        const int kk = k0 + lane;
+        const int my_row = kk < a.K ? a.dst_row[(int64_t)t * a.K + kk] : -1;
+        const float my_w = (a.w && kk < a.K) ? a.w[(int64_t)t * a.w_stride + kk] : 1.0f;
+        const int64_t my_off = entry_row_offset(a, t, kk, my_row);
+        const uint64_t mask = __ballot(my_off >= 0);  // the entries that have rows
+        const int left = (int)__popcll(mask), nk = min(kWave, a.K - k0);
+        if (left == nk) gather_all<true>(mask, left, my_off, my_w, base, acc);  // all of them: the usual case
+        else gather_all<false>(mask, left, my_off, my_w, base, acc);
     }
-    if (active) {
+    if (unit < units) {
         u32x4 o;
 #pragma unroll
         for (int c = 0; c < 4; ++c) o[c] = pack_bf16(acc[2 * c], acc[2 * c + 1]);
