@@ -168,6 +168,11 @@ __global__ __launch_bounds__(256) void dispatch_runs_kernel(DispatchArgs a, RunP
                     row[q] = -1;
                 }
             }
+            if (TPR_SHIFT >= 6) {  // a row piece takes whole waves: token and row, and with them the row
+                                   // addresses, are the same for every lane and live in scalar registers
+                t[q] = __builtin_amdgcn_readfirstlane(t[q]);
+                row[q] = __builtin_amdgcn_readfirstlane(row[q]);
+            }
         }
         float wq[kRunUnroll];
         if (side && a.recv_w) {
