@@ -315,20 +315,32 @@ def once_per_rank(ep, torch, np, spec, sets, rows, stream_ptr):
 
 
 def hbm_copy_reference(ep, hx, torch):
-    """A plain streaming copy of 512 MiB: the reference point for bandwidth, and the kernel of known
-    size that scales the rocprofv3 byte counters."""
+    """Plain streaming kernels over 512 MiB: a copy (the reference point for mixed traffic, and the
+    kernel of known size that scales the rocprofv3 byte counters), a fill and a read (what the memory
+    sustains in one direction: dispatch mostly writes, combine mostly reads)."""
     cal_src = torch.empty(512 << 20, dtype=torch.uint8, device=hx.DEV).fill_(1)
     cal_dst = torch.empty_like(cal_src)
-    cal_ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
-    ep.ep_calibration_copy(cal_dst, cal_src)
-    for j in range(6):
-        cal_ev[j].record()
-        ep.ep_calibration_copy(cal_dst, cal_src)
-    cal_ev[6].record()
-    torch.cuda.synchronize()
-    cal_us = min(cal_ev[j].elapsed_time(cal_ev[j + 1]) for j in range(6)) * 1e3
-    return {"gbps": round(2 * cal_src.numel() / (cal_us * 1e-6) / 1e9, 1),
-            "what": "plain 16-byte-per-lane copy of 512 MiB (read + write bytes / best of 6 launches)"}
+    sink = torch.zeros(4, dtype=torch.int32, device=hx.DEV)
+
+    def best_us(fn):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
+        fn()
+        for j in range(6):
+            ev[j].record()
+            fn()
+        ev[6].record()
+        torch.cuda.synchronize()
+        return min(ev[j].elapsed_time(ev[j + 1]) for j in range(6)) * 1e3
+
+    n = cal_src.numel()
+    cal_us = best_us(lambda: ep.ep_calibration_copy(cal_dst, cal_src))
+    fill_us = best_us(lambda: ep.ep_calibration_fill(cal_dst))
+    read_us = best_us(lambda: ep.ep_calibration_read(cal_src, sink))
+    return {"gbps": round(2 * n / (cal_us * 1e-6) / 1e9, 1),
+            "write_only_gbps": round(n / (fill_us * 1e-6) / 1e9, 1),
+            "read_only_gbps": round(n / (read_us * 1e-6) / 1e9, 1),
+            "what": "plain 16-byte-per-lane kernels over 512 MiB, best of 6 launches each: copy (read + write "
+                    "bytes), fill (bytes written), read (bytes read)"}
 
 
 def extras(ep, hx, wl, torch, np, group, spec, first_set, rows, stream_ptr, iters: int = 20):

@@ -276,6 +276,20 @@ EP_API ep_result_t ep_dispatch_plan(const ep_group_config_t *cfg, int64_t num_to
 EP_API ep_result_t ep_calibration_copy(void *dst, const void *src, size_t bytes, ep_stream_t stream);
 
 /*
+ * Measurement aids like ep_calibration_copy, for the two directions on their own: dispatch
+ * mostly writes (K rows written per token read) and combine mostly reads, so each is
+ * bounded by what the memory sustains in that direction, which differs from the mixed copy.
+ * ep_calibration_fill writes `bytes` (multiple of 16) of the bf16 value 1.0 to the 16-byte
+ * aligned DEVICE pointer dst.  ep_calibration_read reads `bytes` from the 16-byte aligned
+ * DEVICE pointer src and folds them into a checksum; `sink` is a DEVICE pointer to 4
+ * writable bytes that the kernel writes only when a lane's checksum equals one fixed
+ * constant (it exists so that the reads cannot be optimised away; its content means nothing).
+ * Errors: EP_ERR_INVALID_ARG, EP_ERR_HIP.
+ */
+EP_API ep_result_t ep_calibration_fill(void *dst, size_t bytes, ep_stream_t stream);
+EP_API ep_result_t ep_calibration_read(const void *src, size_t bytes, void *sink, ep_stream_t stream);
+
+/*
  * ep_group_create -- Table II "ncclEpCreateGroup" without the communicator.
  * Validates cfg, computes the window geometry and allocates (through alloc_fn or
  * hipMalloc) the handle slabs and, for EP_PATH_RANK_DEDUP, the staging windows:

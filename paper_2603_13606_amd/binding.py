@@ -47,7 +47,7 @@ EP_TAG_EXPERT_TOKENS = 10
 STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW, STATUS_TIMEOUT = 1, 2, 4, 8
 
 EXPORTS = [
-    "ep_error_string", "ep_version", "ep_build_id", "ep_layout_plan", "ep_dispatch_plan", "ep_calibration_copy", "ep_group_create", "ep_group_destroy", "ep_group_query",
+    "ep_error_string", "ep_version", "ep_build_id", "ep_layout_plan", "ep_dispatch_plan", "ep_calibration_copy", "ep_calibration_fill", "ep_calibration_read", "ep_group_create", "ep_group_destroy", "ep_group_query",
     "ep_layout", "ep_layout_prefetch", "ep_layout_static", "ep_layout_dispatch", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
     "ep_dispatch", "ep_combine", "ep_combine_backward", "ep_complete", "ep_group_reset_signals",
 ]
@@ -159,6 +159,8 @@ def load() -> ctypes.CDLL:
             fn.argtypes = [vp, ctypes.POINTER(ep_tensor_t), i32, ctypes.POINTER(ep_tensor_t), i32, i32, vp]
         lib.ep_combine_backward.argtypes = [vp, ctypes.POINTER(ep_tensor_t), i32, ctypes.POINTER(ep_tensor_t), i32, vp]
         lib.ep_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        lib.ep_calibration_fill.argtypes = [vp, ctypes.c_size_t, vp]
+        lib.ep_calibration_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         lib.ep_complete.argtypes = [vp, ctypes.POINTER(ep_complete_config_t), vp]
         lib.ep_group_reset_signals.argtypes = [vp, vp]
         lib.ep_layout_plan.argtypes = [ctypes.c_int64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
@@ -205,6 +207,18 @@ def ep_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> No
     assert dst.numel() * dst.element_size() == nbytes and dst.is_contiguous() and src.is_contiguous()
     _check(load().ep_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream)),
            "ep_calibration_copy")
+
+
+def ep_calibration_fill(dst: torch.Tensor, stream=None) -> None:
+    assert dst.is_contiguous()
+    _check(load().ep_calibration_fill(dst.data_ptr(), dst.numel() * dst.element_size(), _stream_ptr(stream)),
+           "ep_calibration_fill")
+
+
+def ep_calibration_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    assert src.is_contiguous() and sink.numel() * sink.element_size() >= 4
+    _check(load().ep_calibration_read(src.data_ptr(), src.numel() * src.element_size(), sink.data_ptr(),
+                                      _stream_ptr(stream)), "ep_calibration_read")
 
 
 _DTYPES = {torch.bfloat16: EP_DTYPE_BF16, torch.float32: EP_DTYPE_F32, torch.int32: EP_DTYPE_I32,

@@ -377,6 +377,16 @@ ep_result_t ep_calibration_copy(void* dst, const void* src, size_t bytes, ep_str
     return launch_calibration_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
 }
 
+ep_result_t ep_calibration_fill(void* dst, size_t bytes, ep_stream_t stream) {
+    if (!dst || bytes % 16 || ((uintptr_t)dst & 15u)) return EP_ERR_INVALID_ARG;
+    return launch_calibration_fill(dst, bytes, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+}
+
+ep_result_t ep_calibration_read(const void* src, size_t bytes, void* sink, ep_stream_t stream) {
+    if (!src || !sink || bytes % 16 || ((uintptr_t)src & 15u) || ((uintptr_t)sink & 3u)) return EP_ERR_INVALID_ARG;
+    return launch_calibration_read(src, bytes, (uint32_t*)sink, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;
+}
+
 ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_stream_t stream,
                             ep_alloc_fn alloc_fn, ep_free_fn free_fn) {
     if (!group || !cfg) return EP_ERR_INVALID_ARG;

@@ -215,6 +215,8 @@ hipError_t launch_await_counts(int32_t* sig, int n, int spin_limit, int32_t* cou
 hipError_t launch_clear_counts(int32_t* sig, int n, hipStream_t s);
 hipError_t launch_combine_pack(const CombineArgs& a, uint16_t* stage, hipStream_t s);
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+hipError_t launch_calibration_fill(void* dst, size_t bytes, hipStream_t s);
+hipError_t launch_calibration_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
 
 // Host-side planning helpers (pure functions, testable without a GPU).
 void plan_layout(int n, int* passes, int* nwc);

@@ -363,6 +363,9 @@ PATH_CASES = [
     (("skew", dict(K=33)), 300, 520, "ll", 90),
     (("skew", dict(K=64)), 130, 1000, "ht", 0),
     (("skew", dict(K=64)), 130, 256, "ll", 70),
+    # long enough for combine's two 1 KiB segments per wavefront, rows that end inside the second one
+    ("skew", 1100, 8136, "ht", 0),         # 1017 units: the last segment holds 57
+    ("skew", 1100, 7688, "ll", 139),       # 961 units: the last segment holds one; entries without rows
 ]
 
 
@@ -922,6 +925,35 @@ def test_allocator_callbacks_and_lifecycle(ep, hx):
     ep.ep_handle_destroy(h2)
     ep.ep_group_destroy(g)
     assert not held
+
+
+@pytest.mark.parametrize("nbytes", [16, 4096 + 16, (3 << 20) + 48, 17 * 4096 * 16 + 16 * 1023])
+def test_measurement_kernels(ep, hx, nbytes):
+    """The copy, fill and read kernels the bandwidth figures are measured against: the copy moves
+    exactly the bytes given, the fill writes bf16 1.0 to exactly those bytes, the read leaves its
+    source alone; ragged sizes span whole trips and a tail."""
+    _say(f"measurement kernels nbytes={nbytes}")
+    g = torch.Generator().manual_seed(nbytes)
+    host = torch.randint(0, 256, (nbytes + 64,), dtype=torch.uint8, generator=g)
+    src = host.to(hx.DEV)
+    dst = torch.full((nbytes + 64,), 7, dtype=torch.uint8, device=hx.DEV)
+    ep.ep_calibration_copy(dst[:nbytes], src[:nbytes])
+    torch.cuda.synchronize()
+    got = dst.cpu()
+    assert torch.equal(got[:nbytes], host[:nbytes]) and bool((got[nbytes:] == 7).all())
+    ep.ep_calibration_fill(dst[:nbytes])
+    torch.cuda.synchronize()
+    got = dst.cpu()
+    assert bool((got[:nbytes].view(torch.int16) == 0x3F80).all()) and bool((got[nbytes:] == 7).all())
+    sink = torch.zeros(1, dtype=torch.int32, device=hx.DEV)
+    ep.ep_calibration_read(src[:nbytes], sink)
+    torch.cuda.synchronize()
+    assert torch.equal(src.cpu(), host)
+    for bad in (8, 24):
+        with pytest.raises(ep.EpError):
+            ep.ep_calibration_fill(dst[:bad])
+        with pytest.raises(ep.EpError):
+            ep.ep_calibration_read(src[:bad], sink)
 
 
 def test_argument_errors_on_device(ep, hx):
