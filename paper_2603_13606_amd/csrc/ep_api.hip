@@ -168,6 +168,11 @@ int64_t carve_slab(const ep_group_s* g, Slab* s, int32_t* base) {
     return cur;
 }
 
+void free_slab(ep_group_s* g, Slab& s) {
+    if (s.reuse_event) (void)hipEventDestroy(s.reuse_event);
+    dev_free(g, s.base);
+}
+
 // A new slab; the words through which the layout workgroups talk to each other must start
 // out zero (pub and ctl are adjacent), which a small fill kernel on `stream` sees to.
 ep_result_t new_slab(ep_group_s* g, Slab* s, hipStream_t stream) {
@@ -176,18 +181,18 @@ ep_result_t new_slab(ep_group_s* g, Slab* s, hipStream_t stream) {
     if (r != EP_SUCCESS) return r;
     carve_slab(g, s, (int32_t*)p);
     const int64_t ints = (int32_t*)(s->ctl + kLayoutCtlWords) - (int32_t*)s->pub;
-    if (launch_clear_counts((int32_t*)s->pub, (int)ints, stream) != hipSuccess ||
-        hipEventCreateWithFlags(&s->reuse_event, hipEventDisableTiming) != hipSuccess) {
+    if (hipEventCreateWithFlags(&s->reuse_event, hipEventDisableTiming) != hipSuccess) {
+        s->reuse_event = nullptr;
         dev_free(g, p);
+        return EP_ERR_HIP;
+    }
+    if (launch_clear_counts((int32_t*)s->pub, (int)ints, stream) != hipSuccess) {
+        (void)hipStreamSynchronize(stream);  // nothing queued may still write the memory given back below
+        free_slab(g, *s);
         return EP_ERR_HIP;
     }
     s->used = false;
     return EP_SUCCESS;
-}
-
-void free_slab(ep_group_s* g, Slab& s) {
-    if (s.reuse_event) (void)hipEventDestroy(s.reuse_event);
-    dev_free(g, s.base);
 }
 
 const ep_tensor_t* find_tag(const ep_tensor_t* ts, int n, int tag, int tag2 = -1, int tag3 = -1) {
@@ -423,6 +428,7 @@ ep_result_t ep_group_create(ep_group_t* group, const ep_group_config_t* cfg, ep_
     if (hipGetDevice(&g->device) != hipSuccess) { delete g; return EP_ERR_HIP; }
     g->nsets = cfg->staged_buffers;
     auto fail = [&](ep_result_t r) {
+        (void)hipStreamSynchronize((hipStream_t)stream);  // fill kernels queued so far write what is freed here
         for (int i = 0; i < 2; ++i) { dev_free(g, g->staging[i]); dev_free(g, g->signals[i]); dev_free(g, g->comb_stage[i]); }
         for (auto& f : g->free_slabs) free_slab(g, f);
         if (g->drop_hint) (void)hipHostFree(g->drop_hint);
