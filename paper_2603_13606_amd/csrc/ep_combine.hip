@@ -152,6 +152,60 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, int nseg, i
     }
 }
 
+// One wavefront reduces a whole token row of NSEG segments of 1 KiB (rows of exactly that length;
+// NSEG = 14 is the 14 336-byte row of Sec. IV-B): one index fetch per token instead of one per
+// segment, and the output row leaves in one piece.  112 accumulators and the 14 loads of a row
+// fill the registers, so the entries are taken one after the other; the compiler moves the next
+// row's loads up as far as they fit (straight-line code for the usual token: eight entries, all
+// with rows).  A few per cent faster than the segment kernels once the launch has thousands of
+// tokens; anything else -- other row lengths, short launches -- uses those.
+template <int NSEG>
+__device__ __forceinline__ void add_row(float (&acc)[NSEG][8], const uint8_t* p, float wk) {
+    u32x4 v[NSEG];
+#pragma unroll
+    for (int q = 0; q < NSEG; ++q) v[q] = __builtin_nontemporal_load((const u32x4*)(p + q * 1024));
+#pragma unroll
+    for (int q = 0; q < NSEG; ++q) accumulate(acc[q], v[q], wk);
+}
+
+template <int NSEG>
+__global__ __launch_bounds__(256) void combine_row_kernel(CombineArgs a) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int t = blockIdx.x * 4 + wave;
+    if (t >= a.T) return;
+    const uint8_t* base = (const uint8_t*)a.win.base + lane * 16;
+    // lane j holds row index and weight of entry j (K <= 64) and works out where the row lies
+    const int my_row = lane < a.K ? a.dst_row[(int64_t)t * a.K + lane] : -1;
+    const float my_w = (a.w && lane < a.K) ? a.w[(int64_t)t * a.w_stride + lane] : 1.0f;
+    const int64_t my_off = entry_row_offset(a, t, lane, my_row);
+    uint64_t mask = __ballot(my_off >= 0);  // the entries that have rows
+    float acc[NSEG][8];
+#pragma unroll
+    for (int q = 0; q < NSEG; ++q)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[q][c] = 0.0f;
+    if (mask == 0xffu) {  // entries 0..7 and no others: straight-line
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            add_row<NSEG>(acc, base + readlane64(my_off, j), __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), j)));
+    } else {
+        while (mask) {  // lowest k first
+            const int src = __builtin_ctzll(mask);
+            mask &= mask - 1;
+            add_row<NSEG>(acc, base + readlane64(my_off, src), __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(my_w), src)));
+        }
+    }
+    u32x4* o = (u32x4*)(a.out + (int64_t)t * a.out_stride) + lane;
+#pragma unroll
+    for (int q = 0; q < NSEG; ++q) {
+        u32x4 r;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) r[c] = pack_bf16(acc[q][2 * c], acc[q][2 * c + 1]);
+        __builtin_nontemporal_store(r, o + q * kWave);
+    }
+}
+
 // Two-level summation order (Sec. V-A: partial results are accumulated within a node
 // first, then reduced across nodes): for every node in ascending order the products of
 // the entries whose expert lives in that node are summed in ascending k, and the node
@@ -326,18 +380,49 @@ hipError_t launch_combine_backward(const CombineArgs& a, const uint16_t* g, int6
 
 // From this many wavefronts of one segment each on, a launch takes two segments per wavefront.
 constexpr int64_t kTwoSegmentMinWaves = 16384;
+constexpr int kRowSegments = 14;
+
+// Wavefronts of the whole-row kernel that the current GPU holds at a time: two per SIMD (its
+// 230 registers), four SIMDs per compute unit.
+static int64_t whole_row_slots() {
+    static int cus[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 0;
+        cus[dev] = n;
+    }
+    return (int64_t)cus[dev] * 8;
+}
+
+// Rows of exactly kRowSegments segments go whole to one wavefront when the tokens fill the GPU
+// in whole rounds of resident wavefronts, or nearly: a last round that is half empty costs more
+// than the whole-row kernel gains over the segment kernels (T = 2560 on 256 compute units: 65 us
+// against 59 us; T = 4096: 91 against 94).
+static bool whole_rows_pay(int64_t T) {
+    const int64_t slots = whole_row_slots();
+    if (slots <= 0 || T < slots) return false;
+    const int64_t rounds = T / slots, rest = T % slots;
+    return rest == 0 || rounds >= 3 || rest * 8 >= slots * 7;
+}
 
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s) {
     const int units = a.H / 8;
     const int nseg = (units + kWave - 1) / kWave;
     int64_t nwaves = (int64_t)a.T * nseg;
     if (nwaves == 0) return hipSuccess;
-    const bool two = a.ranks_per_node <= 0 && nseg % 2 == 0 && nwaves >= kTwoSegmentMinWaves;
+    const bool flat = a.ranks_per_node <= 0;
+    const bool whole = flat && units == kRowSegments * kWave && whole_rows_pay(a.T);
+    const bool two = flat && !whole && nseg % 2 == 0 && nwaves >= kTwoSegmentMinWaves;
+    if (whole) nwaves = a.T;
     if (two) nwaves /= 2;
     const int64_t nblk = (nwaves + 3) / 4;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     if (a.ranks_per_node > 0)
         hipLaunchKernelGGL(combine_hier_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);
+    else if (whole)
+        hipLaunchKernelGGL(combine_row_kernel<kRowSegments>, dim3((unsigned)nblk), dim3(256), 0, s, a);
     else if (two)
         hipLaunchKernelGGL(combine_kernel<2>, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);
     else

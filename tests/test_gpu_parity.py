@@ -366,6 +366,13 @@ PATH_CASES = [
     # long enough for combine's two 1 KiB segments per wavefront, rows that end inside the second one
     ("skew", 1100, 8136, "ht", 0),         # 1017 units: the last segment holds 57
     ("skew", 1100, 7688, "ll", 139),       # 961 units: the last segment holds one; entries without rows
+    # 14 336-byte rows in whole rounds of resident wavefronts (2048 tokens on 256 compute units): combine gives
+    # a whole row to one wavefront; fewer and more than its eight straight-line entries, entries without rows,
+    # a last workgroup with a token missing
+    (("ht_prefill", dict(K=5)), 2048, None, "ht", 0),
+    (("ht_prefill", dict(K=17)), 2048, None, "ht", 0),
+    ("ht_prefill", 2048, None, "ll", 40),
+    ("ht_prefill", 3899, None, "ht", 0),
 ]
 
 

@@ -45,10 +45,12 @@ def _setup(ep, hx, oracle_mod, name, T, H, mode, path, sets=2, C=0, order=0):
     return w, spec, lay, g, rows, Cc
 
 
-@pytest.mark.parametrize("mode,C,T,order", [("ht", 0, 96, 0), ("ll", 20, 96, 0),
-                                             ("ht", 0, 1100, 1), ("ll", 300, 1100, 2)])  # destination-ordered send phase
-def test_staged_direct_dispatch_and_combine(ep, hx, oracle_mod, mode, C, T, order):
-    w, spec, lay, g, rows, Cc = _setup(ep, hx, oracle_mod, "ll_decode", T, 1024, mode, ep.EP_PATH_DIRECT, C=C,
+@pytest.mark.parametrize("mode,C,T,order,H", [
+    ("ht", 0, 96, 0, 1024), ("ll", 20, 96, 0, 1024),
+    ("ht", 0, 1100, 1, 1024), ("ll", 300, 1100, 2, 1024),  # destination-ordered send phase
+    ("ht", 0, 2048, 1, 7168)])  # the reduce of the staged combine gives whole 14 336-byte rows to one wavefront
+def test_staged_direct_dispatch_and_combine(ep, hx, oracle_mod, mode, C, T, order, H):
+    w, spec, lay, g, rows, Cc = _setup(ep, hx, oracle_mod, "ll_decode", T, H, mode, ep.EP_PATH_DIRECT, C=C,
                                        order=order)
     ll = mode == "ll"
     try:
