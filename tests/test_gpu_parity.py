@@ -163,6 +163,74 @@ def test_layout_empty_batch(ep, hx, oracle_mod):
         ep.ep_group_destroy(g)
 
 
+@pytest.mark.parametrize("mode,kw", [
+    ("ht", {}), ("ll", {}), ("ht", dict(dispatch_order=1)), ("ll", dict(dispatch_order=2)),
+    ("ht", dict(dispatch_order=1, quantize_ahead=1)), ("ht", dict(dispatch_path=1)), ("ll", dict(dispatch_path=1)),
+    ("ht", dict(staged_buffers=2)), ("ht", dict(ranks_per_node=8))])
+def test_empty_batch_through_every_call(ep, hx, oracle_mod, mode, kw):
+    """No tokens: every call succeeds, writes no row, reports zero counts, and leaves the output
+    tensors as they were (the per-expert counter, which it sets to zero, aside)."""
+    _say(f"empty batch mode={mode} {kw}")
+    spec = wl.SPECS["ll_decode"]   # H = 7168: a multiple of 128, so the FP8 calls are allowed
+    ll = mode == "ll"
+    kw = dict(kw)
+    if "dispatch_path" in kw:
+        kw["dispatch_path"] = ep.EP_PATH_RANK_DEDUP
+    g = _group(ep, spec, 64, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=4 if ll else 0, **kw)
+    try:
+        topk = torch.zeros((0, spec.K), dtype=torch.int32, device=hx.DEV)
+        x = torch.zeros((0, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        gate = torch.zeros((0, spec.K), dtype=torch.float32, device=hx.DEV)
+        rows = spec.E * 4 if ll else 8
+        store = hx.poison_bf16((rows, spec.H))
+        recv = store.view(spec.E, 4, spec.H) if ll else store
+        r_w = torch.full((rows,), -3.5, dtype=torch.float32, device=hx.DEV)
+        r_src = torch.full((rows,), -9, dtype=torch.int32, device=hx.DEV)
+        cnt = torch.full((spec.E,), -1, dtype=torch.int32, device=hx.DEV)
+        out = torch.zeros((0, spec.H), dtype=torch.bfloat16, device=hx.DEV)
+        want = oracle_mod.layout(np.zeros((0, spec.K), np.int32), E=spec.E, R=spec.R, layout=int(ll), C=4 if ll else 0, C_rank=64)
+        direct = "dispatch_path" not in kw
+        for call in ("layout", "prefetch", "one call"):
+            if call == "one call":
+                if not direct:
+                    continue
+                h = ep.ep_layout_dispatch(g, topk, x, recv, topk_weights=gate, recv_w=r_w, recv_src=r_src, recv_count=cnt)
+            else:
+                h = ep.ep_layout(g, topk) if call == "layout" else ep.ep_layout_prefetch(g, topk, x)
+                ep.ep_dispatch(h, x, recv, topk_weights=gate, recv_w=r_w, recv_src=r_src, recv_count=cnt,
+                               topk_idx=None if direct else topk)  # the once-per-rank headers carry the routing vector
+            hx.assert_layout_equal(hx.fetch_layout(h, 0, spec.K, spec.E, spec.R), want)
+            assert ep.ep_handle_get_num_recv_tokens(h) == 0
+            ep.ep_combine(h, recv, out, topk_weights=gate)
+            ep.ep_combine(h, recv, out)
+            if direct and not kw.get("ranks_per_node"):
+                gy = hx.poison_bf16((rows, spec.H))
+                gw = torch.zeros((0, spec.K), dtype=torch.float32, device=hx.DEV)
+                gyv = gy.view(spec.E, 4, spec.H) if ll else gy
+                ep.ep_combine_backward(h, out, gyv, topk_weights=gate, y=recv, grad_w=gw)
+                ep.ep_combine_backward(h, out, gyv, topk_weights=gate)
+                if spec.H % 128 == 0:
+                    q = torch.full((rows, spec.H), 0x55, dtype=torch.uint8, device=hx.DEV).view(torch.float8_e4m3fn)
+                    sc = torch.full((rows, spec.H // 128), -2.0, dtype=torch.float32, device=hx.DEV)
+                    ep.ep_dispatch(h, x, q.view(spec.E, 4, spec.H) if ll else q, recv_scales=sc)
+                    torch.cuda.synchronize()
+                    assert bool((q.view(torch.uint8) == 0x55).all()) and bool((sc == -2.0).all())
+                    assert np.all(hx.dev_to_bits(gy) == hx.POISON)
+            if kw.get("staged_buffers"):
+                ep.ep_dispatch(h, x, recv, send_only=1)
+                ep.ep_complete(h)
+                ep.ep_combine(h, recv, out, send_only=1)
+                ep.ep_complete(h)
+            torch.cuda.synchronize()
+            assert np.all(hx.dev_to_bits(store) == hx.POISON)
+            assert bool((r_w == -3.5).all()) and bool((r_src == -9).all())
+            assert np.all(cnt.cpu().numpy() == 0)
+            cnt.fill_(-1)
+            ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
 def test_layout_invalid_ids_are_flagged_and_skipped(ep, hx, oracle_mod):
     spec = wl.SPECS["ll_decode"]
     topk, _, _ = wl.make_routing(spec)
