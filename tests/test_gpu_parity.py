@@ -444,7 +444,8 @@ PATH_CASES = [
 ]
 
 
-def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True, order=0, prefetch=False, fused=False):
+def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True, order=0, prefetch=False, fused=False,
+              reroute=None):
     over = {}
     if isinstance(name, tuple):  # (workload name, overrides of its shape)
         name, over = name[0], dict(name[1])
@@ -452,6 +453,8 @@ def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True
     spec = w.spec
     T = spec.T
     topk = _mess_up(w.topk_idx, spec.E, seed=T + spec.H, frac_masked=masked)
+    if reroute is not None:  # a degenerate routing in place of the seeded one
+        topk = np.ascontiguousarray(reroute(topk, spec).astype(np.int32))
     ll = mode == "ll"
     Cc = (C if C else T) if ll else 0
     lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, layout=int(ll), C=Cc, C_rank=T)
@@ -522,6 +525,41 @@ def _run_path(ep, hx, oracle_mod, name, T, H, mode, C, masked=0.01, weights=True
         ep.ep_handle_destroy(h)
     finally:
         ep.ep_group_destroy(g)
+
+
+def _all_masked(topk, spec):
+    return np.full_like(topk, -1)
+
+
+def _one_expert(topk, spec):          # every token has one entry, all for the same expert
+    out = np.full_like(topk, -1)
+    out[:, 0] = 5
+    return out
+
+
+def _same_experts(topk, spec):        # every token names experts 0 .. K-1: K bins hold everything
+    return np.broadcast_to(np.arange(spec.K, dtype=np.int32), topk.shape).copy()
+
+
+def _k_times_one_expert(topk, spec):  # all K entries of a token name one expert: K rows of it, one message to its rank
+    return np.repeat((np.arange(topk.shape[0], dtype=np.int32) * 7 % spec.E)[:, None], spec.K, axis=1)
+
+
+def _last_expert_only(topk, spec):    # the highest expert id takes everything but a few masked entries
+    out = np.full_like(topk, spec.E - 1)
+    out[::13, 1] = -1
+    return out
+
+
+@pytest.mark.parametrize("order", [0, 1])
+@pytest.mark.parametrize("mode,C", [("ht", 0), ("ll", 139)])
+@pytest.mark.parametrize("reroute", [_all_masked, _one_expert, _same_experts, _k_times_one_expert, _last_expert_only])
+def test_degenerate_routings(ep, hx, oracle_mod, reroute, mode, C, order):
+    """Routings at the edges of what the layout can be given: nothing routed, one expert or K experts
+    taking everything (one long run of rows; in padded windows nearly everything cut), K rows of one
+    token in one expert; in both walks of the dispatch (8800 entries: the destination order applies)."""
+    _say(f"degenerate routing {reroute.__name__} mode={mode} C={C} order={order}")
+    _run_path(ep, hx, oracle_mod, "skew", 1100, 1024, mode, C, masked=0.0, order=order, reroute=reroute)
 
 
 @pytest.mark.parametrize("name,T,H,mode,C", PATH_CASES)
@@ -1078,6 +1116,12 @@ DEDUP_CASES = [
     (("skew", dict(K=17)), 300, 520, "ht", 0, True),                   # headers of 17, 33 and 64 ids (up to 528 bytes)
     (("skew", dict(K=33)), 200, 256, "ll", 80, True),
     (("skew", dict(K=64)), 130, 1000, "ht", 0, False),
+    # degenerate routings: nothing routed; one window takes every message; K rows of one message in one expert
+    (("skew", dict(reroute="all_masked")), 300, 256, "ht", 0, True),
+    (("skew", dict(reroute="one_expert")), 600, 256, "ht", 0, True),
+    (("skew", dict(reroute="same_experts")), 600, 256, "ll", 100, True),
+    (("skew", dict(reroute="k_times_one_expert")), 600, 256, "ht", 0, True),
+    (("skew", dict(reroute="last_expert_only")), 600, 256, "ll", 700, False),
 ]
 
 
@@ -1089,11 +1133,14 @@ def test_once_per_rank_dispatch_parity(ep, hx, oracle_mod, name, T, H, mode, C, 
     if isinstance(name, tuple):
         name, over = name[0], dict(name[1])
     dup = over.pop("dup", False)
+    reroute = over.pop("reroute", None)
     w = wl.make_workload(name, T=T, **({"H": H} if H else {}), **over)
     spec = w.spec
     T = spec.T
-    _say(f"once-per-rank case {name} {over} T={T} H={spec.H} mode={mode} C={C}")
+    _say(f"once-per-rank case {name} {over} {reroute} T={T} H={spec.H} mode={mode} C={C}")
     topk = _mess_up(w.topk_idx, spec.E, seed=T, frac_masked=0.02)
+    if reroute:
+        topk = np.ascontiguousarray(globals()["_" + reroute](topk, spec).astype(np.int32))
     if dup:
         topk[::3, 1] = topk[::3, 0]  # duplicates: each occurrence gets its own row
     ll = mode == "ll"
