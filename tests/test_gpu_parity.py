@@ -562,6 +562,49 @@ def test_degenerate_routings(ep, hx, oracle_mod, reroute, mode, C, order):
     _run_path(ep, hx, oracle_mod, "skew", 1100, 1024, mode, C, masked=0.0, order=order, reroute=reroute)
 
 
+@pytest.mark.parametrize("T,H", [(64, 520), (1100, 8192), (2048, 7168)])  # one segment, two segments, whole rows per wavefront
+def test_combine_special_values(ep, hx, oracle_mod, T, H):
+    """Expert outputs and gate weights full of the values arithmetic treats specially -- NaNs of either
+    sign, infinities, signed zeros, bf16 and float32 subnormals, the largest finite values, weights of
+    0, -0, infinity and NaN -- combine bit for bit like the oracle's ordered float32 sum: products that
+    overflow, inf - inf, 0 * inf, subnormal products (no flush to zero), every NaN leaving as 0x7FC0."""
+    _say(f"combine special values T={T} H={H}")
+    spec = wl.WorkloadSpec("special", 31, R=8, T=T, H=H, E=64, K=8)
+    topk, gate, _ = wl.make_routing(spec)
+    topk = _mess_up(topk, spec.E, seed=T, frac_masked=0.02)
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, C_rank=T)
+    rows = int(lay.expert_offset[-1])
+    rng = np.random.default_rng(H + T)
+    y_bits = wl.f32_to_bf16_bits(rng.standard_normal((rows, H)).astype(np.float32))
+    pool = np.array([0x7FC0, 0xFFC0, 0x7FA1, 0x7F80, 0xFF80, 0x0000, 0x8000, 0x0001, 0x8001, 0x007F, 0x0080,
+                     0x7F7F, 0xFF7F, 0x7F00, 0x0C00, 0x8C00], np.uint16)
+    pick = rng.random((rows, H)) < 0.02
+    y_bits[pick] = pool[rng.integers(0, pool.size, int(pick.sum()))]
+    wpool = np.array([0.0, -0.0, 1.0, -1.0, np.inf, -np.inf, np.nan, 3.0e38, -3.0e38, 1.0e-38, 1.0e-45, 2.0 ** -100],
+                     np.float32)
+    wts = gate.copy()
+    wpick = rng.random(wts.shape) < 0.05
+    wts[wpick] = wpool[rng.integers(0, wpool.size, int(wpick.sum()))]
+    g = _group(ep, spec, T, ep.EP_MODE_HT)
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+        d_y = hx.bits_to_dev(y_bits)
+        d_w = torch.from_numpy(wts).to(hx.DEV)
+        for use_w in (True, False):
+            out = hx.poison_bf16((T, H))
+            ep.ep_combine(h, d_y, out, topk_weights=d_w if use_w else None)
+            torch.cuda.synchronize()
+            got = hx.dev_to_bits(out)
+            want = oracle_mod.combine(y_bits, wts if use_w else None, lay, H, acc="f32")
+            nan = (want & 0x7FFF) > 0x7F80
+            assert nan.any() and ((want & 0x7FFF) == 0x7F80).any()  # the inputs do produce NaNs and infinities
+            assert np.all(want[nan] == 0x7FC0)
+            assert np.array_equal(got, want), f"{int((got != want).sum())} of {got.size} outputs differ"
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
 @pytest.mark.parametrize("name,T,H,mode,C", PATH_CASES)
 def test_dispatch_combine_parity(ep, hx, oracle_mod, name, T, H, mode, C):
     _say(f"path case {name} T={T} H={H} mode={mode} C={C}")
