@@ -154,6 +154,7 @@ class StepBench:
         cfg = ep.make_config(spec.R, E, H, K, T, mode=ep.EP_MODE_LL if self.ll else ep.EP_MODE_HT,
                              slots_per_subregion=self.C, max_handles=nsets + 2,  # no allocation later
                              dispatch_order=order)
+        self.cfg = cfg
         self.group = ep.ep_group_create(cfg)
         self.sets = []
         scale = wl.expert_scale_table(spec)
@@ -616,12 +617,12 @@ def main() -> int:
                                    "dispatch_runs_kernel" if run_order else "dispatch_direct_kernel",
                        "combine": "combine_kernel"}[dom]
         traffic_key = spec.name + ("_padded" if sb.ll else "") + ["_token_order", "", "_destination_order_resident"][args.dispatch_order]
+        if dom == "combine":
+            # rows of 14 336 bytes in whole rounds of resident wavefronts take the library's whole-row combine kernel
+            cus = torch.cuda.get_device_properties(0).multi_processor_count
+            if ep.ep_combine_plan(sb.cfg, T, cus).whole_row:
+                kernel_name = "combine_row_kernel"
         prof = _profiled(traffic_key, kernel_name) or {}
-        if dom == "combine" and _profiled(traffic_key, "combine_row_kernel"):
-            # rows of 14 336 bytes in whole rounds of resident wavefronts: the library's whole-row combine kernel
-            # (the committed profile of this workload names the kernel that ran)
-            kernel_name = "combine_row_kernel"
-            prof = _profiled(traffic_key, kernel_name)
         achieved = dom_bytes / (dom_us * 1e-6) / 1e9
         line["roofline"] = {"bound": "hbm", "kernel": kernel_name, "achieved": round(achieved, 1),
                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),

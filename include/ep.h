@@ -266,6 +266,20 @@ typedef struct {
 EP_API ep_result_t ep_dispatch_plan(const ep_group_config_t *cfg, int64_t num_tokens, int64_t prefetched_rows,
                              ep_dispatch_plan_t *plan);
 
+/* Diagnostic: how ep_combine of a group configured like `cfg` would cut `num_tokens` tokens into
+ * wavefronts on a GPU of `compute_units` compute units (0 = unknown).  A wavefront reduces one
+ * 1 KiB segment of a token row, two adjacent ones in long launches, or -- rows of 14 336 bytes
+ * (Sec. IV-B) whose tokens fill whole rounds of the GPU's resident wavefronts -- the whole row.
+ * Pure host arithmetic; the same function plans the real launches with the device's count.
+ * Errors: EP_ERR_INVALID_ARG. */
+typedef struct {
+    int32_t segments_per_wavefront; /* 1, 2 or 14                                             */
+    int32_t whole_row;              /* 1: one wavefront per token                             */
+    int64_t workgroups;             /* workgroups of 4 wavefronts in the launch               */
+} ep_combine_plan_t;
+EP_API ep_result_t ep_combine_plan(const ep_group_config_t *cfg, int64_t num_tokens, int32_t compute_units,
+                            ep_combine_plan_t *plan);
+
 /*
  * Measurement aid, not part of the paper's API: a plain streaming copy of `bytes`
  * (multiple of 16; dst and src 16-byte aligned DEVICE pointers, not overlapping)

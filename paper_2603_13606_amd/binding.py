@@ -47,7 +47,7 @@ EP_TAG_EXPERT_TOKENS = 10
 STATUS_INVALID_IDS, STATUS_CAPACITY_DROP, STATUS_OUTPUT_OVERFLOW, STATUS_TIMEOUT = 1, 2, 4, 8
 
 EXPORTS = [
-    "ep_error_string", "ep_version", "ep_build_id", "ep_layout_plan", "ep_dispatch_plan", "ep_calibration_copy", "ep_calibration_fill", "ep_calibration_read", "ep_group_create", "ep_group_destroy", "ep_group_query",
+    "ep_error_string", "ep_version", "ep_build_id", "ep_layout_plan", "ep_dispatch_plan", "ep_combine_plan", "ep_calibration_copy", "ep_calibration_fill", "ep_calibration_read", "ep_group_create", "ep_group_destroy", "ep_group_query",
     "ep_layout", "ep_layout_prefetch", "ep_layout_static", "ep_layout_dispatch", "ep_handle_query", "ep_handle_get_num_recv_tokens", "ep_handle_destroy",
     "ep_dispatch", "ep_combine", "ep_combine_backward", "ep_complete", "ep_group_reset_signals",
 ]
@@ -96,6 +96,10 @@ class ep_dispatch_plan_t(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("run_order", "group", "blocks", "block_entries", "splits", "slice_units", "threads_per_piece",
                  "blocks_per_launch", "launches", "read_passes")]
+
+
+class ep_combine_plan_t(ctypes.Structure):
+    _fields_ = [("segments_per_wavefront", ctypes.c_int32), ("whole_row", ctypes.c_int32), ("workgroups", ctypes.c_int64)]
 
 
 class ep_layout_info_t(ctypes.Structure):
@@ -166,6 +170,8 @@ def load() -> ctypes.CDLL:
         lib.ep_layout_plan.argtypes = [ctypes.c_int64, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         lib.ep_dispatch_plan.argtypes = [ctypes.POINTER(ep_group_config_t), ctypes.c_int64, ctypes.c_int64,
                                          ctypes.POINTER(ep_dispatch_plan_t)]
+        lib.ep_combine_plan.argtypes = [ctypes.POINTER(ep_group_config_t), ctypes.c_int64, ctypes.c_int32,
+                                        ctypes.POINTER(ep_combine_plan_t)]
         for name in EXPORTS[3:]:
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
@@ -200,6 +206,13 @@ def ep_layout_plan(num_entries: int):
     p, w = ctypes.c_int32(), ctypes.c_int32()
     _check(load().ep_layout_plan(num_entries, ctypes.byref(p), ctypes.byref(w)), "ep_layout_plan")
     return int(p.value), int(w.value)
+
+
+def ep_combine_plan(cfg: "ep_group_config_t", num_tokens: int, compute_units: int) -> ep_combine_plan_t:
+    """How ep_combine of a group configured like cfg would cut num_tokens tokens into wavefronts (host arithmetic)."""
+    plan = ep_combine_plan_t()
+    _check(load().ep_combine_plan(ctypes.byref(cfg), num_tokens, compute_units, ctypes.byref(plan)), "ep_combine_plan")
+    return plan
 
 
 def ep_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

@@ -377,6 +377,17 @@ ep_result_t ep_dispatch_plan(const ep_group_config_t* cfg, int64_t num_tokens, i
     return EP_SUCCESS;
 }
 
+ep_result_t ep_combine_plan(const ep_group_config_t* cfg, int64_t num_tokens, int32_t compute_units, ep_combine_plan_t* plan) {
+    if (!cfg || !plan || cfg->size != sizeof(ep_group_config_t)) return EP_ERR_INVALID_ARG;
+    if (num_tokens < 0 || compute_units < 0 || cfg->hidden < 8 || cfg->hidden % 8 || num_tokens > (1 << 28)) return EP_ERR_INVALID_ARG;
+    CombinePlan p;
+    plan_combine(num_tokens, cfg->hidden, cfg->ranks_per_node, compute_units, &p);
+    plan->segments_per_wavefront = p.segments;
+    plan->whole_row = p.whole_row;
+    plan->workgroups = p.workgroups;
+    return EP_SUCCESS;
+}
+
 ep_result_t ep_calibration_copy(void* dst, const void* src, size_t bytes, ep_stream_t stream) {
     if (!dst || !src || bytes % 16 || ((uintptr_t)dst & 15u) || ((uintptr_t)src & 15u)) return EP_ERR_INVALID_ARG;
     return launch_calibration_copy(dst, src, bytes, (hipStream_t)stream) == hipSuccess ? EP_SUCCESS : EP_ERR_HIP;

@@ -9,6 +9,8 @@
 // Bound by HBM: K rows read, one row written per token.  Work unit = one
 // wavefront reducing one 1 KiB segment of one token: every lane issues up to 8
 // independent 16-byte loads before it starts to accumulate.
+#include <atomic>
+
 #include "ep_internal.h"
 
 namespace ep {
@@ -382,48 +384,56 @@ hipError_t launch_combine_backward(const CombineArgs& a, const uint16_t* g, int6
 constexpr int64_t kTwoSegmentMinWaves = 16384;
 constexpr int kRowSegments = 14;
 
-// Wavefronts of the whole-row kernel that the current GPU holds at a time: two per SIMD (its
-// 230 registers), four SIMDs per compute unit.
-static int64_t whole_row_slots() {
-    static int cus[64] = {};
+// Compute units of the current device (0 when it cannot be asked).
+static int current_compute_units() {
+    static std::atomic<int> cus[64];  // per device, 0 = not asked yet (any thread may fill it in)
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-    if (cus[dev] == 0) {
-        int n = 0;
+    int n = cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 0;
-        cus[dev] = n;
+        cus[dev].store(n, std::memory_order_relaxed);
     }
-    return (int64_t)cus[dev] * 8;
+    return n;
 }
 
 // Rows of exactly kRowSegments segments go whole to one wavefront when the tokens fill the GPU
-// in whole rounds of resident wavefronts, or nearly: a last round that is half empty costs more
-// than the whole-row kernel gains over the segment kernels (T = 2560 on 256 compute units: 65 us
-// against 59 us; T = 4096: 91 against 94).
-static bool whole_rows_pay(int64_t T) {
-    const int64_t slots = whole_row_slots();
-    if (slots <= 0 || T < slots) return false;
-    const int64_t rounds = T / slots, rest = T % slots;
-    return rest == 0 || rounds >= 3 || rest * 8 >= slots * 7;
+// in whole rounds of resident wavefronts, or nearly (the whole-row kernel holds two wavefronts
+// per SIMD -- its 230 registers -- and a compute unit has four SIMDs): a last round that is half
+// empty costs more than the whole-row kernel gains over the segment kernels (T = 2560 on 256
+// compute units: 65 us against 59 us; T = 4096: 91 against 94).
+void plan_combine(int64_t T, int H, int ranks_per_node, int compute_units, CombinePlan* out) {
+    const int units = H / 8;
+    const int nseg = (units + kWave - 1) / kWave;
+    int64_t nwaves = T * nseg;
+    const bool flat = ranks_per_node <= 0;
+    const int64_t slots = (int64_t)compute_units * 8;
+    bool whole = false;
+    if (flat && units == kRowSegments * kWave && slots > 0 && T >= slots) {
+        const int64_t rounds = T / slots, rest = T % slots;
+        whole = rest == 0 || rounds >= 3 || rest * 8 >= slots * 7;
+    }
+    const bool two = flat && !whole && nseg % 2 == 0 && nwaves >= kTwoSegmentMinWaves;
+    if (whole) nwaves = T;
+    if (two) nwaves /= 2;
+    out->segments = whole ? kRowSegments : two ? 2 : 1;
+    out->whole_row = whole ? 1 : 0;
+    out->workgroups = (nwaves + 3) / 4;
 }
 
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s) {
     const int units = a.H / 8;
     const int nseg = (units + kWave - 1) / kWave;
-    int64_t nwaves = (int64_t)a.T * nseg;
-    if (nwaves == 0) return hipSuccess;
-    const bool flat = a.ranks_per_node <= 0;
-    const bool whole = flat && units == kRowSegments * kWave && whole_rows_pay(a.T);
-    const bool two = flat && !whole && nseg % 2 == 0 && nwaves >= kTwoSegmentMinWaves;
-    if (whole) nwaves = a.T;
-    if (two) nwaves /= 2;
-    const int64_t nblk = (nwaves + 3) / 4;
+    if ((int64_t)a.T * nseg == 0) return hipSuccess;
+    CombinePlan p;
+    plan_combine(a.T, a.H, a.ranks_per_node, current_compute_units(), &p);
+    const int64_t nblk = p.workgroups;
     if (nblk > 0x7fffffffLL) return hipErrorInvalidValue;
     if (a.ranks_per_node > 0)
         hipLaunchKernelGGL(combine_hier_kernel, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);
-    else if (whole)
+    else if (p.whole_row)
         hipLaunchKernelGGL(combine_row_kernel<kRowSegments>, dim3((unsigned)nblk), dim3(256), 0, s, a);
-    else if (two)
+    else if (p.segments == 2)
         hipLaunchKernelGGL(combine_kernel<2>, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);
     else
         hipLaunchKernelGGL(combine_kernel<1>, dim3((unsigned)nblk), dim3(256), 0, s, a, nseg, units);

@@ -205,6 +205,14 @@ hipError_t launch_dispatch_fp8_staged(const DispatchArgs& a, float* recv_scales,
 // Bytes between two rows of the staging copy for hidden size H (a multiple of 128).
 constexpr int64_t quant_row_pitch(int H) { return (int64_t)H + (((int64_t)H / 32 + 15) / 16) * 16; }
 hipError_t launch_combine(const CombineArgs& a, hipStream_t s);
+// How a combine of T tokens of H channels is cut into wavefronts on a GPU of `compute_units`
+// units (host arithmetic; launch_combine plans with the current device's count).
+struct CombinePlan {
+    int segments;   // 1 KiB segments of a token row per wavefront: 1, 2, or the whole row
+    int whole_row;  // 1: one wavefront per token
+    int64_t workgroups;
+};
+void plan_combine(int64_t T, int H, int ranks_per_node, int compute_units, CombinePlan* out);
 // Backward of the weighted combine: a.win = expert outputs y (base may be nullptr: no grad_w), a.w, a.dst_row,
 // T, K, H as for the forward; g = gradient of the combined output [T, H]; gy = windows for grad_y.
 hipError_t launch_combine_backward(const CombineArgs& a, const uint16_t* g, int64_t g_stride, const WindowDesc& gy,

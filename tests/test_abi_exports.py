@@ -165,3 +165,36 @@ def test_dispatch_plan_covers_the_input_and_fits_the_launch_limits(ep):
         assert ep.ep_dispatch_plan(cfg, T).run_order == 0
     with pytest.raises(ep.EpError):
         ep.ep_dispatch_plan(ep.make_config(2, 8, 256, 2, 64), -1)
+
+
+def test_combine_plan_follows_rows_and_rounds(ep):
+    """Host arithmetic of the combine launch: one 1 KiB segment of a token row per wavefront, two in
+    long launches of rows with an even number of segments, the whole row for rows of 14 336 bytes when
+    the tokens fill whole rounds (or nearly) of the two-wavefronts-per-SIMD the whole-row kernel holds;
+    never for the two-level order; the workgroups cover every (token, piece)."""
+    def plan(T, H, cus, **kw):
+        return ep.ep_combine_plan(ep.make_config(8, 64, H, 8, max(T, 1), **kw), T, cus)
+    slots = 256 * 8
+    for T, want in ((4096, 14), (8192, 14), (2048, 14), (2047, 2), (2560, 2), (3072, 2), (3839, 2), (3840, 14), (5120, 2),
+                    (6144, 14), (7168, 14), (6500, 14), (100, 1), (1170, 1), (1171, 2), (0, 1)):
+        p = plan(T, 7168, 256)
+        assert p.segments_per_wavefront == want, (T, p.segments_per_wavefront)
+        assert p.whole_row == (want == 14)
+        pieces = T * (1 if want == 14 else 14 // want)
+        assert p.workgroups == -(-pieces // 4)
+        rounds, rest = divmod(T, slots)
+        assert (want == 14) == (rounds >= 1 and (rest == 0 or rounds >= 3 or rest * 8 >= slots * 7))
+    # other devices: the rounds follow the compute units; an unknown device never takes whole rows
+    assert plan(4096, 7168, 304).segments_per_wavefront == 2 and plan(2432 * 2, 7168, 304).segments_per_wavefront == 14
+    assert plan(4096, 7168, 0).segments_per_wavefront == 2
+    # other rows: 8 segments (two per wavefront when long), 15 segments (odd: one), a ragged 16th segment
+    assert plan(4096, 4096, 256).segments_per_wavefront == 2 and plan(100, 4096, 256).segments_per_wavefront == 1
+    assert plan(4096, 7680, 256).segments_per_wavefront == 1
+    p = plan(4096, 8136, 256)
+    assert p.segments_per_wavefront == 2 and p.workgroups == 4096 * 8 // 4
+    # the two-level summation order has its own kernel: one segment per wavefront whatever the size
+    assert plan(4096, 7168, 256, ranks_per_node=4).segments_per_wavefront == 1
+    with pytest.raises(ep.EpError):
+        plan(-1, 7168, 256)
+    with pytest.raises(ep.EpError):
+        ep.ep_combine_plan(ep.make_config(8, 64, 7168, 8, 16), 16, -1)
