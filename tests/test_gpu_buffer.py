@@ -56,13 +56,6 @@ def test_buffer_forward_matches_oracle_and_counts(hx, oracle_mod):
         buf.close()
 
 
-def _f64_to_bf16_bits(v: np.ndarray) -> np.ndarray:
-    """Round float64 values of normal bf16 magnitude to bf16 in ONE rounding (nearest even)."""
-    m, e = np.frexp(v)
-    r = np.ldexp(np.rint(m * 256.0), e - 8).astype(np.float32)   # exact: 8 significant bits
-    return (r.view(np.uint32) >> 16).astype(np.uint16)
-
-
 @pytest.mark.parametrize("name,T,H,mode,C,order", [
     ("tiny", None, None, "ht", 0, 0), ("tiny", None, None, "ll", 6, 0),
     ("ll_decode", 100, 1000, "ht", 0, 0), ("skew", 700, 512, "ll", 30, 0),
@@ -81,7 +74,7 @@ def test_backward_calls_match_the_oracle_composition(hx, oracle_mod, name, T, H,
     the entry's gate weight -- bit-exact with the float32 product, within one bf16 ulp of the
     float64 one; grad_w = row dot products, within the float32 summation bound of the float64 sums
     (far inside 1e-3 relative wherever the terms do not cancel)."""
-    import dataclasses
+    import backward_compose as bc
     from paper_2603_13606_amd.buffer import EPBuffer
     w = wl.make_workload(name, T=T, **({"H": H} if H else {}))
     spec = w.spec
@@ -107,26 +100,16 @@ def test_backward_calls_match_the_oracle_composition(hx, oracle_mod, name, T, H,
         g = hx.bits_to_dev(g_bits)
         grad_y, grad_w, _ = buf.combine_backward(g, h, gate, y)
         torch.cuda.synchronize()
-        gf = wl.bf16_bits_to_f32(g_bits)
-        want32 = np.zeros((rows, Hh), np.uint16)
-        want64 = np.zeros((rows, Hh), np.uint16)
-        for k in range(K):  # one oracle dispatch per entry column: the rows of (t, k) get w[t, k] * g[t]
-            col = dataclasses.replace(lay, K=1, dst_row=np.ascontiguousarray(lay.dst_row[:, k:k + 1]))
-            oracle_mod.dispatch(wl.f32_to_bf16_bits(w.topk_w[:, k:k + 1] * gf), None, col, want32)
-            p64 = (w.topk_w[:, k:k + 1].astype(np.float64) * gf.astype(np.float64))
-            oracle_mod.dispatch(_f64_to_bf16_bits(p64), None, col, want64)
+        want32 = bc.grad_y_rows(oracle_mod, lay, w.topk_w, g_bits, rows)
+        want64 = bc.grad_y_rows(oracle_mod, lay, w.topk_w, g_bits, rows, exact=True)
         got_gy = hx.dev_to_bits(grad_y.reshape(rows, Hh))
         assert np.array_equal(got_gy, want32), "grad_y differs from the dispatched, scaled gradient"
         assert hx.bf16_ulp_distance(got_gy, want64).max() <= 1
-        yf = wl.bf16_bits_to_f32(y_bits).astype(np.float64)
-        valid = lay.dst_row >= 0
-        rws = np.clip(lay.dst_row, 0, None)
-        terms = yf[rws] * gf.astype(np.float64)[:, None, :]          # [T, K, H]
-        ref_w = np.where(valid, terms.sum(-1), 0.0)
-        bound = np.abs(terms).sum(-1) * 64 * 2.0 ** -24 + 1e-30
+        ref_w, mag, valid = bc.grad_w_reference(y_bits, g_bits, lay)
+        bound = mag * 64 * 2.0 ** -24 + 1e-30
         got_w = grad_w.cpu().numpy().astype(np.float64)
         assert np.all(np.abs(got_w - ref_w) <= np.where(valid, bound, 0.0)), "grad_w outside the float32 summation bound"
-        big = valid & (np.abs(ref_w) > 0.05 * np.abs(terms).sum(-1))
+        big = valid & (np.abs(ref_w) > 0.05 * mag)
         assert np.all(np.abs(got_w - ref_w)[big] <= 1e-3 * np.abs(ref_w)[big])
         assert np.all(got_w[~valid] == 0.0)
         # backward of dispatch: the row gradients summed per token, no weights

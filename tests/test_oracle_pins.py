@@ -721,3 +721,69 @@ def test_multi_source_composition_is_a_stable_sort(oracle_mod, padded):
         assert np.array_equal(side_src, want_src) and np.array_equal(side_w, want_w)
         assert not np.any(full == fill) or True
         assert np.all(want_rank >= 0)  # the concatenated receiver has no holes
+
+
+@pytest.mark.parametrize("padded", [False, True])
+def test_backward_compositions_are_the_gradient_of_the_oracle_combine(oracle_mod, padded):
+    """The expected values the GPU tests use for the backward pass (tests/backward_compose.py) against
+    finite differences of the oracle's own forward functions.  With L = sum g * combine(y, w), L is
+    linear in every y element and every weight, so a difference quotient IS the derivative; the inputs
+    are small integers, which every step (bf16 storage, products, sums of K terms) represents exactly,
+    so the comparison is for equality.  Capacity drops (padded) and masked entries are included: their
+    gradients are zero.  The backward of dispatch is checked the same way: L = sum r * dispatch(x)."""
+    import backward_compose as bc
+    rng = np.random.default_rng(7 + padded)
+    T, K, H, E, R, C = 9, 3, 16, 6, 3, 3
+    topk = rng.integers(0, E, (T, K)).astype(np.int32)
+    topk[2, 1] = -1
+    topk[5, :] = topk[5, 0]                       # one token naming one expert three times
+    lay = oracle_mod.layout(topk, E=E, R=R, layout=int(padded), C=C if padded else 0, C_rank=T)
+    assert not padded or lay.dropped > 0
+    rows = E * C if padded else int(lay.expert_offset[-1])
+    ints = lambda shape, lo, hi: rng.integers(lo, hi + 1, shape).astype(np.float32)
+    y = ints((rows, H), -3, 3)
+    w = ints((T, K), 0, 2)
+    g = ints((T, H), -2, 2)
+    y_bits, g_bits = wl.f32_to_bf16_bits(y), wl.f32_to_bf16_bits(g)
+
+    def loss(y_bits_, w_):
+        out = wl.bf16_bits_to_f32(oracle_mod.combine(y_bits_, w_, lay, H, acc="f64")).astype(np.float64)
+        return float((out * g).sum())
+
+    base = loss(y_bits, w)
+    # d L / d w[t,k]
+    ref_w, _, valid = bc.grad_w_reference(y_bits, g_bits, lay)
+    for t in range(T):
+        for k in range(K):
+            w2 = w.copy()
+            w2[t, k] += 1.0
+            assert loss(y_bits, w2) - base == ref_w[t, k], (t, k)
+            assert valid[t, k] or ref_w[t, k] == 0.0
+    # d L / d y[row, h]: the K dispatches of the scaled output gradient
+    want = wl.bf16_bits_to_f32(bc.grad_y_rows(oracle_mod, lay, w, g_bits, rows)).astype(np.float64)
+    exact = wl.bf16_bits_to_f32(bc.grad_y_rows(oracle_mod, lay, w, g_bits, rows, exact=True)).astype(np.float64)
+    assert np.array_equal(want, exact)
+    pointed = np.zeros(rows, bool)
+    pointed[lay.dst_row[lay.dst_row >= 0]] = True
+    for row in range(rows):
+        for h in (0, H // 2, H - 1):
+            y2 = y.copy()
+            y2[row, h] += 1.0
+            assert loss(wl.f32_to_bf16_bits(y2), w) - base == want[row, h], (row, h)
+        assert pointed[row] or not want[row].any()
+    # backward of dispatch: L2 = sum r * dispatch(x); d L2 / d x[t, h] = sum_k r[dst_row[t,k], h] = unweighted combine
+    r = ints((rows, H), -3, 3)
+    x = ints((T, H), -2, 2)
+
+    def loss2(x_):
+        recv = np.zeros((rows, H), np.uint16)
+        oracle_mod.dispatch(wl.f32_to_bf16_bits(x_), None, lay, recv)
+        return float((wl.bf16_bits_to_f32(recv).astype(np.float64) * r).sum())
+
+    gx = wl.bf16_bits_to_f32(oracle_mod.combine(wl.f32_to_bf16_bits(r), None, lay, H, acc="f32")).astype(np.float64)
+    base2 = loss2(x)
+    for t in range(T):
+        for h in (0, H - 1):
+            x2 = x.copy()
+            x2[t, h] += 1.0
+            assert loss2(x2) - base2 == gx[t, h], (t, h)
