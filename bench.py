@@ -636,6 +636,18 @@ def main() -> int:
                                       "rocprofv3 figures of the committed run named in 'profile'"}
     if copy_reference is not None:
         line["hbm_copy_reference"] = copy_reference
+        if "roofline" in line and rows > 0:
+            # the same kernel against what THIS card sustains in each direction (the plain read and fill kernels
+            # of this process): time the kernel's reads would take alone plus time its writes would take alone
+            rd, wr = (T * row, rows * row) if dom == "dispatch" else (rows * row, T * row)
+            if dom == "dispatch" and sb.prefetch:
+                rd = 0  # the tokens come from the memory-side cache (read there by the layout launch)
+            floor_us = (rd / copy_reference["read_only_gbps"] + wr / copy_reference["write_only_gbps"]) * 1e-3
+            line["roofline"]["against_measured_rates"] = {
+                "floor_us": round(floor_us, 2), "frac": round(floor_us / float(dom_us), 4),
+                "what": "bytes read / read-only rate + bytes written / write-only rate of hbm_copy_reference, over "
+                        "kernel_us_events: how close the kernel is to what plain kernels reach on this card, as "
+                        "opposed to the published peak"}
     if args.graph:
         # one graph per input set: layout + dispatch + combine captured on a side stream
         side = torch.cuda.Stream()
