@@ -563,6 +563,34 @@ def test_degenerate_routings(ep, hx, oracle_mod, reroute, mode, C, order):
 
 
 @pytest.mark.parametrize("T,H", [(64, 520), (1100, 8192), (2048, 7168)])  # one segment, two segments, whole rows per wavefront
+def test_combine_strided_windows_and_output(ep, hx, oracle_mod, T, H):
+    """Expert outputs and the combined tokens as column slices of wider tensors (row pitch larger than H):
+    the rows are found through the strides, and nothing is written between the rows of the output."""
+    _say(f"combine strided T={T} H={H}")
+    spec = wl.WorkloadSpec("strided", 32, R=8, T=T, H=H, E=64, K=8)
+    topk, gate, _ = wl.make_routing(spec)
+    topk = _mess_up(topk, spec.E, seed=T + 1, frac_masked=0.02)
+    lay = oracle_mod.layout(topk, E=spec.E, R=spec.R, C_rank=T)
+    rows = int(lay.expert_offset[-1])
+    rng = np.random.default_rng(H - T)
+    y_bits = wl.f32_to_bf16_bits(rng.standard_normal((rows, H)).astype(np.float32))
+    g = _group(ep, spec, T, ep.EP_MODE_HT)
+    try:
+        h = ep.ep_layout(g, torch.from_numpy(topk).to(hx.DEV))
+        y_wide = hx.poison_bf16((rows, H + 64))
+        y_wide[:, :H] = hx.bits_to_dev(y_bits)
+        out_wide = hx.poison_bf16((T, H + 40))
+        ep.ep_combine(h, y_wide[:, :H], out_wide[:, :H], topk_weights=torch.from_numpy(gate).to(hx.DEV))
+        torch.cuda.synchronize()
+        got = hx.dev_to_bits(out_wide)
+        assert np.array_equal(got[:, :H], oracle_mod.combine(y_bits, gate, lay, H, acc="f32"))
+        assert np.all(got[:, H:] == hx.POISON), "combine wrote between the rows of its output"
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
+@pytest.mark.parametrize("T,H", [(64, 520), (1100, 8192), (2048, 7168)])  # one segment, two segments, whole rows per wavefront
 def test_combine_special_values(ep, hx, oracle_mod, T, H):
     """Expert outputs and gate weights full of the values arithmetic treats specially -- NaNs of either
     sign, infinities, signed zeros, bf16 and float32 subnormals, the largest finite values, weights of
