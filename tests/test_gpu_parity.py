@@ -962,6 +962,75 @@ def test_ll_windows_as_strided_view_of_receiver_tensor(ep, hx, oracle_mod):
         ep.ep_group_destroy(g)
 
 
+@pytest.mark.parametrize("variant", ["order 1 + read-ahead", "order 1", "order 2", "fp8", "fp8 ahead", "once per rank"])
+@pytest.mark.parametrize("mode", ["ht", "ll"])
+def test_large_inputs_through_strided_tensors(ep, hx, oracle_mod, mode, variant):
+    """The kernels of large inputs (8800 entries: destination-ordered copy, token read-ahead, quantising
+    walks, once-per-rank send and fan-out) with every tensor a slice of a wider one: tokens with a row
+    pitch larger than H, concatenated windows likewise, padded windows as this source's sub-regions of
+    a receiver-shaped [E, R*C, H] tensor.  Everything outside the slices keeps its fill."""
+    _say(f"strided large input mode={mode} variant={variant}")
+    w = wl.make_workload("skew", T=1100, H=1024)
+    spec = w.spec
+    T, H, E, R = spec.T, spec.H, spec.E, spec.R
+    ll = mode == "ll"
+    C, my_rank = 139, 2
+    topk = _mess_up(w.topk_idx, E, seed=5, frac_masked=0.01)
+    lay = oracle_mod.layout(topk, E=E, R=R, layout=int(ll), C=C if ll else 0, C_rank=T)
+    fp8 = variant.startswith("fp8")
+    kw = {"order 1 + read-ahead": dict(dispatch_order=1), "order 1": dict(dispatch_order=1), "order 2": dict(dispatch_order=2),
+          "fp8": {}, "fp8 ahead": dict(dispatch_order=1, quantize_ahead=1),
+          "once per rank": dict(dispatch_path=ep.EP_PATH_RANK_DEDUP)}[variant]
+    announce = variant in ("order 1 + read-ahead", "fp8 ahead")
+    g = _group(ep, spec, T, ep.EP_MODE_LL if ll else ep.EP_MODE_HT, C=C if ll else 0, my_rank=my_rank, **kw)
+    try:
+        xw = hx.poison_bf16((T, H + 24))
+        xw[:, 8:8 + H] = hx.bits_to_dev(w.x_bits)
+        x = xw[:, 8:8 + H]
+        d_topk = torch.from_numpy(topk).to(hx.DEV)
+        gate = torch.from_numpy(w.topk_w).to(hx.DEV)
+        h = ep.ep_layout_prefetch(g, d_topk, x) if announce else ep.ep_layout(g, d_topk)
+        elem = torch.uint8 if fp8 else torch.int16
+        fill = 0xAB if fp8 else int(np.array(hx.POISON, np.uint16).view(np.int16))
+        if ll:  # this source's columns [my_rank*C, (my_rank+1)*C) of every expert of the receiver's tensor
+            full = torch.full((E, R * C, H), fill, dtype=elem, device=hx.DEV)
+            recv = full[:, my_rank * C:(my_rank + 1) * C, :]
+            rows = E * C
+        else:
+            rows = int(lay.expert_offset[-1])
+            full = torch.full((rows + 3, H + 48), fill, dtype=elem, device=hx.DEV)
+            recv = full[:rows, :H]
+        recv_t = recv.view(torch.float8_e4m3fn) if fp8 else recv.view(torch.bfloat16)
+        if fp8:
+            G = H // 128
+            scales = torch.full((rows, G), -2.0, dtype=torch.float32, device=hx.DEV)
+            ep.ep_dispatch(h, x, recv_t, topk_weights=gate, recv_scales=scales)
+        else:
+            ep.ep_dispatch(h, x, recv_t, topk_weights=gate, topk_idx=d_topk if variant == "once per rank" else None)
+        torch.cuda.synchronize()
+        got = full.cpu().numpy()
+        if fp8:
+            o_q = np.full((rows, H), 0xAB, np.uint8)
+            o_s = np.full((rows, G), np.float32(-2.0), np.float32)
+            oracle_mod.dispatch_fp8(w.x_bits, lay, o_q, o_s)
+            assert np.array_equal(scales.cpu().numpy().view(np.uint32), o_s.view(np.uint32))
+            want_rows = o_q
+        else:
+            want_rows = np.full((rows, H), hx.POISON, np.uint16)
+            oracle_mod.dispatch(w.x_bits, None, lay, want_rows)
+        if ll:
+            want = np.full((E, R * C, H), fill, got.dtype)
+            want[:, my_rank * C:(my_rank + 1) * C, :] = want_rows.reshape(E, C, H).view(got.dtype)
+        else:
+            want = np.full((rows + 3, H + 48), fill, got.dtype)
+            want[:rows, :H] = want_rows.view(got.dtype)
+        assert np.array_equal(got, want), "rows differ, or something outside the windows was written"
+        assert np.all(hx.dev_to_bits(xw.view(torch.bfloat16))[:, :8] == hx.POISON)  # the tokens' surroundings are only read
+        ep.ep_handle_destroy(h)
+    finally:
+        ep.ep_group_destroy(g)
+
+
 def test_handle_reuse_forward_and_backward(ep, hx, oracle_mod):
     """One handle serves several dispatch/combine pairs (Sec. III-C: shared between the
     forward and backward passes)."""
