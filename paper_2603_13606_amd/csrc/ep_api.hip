@@ -341,7 +341,7 @@ const char* ep_error_string(ep_result_t code) {
     return "unknown error code";
 }
 
-int32_t ep_version(void) { return 400; }  // 0.3.0: ep_group_config_t and ep_group_info_t grew
+int32_t ep_version(void) { return 400; }  // 0.4.0: calibration fill / read and ep_combine_plan added (0.3.0: ep_group_config_t and ep_group_info_t grew)
 
 #ifndef EP_BUILD_ID_STRING
 #define EP_BUILD_ID_STRING "unknown"
